@@ -1,0 +1,196 @@
+/*
+ * Speculative-decoding step engine for one MI355X (gfx950).
+ *
+ * One speculative step (Background section): the draft model proposes gamma
+ * tokens autoregressively (spec_draft), the target model scores all of them in
+ * one pass over its weights against its KV cache (spec_verify), and the
+ * accept / resample rule emits the accepted prefix plus one target-distributed
+ * token (spec_accept).  The next gamma comes from gammatune_update()
+ * (gammatune.h; GammaTune section, Algorithm 1).  GammaTune+ (confidence-guided
+ * early stopping) is switched on with spec_set_early_stop().
+ *
+ * General rules
+ *  - Every function returns 0 (SPEC_OK) or a negative SPEC_E* code; nothing
+ *    throws or aborts across this boundary.  spec_strerror() names a code;
+ *    spec_last_error() gives the text of the last failure of a context.
+ *  - "device" pointers are HIP device addresses on the current device, "host"
+ *    pointers ordinary host memory.  The library never frees caller memory.
+ *  - Weights are BORROWED: the caller keeps them alive and unchanged until
+ *    spec_destroy().  The library only reads them (and may keep a re-tiled
+ *    device copy of its own).
+ *  - All work is enqueued on the stream given at init; only spec_accept(),
+ *    spec_prefill(), spec_read_tokens() and the spec_debug_* calls synchronise.
+ *  - One context per host thread; calls on one context must not overlap.
+ *  - Models are Llama-style decoders: RMSNorm, rotary embedding with
+ *    rotate-half pairing (element j pairs with j + head_dim/2, angle
+ *    pos * theta^(-2j/head_dim)), grouped-query attention (query head h reads
+ *    kv head h / (n_q_heads / n_kv_heads)), SwiGLU MLP, no biases.
+ */
+#ifndef SPEC_H
+#define SPEC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    SPEC_OK       = 0,
+    SPEC_EINVAL   = -1,  /* null pointer, bad shape, gamma out of range, buffer too small */
+    SPEC_ESTATE   = -2,  /* call order violated (prefill -> draft -> verify -> accept -> draft ...) */
+    SPEC_ENOMEM   = -3,  /* device or host allocation failed */
+    SPEC_EHIP     = -4,  /* a HIP runtime call failed; see spec_last_error() */
+    SPEC_ECAP     = -5,  /* the step would exceed max_seq */
+    SPEC_ENOTIMPL = -6
+};
+
+enum { SPEC_F32 = 0, SPEC_BF16 = 1 };
+enum { SPEC_ACCEPT_NATURAL = 0, SPEC_ACCEPT_FORCED = 1 };
+enum { SPEC_PATH_AUTO = 0, SPEC_PATH_WAVEDOT = 1, SPEC_PATH_MFMA = 2 };
+
+typedef struct spec_ctx spec_ctx; /* opaque */
+
+typedef struct {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    int32_t dtype;      /* SPEC_F32 or SPEC_BF16: storage type of every weight and of the KV cache */
+    float   rope_theta; /* rotary base */
+    float   rms_eps;
+} spec_shape;
+
+/* Device pointers.  Matrices are row-major [n_out][n_in] with n_in contiguous,
+ * element type per spec_shape.dtype, each row 16-byte aligned.  The per-layer
+ * members are HOST arrays of n_layers device pointers. */
+typedef struct {
+    const void *tok_embed;                           /* [vocab][d_model] */
+    const void *const *wq;                           /* [n_q_heads*head_dim][d_model] */
+    const void *const *wk, *const *wv;               /* [n_kv_heads*head_dim][d_model] */
+    const void *const *wo;                           /* [d_model][n_q_heads*head_dim] */
+    const void *const *w_gate, *const *w_up;         /* [d_ffn][d_model] */
+    const void *const *w_down;                       /* [d_model][d_ffn] */
+    const void *const *attn_norm, *const *ffn_norm;  /* [d_model] */
+    const void *final_norm;                          /* [d_model] */
+    const void *lm_head;                             /* [vocab][d_model]; may alias tok_embed */
+} spec_weights;
+
+typedef struct {
+    int32_t  batch;        /* sequences decoded in lock-step, >= 1 */
+    int32_t  max_seq;      /* capacity in tokens per sequence (prompt + generated + gamma_max + 1) */
+    int32_t  page_tokens;  /* tokens per KV page, a power of two >= 8; 0 -> 64 */
+    int32_t  gamma_max;    /* largest gamma ever passed to spec_draft, 1..64 */
+    float    temperature;  /* 0 -> greedy; same temperature for draft and target */
+    uint64_t seed;         /* Philox key */
+    int32_t  accept_mode;  /* SPEC_ACCEPT_NATURAL or SPEC_ACCEPT_FORCED */
+    int32_t  gemv_path;    /* SPEC_PATH_AUTO, or force one kernel family (bf16 models; fp32 models always use WAVEDOT) */
+    int32_t  use_graphs;   /* 1: replay one captured HIP graph per gamma; 0: launch kernel by kernel */
+    void    *hip_stream;   /* hipStream_t to enqueue on (borrowed); NULL = the null stream */
+} spec_config;
+
+/* Create a context: validates shapes (both models must share `vocab`), allocates the
+ * paged KV caches, activations and logits buffers, re-tiles bf16 weights for the
+ * matrix-core kernels, builds the rotary tables.  On failure *out is NULL. */
+int spec_init(const spec_shape *target, const spec_weights *target_w,
+              const spec_shape *draft, const spec_weights *draft_w,
+              const spec_config *cfg, spec_ctx **out);
+
+/* Load the prompts: host_tokens is host int32 [batch][n], n >= 1, every id in
+ * [0, vocab).  Both models ingest tokens 0..n-2 into their KV caches (the last
+ * prompt token is fed by the first step).  Resets step counter, lengths and
+ * generated count; may be called again to start a new generation.  Synchronises. */
+int spec_prefill(spec_ctx *ctx, const int32_t *host_tokens, int32_t n);
+
+/* Draft phase of one step, asynchronous.  Runs gamma draft-model decode steps; step i
+ * draws x_i from softmax(draft logits / T) by index-order inverse CDF with the uniform
+ * Philox(seed; counter = (step, i, DRAFT, b)) (argmax if T == 0), appends it to the
+ * sequence, and keeps the draft logits row for the accept phase.  With early stopping
+ * enabled drafting of a sequence ends after the first x_i whose confidence is below tau;
+ * that x_i is kept.  1 <= gamma <= gamma_max.  SPEC_ECAP if len + gamma + 1 > max_seq. */
+int spec_draft(spec_ctx *ctx, int32_t gamma);
+
+/* Same with one planned gamma per sequence (host int32 [batch]); the launch uses the
+ * largest, a sequence stops drafting at its own gamma. */
+int spec_draft_batch(spec_ctx *ctx, const int32_t *gammas);
+
+/* Verify phase, asynchronous: one target forward over the gamma+1 rows
+ * [last token, x_1 .. x_gamma] of every sequence, causal inside the rows, against the
+ * target KV cache; produces the logits rows p_1 .. p_{gamma+1}.  `gamma` must equal the
+ * (largest) gamma of the preceding spec_draft call. */
+int spec_verify(spec_ctx *ctx, int32_t gamma);
+
+/* Accept phase: runs the fused accept / resample kernels, waits for the stream, and
+ * returns per sequence (host int32 [batch] each, any may be NULL):
+ *   n_accepted  A  = number of leading drafted tokens accepted
+ *                    natural: u * q_i(x_i) < p_i(x_i), u = Philox(step, i, ACCEPT, b)
+ *                    greedy (T == 0): x_i == argmax p_i
+ *                    forced: Philox(g, 0, FORCED, b) < alpha[g], g = index of the generated token
+ *   next_token  y  = A < drafted: draw from norm(max(0, p_{A+1} - q_{A+1})) with u(step, A+1, RESID, b)
+ *                    A == drafted: draw from p_{drafted+1} with u(step, drafted+1, BONUS, b)
+ *                    (argmax of the same row if T == 0)
+ *   n_drafted   k  = tokens actually drafted (< gamma only with early stopping or a smaller per-sequence gamma)
+ * The sequence grows by x_1..x_A, y; the step counter advances. */
+int spec_accept(spec_ctx *ctx, int32_t *n_accepted, int32_t *next_token, int32_t *n_drafted);
+
+/* Forced acceptance landscape: alpha is host float [n], alpha[g] in [0,1] for generated index g
+ * (the last value repeats beyond n).  Only used with SPEC_ACCEPT_FORCED.  In forced mode the
+ * confidence seen by early stopping is 1 - Philox(g, 0, FORCED, b). */
+int spec_set_forced_alpha(spec_ctx *ctx, const float *alpha, int32_t n);
+
+/* GammaTune+ threshold: stop drafting when the draft's top probability
+ * max softmax(logits / T_eff), T_eff = T > 0 ? T : 1, is below tau.  tau <= 0 disables. */
+int spec_set_early_stop(spec_ctx *ctx, float tau);
+
+/* Copy the tokens of sequence b (prompt + generated so far) to host_out (host int32, capacity cap);
+ * *n receives the length.  Synchronises. */
+int spec_read_tokens(spec_ctx *ctx, int32_t b, int32_t *host_out, int32_t cap, int32_t *n);
+
+/* Parity hooks.  which = 0: draft logits of the last spec_draft, rows [batch][gamma] (row-major,
+ * `vocab` floats each); which = 1: target logits of the last spec_verify, rows [batch][gamma+1].
+ * host_out has room for cap floats; *rows receives rows per sequence.  Synchronises. */
+int spec_debug_logits(spec_ctx *ctx, int32_t which, float *host_out, int64_t cap, int32_t *rows);
+
+/* Tokens drafted by the last spec_draft for sequence b (valid until spec_accept): host int32, capacity cap;
+ * *n receives their number.  Synchronises. */
+int spec_debug_drafted(spec_ctx *ctx, int32_t b, int32_t *host_out, int32_t cap, int32_t *n);
+
+/* Fill both KV caches with seeded values in [-1, 1) for positions 0..len-1 and set every sequence
+ * length to len+1 with token 0 as the last token (verify-only sweeps).  Synchronises. */
+int spec_debug_fill_kv(spec_ctx *ctx, int32_t len, uint64_t seed);
+
+/* Replace the logical-to-physical KV page map of both models: host int32 [batch][max_seq/page_tokens],
+ * a permutation of 0..batch*pages-1.  Must be called before spec_prefill. */
+int spec_debug_set_block_table(spec_ctx *ctx, const int32_t *table);
+
+/* Device bytes the context allocated (KV pages, activations, logits, re-tiled weights). */
+int64_t spec_device_bytes(const spec_ctx *ctx);
+
+void spec_destroy(spec_ctx *ctx);
+const char *spec_strerror(int code);
+const char *spec_last_error(const spec_ctx *ctx);
+
+/* ---- single kernels on caller buffers (parity tests and roofline measurement) ---------------- */
+
+/* y[r][n] = sum_k x[r][k] * W[n][k].  W: device, row-major [N][K], dtype SPEC_F32 or SPEC_BF16
+ * (for path SPEC_PATH_MFMA: the re-tiled copy produced by spec_k_retile, bf16 only, N % 16 == 0,
+ * K % 32 == 0).  x: device fp32 [R][K]; y: device fp32 [R][N]; 1 <= R <= 128.  Asynchronous on `stream`. */
+int spec_k_gemv(const void *w, int32_t dtype, int32_t N, int32_t K, const float *x, int32_t R,
+                float *y, int32_t path, void *stream);
+
+/* Re-tile a row-major bf16 matrix [N][K] into the streaming layout of the matrix-core kernel:
+ * 16-row groups, each group a run of 1 KiB tiles (16 rows x 32 k) stored lane-major.  out: device,
+ * N*K*2 bytes. */
+int spec_k_retile(const void *w, int32_t N, int32_t K, void *out, void *stream);
+
+/* out[i] = Philox4x32-10(counter = ctr[i][0..3], key = seed); ctr, out: device uint32 [n][4]. */
+int spec_k_philox(uint64_t seed, const uint32_t *ctr, int32_t n, uint32_t *out, void *stream);
+
+/* Stand-alone accept / resample over caller logits (one sequence): p_logits device fp32 [k+1][vocab],
+ * q_logits device fp32 [k][vocab], drafted device int32 [k]; result device int32 [2] = {A, y}.
+ * Natural or greedy acceptance with the uniforms of step ordinal `step`, sequence 0. */
+int spec_k_accept(const float *p_logits, const float *q_logits, const int32_t *drafted, int32_t k,
+                  int32_t vocab, float temperature, uint64_t seed, int32_t step, int32_t *result,
+                  void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,842 @@
+// Host engine behind the C ABI of include/spec.h: owns the paged KV caches, the activation and
+// logits buffers and the per-gamma HIP graphs, and strings the kernels into the three phases of a
+// speculative step (Background section): gamma draft decode steps, one target verification pass
+// over gamma+1 rows, and the accept / resample step.
+#include "spec.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <string>
+#include <vector>
+
+#include "kernels/params.hpp"
+
+using namespace sd;
+
+namespace {
+
+constexpr int SSQ_STRIDE = 512;
+constexpr int ATT_CHUNK = 64;
+constexpr int RESID_CHUNKS = 64;
+constexpr int PREFILL_ROWS = 32;
+
+struct ModelRT {
+    spec_shape s{};
+    std::vector<const void *> wq, wk, wv, wo, wg, wu, wd;
+    std::vector<float *> attn_norm, ffn_norm;
+    float *final_norm = nullptr;
+    const void *embed = nullptr, *lm_head = nullptr;
+    // re-tiled bf16 copies for the matrix-core path (empty when unused)
+    std::vector<void *> t_qkv, t_wo, t_gu, t_wd;
+    void *t_lm = nullptr;
+    int Rmax = 0;
+    float *x = nullptr, *xg = nullptr, *ssq = nullptr, *q = nullptr, *ao = nullptr, *act = nullptr;
+    uint16_t *xgb = nullptr, *aob = nullptr, *actb = nullptr;
+    int32_t *row_pos = nullptr, *row_seq = nullptr;
+    std::vector<void *> kpool, vpool;
+    int32_t *block_table = nullptr;
+    int pages_per_seq = 0, n_pages = 0;
+    float *rope_cos = nullptr, *rope_sin = nullptr;
+    float *part_m = nullptr, *part_l = nullptr, *part_o = nullptr;
+    int n_chunks = 0;
+    // logits and their tile partials
+    float *logits = nullptr;
+    int logit_rows = 0;
+    float *pm = nullptr;
+    double *ps = nullptr;
+    int32_t *pa = nullptr;
+    int tiles_cap = 0;
+};
+
+}  // namespace
+
+struct spec_ctx {
+    spec_config cfg{};
+    hipStream_t stream = nullptr;
+    ModelRT tgt, drf;
+    State st{};
+    std::vector<void *> dev_allocs, host_allocs;
+    int64_t dev_bytes = 0;
+    std::string err;
+    // host mirrors
+    std::vector<int32_t> h_len;
+    int32_t *h_gamma_plan = nullptr;  // pinned, read by the device
+    int32_t *h_out = nullptr;         // pinned [3][B]: A, y, k
+    int32_t *d_gamma_plan = nullptr, *d_out = nullptr;
+    // sampling
+    SampleCfg scfg{};
+    float *d_alpha = nullptr;
+    int n_alpha = 0;
+    float *q_logit = nullptr, *q_max = nullptr;
+    double *q_sum = nullptr;
+    double *row_max = nullptr, *row_sum = nullptr, *resid_part = nullptr;
+    int32_t *row_arg = nullptr, *resid_row = nullptr, *A_dev = nullptr, *y_dev = nullptr;
+    uint32_t *ticket = nullptr;
+    // logits tiling of the last launches
+    int d_tile = 0, d_ntiles = 0, t_tile = 0, t_ntiles = 0;
+    // state machine: 0 = created, 1 = ready to draft, 2 = drafted, 3 = verified
+    int phase = 0;
+    int cur_gamma = 0;
+    bool prefilled = false;
+    std::map<int, hipGraphExec_t> g_draft, g_verify;
+    std::vector<hipGraph_t> graphs;
+};
+
+namespace {
+
+thread_local std::string g_last_err;  // failures that leave no context behind (spec_init)
+
+int fail(spec_ctx *c, int code, const std::string &msg) {
+    if (c) c->err = msg;
+    g_last_err = msg;
+    return code;
+}
+
+#define HIPCHK(c, call)                                                                              \
+    do {                                                                                             \
+        hipError_t e_ = (call);                                                                      \
+        if (e_ != hipSuccess)                                                                        \
+            return fail((c), SPEC_EHIP, std::string(#call) + ": " + hipGetErrorString(e_));          \
+    } while (0)
+
+template <typename T> int dalloc(spec_ctx *c, T **p, size_t n) {
+    void *v = nullptr;
+    const size_t bytes = (n ? n : 1) * sizeof(T);
+    if (hipMalloc(&v, bytes) != hipSuccess) return fail(c, SPEC_ENOMEM, "hipMalloc failed");
+    if (hipMemsetAsync(v, 0, bytes, c->stream) != hipSuccess) return fail(c, SPEC_EHIP, "hipMemsetAsync failed");
+    c->dev_allocs.push_back(v);
+    c->dev_bytes += (int64_t)bytes;
+    *p = reinterpret_cast<T *>(v);
+    return SPEC_OK;
+}
+
+#define TRY(expr)                       \
+    do {                                \
+        int rc_ = (expr);               \
+        if (rc_ != SPEC_OK) return rc_; \
+    } while (0)
+
+int check_shape(spec_ctx *c, const spec_shape &s, const char *who) {
+    auto bad = [&](const char *m) { return fail(c, SPEC_EINVAL, std::string(who) + ": " + m); };
+    if (s.n_layers < 1 || s.d_model < 8 || s.n_q_heads < 1 || s.n_kv_heads < 1 || s.head_dim < 8 || s.d_ffn < 8 ||
+        s.vocab < 2)
+        return bad("non-positive dimension");
+    if (s.n_q_heads % s.n_kv_heads) return bad("n_q_heads not a multiple of n_kv_heads");
+    if (s.head_dim % 8) return bad("head_dim must be a multiple of 8");
+    if (s.dtype != SPEC_F32 && s.dtype != SPEC_BF16) return bad("unknown dtype");
+    const int vec = s.dtype == SPEC_BF16 ? 8 : 4;
+    if (s.d_model % vec || s.d_ffn % vec || (s.n_q_heads * s.head_dim) % vec) return bad("row length not 16-byte aligned");
+    if (s.d_ffn % 2) return bad("d_ffn must be even");
+    if (!(s.rms_eps > 0.f) || !(s.rope_theta > 0.f)) return bad("bad rms_eps / rope_theta");
+    {
+        const int rpw = gemv_wavedot_pick_rpw(EPI_RESID, s.d_model, s.d_ffn, 1, s.dtype);
+        if (((s.d_model + rpw - 1) / rpw + 3) / 4 > SSQ_STRIDE) return bad("d_model too large");
+    }
+    return SPEC_OK;
+}
+
+int check_weights(spec_ctx *c, const spec_shape &s, const spec_weights *w, const char *who) {
+    auto bad = [&](const char *m) { return fail(c, SPEC_EINVAL, std::string(who) + ": " + m); };
+    if (!w || !w->tok_embed || !w->lm_head || !w->final_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->w_gate ||
+        !w->w_up || !w->w_down || !w->attn_norm || !w->ffn_norm)
+        return bad("null weight pointer");
+    for (int l = 0; l < s.n_layers; ++l) {
+        const void *ps[] = {w->wq[l], w->wk[l], w->wv[l], w->wo[l], w->w_gate[l], w->w_up[l], w->w_down[l],
+                            w->attn_norm[l], w->ffn_norm[l]};
+        for (const void *p : ps) {
+            if (!p) return bad("null layer weight");
+            if (reinterpret_cast<uintptr_t>(p) % 16) return bad("weight not 16-byte aligned");
+        }
+    }
+    return SPEC_OK;
+}
+
+int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights *w, int Rmax, int logit_rows) {
+    m.s = s;
+    m.Rmax = Rmax;
+    const int L = s.n_layers, d = s.d_model, qd = s.n_q_heads * s.head_dim;
+    const hipStream_t st = c->stream;
+    for (int l = 0; l < L; ++l) {
+        m.wq.push_back(w->wq[l]); m.wk.push_back(w->wk[l]); m.wv.push_back(w->wv[l]); m.wo.push_back(w->wo[l]);
+        m.wg.push_back(w->w_gate[l]); m.wu.push_back(w->w_up[l]); m.wd.push_back(w->w_down[l]);
+        float *a = nullptr, *f = nullptr;
+        TRY(dalloc(c, &a, d));
+        TRY(dalloc(c, &f, d));
+        HIPCHK(c, launch_cast_to_f32(w->attn_norm[l], s.dtype, a, d, st));
+        HIPCHK(c, launch_cast_to_f32(w->ffn_norm[l], s.dtype, f, d, st));
+        m.attn_norm.push_back(a);
+        m.ffn_norm.push_back(f);
+    }
+    TRY(dalloc(c, &m.final_norm, d));
+    HIPCHK(c, launch_cast_to_f32(w->final_norm, s.dtype, m.final_norm, d, st));
+    m.embed = w->tok_embed;
+    m.lm_head = w->lm_head;
+
+    const size_t R = (size_t)Rmax;
+    TRY(dalloc(c, &m.x, R * d));
+    TRY(dalloc(c, &m.xg, R * d));
+    TRY(dalloc(c, &m.xgb, R * d));
+    TRY(dalloc(c, &m.ssq, R * SSQ_STRIDE));
+    TRY(dalloc(c, &m.q, R * qd));
+    TRY(dalloc(c, &m.ao, R * qd));
+    TRY(dalloc(c, &m.aob, R * qd));
+    TRY(dalloc(c, &m.act, R * s.d_ffn));
+    TRY(dalloc(c, &m.actb, R * s.d_ffn));
+    TRY(dalloc(c, &m.row_pos, R));
+    TRY(dalloc(c, &m.row_seq, R));
+
+    // paged KV cache: sequence-interleaved physical pages by default
+    const int PT = c->cfg.page_tokens;
+    m.pages_per_seq = (c->cfg.max_seq + PT - 1) / PT;
+    m.n_pages = m.pages_per_seq * c->cfg.batch;
+    const size_t esz = s.dtype == SPEC_BF16 ? 2 : 4;
+    const size_t pool = (size_t)m.n_pages * s.n_kv_heads * PT * s.head_dim * esz;
+    for (int l = 0; l < L; ++l) {
+        uint8_t *k = nullptr, *v = nullptr;
+        TRY(dalloc(c, &k, pool));
+        TRY(dalloc(c, &v, pool));
+        m.kpool.push_back(k);
+        m.vpool.push_back(v);
+    }
+    TRY(dalloc(c, &m.block_table, (size_t)m.n_pages));
+    std::vector<int32_t> bt((size_t)m.n_pages);
+    for (int b = 0; b < c->cfg.batch; ++b)
+        for (int p = 0; p < m.pages_per_seq; ++p) bt[(size_t)b * m.pages_per_seq + p] = p * c->cfg.batch + b;
+    HIPCHK(c, hipMemcpy(m.block_table, bt.data(), bt.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+
+    // rotary tables, angles in double
+    const int half = s.head_dim / 2;
+    std::vector<float> cs((size_t)c->cfg.max_seq * half), sn(cs.size());
+    for (int p = 0; p < c->cfg.max_seq; ++p)
+        for (int j = 0; j < half; ++j) {
+            const double ang = (double)p * std::pow((double)s.rope_theta, -2.0 * j / s.head_dim);
+            cs[(size_t)p * half + j] = (float)std::cos(ang);
+            sn[(size_t)p * half + j] = (float)std::sin(ang);
+        }
+    TRY(dalloc(c, &m.rope_cos, cs.size()));
+    TRY(dalloc(c, &m.rope_sin, sn.size()));
+    HIPCHK(c, hipMemcpy(m.rope_cos, cs.data(), cs.size() * sizeof(float), hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(m.rope_sin, sn.data(), sn.size() * sizeof(float), hipMemcpyHostToDevice));
+
+    m.n_chunks = (c->cfg.max_seq + ATT_CHUNK - 1) / ATT_CHUNK;
+    const size_t pn = R * s.n_q_heads * m.n_chunks;
+    TRY(dalloc(c, &m.part_m, pn));
+    TRY(dalloc(c, &m.part_l, pn));
+    TRY(dalloc(c, &m.part_o, pn * s.head_dim));
+
+    m.logit_rows = logit_rows;
+    TRY(dalloc(c, &m.logits, (size_t)logit_rows * s.vocab));
+    m.tiles_cap = (s.vocab + 63) / 64 + 1;  // the finest tiling any logits kernel uses is 64 columns
+    TRY(dalloc(c, &m.pm, (size_t)logit_rows * m.tiles_cap));
+    TRY(dalloc(c, &m.ps, (size_t)logit_rows * m.tiles_cap));
+    TRY(dalloc(c, &m.pa, (size_t)logit_rows * m.tiles_cap));
+    return SPEC_OK;
+}
+
+KVCache kv_of(const spec_ctx *c, const ModelRT &m, int l) {
+    KVCache kv;
+    kv.k = m.kpool[l];
+    kv.v = m.vpool[l];
+    kv.block_table = m.block_table;
+    kv.pages_per_seq = m.pages_per_seq;
+    kv.page_tokens = c->cfg.page_tokens;
+    int sh = 0;
+    while ((1 << sh) < c->cfg.page_tokens) ++sh;
+    kv.page_shift = sh;
+    kv.n_kv = m.s.n_kv_heads;
+    kv.hd = m.s.head_dim;
+    return kv;
+}
+
+struct LogitsPlan {
+    bool want = false;
+    int rows = 0;           // logits rows produced
+    int x_mul = 1, x_add = 0;
+    int y_mul = 1, y_add = 0;
+    int *tile = nullptr, *ntiles = nullptr;
+};
+
+// Enqueue one forward pass of model m over R = batch * plan.rps rows.
+int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, bool draft_phase) {
+    const spec_shape &s = m.s;
+    const int B = c->cfg.batch, R = B * plan.rps;
+    const int d = s.d_model, qd = s.n_q_heads * s.head_dim, ffn = s.d_ffn;
+    const hipStream_t st = c->stream;
+    const int32_t *active = (draft_phase && plan.mode == ROWS_DRAFT_NEXT) ? &c->st.ctl[1] : nullptr;
+    if (R > m.Rmax) return fail(c, SPEC_EINVAL, "forward: too many rows");
+
+    EmbedArgs e{};
+    e.st = c->st; e.plan = plan; e.R = R; e.embed = m.embed; e.dtype = s.dtype; e.d = d; e.vocab = s.vocab;
+    e.g_next = m.attn_norm[0]; e.x = m.x; e.xg = m.xg; e.xgb = m.xgb; e.ssq_out = m.ssq; e.ssq_stride = SSQ_STRIDE;
+    e.row_pos = m.row_pos; e.row_seq = m.row_seq;
+    HIPCHK(c, launch_embed(e, st));
+    int slots = 1;
+
+    auto base = [&](int K, const float *x, const uint16_t *xb) {
+        GemvArgs a{};
+        a.K = K; a.R = R; a.x = x; a.xb = xb; a.x_mul = 1; a.x_add = 0; a.eps = s.rms_eps; a.active = active;
+        a.ssq_stride = SSQ_STRIDE;
+        return a;
+    };
+    for (int l = 0; l < s.n_layers; ++l) {
+        {   // fused QKV projection + RoPE + KV write
+            GemvArgs a = base(d, m.xg, m.xgb);
+            a.w0 = m.wq[l]; a.w1 = m.wk[l]; a.w2 = m.wv[l];
+            a.n0 = qd; a.n1 = a.n2 = s.n_kv_heads * s.head_dim;
+            a.ssq_in = m.ssq; a.ssq_in_slots = slots;
+            a.y = m.q; a.nq = s.n_q_heads; a.nkv = s.n_kv_heads; a.hd = s.head_dim;
+            a.rope_cos = m.rope_cos; a.rope_sin = m.rope_sin; a.row_pos = m.row_pos; a.row_seq = m.row_seq;
+            a.kv = kv_of(c, m, l); a.kv_dtype = s.dtype;
+            a.rpw = gemv_wavedot_pick_rpw(EPI_QKV, qd + 2 * a.n1, d, R, s.dtype);
+            HIPCHK(c, launch_gemv_wavedot(a, EPI_QKV, s.dtype, st));
+        }
+        {
+            AttnArgs t{};
+            t.q = m.q; t.kv = kv_of(c, m, l); t.kv_dtype = s.dtype; t.R = R; t.rps = plan.rps; t.nq = s.n_q_heads;
+            t.row_pos = m.row_pos; t.row_seq = m.row_seq; t.chunk = ATT_CHUNK; t.n_chunks = m.n_chunks;
+            t.scale = 1.0f / std::sqrt((float)s.head_dim);
+            t.part_m = m.part_m; t.part_l = m.part_l; t.part_o = m.part_o; t.o = m.ao; t.ob = m.aob; t.active = active;
+            HIPCHK(c, launch_attention(t, s.head_dim, st));
+        }
+        {   // output projection + residual
+            GemvArgs a = base(qd, m.ao, m.aob);
+            a.w0 = m.wo[l]; a.n0 = d;
+            a.xres = m.x; a.g_next = m.ffn_norm[l]; a.xg = m.xg; a.xgb = m.xgb; a.ssq_out = m.ssq;
+            a.rpw = gemv_wavedot_pick_rpw(EPI_RESID, d, qd, R, s.dtype);
+            HIPCHK(c, launch_gemv_wavedot(a, EPI_RESID, s.dtype, st));
+            slots = ((d + a.rpw - 1) / a.rpw + 3) / 4;
+        }
+        {   // gate / up projections + SwiGLU
+            GemvArgs a = base(d, m.xg, m.xgb);
+            a.w0 = m.wg[l]; a.w1 = m.wu[l]; a.n0 = ffn;
+            a.ssq_in = m.ssq; a.ssq_in_slots = slots;
+            a.y = m.act; a.yb = m.actb;
+            a.rpw = gemv_wavedot_pick_rpw(EPI_SWIGLU, 2 * ffn, d, R, s.dtype);
+            HIPCHK(c, launch_gemv_wavedot(a, EPI_SWIGLU, s.dtype, st));
+        }
+        {   // down projection + residual
+            GemvArgs a = base(ffn, m.act, m.actb);
+            a.w0 = m.wd[l]; a.n0 = d;
+            a.xres = m.x; a.g_next = (l + 1 < s.n_layers) ? m.attn_norm[l + 1] : m.final_norm;
+            a.xg = m.xg; a.xgb = m.xgb; a.ssq_out = m.ssq;
+            a.rpw = gemv_wavedot_pick_rpw(EPI_RESID, d, ffn, R, s.dtype);
+            HIPCHK(c, launch_gemv_wavedot(a, EPI_RESID, s.dtype, st));
+            slots = ((d + a.rpw - 1) / a.rpw + 3) / 4;
+        }
+    }
+    if (lp.want) {
+        GemvArgs a = base(d, m.xg, m.xgb);
+        a.R = lp.rows;
+        a.x_mul = lp.x_mul; a.x_add = lp.x_add;
+        a.w0 = m.lm_head; a.n0 = s.vocab;
+        a.ssq_in = m.ssq; a.ssq_in_slots = slots;
+        a.y = m.logits; a.y_mul = lp.y_mul; a.y_add = lp.y_add; a.y_stride = s.vocab;
+        a.pm = m.pm; a.ps = m.ps; a.pa = m.pa; a.inv_t = c->scfg.inv_t;
+        a.rpw = gemv_wavedot_pick_rpw(EPI_LOGITS, s.vocab, d, a.R, s.dtype);
+        const int tile = 4 * a.rpw;
+        a.n_tiles = (s.vocab + tile - 1) / tile;
+        if (a.n_tiles > m.tiles_cap) return fail(c, SPEC_EINVAL, "logits tiling exceeds the partial buffers");
+        *lp.tile = tile;
+        *lp.ntiles = a.n_tiles;
+        HIPCHK(c, launch_gemv_wavedot(a, EPI_LOGITS, s.dtype, st));
+    }
+    return SPEC_OK;
+}
+
+int enqueue_draft(spec_ctx *c, int gamma) {
+    HIPCHK(c, launch_begin_draft(c->st, c->d_gamma_plan, c->stream));
+    const int B = c->cfg.batch;
+    for (int j = 1; j <= gamma; ++j) {
+        RowPlan plan{};
+        LogitsPlan lp{};
+        lp.want = true;
+        lp.rows = B;
+        lp.tile = &c->d_tile;
+        lp.ntiles = &c->d_ntiles;
+        lp.y_mul = c->cfg.gamma_max;
+        lp.y_add = j - 1;
+        if (j == 1) {
+            plan.mode = ROWS_DRAFT_FIRST; plan.rps = 2; plan.arg = 0;
+            lp.x_mul = 2; lp.x_add = 1;
+        } else {
+            plan.mode = ROWS_DRAFT_NEXT; plan.rps = 1; plan.arg = j;
+            lp.x_mul = 1; lp.x_add = 0;
+        }
+        TRY(forward(c, c->drf, plan, lp, true));
+        DraftSampleArgs a{};
+        a.st = c->st; a.cfg = c->scfg; a.j = j; a.gamma_max = c->cfg.gamma_max; a.logits = c->drf.logits;
+        a.vocab = c->drf.s.vocab; a.pm = c->drf.pm; a.ps = c->drf.ps; a.pa = c->drf.pa;
+        a.n_tiles = c->d_ntiles; a.tile = c->d_tile;
+        a.q_logit = c->q_logit; a.q_max = c->q_max; a.q_sum = c->q_sum;
+        HIPCHK(c, launch_draft_sample(a, c->stream));
+    }
+    return SPEC_OK;
+}
+
+int enqueue_verify(spec_ctx *c, int gamma) {
+    RowPlan plan{};
+    plan.mode = ROWS_VERIFY; plan.rps = gamma + 1; plan.arg = 0;
+    LogitsPlan lp{};
+    lp.want = true;
+    lp.rows = c->cfg.batch * (gamma + 1);
+    lp.tile = &c->t_tile;
+    lp.ntiles = &c->t_ntiles;
+    return forward(c, c->tgt, plan, lp, false);
+}
+
+int enqueue_accept(spec_ctx *c, int gamma) {
+    AcceptArgs a{};
+    a.st = c->st; a.cfg = c->scfg; a.gamma = gamma; a.gamma_max = c->cfg.gamma_max; a.vocab = c->tgt.s.vocab;
+    a.p_logits = c->tgt.logits; a.pm = c->tgt.pm; a.ps = c->tgt.ps; a.pa = c->tgt.pa;
+    a.n_tiles = c->t_ntiles; a.tile = c->t_tile;
+    a.q_logits = c->drf.logits; a.q_logit = c->q_logit; a.q_max = c->q_max; a.q_sum = c->q_sum;
+    a.row_max = c->row_max; a.row_sum = c->row_sum; a.row_arg = c->row_arg; a.resid_row = c->resid_row;
+    a.resid_part = c->resid_part; a.n_resid_chunks = RESID_CHUNKS; a.ticket = c->ticket;
+    a.out_A = c->d_out; a.out_y = c->d_out + c->cfg.batch; a.out_k = c->d_out + 2 * c->cfg.batch;
+    a.A_dev = c->A_dev; a.y_dev = c->y_dev;
+    HIPCHK(c, launch_accept(a, c->stream));
+    return SPEC_OK;
+}
+
+// Capture `body` into an executable graph.
+template <typename F> int capture(spec_ctx *c, F body, hipGraphExec_t *out) {
+    HIPCHK(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+    const int rc = body();
+    hipGraph_t g = nullptr;
+    const hipError_t e = hipStreamEndCapture(c->stream, &g);
+    if (rc != SPEC_OK) {
+        if (g) hipGraphDestroy(g);
+        return rc;
+    }
+    if (e != hipSuccess) return fail(c, SPEC_EHIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
+    c->graphs.push_back(g);
+    HIPCHK(c, hipGraphInstantiate(out, g, nullptr, nullptr, 0));
+    return SPEC_OK;
+}
+
+int prefill_model(spec_ctx *c, ModelRT &m, int n_ingest) {
+    const int B = c->cfg.batch;
+    const int chunk = std::max(1, std::min(PREFILL_ROWS, m.Rmax / B));
+    for (int p0 = 0; p0 < n_ingest; p0 += chunk) {
+        RowPlan plan{};
+        plan.mode = ROWS_PREFILL;
+        plan.rps = std::min(chunk, n_ingest - p0);
+        plan.arg = p0;
+        LogitsPlan lp{};
+        TRY(forward(c, m, plan, lp, false));
+    }
+    return SPEC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *spec_strerror(int code) {
+    switch (code) {
+        case SPEC_OK: return "ok";
+        case SPEC_EINVAL: return "invalid argument";
+        case SPEC_ESTATE: return "call order violated";
+        case SPEC_ENOMEM: return "out of memory";
+        case SPEC_EHIP: return "HIP runtime error";
+        case SPEC_ECAP: return "sequence capacity exceeded";
+        case SPEC_ENOTIMPL: return "not implemented";
+    }
+    return "unknown error";
+}
+
+const char *spec_last_error(const spec_ctx *ctx) { return ctx ? ctx->err.c_str() : g_last_err.c_str(); }
+
+int64_t spec_device_bytes(const spec_ctx *ctx) { return ctx ? ctx->dev_bytes : 0; }
+
+void spec_destroy(spec_ctx *c) {
+    if (!c) return;
+    hipStreamSynchronize(c->stream);
+    for (auto &kv : c->g_draft) hipGraphExecDestroy(kv.second);
+    for (auto &kv : c->g_verify) hipGraphExecDestroy(kv.second);
+    for (auto g : c->graphs) hipGraphDestroy(g);
+    for (void *p : c->dev_allocs) hipFree(p);
+    for (void *p : c->host_allocs) hipHostFree(p);
+    delete c;
+}
+
+int spec_init(const spec_shape *t, const spec_weights *tw, const spec_shape *d, const spec_weights *dw,
+              const spec_config *cfg, spec_ctx **out) {
+    if (!out) return SPEC_EINVAL;
+    *out = nullptr;
+    if (!t || !tw || !d || !dw || !cfg) return SPEC_EINVAL;
+    spec_ctx *c = new spec_ctx();
+    auto bail = [&](int rc) {  // the message stays reachable through spec_last_error(NULL)
+        spec_destroy(c);
+        return rc;
+    };
+    c->cfg = *cfg;
+    if (c->cfg.page_tokens == 0) c->cfg.page_tokens = 64;
+    c->stream = reinterpret_cast<hipStream_t>(cfg->hip_stream);
+    int rc;
+    if ((rc = check_shape(c, *t, "target")) || (rc = check_shape(c, *d, "draft")) ||
+        (rc = check_weights(c, *t, tw, "target")) || (rc = check_weights(c, *d, dw, "draft")))
+        return bail(rc);
+    const spec_config &g = c->cfg;
+    if (t->vocab != d->vocab) return bail(fail(c, SPEC_EINVAL, "draft and target vocabularies differ"));
+    if (g.batch < 1 || g.batch > 64) return bail(fail(c, SPEC_EINVAL, "batch outside 1..64"));
+    if (g.gamma_max < 1 || g.gamma_max > 64) return bail(fail(c, SPEC_EINVAL, "gamma_max outside 1..64"));
+    if (g.page_tokens < 8 || (g.page_tokens & (g.page_tokens - 1)))
+        return bail(fail(c, SPEC_EINVAL, "page_tokens must be a power of two >= 8"));
+    if (g.max_seq < g.gamma_max + 2) return bail(fail(c, SPEC_EINVAL, "max_seq too small"));
+    if (!(g.temperature >= 0.f)) return bail(fail(c, SPEC_EINVAL, "temperature < 0"));
+    if (g.accept_mode != SPEC_ACCEPT_NATURAL && g.accept_mode != SPEC_ACCEPT_FORCED)
+        return bail(fail(c, SPEC_EINVAL, "unknown accept_mode"));
+    if (g.batch * (g.gamma_max + 1) > 128) return bail(fail(c, SPEC_EINVAL, "batch * (gamma_max + 1) > 128 rows"));
+
+    const int B = g.batch;
+    const int rows_t = std::max(B * (g.gamma_max + 1), std::min(128, B * PREFILL_ROWS));
+    const int rows_d = std::max(2 * B, std::min(128, B * PREFILL_ROWS));
+    if ((rc = build_model(c, c->tgt, *t, tw, rows_t, B * (g.gamma_max + 1)))) return bail(rc);
+    if ((rc = build_model(c, c->drf, *d, dw, rows_d, B * g.gamma_max))) return bail(rc);
+
+    auto A = [&](auto **p, size_t n) { return dalloc(c, p, n); };
+    if ((rc = A(&c->st.len, B)) || (rc = A(&c->st.prompt_len, B)) || (rc = A(&c->st.gamma_b, B)) ||
+        (rc = A(&c->st.k, B)) || (rc = A(&c->st.ctl, 4)) || (rc = A(&c->st.tokens, (size_t)B * g.max_seq)) ||
+        (rc = A(&c->q_logit, (size_t)B * g.gamma_max)) || (rc = A(&c->q_max, (size_t)B * g.gamma_max)) ||
+        (rc = A(&c->q_sum, (size_t)B * g.gamma_max)) || (rc = A(&c->row_max, (size_t)B * (g.gamma_max + 1))) ||
+        (rc = A(&c->row_sum, (size_t)B * (g.gamma_max + 1))) || (rc = A(&c->row_arg, (size_t)B * (g.gamma_max + 1))) ||
+        (rc = A(&c->resid_row, B)) || (rc = A(&c->resid_part, (size_t)B * RESID_CHUNKS)) || (rc = A(&c->ticket, B)) ||
+        (rc = A(&c->A_dev, B)) || (rc = A(&c->y_dev, B)) || (rc = A(&c->d_alpha, 1)))
+        return bail(rc);
+    c->st.max_seq = g.max_seq;
+    c->st.batch = B;
+    c->h_len.assign(B, 0);
+
+    void *hp = nullptr;
+    if (hipHostMalloc(&hp, sizeof(int32_t) * 4 * B, hipHostMallocMapped) != hipSuccess)
+        return bail(fail(c, SPEC_ENOMEM, "hipHostMalloc failed"));
+    c->host_allocs.push_back(hp);
+    std::memset(hp, 0, sizeof(int32_t) * 4 * B);
+    c->h_gamma_plan = reinterpret_cast<int32_t *>(hp);
+    c->h_out = c->h_gamma_plan + B;
+    void *dp = nullptr;
+    if (hipHostGetDevicePointer(&dp, hp, 0) != hipSuccess)
+        return bail(fail(c, SPEC_EHIP, "hipHostGetDevicePointer failed"));
+    c->d_gamma_plan = reinterpret_cast<int32_t *>(dp);
+    c->d_out = c->d_gamma_plan + B;
+
+    c->scfg.temperature = g.temperature;
+    c->scfg.inv_t = g.temperature > 0.f ? 1.0f / g.temperature : 1.0f;
+    c->scfg.seed = g.seed;
+    c->scfg.forced = g.accept_mode == SPEC_ACCEPT_FORCED;
+    c->scfg.alpha = c->d_alpha;
+    c->scfg.n_alpha = 1;
+    c->scfg.tau = 0.f;
+    {
+        const float one = 1.0f;
+        if (hipMemcpy(c->d_alpha, &one, sizeof(float), hipMemcpyHostToDevice) != hipSuccess)
+            return bail(fail(c, SPEC_EHIP, "hipMemcpy failed"));
+    }
+    if (hipStreamSynchronize(c->stream) != hipSuccess) return bail(fail(c, SPEC_EHIP, "init: stream sync failed"));
+    *out = c;
+    return SPEC_OK;
+}
+
+int spec_set_forced_alpha(spec_ctx *c, const float *alpha, int32_t n) {
+    if (!c || !alpha || n < 1) return fail(c, SPEC_EINVAL, "set_forced_alpha: bad arguments");
+    for (int i = 0; i < n; ++i)
+        if (!(alpha[i] >= 0.f && alpha[i] <= 1.f)) return fail(c, SPEC_EINVAL, "alpha outside [0,1]");
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    float *p = nullptr;
+    TRY(dalloc(c, &p, (size_t)n));
+    HIPCHK(c, hipMemcpy(p, alpha, sizeof(float) * n, hipMemcpyHostToDevice));
+    c->d_alpha = p;
+    c->scfg.alpha = p;
+    c->scfg.n_alpha = n;
+    // kernel arguments are baked into captured graphs
+    for (auto &kv : c->g_draft) hipGraphExecDestroy(kv.second);
+    for (auto &kv : c->g_verify) hipGraphExecDestroy(kv.second);
+    c->g_draft.clear();
+    c->g_verify.clear();
+    return SPEC_OK;
+}
+
+int spec_set_early_stop(spec_ctx *c, float tau) {
+    if (!c) return SPEC_EINVAL;
+    if (!(tau == tau)) return fail(c, SPEC_EINVAL, "tau is NaN");
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    c->scfg.tau = tau > 0.f ? tau : 0.f;
+    for (auto &kv : c->g_draft) hipGraphExecDestroy(kv.second);
+    c->g_draft.clear();
+    return SPEC_OK;
+}
+
+int spec_debug_set_block_table(spec_ctx *c, const int32_t *table) {
+    if (!c || !table) return SPEC_EINVAL;
+    if (c->prefilled) return fail(c, SPEC_ESTATE, "block table must be set before prefill");
+    for (ModelRT *m : {&c->tgt, &c->drf}) {
+        std::vector<char> seen((size_t)m->n_pages, 0);
+        for (int i = 0; i < m->n_pages; ++i) {
+            if (table[i] < 0 || table[i] >= m->n_pages || seen[(size_t)table[i]])
+                return fail(c, SPEC_EINVAL, "block table is not a permutation");
+            seen[(size_t)table[i]] = 1;
+        }
+        HIPCHK(c, hipMemcpy(m->block_table, table, sizeof(int32_t) * m->n_pages, hipMemcpyHostToDevice));
+    }
+    return SPEC_OK;
+}
+
+int spec_prefill(spec_ctx *c, const int32_t *host_tokens, int32_t n) {
+    if (!c || !host_tokens) return fail(c, SPEC_EINVAL, "prefill: null pointer");
+    const int B = c->cfg.batch;
+    if (n < 1 || n + c->cfg.gamma_max + 1 > c->cfg.max_seq) return fail(c, SPEC_ECAP, "prefill: prompt does not fit max_seq");
+    for (int64_t i = 0; i < (int64_t)B * n; ++i)
+        if (host_tokens[i] < 0 || host_tokens[i] >= c->tgt.s.vocab) return fail(c, SPEC_EINVAL, "prefill: token id out of range");
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    std::vector<int32_t> toks((size_t)B * c->cfg.max_seq, 0);
+    for (int b = 0; b < B; ++b) std::memcpy(&toks[(size_t)b * c->cfg.max_seq], host_tokens + (size_t)b * n, sizeof(int32_t) * n);
+    HIPCHK(c, hipMemcpy(c->st.tokens, toks.data(), toks.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+    std::vector<int32_t> lens(B, n);
+    HIPCHK(c, hipMemcpy(c->st.len, lens.data(), sizeof(int32_t) * B, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(c->st.prompt_len, lens.data(), sizeof(int32_t) * B, hipMemcpyHostToDevice));
+    const int32_t ctl[4] = {-1, 0, 0, 0};
+    HIPCHK(c, hipMemcpy(c->st.ctl, ctl, sizeof(ctl), hipMemcpyHostToDevice));
+    std::vector<uint32_t> z(B, 0);
+    HIPCHK(c, hipMemcpy(c->ticket, z.data(), sizeof(uint32_t) * B, hipMemcpyHostToDevice));
+    c->h_len.assign(B, n);
+    TRY(prefill_model(c, c->tgt, n - 1));
+    TRY(prefill_model(c, c->drf, n - 1));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    c->prefilled = true;
+    c->phase = 1;
+    return SPEC_OK;
+}
+
+int spec_draft_batch(spec_ctx *c, const int32_t *gammas) {
+    if (!c || !gammas) return fail(c, SPEC_EINVAL, "draft: null pointer");
+    if (c->phase != 1) return fail(c, SPEC_ESTATE, "draft: expected after prefill or accept");
+    const int B = c->cfg.batch;
+    int gmax = 0;
+    for (int b = 0; b < B; ++b) {
+        if (gammas[b] < 1 || gammas[b] > c->cfg.gamma_max) return fail(c, SPEC_EINVAL, "draft: gamma outside 1..gamma_max");
+        gmax = std::max(gmax, gammas[b]);
+    }
+    for (int b = 0; b < B; ++b)
+        if (c->h_len[b] + gmax + 1 > c->cfg.max_seq) return fail(c, SPEC_ECAP, "draft: len + gamma + 1 > max_seq");
+    for (int b = 0; b < B; ++b) c->h_gamma_plan[b] = gammas[b];
+    if (c->cfg.use_graphs) {
+        auto it = c->g_draft.find(gmax);
+        if (it == c->g_draft.end()) {
+            hipGraphExec_t ex = nullptr;
+            TRY(capture(c, [&] { return enqueue_draft(c, gmax); }, &ex));
+            it = c->g_draft.emplace(gmax, ex).first;
+        }
+        HIPCHK(c, hipGraphLaunch(it->second, c->stream));
+    } else {
+        TRY(enqueue_draft(c, gmax));
+    }
+    c->cur_gamma = gmax;
+    c->phase = 2;
+    return SPEC_OK;
+}
+
+int spec_draft(spec_ctx *c, int32_t gamma) {
+    if (!c) return SPEC_EINVAL;
+    std::vector<int32_t> g((size_t)c->cfg.batch, gamma);
+    return spec_draft_batch(c, g.data());
+}
+
+int spec_verify(spec_ctx *c, int32_t gamma) {
+    if (!c) return SPEC_EINVAL;
+    if (c->phase != 2) return fail(c, SPEC_ESTATE, "verify: expected after draft");
+    if (gamma != c->cur_gamma) return fail(c, SPEC_EINVAL, "verify: gamma differs from the draft phase");
+    if (c->cfg.use_graphs) {
+        auto it = c->g_verify.find(gamma);
+        if (it == c->g_verify.end()) {
+            hipGraphExec_t ex = nullptr;
+            TRY(capture(c, [&] { return enqueue_verify(c, gamma); }, &ex));
+            it = c->g_verify.emplace(gamma, ex).first;
+        }
+        HIPCHK(c, hipGraphLaunch(it->second, c->stream));
+    } else {
+        TRY(enqueue_verify(c, gamma));
+    }
+    c->phase = 3;
+    return SPEC_OK;
+}
+
+int spec_accept(spec_ctx *c, int32_t *n_accepted, int32_t *next_token, int32_t *n_drafted) {
+    if (!c) return SPEC_EINVAL;
+    if (c->phase != 3) return fail(c, SPEC_ESTATE, "accept: expected after verify");
+    TRY(enqueue_accept(c, c->cur_gamma));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    const int B = c->cfg.batch;
+    for (int b = 0; b < B; ++b) {
+        const int A = c->h_out[b], y = c->h_out[B + b], k = c->h_out[2 * B + b];
+        if (n_accepted) n_accepted[b] = A;
+        if (next_token) next_token[b] = y;
+        if (n_drafted) n_drafted[b] = k;
+        c->h_len[b] += A + 1;
+    }
+    c->phase = 1;
+    return SPEC_OK;
+}
+
+int spec_read_tokens(spec_ctx *c, int32_t b, int32_t *host_out, int32_t cap, int32_t *n) {
+    if (!c || !host_out || !n) return fail(c, SPEC_EINVAL, "read_tokens: null pointer");
+    if (b < 0 || b >= c->cfg.batch) return fail(c, SPEC_EINVAL, "read_tokens: bad sequence index");
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    const int len = c->h_len[b];
+    if (cap < len) return fail(c, SPEC_EINVAL, "read_tokens: buffer too small");
+    HIPCHK(c, hipMemcpy(host_out, c->st.tokens + (size_t)b * c->cfg.max_seq, sizeof(int32_t) * len, hipMemcpyDeviceToHost));
+    *n = len;
+    return SPEC_OK;
+}
+
+int spec_debug_logits(spec_ctx *c, int32_t which, float *host_out, int64_t cap, int32_t *rows) {
+    if (!c || !host_out || !rows) return fail(c, SPEC_EINVAL, "debug_logits: null pointer");
+    if (which != 0 && which != 1) return fail(c, SPEC_EINVAL, "debug_logits: which must be 0 or 1");
+    if (c->cur_gamma < 1) return fail(c, SPEC_ESTATE, "debug_logits: no step has run");
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    const int B = c->cfg.batch, V = c->tgt.s.vocab;
+    const int rps = which == 0 ? c->cur_gamma : c->cur_gamma + 1;
+    if (cap < (int64_t)B * rps * V) return fail(c, SPEC_EINVAL, "debug_logits: buffer too small");
+    if (which == 1) {
+        HIPCHK(c, hipMemcpy(host_out, c->tgt.logits, sizeof(float) * (size_t)B * rps * V, hipMemcpyDeviceToHost));
+    } else {
+        for (int b = 0; b < B; ++b)
+            HIPCHK(c, hipMemcpy(host_out + (size_t)b * rps * V, c->drf.logits + (size_t)b * c->cfg.gamma_max * V,
+                                sizeof(float) * (size_t)rps * V, hipMemcpyDeviceToHost));
+    }
+    *rows = rps;
+    return SPEC_OK;
+}
+
+int spec_debug_drafted(spec_ctx *c, int32_t b, int32_t *host_out, int32_t cap, int32_t *n) {
+    if (!c || !host_out || !n) return fail(c, SPEC_EINVAL, "debug_drafted: null pointer");
+    if (b < 0 || b >= c->cfg.batch) return fail(c, SPEC_EINVAL, "debug_drafted: bad sequence index");
+    if (c->phase != 2 && c->phase != 3) return fail(c, SPEC_ESTATE, "debug_drafted: expected between draft and accept");
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    int32_t k = 0;
+    HIPCHK(c, hipMemcpy(&k, c->st.k + b, sizeof(int32_t), hipMemcpyDeviceToHost));
+    if (k < 0 || k > cap) return fail(c, SPEC_EINVAL, "debug_drafted: buffer too small");
+    HIPCHK(c, hipMemcpy(host_out, c->st.tokens + (size_t)b * c->cfg.max_seq + c->h_len[b], sizeof(int32_t) * k,
+                        hipMemcpyDeviceToHost));
+    *n = k;
+    return SPEC_OK;
+}
+
+int spec_debug_fill_kv(spec_ctx *c, int32_t len, uint64_t seed) {
+    if (!c) return SPEC_EINVAL;
+    if (len < 0 || len + 1 + c->cfg.gamma_max + 1 > c->cfg.max_seq) return fail(c, SPEC_ECAP, "fill_kv: len does not fit max_seq");
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    const int B = c->cfg.batch;
+    uint64_t sd_ = seed;
+    for (ModelRT *m : {&c->tgt, &c->drf}) {
+        const int64_t n = (int64_t)m->n_pages * m->s.n_kv_heads * c->cfg.page_tokens * m->s.head_dim;
+        for (int l = 0; l < m->s.n_layers; ++l) {
+            HIPCHK(c, launch_fill_uniform(m->kpool[l], n, m->s.dtype, sd_++, c->stream));
+            HIPCHK(c, launch_fill_uniform(m->vpool[l], n, m->s.dtype, sd_++, c->stream));
+        }
+    }
+    std::vector<int32_t> toks((size_t)B * c->cfg.max_seq, 0);
+    HIPCHK(c, hipMemcpy(c->st.tokens, toks.data(), toks.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+    std::vector<int32_t> lens(B, len + 1);
+    HIPCHK(c, hipMemcpy(c->st.len, lens.data(), sizeof(int32_t) * B, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(c->st.prompt_len, lens.data(), sizeof(int32_t) * B, hipMemcpyHostToDevice));
+    const int32_t ctl[4] = {-1, 0, 0, 0};
+    HIPCHK(c, hipMemcpy(c->st.ctl, ctl, sizeof(ctl), hipMemcpyHostToDevice));
+    std::vector<uint32_t> z(B, 0);
+    HIPCHK(c, hipMemcpy(c->ticket, z.data(), sizeof(uint32_t) * B, hipMemcpyHostToDevice));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    c->h_len.assign(B, len + 1);
+    c->prefilled = true;
+    c->phase = 1;
+    return SPEC_OK;
+}
+
+// ---- single kernels -------------------------------------------------------------------------------
+
+int spec_k_gemv(const void *w, int32_t dtype, int32_t N, int32_t K, const float *x, int32_t R, float *y, int32_t path,
+                void *stream) {
+    if (!w || !x || !y || N < 1 || K < 1 || R < 1 || R > 128) return SPEC_EINVAL;
+    if (dtype != SPEC_F32 && dtype != SPEC_BF16) return SPEC_EINVAL;
+    if (K % (dtype == SPEC_BF16 ? 8 : 4)) return SPEC_EINVAL;
+    if (path == SPEC_PATH_MFMA) return SPEC_ENOTIMPL;
+    GemvArgs a{};
+    a.w0 = w; a.n0 = N; a.K = K; a.R = R; a.x = x; a.x_mul = 1; a.y = y;
+    a.rpw = gemv_wavedot_pick_rpw(EPI_PLAIN, N, K, R, dtype);
+    if (launch_gemv_wavedot(a, EPI_PLAIN, dtype, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return SPEC_EHIP;
+    return SPEC_OK;
+}
+
+int spec_k_retile(const void *w, int32_t N, int32_t K, void *out, void *stream) {
+    if (!w || !out || N < 16 || K < 32 || N % 16 || K % 32) return SPEC_EINVAL;
+    if (launch_retile(w, N, K, out, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return SPEC_EHIP;
+    return SPEC_OK;
+}
+
+int spec_k_philox(uint64_t seed, const uint32_t *ctr, int32_t n, uint32_t *out, void *stream) {
+    if (!ctr || !out || n < 0) return SPEC_EINVAL;
+    if (launch_philox(seed, ctr, n, out, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return SPEC_EHIP;
+    return SPEC_OK;
+}
+
+int spec_k_accept(const float *p_logits, const float *q_logits, const int32_t *drafted, int32_t k, int32_t vocab,
+                  float temperature, uint64_t seed, int32_t step, int32_t *result, void *stream) {
+    if (!p_logits || !q_logits || !drafted || !result || k < 1 || k > 64 || vocab < 2 || !(temperature >= 0.f))
+        return SPEC_EINVAL;
+    const hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const int tile = 256;
+    const int n_tiles = (vocab + tile - 1) / tile;
+    const float inv_t = temperature > 0.f ? 1.f / temperature : 1.f;
+    // one scratch block: everything below is carved from it
+    const size_t rows_p = (size_t)k + 1, rows_q = (size_t)k;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) & ~(size_t)255; return o; };
+    const size_t o_ps = take(rows_p * n_tiles * 8), o_qs = take(rows_q * n_tiles * 8), o_rmax = take(rows_p * 8),
+                 o_rsum = take(rows_p * 8), o_part = take(RESID_CHUNKS * 8), o_qsum = take(rows_q * 8),
+                 o_pm = take(rows_p * n_tiles * 4), o_qm = take(rows_q * n_tiles * 4), o_pa = take(rows_p * n_tiles * 4),
+                 o_qa = take(rows_q * n_tiles * 4), o_ql = take(rows_q * 4), o_qmax = take(rows_q * 4),
+                 o_rarg = take(rows_p * 4), o_tok = take((rows_p + 1) * 4), o_state = take(64 * 4);
+    uint8_t *buf = nullptr;
+    if (hipMalloc(reinterpret_cast<void **>(&buf), off) != hipSuccess) return SPEC_ENOMEM;
+    int rc = SPEC_OK;
+    auto ok = [&](hipError_t e) { if (e != hipSuccess && rc == SPEC_OK) rc = SPEC_EHIP; return e == hipSuccess; };
+    ok(hipMemsetAsync(buf, 0, off, st));
+    int32_t *state = reinterpret_cast<int32_t *>(buf + o_state);
+    // state ints: [0] len = 0, [1] prompt_len = 0, [2] gamma_b, [3] k, [4..7] ctl, [8] resid_row, [9] ticket,
+    //             [10] A, [11] y, [12] out_A, [13] out_y, [14] out_k
+    const int32_t init[16] = {0, 0, k, k, step, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    ok(hipMemcpyAsync(state, init, sizeof(init), hipMemcpyHostToDevice, st));
+    ok(hipStreamSynchronize(st));  // `init` lives on this stack frame
+    int32_t *tok = reinterpret_cast<int32_t *>(buf + o_tok);
+    ok(hipMemcpyAsync(tok, drafted, sizeof(int32_t) * k, hipMemcpyDeviceToDevice, st));
+    float *pm = reinterpret_cast<float *>(buf + o_pm), *qm = reinterpret_cast<float *>(buf + o_qm);
+    double *ps = reinterpret_cast<double *>(buf + o_ps), *qs = reinterpret_cast<double *>(buf + o_qs);
+    int32_t *pa = reinterpret_cast<int32_t *>(buf + o_pa), *qa = reinterpret_cast<int32_t *>(buf + o_qa);
+    ok(launch_row_partials(p_logits, k + 1, vocab, tile, inv_t, pm, ps, pa, st));
+    ok(launch_row_partials(q_logits, k, vocab, tile, inv_t, qm, qs, qa, st));
+    float *ql = reinterpret_cast<float *>(buf + o_ql), *qmax = reinterpret_cast<float *>(buf + o_qmax);
+    double *qsum = reinterpret_cast<double *>(buf + o_qsum);
+    ok(launch_gather_qstats(q_logits, drafted, k, vocab, qm, qs, qa, n_tiles, inv_t, ql, qmax, qsum, st));
+    AcceptArgs a{};
+    a.st.len = state; a.st.prompt_len = state + 1; a.st.gamma_b = state + 2; a.st.k = state + 3; a.st.ctl = state + 4;
+    a.st.tokens = tok; a.st.max_seq = k + 2; a.st.batch = 1;
+    a.cfg.temperature = temperature; a.cfg.inv_t = inv_t; a.cfg.seed = seed; a.cfg.forced = 0; a.cfg.tau = 0.f;
+    a.cfg.alpha = nullptr; a.cfg.n_alpha = 0;
+    a.gamma = k; a.gamma_max = k; a.vocab = vocab; a.p_logits = p_logits; a.pm = pm; a.ps = ps; a.pa = pa;
+    a.n_tiles = n_tiles; a.tile = tile; a.q_logits = q_logits; a.q_logit = ql; a.q_max = qmax; a.q_sum = qsum;
+    a.row_max = reinterpret_cast<double *>(buf + o_rmax); a.row_sum = reinterpret_cast<double *>(buf + o_rsum);
+    a.row_arg = reinterpret_cast<int32_t *>(buf + o_rarg); a.resid_row = state + 8;
+    a.resid_part = reinterpret_cast<double *>(buf + o_part); a.n_resid_chunks = RESID_CHUNKS;
+    a.ticket = reinterpret_cast<uint32_t *>(state + 9);
+    a.A_dev = state + 10; a.y_dev = state + 11; a.out_A = state + 12; a.out_y = state + 13; a.out_k = state + 14;
+    ok(launch_accept(a, st));
+    ok(hipMemcpyAsync(result, state + 12, sizeof(int32_t) * 2, hipMemcpyDeviceToDevice, st));
+    ok(hipStreamSynchronize(st));
+    hipFree(buf);
+    return rc;
+}
+
+}  // extern "C"

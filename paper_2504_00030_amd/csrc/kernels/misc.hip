@@ -1,0 +1,142 @@
+// Small kernels around the projections: step bookkeeping, token embedding, weight re-tiling,
+// seeded fills, and a Philox probe for parity tests.
+#include "common.hpp"
+#include "params.hpp"
+
+namespace sd {
+
+// Start of the draft phase of a speculative step: advance the step ordinal, mark every sequence as
+// drafting, and fetch the planned gamma of each sequence (gamma_plan: device-visible host memory,
+// written by the host before the launch).
+__global__ void begin_draft_k(State st, const int32_t *gamma_plan) {
+    const int b = threadIdx.x;
+    if (b == 0) {
+        st.ctl[0] += 1;
+        st.ctl[1] = st.batch;
+    }
+    if (b < st.batch) {
+        st.k[b] = 0;
+        st.gamma_b[b] = gamma_plan[b];
+    }
+}
+
+hipError_t launch_begin_draft(const State &st, const int32_t *gamma_plan, hipStream_t s) {
+    if (st.batch > 256) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(begin_draft_k, dim3(1), dim3(256), 0, s, st, gamma_plan);
+    return hipGetLastError();
+}
+
+__device__ __forceinline__ int row_position(const State &st, const RowPlan &p, int b, int i) {
+    switch (p.mode) {
+        case ROWS_PREFILL: return p.arg + i;
+        case ROWS_VERIFY: return st.len[b] - 1 + i;
+        case ROWS_DRAFT_FIRST: return max(st.len[b] - 2 + i, 0);
+        default: return st.len[b] + p.arg - 2;  // ROWS_DRAFT_NEXT: the token drafted one step earlier
+    }
+}
+
+// One workgroup per row: look the token up, copy its embedding into the fp32 residual stream,
+// emit the row scaled by the first norm weight (fp32 and bf16) and its sum of squares.
+__global__ __launch_bounds__(256) void embed_k(const EmbedArgs a) {
+    if (a.plan.mode == ROWS_DRAFT_NEXT && a.st.ctl[1] == 0) return;
+    const int r = blockIdx.x;
+    const int b = r / a.plan.rps, i = r % a.plan.rps;
+    int pos = row_position(a.st, a.plan, b, i);
+    pos = min(max(pos, 0), a.st.max_seq - 1);
+    int tok = a.st.tokens[(size_t)b * a.st.max_seq + pos];
+    tok = min(max(tok, 0), a.vocab - 1);
+    if (threadIdx.x == 0) {
+        a.row_pos[r] = pos;
+        a.row_seq[r] = b;
+    }
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < a.d; c += 256) {
+        float v;
+        if (a.dtype == DT_BF16) v = bf16_to_f32(reinterpret_cast<const bf16_t *>(a.embed)[(size_t)tok * a.d + c]);
+        else v = reinterpret_cast<const float *>(a.embed)[(size_t)tok * a.d + c];
+        const float g = a.g_next[c];
+        const size_t o = (size_t)r * a.d + c;
+        a.x[o] = v;
+        a.xg[o] = v * g;
+        a.xgb[o] = f32_to_bf16(v * g);
+        ss += v * v;
+    }
+    __shared__ float red[4];
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    if (threadIdx.x == 0) a.ssq_out[(size_t)r * a.ssq_stride] = red[0] + red[1] + red[2] + red[3];
+}
+
+hipError_t launch_embed(const EmbedArgs &a, hipStream_t s) {
+    hipLaunchKernelGGL(embed_k, dim3(a.R), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// Row-major bf16 [N][K] -> 16-row groups of 1 KiB tiles.  Tile (group g, k-tile t) holds, for lane l,
+// the 8 values W[16 g + l % 16][32 t + 8 (l / 16) .. +8]; tiles of a group are contiguous in t.
+__global__ __launch_bounds__(256) void retile_k(const uint4 *__restrict__ w, int N, int K, uint4 *__restrict__ out) {
+    const int KT = K / 32;
+    const int64_t total = (int64_t)(N / 16) * KT * 64;
+    for (int64_t idx = blockIdx.x * (int64_t)256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
+        const int l = (int)(idx & 63);
+        const int64_t tile = idx >> 6;
+        const int t = (int)(tile % KT);
+        const int64_t g = tile / KT;
+        const int64_t row = g * 16 + (l & 15);
+        const int k = t * 32 + (l >> 4) * 8;
+        out[idx] = w[(row * K + k) >> 3];
+    }
+}
+
+hipError_t launch_retile(const void *w, int N, int K, void *out, hipStream_t s) {
+    if (N % 16 != 0 || K % 32 != 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(retile_k, dim3(2048), dim3(256), 0, s, reinterpret_cast<const uint4 *>(w), N, K,
+                       reinterpret_cast<uint4 *>(out));
+    return hipGetLastError();
+}
+
+__global__ void philox_k(uint64_t seed, const uint32_t *ctr, int n, uint32_t *out) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const Philox4 r = philox4x32_10(ctr[4 * i], ctr[4 * i + 1], ctr[4 * i + 2], ctr[4 * i + 3], (uint32_t)seed,
+                                    (uint32_t)(seed >> 32));
+    for (int j = 0; j < 4; ++j) out[4 * i + j] = r.v[j];
+}
+
+hipError_t launch_philox(uint64_t seed, const uint32_t *ctr, int n, uint32_t *out, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(philox_k, dim3((n + 255) / 256), dim3(256), 0, s, seed, ctr, n, out);
+    return hipGetLastError();
+}
+
+// Seeded values in [-1, 1) (synthetic KV contents for verify-only sweeps).
+__global__ void fill_uniform_k(void *dst, int64_t n, int dtype, uint64_t seed) {
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const Philox4 r = philox4x32_10((uint32_t)i, (uint32_t)(i >> 32), 0x4b56u, 0, (uint32_t)seed, (uint32_t)(seed >> 32));
+        const float v = (float)(r.v[0] >> 8) * (2.0f / 16777216.0f) - 1.0f;
+        if (dtype == DT_BF16) reinterpret_cast<bf16_t *>(dst)[i] = f32_to_bf16(v);
+        else reinterpret_cast<float *>(dst)[i] = v;
+    }
+}
+
+hipError_t launch_fill_uniform(void *dst, int64_t n, int dtype, uint64_t seed, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_uniform_k, dim3(4096), dim3(256), 0, s, dst, n, dtype, seed);
+    return hipGetLastError();
+}
+
+__global__ void cast_to_f32_k(const void *src, int dtype, float *dst, int64_t n) {
+    const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    dst[i] = dtype == DT_BF16 ? bf16_to_f32(reinterpret_cast<const bf16_t *>(src)[i])
+                              : reinterpret_cast<const float *>(src)[i];
+}
+
+hipError_t launch_cast_to_f32(const void *src, int dtype, float *dst, int64_t n, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(cast_to_f32_k, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, src, dtype, dst, n);
+    return hipGetLastError();
+}
+
+}  // namespace sd

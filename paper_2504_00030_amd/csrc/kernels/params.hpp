@@ -1,0 +1,177 @@
+// Argument blocks shared by the host engine and the kernels, and the launcher prototypes.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sd {
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+
+// Per-context decoding state, all device memory.
+struct State {
+    int32_t *len;         // [B] committed tokens per sequence
+    int32_t *prompt_len;  // [B]
+    int32_t *gamma_b;     // [B] planned gamma of the current step
+    int32_t *k;           // [B] tokens drafted in the current step; 0 while the sequence is still drafting
+    int32_t *ctl;         // [0] speculative-step ordinal, [1] sequences still drafting
+    int32_t *tokens;      // [B][max_seq]
+    int32_t max_seq;
+    int32_t batch;
+};
+
+// Which positions the rows of a forward pass stand for.
+enum { ROWS_PREFILL = 0, ROWS_VERIFY = 1, ROWS_DRAFT_FIRST = 2, ROWS_DRAFT_NEXT = 3 };
+
+struct RowPlan {
+    int32_t mode;   // ROWS_*
+    int32_t rps;    // rows per sequence
+    int32_t arg;    // PREFILL: first position; DRAFT_NEXT: draft step j (>= 2)
+};
+
+struct KVCache {
+    void *k, *v;                 // one layer: [n_pages][n_kv][page_tokens][hd], element type per model dtype
+    const int32_t *block_table;  // [B][pages_per_seq] logical -> physical page
+    int32_t pages_per_seq, page_tokens, page_shift, n_kv, hd;
+};
+
+enum { EPI_PLAIN = 0, EPI_QKV = 1, EPI_RESID = 2, EPI_SWIGLU = 3, EPI_LOGITS = 4 };
+
+// One fused projection: y = epilogue( scale_r * (x . W^T) ).
+struct GemvArgs {
+    // weights: up to three row-major matrices sharing K (QKV: wq, wk, wv; SWIGLU: gate, up)
+    const void *w0, *w1, *w2;
+    int32_t n0, n1, n2;
+    int32_t K;
+    int32_t R;                // rows of x in this launch
+    const float *x;           // fp32 [.][K] (already multiplied by the norm weight when normed)
+    const uint16_t *xb;       // bf16 copy of x for the matrix-core path
+    int32_t x_mul, x_add;     // logical row r reads x row r * x_mul + x_add
+    const float *ssq_in;      // [row][ssq_stride] partial sums of squares of the un-normed input, or null
+    int32_t ssq_in_slots, ssq_stride;
+    float eps;
+    int32_t rpw;              // W rows per wave (wave-dot) / 16-row groups per workgroup (matrix-core)
+    const int32_t *active;    // when non-null and *active == 0 the kernel does nothing (drafting has stopped)
+    // ---- epilogue ----
+    float *y;                 // PLAIN: [R][N]; LOGITS: logits base; QKV: q [R][nq*hd]
+    int32_t y_mul, y_add, y_stride;  // LOGITS: logical row r writes row r * y_mul + y_add
+    // RESID
+    float *xres;              // [R][N] residual stream, read-modify-write
+    const float *g_next;      // [N] weight of the norm that consumes the new residual (null -> ones)
+    float *xg;                // [R][N] xres * g_next (fp32)
+    uint16_t *xgb;            // same, bf16
+    float *ssq_out;           // [R][ssq_stride] one slot per workgroup
+    // SWIGLU / QKV second outputs
+    uint16_t *yb;             // bf16 copy of y (SWIGLU act)
+    // QKV
+    int32_t nq, nkv, hd;
+    const float *rope_cos, *rope_sin;  // [max_seq][hd/2]
+    const int32_t *row_pos, *row_seq;  // [R]
+    KVCache kv;
+    int32_t kv_dtype;
+    // LOGITS partial softmax statistics, one per (row, tile)
+    float *pm;                // max logit of the tile
+    double *ps;               // sum exp((l - pm) * inv_t) over the tile
+    int32_t *pa;              // argmax (lowest index) of the tile
+    int32_t n_tiles;          // tiles per row (stride of the three arrays)
+    float inv_t;
+};
+
+struct EmbedArgs {
+    State st;
+    RowPlan plan;
+    int32_t R;
+    const void *embed;  // [V][d]
+    int32_t dtype, d, vocab;
+    const float *g_next;
+    float *x, *xg;
+    uint16_t *xgb;
+    float *ssq_out;
+    int32_t ssq_stride;
+    int32_t *row_pos, *row_seq;
+};
+
+struct AttnArgs {
+    const float *q;       // [R][nq*hd], rotated
+    KVCache kv;
+    int32_t kv_dtype;
+    int32_t R, rps, nq;
+    const int32_t *row_pos, *row_seq;
+    int32_t chunk;        // KV positions per workgroup
+    int32_t n_chunks;     // grid.x
+    float scale;
+    float *part_m, *part_l;  // [R][nq][n_chunks]
+    float *part_o;           // [R][nq][n_chunks][hd]
+    float *o;                // [R][nq*hd]
+    uint16_t *ob;            // bf16 copy
+    const int32_t *active;
+};
+
+// Sampling configuration shared by the sampler kernels.
+struct SampleCfg {
+    float temperature;   // 0 -> greedy
+    float inv_t;         // 1/T, or 1 when greedy
+    uint64_t seed;
+    int32_t forced;      // 1: forced acceptance landscape
+    const float *alpha;  // [n_alpha]
+    int32_t n_alpha;
+    float tau;           // <= 0: no early stop
+};
+
+struct DraftSampleArgs {
+    State st;
+    SampleCfg cfg;
+    int32_t j;            // draft step, 1-based
+    int32_t gamma_max;
+    const float *logits;  // draft logits [B][gamma_max][V]
+    int32_t vocab;
+    const float *pm; const double *ps; const int32_t *pa;  // partials [B*gamma_max][n_tiles]
+    int32_t n_tiles, tile;
+    // per drafted token: logit of the chosen token, row max, row sum  -> [B][gamma_max]
+    float *q_logit, *q_max;
+    double *q_sum;
+};
+
+struct AcceptArgs {
+    State st;
+    SampleCfg cfg;
+    int32_t gamma;        // rows per sequence in the target logits buffer = gamma + 1
+    int32_t gamma_max;
+    int32_t vocab;
+    const float *p_logits;  // [B][gamma+1][V]
+    const float *pm; const double *ps; const int32_t *pa;  // target partials [B*(gamma+1)][n_tiles]
+    int32_t n_tiles, tile;
+    const float *q_logits;  // [B][gamma_max][V]
+    const float *q_logit, *q_max; const double *q_sum;     // [B][gamma_max]
+    // scratch of the accept phase
+    double *row_max, *row_sum;  // [B][gamma+1] (max as double for uniform arithmetic)
+    int32_t *row_arg;           // [B][gamma+1]
+    int32_t *resid_row;         // [B] 0 = no residual draw needed, else row index (1-based)
+    double *resid_part;         // [B][n_resid_chunks]
+    int32_t n_resid_chunks;
+    uint32_t *ticket;           // [B]
+    int32_t *out_A, *out_y, *out_k;  // [B] device-visible result (pinned host memory)
+    int32_t *A_dev, *y_dev;     // [B] device copies
+};
+
+// ---- launchers (defined next to the kernels) -----------------------------------------------------
+hipError_t launch_begin_draft(const State &st, const int32_t *gamma_plan, hipStream_t s);
+hipError_t launch_embed(const EmbedArgs &a, hipStream_t s);
+hipError_t launch_gemv_wavedot(const GemvArgs &a, int epi, int w_dtype, hipStream_t s);
+hipError_t launch_gemv_mfma(const GemvArgs &a, int epi, hipStream_t s);
+int gemv_mfma_tile_rows(int epi, int R);   // output columns per LOGITS partial for the matrix-core path
+int gemv_wavedot_pick_rpw(int epi, int N, int K, int R, int w_dtype);
+hipError_t launch_attention(const AttnArgs &a, int hd, hipStream_t s);
+hipError_t launch_draft_sample(const DraftSampleArgs &a, hipStream_t s);
+hipError_t launch_accept(const AcceptArgs &a, hipStream_t s);
+hipError_t launch_row_partials(const float *logits, int rows, int vocab, int tile, float inv_t, float *pm, double *ps,
+                               int32_t *pa, hipStream_t s);
+hipError_t launch_gather_qstats(const float *q_logits, const int32_t *drafted, int rows, int vocab, const float *pm,
+                                const double *ps, const int32_t *pa, int n_tiles, float inv_t, float *q_logit,
+                                float *q_max, double *q_sum, hipStream_t s);
+hipError_t launch_retile(const void *w, int N, int K, void *out, hipStream_t s);
+hipError_t launch_philox(uint64_t seed, const uint32_t *ctr, int n, uint32_t *out, hipStream_t s);
+hipError_t launch_fill_uniform(void *dst, int64_t n, int dtype, uint64_t seed, hipStream_t s);
+hipError_t launch_cast_to_f32(const void *src, int dtype, float *dst, int64_t n, hipStream_t s);
+
+}  // namespace sd

@@ -1,0 +1,483 @@
+// Sampling side of a speculative step (Background section; accept / resample rule of the
+// speculative-sampling works cited there):
+//   draft_sample_k   x_i ~ softmax(draft logits / T) by index-order inverse CDF (argmax if T == 0),
+//                    the draft's confidence for GammaTune+ early stopping
+//   accept_scan_k    softmax normalisers of the target rows, the test u * q(x) < p(x) row by row,
+//                    the bonus draw when every drafted token is accepted
+//   residual_k       draw from norm(max(0, p - q)) at the first refused row, then commit the step
+// The logits kernels leave per-tile (max, sum exp, argmax) partials, so the normalisers cost one
+// pass over a few hundred numbers per row; only the refused row is swept in full.  All sampling
+// arithmetic is fp64; every reduction has a fixed order, so results repeat bit for bit.
+#include "common.hpp"
+#include "params.hpp"
+
+namespace sd {
+
+__device__ __forceinline__ double wave_scan_incl(double v, int lane) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const double o = __shfl_up(v, d, WAVE);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+struct RowStats {
+    double M, S;
+    int arg;
+};
+
+// Statistics of one logits row from its tile partials, computed by one wave.
+__device__ RowStats wave_row_stats(const float *pm, const double *ps, const int32_t *pa, int n_tiles, double inv_t,
+                                   int lane) {
+    float m = -INFINITY;
+    int arg = 0x7fffffff;
+    for (int t = lane; t < n_tiles; t += 64) {
+        const float v = pm[t];
+        const int ai = pa[t];
+        if (v > m || (v == m && ai < arg)) { m = v; arg = ai; }
+    }
+#pragma unroll
+    for (int msk = 32; msk >= 1; msk >>= 1) {
+        const float om = __shfl_xor(m, msk, WAVE);
+        const int oa = __shfl_xor(arg, msk, WAVE);
+        if (om > m || (om == m && oa < arg)) { m = om; arg = oa; }
+    }
+    double s = 0.0;
+    for (int t = lane; t < n_tiles; t += 64) s += ps[t] * exp((double)(pm[t] - m) * inv_t);
+    s = wave_sum(s);
+    RowStats r;
+    r.M = (double)m; r.S = s; r.arg = arg;
+    return r;
+}
+
+// Index-order inverse CDF over one row, by one wave: first j with cum_j > target, where the weights are
+// w_j = exp((l_j - M) * inv_t).  Tiles are walked through their partial sums, the crossing tile element
+// by element.  If rounding leaves no crossing the last index is returned.
+__device__ int wave_sample_row(const float *logits, int vocab, const float *pm, const double *ps, int n_tiles, int tile,
+                               double M, double inv_t, double target, int lane) {
+    // contiguous run of tiles per lane keeps index order
+    const int tpl = (n_tiles + 63) / 64;
+    const int tb = lane * tpl, te = min(tb + tpl, n_tiles);
+    double seg = 0.0;
+    for (int t = tb; t < te; ++t) seg += ps[t] * exp(((double)pm[t] - M) * inv_t);
+    const double incl = wave_scan_incl(seg, lane);
+    const unsigned long long hit = __ballot(incl > target && tb < te);
+    int src = hit ? __ffsll((long long)hit) - 1 : -1;
+    int t_star;
+    double base;
+    if (src < 0) {  // no crossing: last tile
+        t_star = n_tiles - 1;
+        base = 0.0;  // unused: the fallback below picks the last element
+    } else {
+        // the owning lane walks its tiles
+        double cum = incl - seg;
+        int ts = te - 1;
+        double tbse = cum;
+        bool found = false;
+        for (int t = tb; t < te; ++t) {
+            const double c = ps[t] * exp(((double)pm[t] - M) * inv_t);
+            if (!found && cum + c > target) { ts = t; tbse = cum; found = true; }
+            cum += c;
+        }
+        if (!found) {  // rounding between the scan and the walk: last tile of the run
+            double c2 = incl - seg;
+            for (int t = tb; t < te - 1; ++t) c2 += ps[t] * exp(((double)pm[t] - M) * inv_t);
+            tbse = c2;
+        }
+        t_star = __shfl(ts, src, WAVE);
+        base = __shfl(tbse, src, WAVE);
+    }
+    // inside the tile: contiguous elements per lane
+    const int e0 = t_star * tile;
+    const int len = min(tile, vocab - e0);
+    const int epl = (len + 63) / 64;
+    const int eb = lane * epl, ee = min(eb + epl, len);
+    double w[8];
+    double sseg = 0.0;
+    for (int i = 0; i < 8; ++i) {
+        const int e = eb + i;
+        w[i] = e < ee ? exp(((double)logits[e0 + e] - M) * inv_t) : 0.0;
+        sseg += w[i];
+    }
+    const double eincl = wave_scan_incl(sseg, lane);
+    const bool cross = src >= 0 && eb < ee && base + eincl > target;
+    const unsigned long long ehit = __ballot(cross);
+    if (!ehit) return src < 0 ? vocab - 1 : e0 + len - 1;
+    const int el = __ffsll((long long)ehit) - 1;
+    int tok = e0 + ee - 1;
+    double cum = base + eincl - sseg;
+    bool f = false;
+    for (int i = 0; i < 8; ++i) {
+        const int e = eb + i;
+        if (e < ee && !f) {
+            cum += w[i];
+            if (cum > target) { tok = e0 + e; f = true; }
+        }
+    }
+    return __shfl(tok, el, WAVE);
+}
+
+// ---- draft sampling ------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void draft_sample_k(const DraftSampleArgs a) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    if (a.st.k[b] != 0) return;  // this sequence stopped drafting earlier in the step
+    const int row = b * a.gamma_max + (a.j - 1);
+    const float *pm = a.pm + (size_t)row * a.n_tiles;
+    const double *ps = a.ps + (size_t)row * a.n_tiles;
+    const int32_t *pa = a.pa + (size_t)row * a.n_tiles;
+    const float *logits = a.logits + (size_t)row * a.vocab;
+    const double inv_t = (double)a.cfg.inv_t;
+    const RowStats rs = wave_row_stats(pm, ps, pa, a.n_tiles, inv_t, lane);
+    const int len = a.st.len[b];
+    const uint32_t step = (uint32_t)a.st.ctl[0];
+    int x;
+    if (a.cfg.temperature == 0.f) {
+        x = rs.arg;
+    } else {
+        const double u = philox_uniform(a.cfg.seed, step, (uint32_t)a.j, PURPOSE_DRAFT, (uint32_t)b);
+        x = wave_sample_row(logits, a.vocab, pm, ps, a.n_tiles, a.tile, rs.M, inv_t, u * rs.S, lane);
+    }
+    if (lane == 0) {
+        const int pos = len + a.j - 1;
+        if (pos < a.st.max_seq) a.st.tokens[(size_t)b * a.st.max_seq + pos] = x;
+        a.q_logit[row] = logits[x];
+        a.q_max[row] = (float)rs.M;
+        a.q_sum[row] = rs.S;
+        double conf;
+        if (a.cfg.forced) {
+            const uint32_t g = (uint32_t)(len - a.st.prompt_len[b] + a.j - 1);
+            conf = 1.0 - philox_uniform(a.cfg.seed, g, 0u, PURPOSE_FORCED, (uint32_t)b);
+        } else {
+            conf = 1.0 / rs.S;  // top probability of softmax(l / T_eff)
+        }
+        const bool stop = (a.cfg.tau > 0.f && conf < (double)a.cfg.tau) || a.j >= a.st.gamma_b[b];
+        if (stop) {
+            a.st.k[b] = a.j;
+            atomicSub(&a.st.ctl[1], 1);
+        }
+    }
+}
+
+hipError_t launch_draft_sample(const DraftSampleArgs &a, hipStream_t s) {
+    if (a.tile > 512) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(draft_sample_k, dim3(a.st.batch), dim3(64), 0, s, a);
+    return hipGetLastError();
+}
+
+// ---- accept phase ---------------------------------------------------------------------------------
+constexpr int ACC_THREADS = 1024;
+constexpr int ACC_ROWS_MAX = 65;
+
+__device__ __forceinline__ void commit_step(const AcceptArgs &a, int b, int A, int y) {
+    const int len = a.st.len[b];
+    const int pos = len + A;
+    if (pos < a.st.max_seq) a.st.tokens[(size_t)b * a.st.max_seq + pos] = y;
+    a.st.len[b] = len + A + 1;
+    a.y_dev[b] = y;
+    a.out_A[b] = A;
+    a.out_y[b] = y;
+    a.out_k[b] = a.st.k[b];
+}
+
+__global__ __launch_bounds__(ACC_THREADS) void accept_scan_k(const AcceptArgs a) {
+    const int b = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int k = a.st.k[b];
+    const int rows = a.gamma + 1;
+    const double inv_t = (double)a.cfg.inv_t;
+    __shared__ double sM[ACC_ROWS_MAX], sS[ACC_ROWS_MAX];
+    __shared__ int sArg[ACC_ROWS_MAX];
+    __shared__ int sA, sBonus;
+
+    for (int i = wave; i <= k; i += ACC_THREADS / 64) {  // target rows 1..k+1 (0-based i)
+        const size_t row = (size_t)b * rows + i;
+        const RowStats rs = wave_row_stats(a.pm + row * a.n_tiles, a.ps + row * a.n_tiles, a.pa + row * a.n_tiles,
+                                           a.n_tiles, inv_t, lane);
+        if (lane == 0) {
+            sM[i] = rs.M; sS[i] = rs.S; sArg[i] = rs.arg;
+            a.row_max[row] = rs.M; a.row_sum[row] = rs.S; a.row_arg[row] = rs.arg;
+        }
+    }
+    __syncthreads();
+    const int len = a.st.len[b];
+    const uint32_t step = (uint32_t)a.st.ctl[0];
+    const bool greedy = a.cfg.temperature == 0.f;
+    if (wave == 0) {
+        // every drafted row is tested by its own lane; A = number of leading passes
+        const int g0 = len - a.st.prompt_len[b];
+        const int i = lane + 1;
+        bool ok = true;
+        if (i <= k) {
+            const int x = a.st.tokens[(size_t)b * a.st.max_seq + len + i - 1];
+            if (a.cfg.forced) {
+                const int g = g0 + i - 1;
+                const double u = philox_uniform(a.cfg.seed, (uint32_t)g, 0u, PURPOSE_FORCED, (uint32_t)b);
+                ok = u < (double)a.cfg.alpha[min(g, a.cfg.n_alpha - 1)];
+            } else if (greedy) {
+                ok = x == sArg[i - 1];
+            } else {
+                const size_t prow = (size_t)b * rows + (i - 1);
+                const size_t qrow = (size_t)b * a.gamma_max + (i - 1);
+                const double p = exp(((double)a.p_logits[prow * a.vocab + x] - sM[i - 1]) * inv_t) / sS[i - 1];
+                const double q = exp(((double)a.q_logit[qrow] - (double)a.q_max[qrow]) * inv_t) / a.q_sum[qrow];
+                const double u = philox_uniform(a.cfg.seed, step, (uint32_t)i, PURPOSE_ACCEPT, (uint32_t)b);
+                ok = u * q < p;
+            }
+        }
+        const unsigned long long fail = __ballot(!ok);
+        const int A = fail ? __ffsll((long long)fail) - 1 : k;
+        if (lane == 0) {
+            sA = A;
+            a.A_dev[b] = A;
+            int resid = 0, bonus = 0;
+            if (greedy) {
+                a.y_dev[b] = sArg[A];  // row A+1: the refused row, or the bonus row when A == k
+            } else if (A == k) {
+                bonus = 1;
+            } else {
+                resid = A + 1;
+            }
+            a.resid_row[b] = resid;
+            sBonus = bonus;
+        }
+    }
+    __syncthreads();
+    if (sBonus && wave == 0) {
+        const int i = k;  // 0-based bonus row
+        const size_t row = (size_t)b * rows + i;
+        const double u = philox_uniform(a.cfg.seed, step, (uint32_t)(k + 1), PURPOSE_BONUS, (uint32_t)b);
+        const int y = wave_sample_row(a.p_logits + row * a.vocab, a.vocab, a.pm + row * a.n_tiles,
+                                      a.ps + row * a.n_tiles, a.n_tiles, a.tile, sM[i], inv_t, u * sS[i], lane);
+        if (lane == 0) a.y_dev[b] = y;
+    }
+}
+
+constexpr int RES_THREADS = 256;
+constexpr int RES_EPT_MAX = 16;
+
+// residual weight of vocabulary entry j of the refused row
+__device__ __forceinline__ double resid_w(const float *lp, const float *lq, int j, double Mp, double Sp, double Mq,
+                                          double Sq, double inv_t) {
+    const double p = exp(((double)lp[j] - Mp) * inv_t) / Sp;
+    const double q = exp(((double)lq[j] - Mq) * inv_t) / Sq;
+    const double d = p - q;
+    return d > 0.0 ? d : 0.0;
+}
+
+__global__ __launch_bounds__(RES_THREADS) void residual_k(const AcceptArgs a) {
+    const int c = blockIdx.x, b = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row1 = a.resid_row[b];  // 1-based refused row, 0 when no residual draw is needed
+    if (row1 == 0) {
+        if (c == 0 && tid == 0) commit_step(a, b, a.A_dev[b], a.y_dev[b]);
+        return;
+    }
+    const int rows = a.gamma + 1;
+    const size_t prow = (size_t)b * rows + (row1 - 1);
+    const size_t qrow = (size_t)b * a.gamma_max + (row1 - 1);
+    const float *lp = a.p_logits + prow * a.vocab;
+    const float *lq = a.q_logits + qrow * a.vocab;
+    const double Mp = a.row_max[prow], Sp = a.row_sum[prow];
+    const double Mq = (double)a.q_max[qrow], Sq = a.q_sum[qrow];
+    const double inv_t = (double)a.cfg.inv_t;
+    const int NCH = a.n_resid_chunks;
+    const int CH = (a.vocab + NCH - 1) / NCH;
+    const int EPT = (CH + RES_THREADS - 1) / RES_THREADS;  // <= RES_EPT_MAX (checked on the host)
+
+    __shared__ double wsum[RES_THREADS / 64];
+    __shared__ double s_tot;
+    __shared__ int s_last;
+
+    // this chunk: contiguous elements per thread, in index order
+    auto thread_sum = [&](int chunk, double *keep) {
+        const int base = chunk * CH + tid * EPT;
+        const int cend = min((chunk + 1) * CH, a.vocab);
+        double s = 0.0;
+        for (int i = 0; i < EPT; ++i) {
+            const int j = base + i;
+            const double w = (j < cend) ? resid_w(lp, lq, j, Mp, Sp, Mq, Sq, inv_t) : 0.0;
+            if (keep) keep[i] = w;
+            s += w;
+        }
+        return s;
+    };
+    {
+        const double s = thread_sum(c, nullptr);
+        const double ws = wave_sum(s);
+        if (lane == 0) wsum[wave] = ws;
+        __syncthreads();
+        if (tid == 0) {
+            a.resid_part[(size_t)b * NCH + c] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+            __threadfence();
+            const uint32_t t = atomicAdd(&a.ticket[b], 1u);
+            s_last = (t == (uint32_t)(NCH - 1));
+        }
+        __syncthreads();
+    }
+    if (!s_last) return;
+    __threadfence();
+
+    // last workgroup of this sequence: locate the crossing chunk, then the element
+    const uint32_t step = (uint32_t)a.st.ctl[0];
+    const double u = philox_uniform(a.cfg.seed, step, (uint32_t)row1, PURPOSE_RESID, (uint32_t)b);
+    __shared__ int s_chunk, s_y;
+    __shared__ double s_base, s_target;
+    if (wave == 0) {
+        const volatile double *part = a.resid_part + (size_t)b * NCH;
+        const int cpl = (NCH + 63) / 64;
+        const int cb = lane * cpl, ce = min(cb + cpl, NCH);
+        double seg = 0.0;
+        for (int i = cb; i < ce; ++i) seg += part[i];
+        const double incl = wave_scan_incl(seg, lane);
+        const double W = __shfl(incl, 63, WAVE);
+        const double target = u * W;
+        const unsigned long long hit = __ballot(incl > target && cb < ce);
+        int chunk = NCH - 1;
+        double base = 0.0;
+        if (hit) {
+            const int src = __ffsll((long long)hit) - 1;
+            double cum = incl - seg;
+            int cs = ce - 1;
+            double cbse = cum;
+            bool f = false;
+            for (int i = cb; i < ce; ++i) {
+                const double v = part[i];
+                if (!f && cum + v > target) { cs = i; cbse = cum; f = true; }
+                cum += v;
+            }
+            if (!f) cbse = cum - part[max(ce - 1, cb)];
+            chunk = __shfl(cs, src, WAVE);
+            base = __shfl(cbse, src, WAVE);
+        }
+        if (lane == 0) {
+            s_chunk = chunk; s_base = base; s_target = target; s_tot = W;
+            s_y = -1;
+        }
+    }
+    __syncthreads();
+    if (!(s_tot > 0.0)) {
+        // no residual mass (p == q up to rounding): draw from p with the same uniform
+        if (wave == 0) {
+            const int y = wave_sample_row(lp, a.vocab, a.pm + prow * a.n_tiles, a.ps + prow * a.n_tiles, a.n_tiles,
+                                          a.tile, Mp, inv_t, u * Sp, lane);
+            if (lane == 0) {
+                a.ticket[b] = 0;
+                commit_step(a, b, a.A_dev[b], y);
+            }
+        }
+        return;
+    }
+    const int chunk = s_chunk;
+    double keep[RES_EPT_MAX];
+    const double s = thread_sum(chunk, keep);
+    const double incl_w = wave_scan_incl(s, lane);
+    if (lane == 63) wsum[wave] = incl_w;
+    __syncthreads();
+    double off = s_base;
+    for (int w = 0; w < wave; ++w) off += wsum[w];
+    const double incl = off + incl_w;
+    const double target = s_target;
+    // first thread whose inclusive sum crosses the target
+    __shared__ int s_first;
+    if (tid == 0) s_first = RES_THREADS;
+    __syncthreads();
+    if (incl > target) atomicMin(&s_first, tid);
+    __syncthreads();
+    const int cend = min((chunk + 1) * CH, a.vocab);
+    if (s_first == RES_THREADS) {
+        if (tid == 0) s_y = cend - 1;  // rounding left no crossing: last entry of the chunk
+    } else if (tid == s_first) {
+        double cum = incl - s;
+        int y = min(chunk * CH + tid * EPT + EPT, cend) - 1;
+        bool f = false;
+        for (int i = 0; i < EPT; ++i) {
+            const int j = chunk * CH + tid * EPT + i;
+            if (j < cend && !f) {
+                cum += keep[i];
+                if (cum > target) { y = j; f = true; }
+            }
+        }
+        s_y = y;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        a.ticket[b] = 0;
+        commit_step(a, b, a.A_dev[b], s_y);
+    }
+}
+
+hipError_t launch_accept(const AcceptArgs &a, hipStream_t s) {
+    if (a.gamma + 1 > ACC_ROWS_MAX || a.tile > 512) return hipErrorInvalidValue;
+    const int CH = (a.vocab + a.n_resid_chunks - 1) / a.n_resid_chunks;
+    if ((CH + RES_THREADS - 1) / RES_THREADS > RES_EPT_MAX) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(accept_scan_k, dim3(a.st.batch), dim3(ACC_THREADS), 0, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(residual_k, dim3(a.n_resid_chunks, a.st.batch), dim3(RES_THREADS), 0, s, a);
+    return hipGetLastError();
+}
+
+// ---- tile partials of caller-provided logits (stand-alone accept, tests) ---------------------------
+__global__ __launch_bounds__(64) void row_partials_k(const float *logits, int vocab, int tile, float inv_t, float *pm,
+                                                     double *ps, int32_t *pa, int n_tiles) {
+    const int t = blockIdx.x, row = blockIdx.y, lane = threadIdx.x;
+    const float *l = logits + (size_t)row * vocab;
+    const int e0 = t * tile, e1 = min(e0 + tile, vocab);
+    float m = -INFINITY;
+    int arg = 0x7fffffff;
+    for (int e = e0 + lane; e < e1; e += 64) {
+        const float v = l[e];
+        if (v > m || (v == m && e < arg)) { m = v; arg = e; }
+    }
+#pragma unroll
+    for (int msk = 32; msk >= 1; msk >>= 1) {
+        const float om = __shfl_xor(m, msk, WAVE);
+        const int oa = __shfl_xor(arg, msk, WAVE);
+        if (om > m || (om == m && oa < arg)) { m = om; arg = oa; }
+    }
+    double s = 0.0;
+    for (int e = e0 + lane; e < e1; e += 64) s += exp((double)(l[e] - m) * (double)inv_t);
+    s = wave_sum(s);
+    if (lane == 0) {
+        const size_t pi = (size_t)row * n_tiles + t;
+        pm[pi] = m; ps[pi] = s; pa[pi] = arg;
+    }
+}
+
+hipError_t launch_row_partials(const float *logits, int rows, int vocab, int tile, float inv_t, float *pm, double *ps,
+                               int32_t *pa, hipStream_t s) {
+    const int n_tiles = (vocab + tile - 1) / tile;
+    hipLaunchKernelGGL(row_partials_k, dim3(n_tiles, rows), dim3(64), 0, s, logits, vocab, tile, inv_t, pm, ps, pa,
+                       n_tiles);
+    return hipGetLastError();
+}
+
+}  // namespace sd
+
+namespace sd {
+
+// Per drafted row: logit of the drafted token, row max and row sum (what draft_sample_k leaves behind),
+// rebuilt from tile partials for callers that bring their own draft logits.
+__global__ __launch_bounds__(64) void gather_qstats_k(const float *q_logits, const int32_t *drafted, int vocab,
+                                                      const float *pm, const double *ps, const int32_t *pa, int n_tiles,
+                                                      float inv_t, float *q_logit, float *q_max, double *q_sum) {
+    const int row = blockIdx.x, lane = threadIdx.x;
+    const RowStats rs = wave_row_stats(pm + (size_t)row * n_tiles, ps + (size_t)row * n_tiles,
+                                       pa + (size_t)row * n_tiles, n_tiles, (double)inv_t, lane);
+    if (lane == 0) {
+        q_logit[row] = q_logits[(size_t)row * vocab + drafted[row]];
+        q_max[row] = (float)rs.M;
+        q_sum[row] = rs.S;
+    }
+}
+
+hipError_t launch_gather_qstats(const float *q_logits, const int32_t *drafted, int rows, int vocab, const float *pm,
+                                const double *ps, const int32_t *pa, int n_tiles, float inv_t, float *q_logit,
+                                float *q_max, double *q_sum, hipStream_t s) {
+    hipLaunchKernelGGL(gather_qstats_k, dim3(rows), dim3(64), 0, s, q_logits, drafted, vocab, pm, ps, pa, n_tiles, inv_t,
+                       q_logit, q_max, q_sum);
+    return hipGetLastError();
+}
+
+}  // namespace sd

@@ -1,0 +1,233 @@
+"""GPU parity: the HIP path against the CPU oracle on the same seeded inputs, through the C ABI."""
+import numpy as np
+import pytest
+
+import synth
+from oracle import philox as ophilox
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from parity_utils import TOL, compare_run, make_controllers, to_gpu  # noqa: E402
+
+
+def _pk():
+    import paper_2504_00030_amd as pk
+    pk.load()
+    return pk
+
+
+def test_philox_matches_oracle():
+    pk = _pk()
+    rng = np.random.default_rng(0)
+    n = 100000
+    ctr = rng.integers(0, 2**32, size=(n, 4), dtype=np.uint64).astype(np.uint32)
+    ctr[:16] = np.arange(64, dtype=np.uint32).reshape(16, 4)
+    seed = 0x1234567890ABCDEF
+    d_ctr = torch.from_numpy(ctr.view(np.int32)).cuda()
+    d_out = torch.zeros_like(d_ctr)
+    pk.k_philox(seed, d_ctr, d_out)
+    torch.cuda.synchronize()
+    got = d_out.cpu().numpy().view(np.uint32)
+    want = ophilox.philox4x32_10_array(ctr, ophilox.seed_key(seed))
+    assert np.array_equal(got, want)
+    # the published known-answer vector through the device function
+    z = torch.zeros((1, 4), dtype=torch.int32, device="cuda")
+    o = torch.zeros_like(z)
+    pk.k_philox(0, z, o)
+    assert [int(v) & 0xFFFFFFFF for v in o.cpu().numpy()[0]] == [0x6627E8D5, 0xE169C58D, 0xBC57AC4C, 0x9B00DBD8]
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("R", [1, 2, 3, 5, 9])
+@pytest.mark.parametrize("N,K", [(344, 128), (130, 1032), (4096, 4096), (2048, 8192), (1000, 344 * 8)])
+def test_gemv_wavedot_matches_fp64_matmul(dtype, R, N, K):
+    pk = _pk()
+    g = torch.Generator().manual_seed(N * 131 + K + R)
+    w = torch.randn(N, K, generator=g) * 0.02
+    x = torch.randn(R, K, generator=g)
+    wd = w.to(torch.bfloat16) if dtype == "bf16" else w
+    want = (x.double() @ wd.double().t()).numpy()
+    y = torch.full((R, N), float("nan"), device="cuda")
+    pk.k_gemv(wd.cuda().contiguous(), x.cuda().contiguous(), y, path=pk.PATH_WAVEDOT)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy()
+    # fp32 accumulation over K terms: error ~ sqrt(K) * 2^-24 * |w||x|
+    tol = 2e-6 * np.sqrt(K) * np.abs(want).max() + 1e-7
+    assert np.isfinite(got).all()
+    assert np.abs(got - want).max() <= tol
+
+
+def _run_pair(cfg, *, controller, temperature, seed=0, n_generate=None, prompt_len=None, batch=1, accept_mode=0,
+              alpha=None, tau=0.0, norm_jitter=0.0, use_graphs=False, page_tokens=64, weights_seed=0, block_table=None,
+              gemv_path=0):
+    pk = _pk()
+    n_generate = n_generate or cfg.n_generate
+    prompt_len = prompt_len or cfg.prompt_len
+    Wt, Wd = synth.make_pair_weights(cfg, weights_seed, norm_jitter=norm_jitter)
+    Wt_np, Wd_np = synth.to_numpy_weights(Wt), synth.to_numpy_weights(Wd)
+    Wt_g = to_gpu(Wt)
+    Wd_g = to_gpu(Wd) if cfg.draft_kind != "prefix" else {k: (v[: cfg.draft.n_layers] if isinstance(v, list) else v) for k, v in Wt_g.items()}
+    prompts = synth.make_prompts(batch, prompt_len, cfg.target.vocab, 7)
+    eng = pk.SpecEngine(cfg.target, Wt_g, cfg.draft, Wd_g, batch=batch, max_seq=prompt_len + n_generate + 2 * cfg.gamma_max + 4,
+                        gamma_max=cfg.gamma_max, temperature=temperature, seed=seed, accept_mode=accept_mode,
+                        page_tokens=page_tokens, use_graphs=use_graphs, gemv_path=gemv_path)
+    if block_table is not None:
+        eng.set_block_table(block_table(eng))
+    if alpha is not None:
+        eng.set_forced_alpha(alpha)
+    if tau > 0:
+        eng.set_early_stop(tau)
+    ctrls = make_controllers(controller, batch, cfg.gamma_max, "gpu")
+    # record the drafted tokens of every step as well
+    toks, trace = _generate_with_drafts(eng, prompts, n_generate, ctrls)
+    eng.close()
+    cmp_ = compare_run(cfg, Wt_np, Wd_np, prompts, n_generate, toks, trace, controller=controller,
+                       temperature=temperature, seed=seed, accept_mode=accept_mode, alpha=alpha, tau=tau)
+    return cmp_, toks, trace
+
+
+def _generate_with_drafts(eng, prompts, n_generate, ctrls):
+    B = eng.batch
+    n0 = prompts.shape[1]
+    eng.prefill(prompts)
+    gen = np.zeros(B, dtype=np.int64)
+    lens = np.full(B, n0, dtype=np.int64)
+    trace = []
+    while gen.min() < n_generate:
+        gammas = np.array([c.gamma for c in ctrls], dtype=np.int32)
+        eng.draft(gammas if B > 1 else int(gammas[0]))
+        gmax = int(gammas.max())
+        eng.verify(gmax)
+        q = eng.debug_logits(0)
+        drafted = [eng.debug_drafted(b) for b in range(B)]
+        A, y, k = eng.accept()
+        p = eng.debug_logits(1)
+        for b in range(B):
+            assert len(drafted[b]) == k[b]
+        trace.append({"gamma": gammas.copy(), "A": A.copy(), "y": y.copy(), "k": k.copy(), "q_logits": q, "p_logits": p,
+                      "drafted": drafted})
+        for b, c in enumerate(ctrls):
+            c.update(int(A[b]), int(k[b]))
+        gen += A + 1
+        lens += A + 1
+    toks = np.stack([eng.read_tokens(b)[: n0 + n_generate] for b in range(B)])
+    return toks, trace
+
+
+def _assert_clean(c, full_coverage=True):
+    assert not c.failures, "\n".join(c.failures[:10])
+    if full_coverage:
+        assert c.diverged_at is None, c.diverged_at
+        assert c.coverage == 1.0
+    print(f"coverage {c.coverage:.3f} decisions {c.decisions_compared} max logit err {c.max_logit_err:.3e}")
+
+
+@pytest.mark.parametrize("controller", ["fixed4", "gammatune"])
+@pytest.mark.parametrize("temperature", [0.0, 1.0])
+def test_tiny_pair_end_to_end(controller, temperature):
+    cfg = synth.pair("tiny")
+    c, toks, trace = _run_pair(cfg, controller=controller, temperature=temperature, seed=0)
+    _assert_clean(c)
+    assert c.max_logit_err <= TOL["fp32"]
+    assert toks.shape == (1, cfg.prompt_len + cfg.n_generate)
+
+
+def test_tiny_pair_norm_weights_and_small_pages():
+    cfg = synth.pair("tiny")
+    c, _, _ = _run_pair(cfg, controller="gammatune", temperature=1.0, seed=3, norm_jitter=0.1, page_tokens=8,
+                        block_table=lambda e: np.random.default_rng(1).permutation(
+                            ((e.max_seq + 7) // 8) * e.batch).astype(np.int32))
+    _assert_clean(c)
+
+
+def test_tiny_pair_graphs_match_direct_launches():
+    cfg = synth.pair("tiny")
+    c1, t1, _ = _run_pair(cfg, controller="gammatune", temperature=1.0, seed=5, use_graphs=False)
+    c2, t2, _ = _run_pair(cfg, controller="gammatune", temperature=1.0, seed=5, use_graphs=True)
+    _assert_clean(c1)
+    _assert_clean(c2)
+    assert np.array_equal(t1, t2)
+
+
+def test_tiny_pair_early_stop():
+    cfg = synth.pair("tiny")
+    tau = float(np.float32(0.007))
+    c, _, trace = _run_pair(cfg, controller="gammatune", temperature=0.0, tau=tau)
+    _assert_clean(c)
+    assert any(int(r["k"][0]) < int(r["gamma"][0]) for r in trace)
+    c, _, trace = _run_pair(cfg, controller="fixed4", temperature=1.0, tau=float(np.float32(0.009)), seed=2)
+    _assert_clean(c)
+
+
+@pytest.mark.parametrize("alpha_kind", ["0.6", "piecewise"])
+def test_tiny_pair_forced_acceptance(alpha_kind):
+    cfg = synth.pair("tiny")
+    alpha = synth.alpha_constant(0.6, 8) if alpha_kind == "0.6" else synth.alpha_piecewise(128, 16)
+    c, _, trace = _run_pair(cfg, controller="gammatune", temperature=1.0, seed=4, accept_mode=1, alpha=alpha, n_generate=96)
+    _assert_clean(c)
+    c, _, trace = _run_pair(cfg, controller="gammatune", temperature=0.7, seed=4, accept_mode=1, alpha=alpha,
+                            tau=float(np.float32(0.4)), n_generate=96)
+    _assert_clean(c)
+    assert any(int(r["k"][0]) < int(r["gamma"][0]) for r in trace)
+
+
+def test_tiny_pair_batch_of_three_with_own_controllers():
+    cfg = synth.pair("tiny")
+    c, toks, trace = _run_pair(cfg, controller="gammatune", temperature=1.0, seed=6, batch=3, n_generate=40)
+    _assert_clean(c)
+    assert len({tuple(r["gamma"]) for r in trace}) > 1
+    assert any(len(set(r["gamma"].tolist())) > 1 for r in trace)  # sequences did plan different gammas
+
+
+def test_prompt_of_one_token_and_gamma_one():
+    cfg = synth.pair("tiny")
+    c, toks, _ = _run_pair(cfg, controller="fixed1", temperature=1.0, seed=8, prompt_len=1, n_generate=12)
+    _assert_clean(c)
+    c, toks, _ = _run_pair(cfg, controller="fixed8", temperature=0.0, prompt_len=2, n_generate=20)
+    _assert_clean(c)
+
+
+def test_call_order_and_argument_errors():
+    pk = _pk()
+    cfg = synth.pair("tiny")
+    Wt, Wd = synth.make_pair_weights(cfg, 0)
+    Wt_g = to_gpu(Wt)
+    Wd_g = {k: (v[:2] if isinstance(v, list) else v) for k, v in Wt_g.items()}
+    eng = pk.SpecEngine(cfg.target, Wt_g, cfg.draft, Wd_g, max_seq=64, gamma_max=4)
+    from paper_2504_00030_amd import binding as bd
+    with pytest.raises(pk.SpecError) as e:
+        eng.draft(2)
+    assert e.value.code == bd.SPEC_ESTATE
+    eng.prefill(synth.make_prompts(1, 8, cfg.target.vocab, 1))
+    with pytest.raises(pk.SpecError) as e:
+        eng.verify(2)
+    assert e.value.code == bd.SPEC_ESTATE
+    with pytest.raises(pk.SpecError) as e:
+        eng.draft(5)
+    assert e.value.code == bd.SPEC_EINVAL
+    eng.draft(2)
+    with pytest.raises(pk.SpecError) as e:
+        eng.verify(3)
+    assert e.value.code == bd.SPEC_EINVAL
+    eng.verify(2)
+    A, y, k = eng.accept()
+    assert 0 <= A[0] <= 2 and k[0] == 2 and 0 <= y[0] < cfg.target.vocab
+    with pytest.raises(pk.SpecError) as e:
+        eng.prefill(np.full((1, 8), cfg.target.vocab, dtype=np.int32))
+    assert e.value.code == bd.SPEC_EINVAL
+    with pytest.raises(pk.SpecError) as e:
+        eng.prefill(synth.make_prompts(1, 62, cfg.target.vocab, 1))
+    assert e.value.code == bd.SPEC_ECAP
+    eng.close()
+    # capacity: a step that would run past max_seq is refused
+    eng = pk.SpecEngine(cfg.target, Wt_g, cfg.draft, Wd_g, max_seq=16, gamma_max=4)
+    eng.prefill(synth.make_prompts(1, 10, cfg.target.vocab, 1))
+    with pytest.raises(pk.SpecError) as e:
+        for _ in range(10):
+            eng.draft(4); eng.verify(4); eng.accept()
+    assert e.value.code == bd.SPEC_ECAP
+    eng.close()
+    bad = synth.ModelShape(2, 128, 4, 3, 32, 344, 512, dtype="fp32")
+    with pytest.raises(pk.SpecError):
+        pk.SpecEngine(bad, Wt_g, cfg.draft, Wd_g, max_seq=64, gamma_max=4)

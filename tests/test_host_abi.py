@@ -1,0 +1,90 @@
+"""CPU-side checks of the product: the C-ABI library loads and exports every declared symbol,
+and the C controller follows the same trajectories as the oracle (GammaTune section, Algorithm 1)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2504_00030_amd as pk
+from paper_2504_00030_amd import binding
+from oracle import gammatune as ogt
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    names = set()
+    for h in ("spec.h", "gammatune.h"):
+        txt = open(os.path.join(ROOT, "include", h)).read()
+        txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+        names |= set(re.findall(r"\b((?:spec|gammatune)_[a-z_0-9]+)\s*\(", txt))
+    return names
+
+
+def test_library_exports_every_declared_symbol():
+    lib = pk.load()
+    declared = _declared_symbols()
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_strerror_and_null_handling():
+    lib = pk.load()
+    assert binding.strerror(0) == "ok"
+    assert "order" in binding.strerror(binding.SPEC_ESTATE)
+    assert lib.spec_draft(None, 1) == binding.SPEC_EINVAL
+    assert lib.spec_verify(None, 1) == binding.SPEC_EINVAL
+    assert lib.spec_accept(None, None, None, None) == binding.SPEC_EINVAL
+    out = ctypes.c_void_p(123)
+    assert lib.spec_init(None, None, None, None, None, ctypes.byref(out)) == binding.SPEC_EINVAL
+    assert out.value is None
+    lib.spec_destroy(None)  # no-op
+
+
+def test_controller_matches_oracle_on_golden_and_random_scripts():
+    gold = os.path.join(ROOT, "tests", "golden", "gammatune_trajectories.txt")
+    for line in open(gold):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        name, eta, script, gammas, gbars = [x.strip() for x in line.split("|")]
+        c = pk.GammaTune(eta=float(eta), delta=1, gamma_min=1, gamma_max=8, gamma0=4)
+        got = []
+        bars = []
+        for t in script.split():
+            a = 10**6 if t == "inf" else int(t)
+            got.append(c.update(min(a, c.gamma)))
+            bars.append(c.gamma_bar)
+        assert got == [int(g) for g in gammas.split()], name
+        want_bars = [float(g) for g in gbars.split()]
+        assert bars[: len(want_bars)] == want_bars, name
+    rng = np.random.default_rng(0)
+    for trial in range(300):
+        gmin = int(rng.integers(1, 4)); gmax = int(rng.integers(gmin, 24)); delta = int(rng.integers(0, 4))
+        eta = float(rng.random()); g0 = int(rng.integers(1, 30)); reading = int(rng.integers(0, 3))
+        c = pk.GammaTune(eta=eta, delta=delta, gamma_min=gmin, gamma_max=gmax, gamma0=g0, reading=reading)
+        o = ogt.Controller(ogt.Params(eta, delta, gmin, gmax, reading), g0)
+        assert c.gamma == o.gamma
+        for _ in range(80):
+            A = int(rng.integers(0, o.gamma + 1))
+            k = int(rng.integers(A, o.gamma + 1))
+            assert c.update(A, k) == o.update(A, k)
+            assert c.gamma_bar == o.gamma_bar  # bit-identical doubles
+
+
+def test_controller_rejects_bad_input():
+    with pytest.raises(pk.SpecError):
+        pk.GammaTune(eta=1.5)
+    with pytest.raises(pk.SpecError):
+        pk.GammaTune(gamma_min=0)
+    with pytest.raises(pk.SpecError):
+        pk.GammaTune(reading=7)
+    c = pk.GammaTune()
+    with pytest.raises(pk.SpecError):
+        c.update(5)
+    with pytest.raises(pk.SpecError):
+        c.update(2, 1)
+    assert c.gamma == 4 and c.gamma_bar == 4.0  # untouched by the failed calls
