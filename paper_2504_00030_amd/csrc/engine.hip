@@ -57,6 +57,7 @@ struct ModelRT {
 struct spec_ctx {
     spec_config cfg{};
     hipStream_t stream = nullptr;
+    bool own_stream = false;
     ModelRT tgt, drf;
     State st{};
     std::vector<void *> dev_allocs, host_allocs;
@@ -206,6 +207,7 @@ int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights
     std::vector<int32_t> bt((size_t)m.n_pages);
     for (int b = 0; b < c->cfg.batch; ++b)
         for (int p = 0; p < m.pages_per_seq; ++p) bt[(size_t)b * m.pages_per_seq + p] = p * c->cfg.batch + b;
+    HIPCHK(c, hipStreamSynchronize(c->stream));  // the zero fills above run on the context's stream
     HIPCHK(c, hipMemcpy(m.block_table, bt.data(), bt.size() * sizeof(int32_t), hipMemcpyHostToDevice));
 
     // rotary tables, angles in double
@@ -219,6 +221,7 @@ int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights
         }
     TRY(dalloc(c, &m.rope_cos, cs.size()));
     TRY(dalloc(c, &m.rope_sin, sn.size()));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
     HIPCHK(c, hipMemcpy(m.rope_cos, cs.data(), cs.size() * sizeof(float), hipMemcpyHostToDevice));
     HIPCHK(c, hipMemcpy(m.rope_sin, sn.data(), sn.size() * sizeof(float), hipMemcpyHostToDevice));
 
@@ -461,6 +464,7 @@ void spec_destroy(spec_ctx *c) {
     for (auto g : c->graphs) hipGraphDestroy(g);
     for (void *p : c->dev_allocs) hipFree(p);
     for (void *p : c->host_allocs) hipHostFree(p);
+    if (c->own_stream) hipStreamDestroy(c->stream);
     delete c;
 }
 
@@ -477,6 +481,14 @@ int spec_init(const spec_shape *t, const spec_weights *tw, const spec_shape *d, 
     c->cfg = *cfg;
     if (c->cfg.page_tokens == 0) c->cfg.page_tokens = 64;
     c->stream = reinterpret_cast<hipStream_t>(cfg->hip_stream);
+    // whatever produced the weights (on any stream) must have finished before they are read here
+    if (hipDeviceSynchronize() != hipSuccess) return bail(fail(c, SPEC_EHIP, "init: device sync failed"));
+    if (c->stream == nullptr) {
+        // the null stream cannot be captured into a graph: work runs on a stream of the context's own
+        if (hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking) != hipSuccess)
+            return bail(fail(c, SPEC_EHIP, "init: hipStreamCreate failed"));
+        c->own_stream = true;
+    }
     int rc;
     if ((rc = check_shape(c, *t, "target")) || (rc = check_shape(c, *d, "draft")) ||
         (rc = check_weights(c, *t, tw, "target")) || (rc = check_weights(c, *d, dw, "draft")))
@@ -534,6 +546,7 @@ int spec_init(const spec_shape *t, const spec_weights *tw, const spec_shape *d, 
     c->scfg.tau = 0.f;
     {
         const float one = 1.0f;
+        if (hipStreamSynchronize(c->stream) != hipSuccess) return bail(fail(c, SPEC_EHIP, "init: stream sync failed"));
         if (hipMemcpy(c->d_alpha, &one, sizeof(float), hipMemcpyHostToDevice) != hipSuccess)
             return bail(fail(c, SPEC_EHIP, "hipMemcpy failed"));
     }
@@ -549,6 +562,7 @@ int spec_set_forced_alpha(spec_ctx *c, const float *alpha, int32_t n) {
     HIPCHK(c, hipStreamSynchronize(c->stream));
     float *p = nullptr;
     TRY(dalloc(c, &p, (size_t)n));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
     HIPCHK(c, hipMemcpy(p, alpha, sizeof(float) * n, hipMemcpyHostToDevice));
     c->d_alpha = p;
     c->scfg.alpha = p;

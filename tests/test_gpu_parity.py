@@ -69,7 +69,8 @@ def _run_pair(cfg, *, controller, temperature, seed=0, n_generate=None, prompt_l
     Wt_g = to_gpu(Wt)
     Wd_g = to_gpu(Wd) if cfg.draft_kind != "prefix" else {k: (v[: cfg.draft.n_layers] if isinstance(v, list) else v) for k, v in Wt_g.items()}
     prompts = synth.make_prompts(batch, prompt_len, cfg.target.vocab, 7)
-    eng = pk.SpecEngine(cfg.target, Wt_g, cfg.draft, Wd_g, batch=batch, max_seq=prompt_len + n_generate + 2 * cfg.gamma_max + 4,
+    eng = pk.SpecEngine(cfg.target, Wt_g, cfg.draft, Wd_g, batch=batch,
+                        max_seq=prompt_len + (n_generate + 2 * cfg.gamma_max + 4) * (4 if batch > 1 else 1),
                         gamma_max=cfg.gamma_max, temperature=temperature, seed=seed, accept_mode=accept_mode,
                         page_tokens=page_tokens, use_graphs=use_graphs, gemv_path=gemv_path)
     if block_table is not None:
