@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Speculative-decoding throughput on one MI355X.
+
+A "step" is one whole generation over one batch of synthetic input: the prompt is prefilled
+(untimed, reported separately) and then speculative steps (draft gamma tokens, verify gamma+1
+rows, accept / resample, controller update) run until n_generate tokens exist.  The timed region
+of a step is its decode loop, bracketed by device synchronisation on both sides.
+
+Default workload: the 8B-shaped target with the 1B-shaped draft, batch 1, prompt 1024, 512 new
+tokens, GammaTune+ (gamma in [1,16], tau 0.4), temperature 0.7, forced acceptance landscape that
+alternates alpha = 0.9 / 0.3 every 32 tokens.  Weights are seeded random-init, generated on the GPU.
+
+Prints ONE JSON line (see the keys below).  `roofline` times the dominant kernel (the target's
+gate/up projection, which streams 2*d_ffn*d_model bf16 weights per launch) with HIP event pairs
+around its launches on the engine's stream; `cpu_baseline` times the fp64 CPU oracle on a bounded
+sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--pair", default="8b", choices=["tiny", "1b", "7b", "8b"])
+    ap.add_argument("--alpha", default="piecewise", help="piecewise | a constant such as 0.6")
+    ap.add_argument("--controller", default="gammatune+", choices=["gammatune", "gammatune+", "fixed"])
+    ap.add_argument("--gamma0", type=int, default=4)
+    ap.add_argument("--temperature", type=float, default=0.7)
+    ap.add_argument("--n-generate", type=int, default=0)
+    ap.add_argument("--prompt-len", type=int, default=0)
+    ap.add_argument("--no-graphs", action="store_true")
+    ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--skip-roofline", action="store_true")
+    ap.add_argument("--gemv-path", type=int, default=0)
+    return ap.parse_args()
+
+
+def decode_loop(eng, ctrl, n_generate):
+    gen, steps, acc, drafted, gsum = 0, 0, 0, 0, 0
+    while gen < n_generate:
+        g = ctrl.gamma
+        eng.draft(g)
+        eng.verify(g)
+        A, y, k = eng.accept()
+        ctrl.update(int(A[0]), int(k[0]))
+        gen += int(A[0]) + 1
+        steps += 1
+        acc += int(A[0])
+        drafted += int(k[0])
+        gsum += g
+    return dict(generated=gen, spec_steps=steps, accepted=acc, drafted=drafted, gamma_sum=gsum)
+
+
+def make_controller(pk, args, gamma_max):
+    if args.controller == "fixed":
+        return pk.FixedGamma(args.gamma0)
+    return pk.GammaTune(eta=0.25, delta=1, gamma_min=1, gamma_max=gamma_max, gamma0=args.gamma0)
+
+
+def cpu_baseline(cfg, Wt, Wd, tokens_per_step, mean_gamma):
+    """Time the fp64 oracle at full width on a bounded sample and extrapolate over the layers."""
+    import synth
+    from oracle import model as om
+
+    def oshape(ms, L):
+        return om.Shape(L, ms.d_model, ms.n_q_heads, ms.n_kv_heads, ms.head_dim, ms.d_ffn, ms.vocab, ms.rope_theta,
+                        ms.rms_eps, ms.dtype == "bf16")
+
+    def host(W, L):
+        return synth.to_numpy_weights({k: (v[:L] if isinstance(v, list) else v) for k, v in W.items()})
+
+    prompt = synth.make_prompts(1, 32, cfg.target.vocab, 11)[0]
+    gamma = max(1, int(round(mean_gamma)))
+    out = {}
+    t_all0 = time.time()
+    for name, ms, W, Ls, rows in (("target", cfg.target, Wt, (0, 1), gamma + 1), ("draft", cfg.draft, Wd, (0, 1), 1)):
+        t = {}
+        for L in Ls:
+            Wn = host(W, L)
+            cache = om.KVCache(oshape(ms, L))
+            om.forward(oshape(ms, L), Wn, prompt, cache)         # context, untimed
+            t0 = time.time()
+            om.forward(oshape(ms, L), Wn, prompt[:rows], cache)  # the timed rows
+            t[L] = time.time() - t0
+        per_layer = max(t[1] - t[0], 0.0)
+        out[name] = t[0] + per_layer * ms.n_layers
+    step_s = gamma * out["draft"] + out["target"]
+    return {
+        "value": tokens_per_step / step_s,
+        "unit": "tokens/s",
+        "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
+        "kind": "oracle",
+        "sample": (f"fp64 oracle, full width: one {gamma + 1}-row target pass and one 1-row draft pass after a 32-token "
+                   f"context, timed with 0 and 1 layers (+ embedding, final norm, LM head) and extrapolated linearly to "
+                   f"{cfg.target.n_layers}/{cfg.draft.n_layers} layers; step = {gamma} draft passes + 1 target pass, "
+                   f"{tokens_per_step:.2f} tokens per step as measured on the GPU run; sample took {time.time() - t_all0:.1f} s"),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import synth
+    import paper_2504_00030_amd as pk
+
+    pk.load()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    cfg = synth.pair(args.pair)
+    n_gen = args.n_generate or cfg.n_generate
+    n_prompt = args.prompt_len or cfg.prompt_len
+    t0 = time.time()
+    Wt, Wd = synth.make_pair_weights(cfg, 0, device="cuda")
+    torch.cuda.synchronize()
+    t_weights = time.time() - t0
+
+    if args.alpha == "piecewise":
+        alpha = synth.alpha_piecewise(n_gen + 64, 32, 0.9, 0.3)
+    else:
+        alpha = synth.alpha_constant(float(args.alpha), 4)
+    tau = float(np.float32(0.4)) if args.controller == "gammatune+" else 0.0
+    max_seq = n_prompt + n_gen + 2 * cfg.gamma_max + 8
+    prompts = synth.make_prompts(1, n_prompt, cfg.target.vocab, 7)
+
+    def engine(use_graphs):
+        e = pk.SpecEngine(cfg.target, Wt, cfg.draft, Wd, batch=1, max_seq=max_seq, gamma_max=cfg.gamma_max,
+                          temperature=args.temperature, seed=0, accept_mode=pk.ACCEPT_FORCED, use_graphs=use_graphs,
+                          gemv_path=args.gemv_path)
+        e.set_forced_alpha(alpha)
+        if tau > 0:
+            e.set_early_stop(tau)
+        return e
+
+    eng = engine(not args.no_graphs)
+    stats = None
+    t_prefill = 0.0
+    for _ in range(args.warmup):
+        eng.prefill(prompts)
+        decode_loop(eng, make_controller(pk, args, cfg.gamma_max), n_gen)
+    total = 0.0
+    for _ in range(args.steps):
+        torch.cuda.synchronize()
+        tp = time.perf_counter()
+        eng.prefill(prompts)
+        torch.cuda.synchronize()
+        t_prefill += time.perf_counter() - tp
+        ctrl = make_controller(pk, args, cfg.gamma_max)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        stats = decode_loop(eng, ctrl, n_gen)
+        torch.cuda.synchronize()
+        total += time.perf_counter() - t1
+    steps = max(args.steps, 1)
+    tok_s = steps * n_gen / total if total > 0 else 0.0
+    eng.close()
+
+    roofline = None
+    if not args.skip_roofline:
+        e2 = engine(False)
+        e2.prefill(prompts)
+        e2.profile_kernel(1, 3)  # target model, gate/up projection + SwiGLU
+        c2 = make_controller(pk, args, cfg.gamma_max)
+        decode_loop(e2, c2, min(n_gen, 128))
+        n_launch, ms = e2.profile_read()
+        e2.close()
+        bytes_per_launch = 2 * cfg.target.d_ffn * cfg.target.d_model * (2 if cfg.target.dtype == "bf16" else 4)
+        avg_ms = ms / max(n_launch, 1)
+        achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "target gate/up projection + SwiGLU",
+                    "launches": n_launch, "avg_us": avg_ms * 1e3, "bytes_per_launch": bytes_per_launch}
+
+    tokens_per_step = stats["generated"] / max(stats["spec_steps"], 1)
+    mean_gamma = stats["gamma_sum"] / max(stats["spec_steps"], 1)
+    cpu = None
+    if not args.skip_cpu:
+        cpu = cpu_baseline(cfg, Wt, Wd, tokens_per_step, mean_gamma)
+
+    line = {
+        "metric": "generated tokens/s (8B-shaped pair, bs1); verify-pass HBM GB/s % of peak" if args.pair == "8b" else f"generated tokens/s ({args.pair} pair, bs1)",
+        "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * total / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.target.dtype, "data": "synthetic",
+        "config": {
+            "workload": (f"{args.pair}: target {cfg.target.n_layers}L d{cfg.target.d_model} ffn{cfg.target.d_ffn} "
+                         f"V{cfg.target.vocab}, draft {cfg.draft.n_layers}L d{cfg.draft.d_model}; batch 1, prompt {n_prompt}, "
+                         f"generate {n_gen}; {args.controller} gamma in [1,{cfg.gamma_max}] gamma0 {args.gamma0}, "
+                         f"T={args.temperature}, forced alpha {args.alpha}, tau {tau}; seeded random-init weights"),
+            "graphs": not args.no_graphs, "spec_steps": stats["spec_steps"], "tokens_per_spec_step": tokens_per_step,
+            "mean_gamma": mean_gamma, "mean_accepted": stats["accepted"] / max(stats["spec_steps"], 1),
+            "mean_drafted": stats["drafted"] / max(stats["spec_steps"], 1),
+            "prefill_ms": 1e3 * t_prefill / steps, "weights_s": t_weights,
+        },
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -160,6 +160,14 @@ int spec_debug_fill_kv(spec_ctx *ctx, int32_t len, uint64_t seed);
  * a permutation of 0..batch*pages-1.  Must be called before spec_prefill. */
 int spec_debug_set_block_table(spec_ctx *ctx, const int32_t *table);
 
+/* Time one kernel class with HIP event pairs on the context's stream.  model: 0 draft, 1 target.
+ * kind: 1 QKV projection, 2 output/down projection with residual, 3 gate/up projection with SwiGLU,
+ * 4 LM head; -1 switches timing off.  Only launches made outside captured graphs (use_graphs = 0)
+ * are timed.  spec_profile_read() waits for the stream, returns the number of timed launches and the
+ * sum of their durations in milliseconds since the last read, and clears the record. */
+int spec_profile_kernel(spec_ctx *ctx, int32_t model, int32_t kind);
+int spec_profile_read(spec_ctx *ctx, int32_t *launches, double *total_ms);
+
 /* Device bytes the context allocated (KV pages, activations, logits, re-tiled weights). */
 int64_t spec_device_bytes(const spec_ctx *ctx);
 

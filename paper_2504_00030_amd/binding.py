@@ -26,7 +26,7 @@ GT_EXPAND_A, GT_LITERAL, GT_SHORT_TERM = 0, 1, 2
 EXPORTS = [
     "spec_init", "spec_prefill", "spec_draft", "spec_draft_batch", "spec_verify", "spec_accept",
     "spec_set_forced_alpha", "spec_set_early_stop", "spec_read_tokens", "spec_debug_logits",
-    "spec_debug_drafted", "spec_debug_fill_kv", "spec_debug_set_block_table", "spec_device_bytes", "spec_destroy",
+    "spec_debug_drafted", "spec_debug_fill_kv", "spec_debug_set_block_table", "spec_device_bytes", "spec_profile_kernel", "spec_profile_read", "spec_destroy",
     "spec_strerror", "spec_last_error", "spec_k_gemv", "spec_k_retile", "spec_k_philox", "spec_k_accept",
     "gammatune_init", "gammatune_update",
 ]
@@ -93,6 +93,8 @@ def load() -> C.CDLL:
     lib.spec_debug_drafted.argtypes = [C.c_void_p, C.c_int32, i32p, C.c_int32, i32p]
     lib.spec_debug_fill_kv.argtypes = [C.c_void_p, C.c_int32, C.c_uint64]
     lib.spec_debug_set_block_table.argtypes = [C.c_void_p, i32p]
+    lib.spec_profile_kernel.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+    lib.spec_profile_read.argtypes = [C.c_void_p, i32p, C.POINTER(C.c_double)]
     lib.spec_device_bytes.argtypes = [C.c_void_p]
     lib.spec_device_bytes.restype = C.c_int64
     lib.spec_destroy.argtypes = [C.c_void_p]
@@ -267,6 +269,15 @@ class SpecEngine:
 
     def fill_kv(self, length: int, seed: int = 0):
         self._chk(self._lib.spec_debug_fill_kv(self._ctx, int(length), int(seed)), "spec_debug_fill_kv")
+
+    def profile_kernel(self, model: int, kind: int):
+        self._chk(self._lib.spec_profile_kernel(self._ctx, model, kind), "spec_profile_kernel")
+
+    def profile_read(self):
+        n = C.c_int32()
+        ms = C.c_double()
+        self._chk(self._lib.spec_profile_read(self._ctx, C.byref(n), C.byref(ms)), "spec_profile_read")
+        return n.value, ms.value
 
     def device_bytes(self) -> int:
         return int(self._lib.spec_device_bytes(self._ctx))

@@ -85,6 +85,11 @@ struct spec_ctx {
     bool prefilled = false;
     std::map<int, hipGraphExec_t> g_draft, g_verify;
     std::vector<hipGraph_t> graphs;
+    // optional timing of one kernel class with event pairs (direct launches only)
+    int prof_epi = -1, prof_model = 0;
+    bool capturing = false;
+    std::vector<hipEvent_t> prof_events;  // start, stop, start, stop, ...
+    size_t prof_used = 0;
 };
 
 namespace {
@@ -255,6 +260,28 @@ KVCache kv_of(const spec_ctx *c, const ModelRT &m, int l) {
     return kv;
 }
 
+// Bracket the next launch with an event pair when its kernel class is being timed.
+struct ProfScope {
+    spec_ctx *c;
+    bool on;
+    ProfScope(spec_ctx *c_, const ModelRT &m, int epi) : c(c_), on(false) {
+        if (c->prof_epi != epi || c->capturing) return;
+        if ((c->prof_model == 1) != (&m == &c->tgt)) return;
+        if (c->prof_used + 2 > c->prof_events.size()) {
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
+            c->prof_events.push_back(a);
+            c->prof_events.push_back(b);
+        }
+        on = hipEventRecord(c->prof_events[c->prof_used], c->stream) == hipSuccess;
+    }
+    ~ProfScope() {
+        if (!on) return;
+        (void)hipEventRecord(c->prof_events[c->prof_used + 1], c->stream);
+        c->prof_used += 2;
+    }
+};
+
 struct LogitsPlan {
     bool want = false;
     int rows = 0;           // logits rows produced
@@ -295,6 +322,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             a.rope_cos = m.rope_cos; a.rope_sin = m.rope_sin; a.row_pos = m.row_pos; a.row_seq = m.row_seq;
             a.kv = kv_of(c, m, l); a.kv_dtype = s.dtype;
             a.rpw = gemv_wavedot_pick_rpw(EPI_QKV, qd + 2 * a.n1, d, R, s.dtype);
+            ProfScope ps_(c, m, EPI_QKV);
             HIPCHK(c, launch_gemv_wavedot(a, EPI_QKV, s.dtype, st));
         }
         {
@@ -319,6 +347,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             a.ssq_in = m.ssq; a.ssq_in_slots = slots;
             a.y = m.act; a.yb = m.actb;
             a.rpw = gemv_wavedot_pick_rpw(EPI_SWIGLU, 2 * ffn, d, R, s.dtype);
+            ProfScope ps_(c, m, EPI_SWIGLU);
             HIPCHK(c, launch_gemv_wavedot(a, EPI_SWIGLU, s.dtype, st));
         }
         {   // down projection + residual
@@ -327,6 +356,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             a.xres = m.x; a.g_next = (l + 1 < s.n_layers) ? m.attn_norm[l + 1] : m.final_norm;
             a.xg = m.xg; a.xgb = m.xgb; a.ssq_out = m.ssq;
             a.rpw = gemv_wavedot_pick_rpw(EPI_RESID, d, ffn, R, s.dtype);
+            ProfScope ps_(c, m, EPI_RESID);
             HIPCHK(c, launch_gemv_wavedot(a, EPI_RESID, s.dtype, st));
             slots = ((d + a.rpw - 1) / a.rpw + 3) / 4;
         }
@@ -345,6 +375,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
         if (a.n_tiles > m.tiles_cap) return fail(c, SPEC_EINVAL, "logits tiling exceeds the partial buffers");
         *lp.tile = tile;
         *lp.ntiles = a.n_tiles;
+        ProfScope ps_(c, m, EPI_LOGITS);
         HIPCHK(c, launch_gemv_wavedot(a, EPI_LOGITS, s.dtype, st));
     }
     return SPEC_OK;
@@ -408,7 +439,9 @@ int enqueue_accept(spec_ctx *c, int gamma) {
 // Capture `body` into an executable graph.
 template <typename F> int capture(spec_ctx *c, F body, hipGraphExec_t *out) {
     HIPCHK(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+    c->capturing = true;
     const int rc = body();
+    c->capturing = false;
     hipGraph_t g = nullptr;
     const hipError_t e = hipStreamEndCapture(c->stream, &g);
     if (rc != SPEC_OK) {
@@ -464,6 +497,7 @@ void spec_destroy(spec_ctx *c) {
     for (auto g : c->graphs) hipGraphDestroy(g);
     for (void *p : c->dev_allocs) hipFree(p);
     for (void *p : c->host_allocs) hipHostFree(p);
+    for (hipEvent_t e : c->prof_events) hipEventDestroy(e);
     if (c->own_stream) hipStreamDestroy(c->stream);
     delete c;
 }
@@ -766,6 +800,32 @@ int spec_debug_fill_kv(spec_ctx *c, int32_t len, uint64_t seed) {
     c->h_len.assign(B, len + 1);
     c->prefilled = true;
     c->phase = 1;
+    return SPEC_OK;
+}
+
+int spec_profile_kernel(spec_ctx *c, int32_t model, int32_t kind) {
+    if (!c) return SPEC_EINVAL;
+    if (model != 0 && model != 1) return fail(c, SPEC_EINVAL, "profile: model must be 0 (draft) or 1 (target)");
+    if (kind < -1 || kind > EPI_LOGITS || kind == EPI_PLAIN) return fail(c, SPEC_EINVAL, "profile: unknown kernel class");
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    c->prof_epi = kind;
+    c->prof_model = model;
+    c->prof_used = 0;
+    return SPEC_OK;
+}
+
+int spec_profile_read(spec_ctx *c, int32_t *launches, double *total_ms) {
+    if (!c || !launches || !total_ms) return fail(c, SPEC_EINVAL, "profile_read: null pointer");
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    double tot = 0.0;
+    for (size_t i = 0; i + 1 < c->prof_used; i += 2) {
+        float ms = 0.f;
+        HIPCHK(c, hipEventElapsedTime(&ms, c->prof_events[i], c->prof_events[i + 1]));
+        tot += ms;
+    }
+    *launches = (int32_t)(c->prof_used / 2);
+    *total_ms = tot;
+    c->prof_used = 0;
     return SPEC_OK;
 }
 
