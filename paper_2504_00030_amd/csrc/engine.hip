@@ -33,6 +33,7 @@ struct ModelRT {
     // re-tiled bf16 copies for the matrix-core path (empty when unused)
     std::vector<void *> t_qkv, t_wo, t_gu, t_wd;
     void *t_lm = nullptr;
+    bool mfma_ok = false;
     int Rmax = 0;
     float *x = nullptr, *xg = nullptr, *ssq = nullptr, *q = nullptr, *ao = nullptr, *act = nullptr;
     uint16_t *xgb = nullptr, *aob = nullptr, *actb = nullptr;
@@ -120,6 +121,17 @@ template <typename T> int dalloc(spec_ctx *c, T **p, size_t n) {
     return SPEC_OK;
 }
 
+// device allocation that is fully overwritten by its first use (no zero fill)
+template <typename T> int dalloc_raw(spec_ctx *c, T **p, size_t n) {
+    void *v = nullptr;
+    const size_t bytes = (n ? n : 1) * sizeof(T);
+    if (hipMalloc(&v, bytes) != hipSuccess) return fail(c, SPEC_ENOMEM, "hipMalloc failed");
+    c->dev_allocs.push_back(v);
+    c->dev_bytes += (int64_t)bytes;
+    *p = reinterpret_cast<T *>(v);
+    return SPEC_OK;
+}
+
 #define TRY(expr)                       \
     do {                                \
         int rc_ = (expr);               \
@@ -182,6 +194,31 @@ int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights
     m.embed = w->tok_embed;
     m.lm_head = w->lm_head;
 
+    // re-tiled copies for the matrix-core kernels
+    const int kvd = s.n_kv_heads * s.head_dim;
+    m.mfma_ok = s.dtype == SPEC_BF16 && c->cfg.gemv_path != SPEC_PATH_WAVEDOT && d % 32 == 0 && qd % 32 == 0 &&
+                s.d_ffn % 32 == 0 && s.vocab % 16 == 0 && (s.head_dim / 2) % 8 == 0 && d % 16 == 0;
+    if (m.mfma_ok) {
+        auto retile = [&](int mode, const void *w0, const void *w1, const void *w2, int Ntot, int K, void **out) {
+            uint16_t *buf = nullptr;
+            TRY(dalloc_raw(c, &buf, (size_t)Ntot * K));
+            RetileArgs ra{};
+            ra.w0 = w0; ra.w1 = w1; ra.w2 = w2; ra.mode = mode; ra.Ntot = Ntot; ra.K = K;
+            ra.nq = s.n_q_heads; ra.nkv = s.n_kv_heads; ra.hd = s.head_dim;
+            HIPCHK(c, launch_retile(ra, buf, st));
+            *out = buf;
+            return (int)SPEC_OK;
+        };
+        for (int l = 0; l < L; ++l) {
+            void *t = nullptr;
+            TRY(retile(EPI_QKV, w->wq[l], w->wk[l], w->wv[l], qd + 2 * kvd, d, &t)); m.t_qkv.push_back(t);
+            TRY(retile(EPI_PLAIN, w->wo[l], nullptr, nullptr, d, qd, &t)); m.t_wo.push_back(t);
+            TRY(retile(EPI_SWIGLU, w->w_gate[l], w->w_up[l], nullptr, 2 * s.d_ffn, d, &t)); m.t_gu.push_back(t);
+            TRY(retile(EPI_PLAIN, w->w_down[l], nullptr, nullptr, d, s.d_ffn, &t)); m.t_wd.push_back(t);
+        }
+        TRY(retile(EPI_PLAIN, w->lm_head, nullptr, nullptr, s.vocab, d, &m.t_lm));
+    }
+
     const size_t R = (size_t)Rmax;
     TRY(dalloc(c, &m.x, R * d));
     TRY(dalloc(c, &m.xg, R * d));
@@ -238,7 +275,7 @@ int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights
 
     m.logit_rows = logit_rows;
     TRY(dalloc(c, &m.logits, (size_t)logit_rows * s.vocab));
-    m.tiles_cap = (s.vocab + 63) / 64 + 1;  // the finest tiling any logits kernel uses is 64 columns
+    m.tiles_cap = (s.vocab + 15) / 16 + 1;  // the finest tiling any logits kernel uses is 16 columns
     TRY(dalloc(c, &m.pm, (size_t)logit_rows * m.tiles_cap));
     TRY(dalloc(c, &m.ps, (size_t)logit_rows * m.tiles_cap));
     TRY(dalloc(c, &m.pa, (size_t)logit_rows * m.tiles_cap));
@@ -282,6 +319,40 @@ struct ProfScope {
     }
 };
 
+constexpr int MFMA_MIN_ROWS = 3;  // fewer rows run as wave dot products on fp32 activations
+
+bool use_mfma(const spec_ctx *c, const ModelRT &m, int R) {
+    if (!m.mfma_ok) return false;
+    return c->cfg.gemv_path == SPEC_PATH_MFMA || R >= MFMA_MIN_ROWS;
+}
+
+// Launch one fused projection on whichever kernel family serves R rows; `tiled` is the re-tiled
+// copy of the same matrices.  Returns the number of workgroups through *blocks.
+int launch_proj(spec_ctx *c, ModelRT &m, GemvArgs a, int epi, const void *tiled, int Ntot, int *blocks,
+                int *tile_cols) {
+    ProfScope ps_(c, m, epi);
+    if (use_mfma(c, m, a.R)) {
+        a.w0 = tiled; a.w1 = a.w2 = nullptr;
+        const int ng = gemv_mfma_groups_per_wg(epi, Ntot);
+        const int nb = (Ntot / 16 + ng - 1) / ng;
+        if (epi == EPI_LOGITS) a.n_tiles = nb;
+        if (blocks) *blocks = nb;
+        if (tile_cols) *tile_cols = 16 * ng;
+        if (epi == EPI_LOGITS && nb > m.tiles_cap) return fail(c, SPEC_EINVAL, "logits tiling exceeds the partial buffers");
+        if (epi == EPI_RESID && nb > SSQ_STRIDE) return fail(c, SPEC_EINVAL, "too many statistics slots");
+        HIPCHK(c, launch_gemv_mfma(a, epi, c->stream));
+        return SPEC_OK;
+    }
+    a.rpw = gemv_wavedot_pick_rpw(epi, Ntot, a.K, a.R, m.s.dtype);
+    const int nb = ((Ntot + a.rpw - 1) / a.rpw + 3) / 4;
+    if (epi == EPI_LOGITS) a.n_tiles = nb;
+    if (blocks) *blocks = nb;
+    if (tile_cols) *tile_cols = 4 * a.rpw;
+    if (epi == EPI_LOGITS && nb > m.tiles_cap) return fail(c, SPEC_EINVAL, "logits tiling exceeds the partial buffers");
+    HIPCHK(c, launch_gemv_wavedot(a, epi, m.s.dtype, c->stream));
+    return SPEC_OK;
+}
+
 struct LogitsPlan {
     bool want = false;
     int rows = 0;           // logits rows produced
@@ -312,18 +383,18 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
         a.ssq_stride = SSQ_STRIDE;
         return a;
     };
+    const int kvd = s.n_kv_heads * s.head_dim;
+    const bool tiled = m.mfma_ok;
     for (int l = 0; l < s.n_layers; ++l) {
         {   // fused QKV projection + RoPE + KV write
             GemvArgs a = base(d, m.xg, m.xgb);
             a.w0 = m.wq[l]; a.w1 = m.wk[l]; a.w2 = m.wv[l];
-            a.n0 = qd; a.n1 = a.n2 = s.n_kv_heads * s.head_dim;
+            a.n0 = qd; a.n1 = a.n2 = kvd;
             a.ssq_in = m.ssq; a.ssq_in_slots = slots;
             a.y = m.q; a.nq = s.n_q_heads; a.nkv = s.n_kv_heads; a.hd = s.head_dim;
             a.rope_cos = m.rope_cos; a.rope_sin = m.rope_sin; a.row_pos = m.row_pos; a.row_seq = m.row_seq;
             a.kv = kv_of(c, m, l); a.kv_dtype = s.dtype;
-            a.rpw = gemv_wavedot_pick_rpw(EPI_QKV, qd + 2 * a.n1, d, R, s.dtype);
-            ProfScope ps_(c, m, EPI_QKV);
-            HIPCHK(c, launch_gemv_wavedot(a, EPI_QKV, s.dtype, st));
+            TRY(launch_proj(c, m, a, EPI_QKV, tiled ? m.t_qkv[l] : nullptr, qd + 2 * kvd, nullptr, nullptr));
         }
         {
             AttnArgs t{};
@@ -337,28 +408,21 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             GemvArgs a = base(qd, m.ao, m.aob);
             a.w0 = m.wo[l]; a.n0 = d;
             a.xres = m.x; a.g_next = m.ffn_norm[l]; a.xg = m.xg; a.xgb = m.xgb; a.ssq_out = m.ssq;
-            a.rpw = gemv_wavedot_pick_rpw(EPI_RESID, d, qd, R, s.dtype);
-            HIPCHK(c, launch_gemv_wavedot(a, EPI_RESID, s.dtype, st));
-            slots = ((d + a.rpw - 1) / a.rpw + 3) / 4;
+            TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wo[l] : nullptr, d, &slots, nullptr));
         }
         {   // gate / up projections + SwiGLU
             GemvArgs a = base(d, m.xg, m.xgb);
             a.w0 = m.wg[l]; a.w1 = m.wu[l]; a.n0 = ffn;
             a.ssq_in = m.ssq; a.ssq_in_slots = slots;
             a.y = m.act; a.yb = m.actb;
-            a.rpw = gemv_wavedot_pick_rpw(EPI_SWIGLU, 2 * ffn, d, R, s.dtype);
-            ProfScope ps_(c, m, EPI_SWIGLU);
-            HIPCHK(c, launch_gemv_wavedot(a, EPI_SWIGLU, s.dtype, st));
+            TRY(launch_proj(c, m, a, EPI_SWIGLU, tiled ? m.t_gu[l] : nullptr, 2 * ffn, nullptr, nullptr));
         }
         {   // down projection + residual
             GemvArgs a = base(ffn, m.act, m.actb);
             a.w0 = m.wd[l]; a.n0 = d;
             a.xres = m.x; a.g_next = (l + 1 < s.n_layers) ? m.attn_norm[l + 1] : m.final_norm;
             a.xg = m.xg; a.xgb = m.xgb; a.ssq_out = m.ssq;
-            a.rpw = gemv_wavedot_pick_rpw(EPI_RESID, d, ffn, R, s.dtype);
-            ProfScope ps_(c, m, EPI_RESID);
-            HIPCHK(c, launch_gemv_wavedot(a, EPI_RESID, s.dtype, st));
-            slots = ((d + a.rpw - 1) / a.rpw + 3) / 4;
+            TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wd[l] : nullptr, d, &slots, nullptr));
         }
     }
     if (lp.want) {
@@ -369,14 +433,10 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
         a.ssq_in = m.ssq; a.ssq_in_slots = slots;
         a.y = m.logits; a.y_mul = lp.y_mul; a.y_add = lp.y_add; a.y_stride = s.vocab;
         a.pm = m.pm; a.ps = m.ps; a.pa = m.pa; a.inv_t = c->scfg.inv_t;
-        a.rpw = gemv_wavedot_pick_rpw(EPI_LOGITS, s.vocab, d, a.R, s.dtype);
-        const int tile = 4 * a.rpw;
-        a.n_tiles = (s.vocab + tile - 1) / tile;
-        if (a.n_tiles > m.tiles_cap) return fail(c, SPEC_EINVAL, "logits tiling exceeds the partial buffers");
+        int nb = 0, tile = 0;
+        TRY(launch_proj(c, m, a, EPI_LOGITS, tiled ? m.t_lm : nullptr, s.vocab, &nb, &tile));
         *lp.tile = tile;
-        *lp.ntiles = a.n_tiles;
-        ProfScope ps_(c, m, EPI_LOGITS);
-        HIPCHK(c, launch_gemv_wavedot(a, EPI_LOGITS, s.dtype, st));
+        *lp.ntiles = nb;
     }
     return SPEC_OK;
 }
@@ -836,9 +896,22 @@ int spec_k_gemv(const void *w, int32_t dtype, int32_t N, int32_t K, const float 
     if (!w || !x || !y || N < 1 || K < 1 || R < 1 || R > 128) return SPEC_EINVAL;
     if (dtype != SPEC_F32 && dtype != SPEC_BF16) return SPEC_EINVAL;
     if (K % (dtype == SPEC_BF16 ? 8 : 4)) return SPEC_EINVAL;
-    if (path == SPEC_PATH_MFMA) return SPEC_ENOTIMPL;
     GemvArgs a{};
     a.w0 = w; a.n0 = N; a.K = K; a.R = R; a.x = x; a.x_mul = 1; a.y = y;
+    if (path == SPEC_PATH_MFMA) {
+        // x is rounded to bf16 into a scratch copy: the matrix-core kernel reads 16-bit rows
+        if (dtype != SPEC_BF16 || N % 16 || K % 32) return SPEC_EINVAL;
+        const hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+        uint16_t *xb = nullptr;
+        if (hipMalloc(reinterpret_cast<void **>(&xb), (size_t)R * K * 2) != hipSuccess) return SPEC_ENOMEM;
+        int rc = SPEC_OK;
+        if (launch_cast_to_bf16(x, xb, (int64_t)R * K, st) != hipSuccess) rc = SPEC_EHIP;
+        a.xb = xb;
+        if (rc == SPEC_OK && launch_gemv_mfma(a, EPI_PLAIN, st) != hipSuccess) rc = SPEC_EHIP;
+        if (hipStreamSynchronize(st) != hipSuccess) rc = SPEC_EHIP;
+        (void)hipFree(xb);
+        return rc;
+    }
     a.rpw = gemv_wavedot_pick_rpw(EPI_PLAIN, N, K, R, dtype);
     if (launch_gemv_wavedot(a, EPI_PLAIN, dtype, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return SPEC_EHIP;
     return SPEC_OK;
@@ -846,7 +919,9 @@ int spec_k_gemv(const void *w, int32_t dtype, int32_t N, int32_t K, const float 
 
 int spec_k_retile(const void *w, int32_t N, int32_t K, void *out, void *stream) {
     if (!w || !out || N < 16 || K < 32 || N % 16 || K % 32) return SPEC_EINVAL;
-    if (launch_retile(w, N, K, out, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return SPEC_EHIP;
+    RetileArgs ra{};
+    ra.w0 = w; ra.mode = EPI_PLAIN; ra.Ntot = N; ra.K = K;
+    if (launch_retile(ra, out, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return SPEC_EHIP;
     return SPEC_OK;
 }
 

@@ -73,26 +73,51 @@ hipError_t launch_embed(const EmbedArgs &a, hipStream_t s) {
     return hipGetLastError();
 }
 
-// Row-major bf16 [N][K] -> 16-row groups of 1 KiB tiles.  Tile (group g, k-tile t) holds, for lane l,
-// the 8 values W[16 g + l % 16][32 t + 8 (l / 16) .. +8]; tiles of a group are contiguous in t.
-__global__ __launch_bounds__(256) void retile_k(const uint4 *__restrict__ w, int N, int K, uint4 *__restrict__ out) {
-    const int KT = K / 32;
-    const int64_t total = (int64_t)(N / 16) * KT * 64;
+// Row-major bf16 -> 16-row groups of 1 KiB tiles.  Tile (group g, k-tile t) holds, for lane l, the 8
+// values of packed row 16 g + l % 16 at k = 32 t + 8 (l / 16) .. +8; tiles of a group are contiguous in t.
+// Packed rows of the fused matrices are ordered so that an epilogue finds both partners of a pair in
+// one group: rows 0-7 of a group are first elements (gate rows, or RoPE elements j), rows 8-15 the
+// matching second elements (up rows, or RoPE elements j + hd/2).
+__device__ __forceinline__ const uint16_t *retile_src(const RetileArgs &a, int p) {
+    const uint16_t *w0 = reinterpret_cast<const uint16_t *>(a.w0);
+    if (a.mode == EPI_SWIGLU) {
+        const int gi = p >> 4, pos = p & 15;
+        const int j = gi * 8 + (pos & 7);
+        const uint16_t *base = pos < 8 ? w0 : reinterpret_cast<const uint16_t *>(a.w1);
+        return base + (size_t)j * a.K;
+    }
+    if (a.mode == EPI_QKV) {
+        const int half = a.hd >> 1;
+        const int gi = p >> 4, pos = p & 15;
+        const int P = gi * 8 + (pos & 7);
+        int hh = P / half;
+        const int j = P % half + (pos < 8 ? 0 : half);
+        const uint16_t *base = w0;
+        if (hh >= a.nq + a.nkv) { base = reinterpret_cast<const uint16_t *>(a.w2); hh -= a.nq + a.nkv; }
+        else if (hh >= a.nq) { base = reinterpret_cast<const uint16_t *>(a.w1); hh -= a.nq; }
+        return base + ((size_t)hh * a.hd + j) * a.K;
+    }
+    return w0 + (size_t)p * a.K;
+}
+
+__global__ __launch_bounds__(256) void retile_k(const RetileArgs a, uint4 *__restrict__ out) {
+    const int KT = a.K / 32;
+    const int64_t total = (int64_t)(a.Ntot / 16) * KT * 64;
     for (int64_t idx = blockIdx.x * (int64_t)256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
         const int l = (int)(idx & 63);
         const int64_t tile = idx >> 6;
         const int t = (int)(tile % KT);
-        const int64_t g = tile / KT;
-        const int64_t row = g * 16 + (l & 15);
-        const int k = t * 32 + (l >> 4) * 8;
-        out[idx] = w[(row * K + k) >> 3];
+        const int g = (int)(tile / KT);
+        const uint16_t *row = retile_src(a, g * 16 + (l & 15));
+        out[idx] = *reinterpret_cast<const uint4 *>(row + t * 32 + (l >> 4) * 8);
     }
 }
 
-hipError_t launch_retile(const void *w, int N, int K, void *out, hipStream_t s) {
-    if (N % 16 != 0 || K % 32 != 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(retile_k, dim3(2048), dim3(256), 0, s, reinterpret_cast<const uint4 *>(w), N, K,
-                       reinterpret_cast<uint4 *>(out));
+hipError_t launch_retile(const RetileArgs &a, void *out, hipStream_t s) {
+    if (a.Ntot % 16 != 0 || a.K % 32 != 0) return hipErrorInvalidValue;
+    if (a.mode == EPI_QKV && ((a.hd / 2) % 8 != 0)) return hipErrorInvalidValue;
+    if (a.mode == EPI_SWIGLU && (a.Ntot / 2) % 8 != 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(retile_k, dim3(4096), dim3(256), 0, s, a, reinterpret_cast<uint4 *>(out));
     return hipGetLastError();
 }
 
@@ -131,6 +156,17 @@ __global__ void cast_to_f32_k(const void *src, int dtype, float *dst, int64_t n)
     if (i >= n) return;
     dst[i] = dtype == DT_BF16 ? bf16_to_f32(reinterpret_cast<const bf16_t *>(src)[i])
                               : reinterpret_cast<const float *>(src)[i];
+}
+
+__global__ void cast_to_bf16_k(const float *src, uint16_t *dst, int64_t n) {
+    const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = f32_to_bf16(src[i]);
+}
+
+hipError_t launch_cast_to_bf16(const float *src, uint16_t *dst, int64_t n, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(cast_to_bf16_k, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, src, dst, n);
+    return hipGetLastError();
 }
 
 hipError_t launch_cast_to_f32(const void *src, int dtype, float *dst, int64_t n, hipStream_t s) {

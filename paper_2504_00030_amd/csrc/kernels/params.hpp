@@ -77,6 +77,13 @@ struct GemvArgs {
     float inv_t;
 };
 
+// Source of a re-tiled matrix: mode EPI_PLAIN (w0, Ntot rows), EPI_SWIGLU (gate = w0, up = w1,
+// Ntot = 2 * d_ffn) or EPI_QKV (wq, wk, wv; Ntot = (nq + 2 nkv) * hd).
+struct RetileArgs {
+    const void *w0, *w1, *w2;
+    int32_t mode, Ntot, K, nq, nkv, hd;
+};
+
 struct EmbedArgs {
     State st;
     RowPlan plan;
@@ -159,7 +166,7 @@ hipError_t launch_begin_draft(const State &st, const int32_t *gamma_plan, hipStr
 hipError_t launch_embed(const EmbedArgs &a, hipStream_t s);
 hipError_t launch_gemv_wavedot(const GemvArgs &a, int epi, int w_dtype, hipStream_t s);
 hipError_t launch_gemv_mfma(const GemvArgs &a, int epi, hipStream_t s);
-int gemv_mfma_tile_rows(int epi, int R);   // output columns per LOGITS partial for the matrix-core path
+int gemv_mfma_groups_per_wg(int epi, int Ntot);  // 16-row groups per workgroup of the matrix-core path
 int gemv_wavedot_pick_rpw(int epi, int N, int K, int R, int w_dtype);
 hipError_t launch_attention(const AttnArgs &a, int hd, hipStream_t s);
 hipError_t launch_draft_sample(const DraftSampleArgs &a, hipStream_t s);
@@ -169,9 +176,10 @@ hipError_t launch_row_partials(const float *logits, int rows, int vocab, int til
 hipError_t launch_gather_qstats(const float *q_logits, const int32_t *drafted, int rows, int vocab, const float *pm,
                                 const double *ps, const int32_t *pa, int n_tiles, float inv_t, float *q_logit,
                                 float *q_max, double *q_sum, hipStream_t s);
-hipError_t launch_retile(const void *w, int N, int K, void *out, hipStream_t s);
+hipError_t launch_retile(const RetileArgs &a, void *out, hipStream_t s);
 hipError_t launch_philox(uint64_t seed, const uint32_t *ctr, int n, uint32_t *out, hipStream_t s);
 hipError_t launch_fill_uniform(void *dst, int64_t n, int dtype, uint64_t seed, hipStream_t s);
+hipError_t launch_cast_to_bf16(const float *src, uint16_t *dst, int64_t n, hipStream_t s);
 hipError_t launch_cast_to_f32(const void *src, int dtype, float *dst, int64_t n, hipStream_t s);
 
 }  // namespace sd

@@ -61,7 +61,12 @@ _D2 = ModelShape(12, 768, 12, 12, 64, 3072, 32000, 10000.0, 1e-5, "bf16")
 _T3 = ModelShape(32, 4096, 32, 8, 128, 14336, 128256, 500000.0, 1e-5, "bf16")
 _T4 = ModelShape(40, 5120, 40, 40, 128, 13824, 32000, 10000.0, 1e-5, "bf16")
 
+_TS = ModelShape(3, 256, 8, 2, 32, 512, 1024, 500000.0, 1e-5, "bf16")
+_DS = ModelShape(2, 128, 4, 4, 32, 256, 1024, 500000.0, 1e-5, "bf16")
+
 PAIRS: Dict[str, PairConfig] = {
+    # small bf16 pair with grouped-query attention: exercises the 16-bit kernels at test speed
+    "small-bf16": PairConfig("small-bf16", _TS, _DS, "independent", 48, 64, 16),
     # tiny fp32 pair; draft = first two target layers with the tied embedding / head
     "tiny": PairConfig("tiny", _T0, replace(_T0, n_layers=2), "prefix", 32, 64, 8),
     # 1B-shaped target with a 2-layer d=768 draft

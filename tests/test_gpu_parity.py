@@ -58,6 +58,25 @@ def test_gemv_wavedot_matches_fp64_matmul(dtype, R, N, K):
     assert np.abs(got - want).max() <= tol
 
 
+@pytest.mark.parametrize("R", [1, 3, 16, 17, 40, 128])
+@pytest.mark.parametrize("N,K", [(4096, 4096), (1024, 11008), (2064, 768), (32000, 1024)])
+def test_gemv_mfma_matches_fp64_matmul(R, N, K):
+    pk = _pk()
+    g = torch.Generator().manual_seed(N * 7 + K + R)
+    w = (torch.randn(N, K, generator=g) * 0.02).to(torch.bfloat16)
+    x = torch.randn(R, K, generator=g).to(torch.bfloat16).float()  # the kernel's A operand is bf16 by design
+    want = (x.double() @ w.double().t()).numpy()
+    wt = torch.empty_like(w, device="cuda")
+    pk.k_retile(w.cuda().contiguous(), wt)
+    y = torch.full((R, N), float("nan"), device="cuda")
+    pk.k_gemv(wt, x.cuda().contiguous(), y, path=pk.PATH_MFMA, N=N, K=K)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy()
+    tol = 2e-6 * np.sqrt(K) * np.abs(want).max() + 1e-7
+    assert np.isfinite(got).all()
+    assert np.abs(got - want).max() <= tol
+
+
 def _run_pair(cfg, *, controller, temperature, seed=0, n_generate=None, prompt_len=None, batch=1, accept_mode=0,
               alpha=None, tau=0.0, norm_jitter=0.0, use_graphs=False, page_tokens=64, weights_seed=0, block_table=None,
               gemv_path=0):
@@ -179,6 +198,26 @@ def test_tiny_pair_batch_of_three_with_own_controllers():
     _assert_clean(c)
     assert len({tuple(r["gamma"]) for r in trace}) > 1
     assert any(len(set(r["gamma"].tolist())) > 1 for r in trace)  # sequences did plan different gammas
+
+
+@pytest.mark.parametrize("path", [0, 1, 2], ids=["auto", "wavedot", "mfma"])
+@pytest.mark.parametrize("temperature", [0.0, 1.0])
+def test_small_bf16_pair_end_to_end(path, temperature):
+    cfg = synth.pair("small-bf16")
+    c, toks, trace = _run_pair(cfg, controller="gammatune", temperature=temperature, seed=1, gemv_path=path,
+                               norm_jitter=0.05)
+    _assert_clean(c, full_coverage=False)
+    assert c.max_logit_err <= TOL["bf16"]
+    assert c.steps_compared >= 3
+
+
+def test_small_bf16_pair_batch_forced_early_stop_graphs():
+    cfg = synth.pair("small-bf16")
+    alpha = synth.alpha_piecewise(256, 16)
+    c, toks, trace = _run_pair(cfg, controller="gammatune", temperature=0.7, seed=2, batch=2, accept_mode=1, alpha=alpha,
+                               tau=float(np.float32(0.4)), use_graphs=True, n_generate=48)
+    _assert_clean(c, full_coverage=False)
+    assert max(int(r["gamma"].max()) for r in trace) >= 3
 
 
 def test_prompt_of_one_token_and_gamma_one():
