@@ -99,6 +99,10 @@ int spec_init(const spec_shape *target, const spec_weights *target_w,
  * generated count; may be called again to start a new generation.  Synchronises. */
 int spec_prefill(spec_ctx *ctx, const int32_t *host_tokens, int32_t n);
 
+/* Same for prompts of different lengths: host_tokens is host int32 [batch][n_max], sequence b uses its
+ * first lens[b] entries (1 <= lens[b] <= n_max). */
+int spec_prefill_ragged(spec_ctx *ctx, const int32_t *host_tokens, int32_t n_max, const int32_t *lens);
+
 /* Draft phase of one step, asynchronous.  Runs gamma draft-model decode steps; step i
  * draws x_i from softmax(draft logits / T) by index-order inverse CDF with the uniform
  * Philox(seed; counter = (step, i, DRAFT, b)) (argmax if T == 0), appends it to the
@@ -132,7 +136,7 @@ int spec_accept(spec_ctx *ctx, int32_t *n_accepted, int32_t *next_token, int32_t
 
 /* Forced acceptance landscape: alpha is host float [n], alpha[g] in [0,1] for generated index g
  * (the last value repeats beyond n).  Only used with SPEC_ACCEPT_FORCED.  In forced mode the
- * confidence seen by early stopping is 1 - Philox(g, 0, FORCED, b). */
+ * confidence seen by early stopping is the synthetic clamp(alpha[g] + (0.5 - Philox(g, 0, FORCED, b)) / 2, 0, 1). */
 int spec_set_forced_alpha(spec_ctx *ctx, const float *alpha, int32_t n);
 
 /* GammaTune+ threshold: stop drafting when the draft's top probability
@@ -151,6 +155,12 @@ int spec_debug_logits(spec_ctx *ctx, int32_t which, float *host_out, int64_t cap
 /* Tokens drafted by the last spec_draft for sequence b (valid until spec_accept): host int32, capacity cap;
  * *n receives their number.  Synchronises. */
 int spec_debug_drafted(spec_ctx *ctx, int32_t b, int32_t *host_out, int32_t cap, int32_t *n);
+
+/* Continue a generation that was loaded with spec_prefill*: the next step gets ordinal `step`
+ * (Philox counters) and sequence b counts its first prompt_lens[b] tokens as the prompt (forced
+ * acceptance is indexed by tokens generated after the prompt).  Parity tests use it to restart
+ * the library from a token sequence produced elsewhere. */
+int spec_debug_set_step(spec_ctx *ctx, int32_t step, const int32_t *prompt_lens);
 
 /* Fill both KV caches with seeded values in [-1, 1) for positions 0..len-1 and set every sequence
  * length to len+1 with token 0 as the last token (verify-only sweeps).  Synchronises. */

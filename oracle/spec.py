@@ -17,8 +17,9 @@ b = sequence index, g0 = tokens generated before the step):
       x_i  = argmax lq_i                      (T == 0)
            = inverse-CDF draw from softmax(lq_i / T) with u(s, i, DRAFT, b)
       conf_i = max softmax(lq_i / T_eff), T_eff = T if T > 0 else 1
-               (forced mode: conf_i = 1 - u(g0+i-1, FORCED), a synthetic
-                confidence that is monotone in the hidden acceptance draw)
+               (forced mode: conf_i = clamp(alpha(g) + (0.5 - u(g, FORCED)) / 2, 0, 1) with
+                g = g0+i-1, a synthetic confidence centred on the acceptance rate of the
+                position and monotone in the hidden acceptance draw)
       if tau > 0 and conf_i < tau: stop drafting, x_i is kept        [k = i]
   k = number of drafted tokens
   lp_1..lp_{k+1} = target logits for the tokens after t, t+x_1, ..., t+x_1..x_k
@@ -121,7 +122,9 @@ def speculative_step(
         res.drafted.append(x)
         cur.append(x)
         if forced:
-            conf = 1.0 - uniform(g0 + i - 1, 0, philox.FORCED, b)
+            g = g0 + i - 1
+            conf = _alpha_at(cfg.alpha, g) + (0.5 - uniform(g, 0, philox.FORCED, b)) * 0.5
+            conf = min(1.0, max(0.0, conf))
         else:
             conf = S.top_probability(lq, T_eff)
         res.conf.append(conf)

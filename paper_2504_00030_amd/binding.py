@@ -24,7 +24,7 @@ GT_EXPAND_A, GT_LITERAL, GT_SHORT_TERM = 0, 1, 2
 
 # every symbol include/spec.h and include/gammatune.h declare
 EXPORTS = [
-    "spec_init", "spec_prefill", "spec_draft", "spec_draft_batch", "spec_verify", "spec_accept",
+    "spec_init", "spec_prefill", "spec_prefill_ragged", "spec_debug_set_step", "spec_draft", "spec_draft_batch", "spec_verify", "spec_accept",
     "spec_set_forced_alpha", "spec_set_early_stop", "spec_read_tokens", "spec_debug_logits",
     "spec_debug_drafted", "spec_debug_fill_kv", "spec_debug_set_block_table", "spec_device_bytes", "spec_profile_kernel", "spec_profile_read", "spec_destroy",
     "spec_strerror", "spec_last_error", "spec_k_gemv", "spec_k_retile", "spec_k_philox", "spec_k_accept",
@@ -82,6 +82,8 @@ def load() -> C.CDLL:
     lib.spec_init.argtypes = [C.POINTER(SpecShape), C.POINTER(SpecWeights), C.POINTER(SpecShape), C.POINTER(SpecWeights),
                               C.POINTER(SpecConfig), C.POINTER(C.c_void_p)]
     lib.spec_prefill.argtypes = [C.c_void_p, i32p, C.c_int32]
+    lib.spec_prefill_ragged.argtypes = [C.c_void_p, i32p, C.c_int32, i32p]
+    lib.spec_debug_set_step.argtypes = [C.c_void_p, C.c_int32, i32p]
     lib.spec_draft.argtypes = [C.c_void_p, C.c_int32]
     lib.spec_draft_batch.argtypes = [C.c_void_p, i32p]
     lib.spec_verify.argtypes = [C.c_void_p, C.c_int32]
@@ -213,6 +215,21 @@ class SpecEngine:
     def prefill(self, tokens: np.ndarray):
         t = np.ascontiguousarray(tokens, dtype=np.int32).reshape(self.batch, -1)
         self._chk(self._lib.spec_prefill(self._ctx, t.ctypes.data_as(C.POINTER(C.c_int32)), t.shape[1]), "spec_prefill")
+
+    def prefill_ragged(self, seqs):
+        """seqs: list of token lists, one per sequence."""
+        lens = np.array([len(t) for t in seqs], dtype=np.int32)
+        n_max = int(lens.max())
+        t = np.zeros((self.batch, n_max), dtype=np.int32)
+        for b, q in enumerate(seqs):
+            t[b, : len(q)] = q
+        self._chk(self._lib.spec_prefill_ragged(self._ctx, t.ctypes.data_as(C.POINTER(C.c_int32)), n_max,
+                                                lens.ctypes.data_as(C.POINTER(C.c_int32))), "spec_prefill_ragged")
+
+    def set_step(self, step: int, prompt_lens):
+        p = np.ascontiguousarray(prompt_lens, dtype=np.int32)
+        self._chk(self._lib.spec_debug_set_step(self._ctx, int(step), p.ctypes.data_as(C.POINTER(C.c_int32))),
+                  "spec_debug_set_step")
 
     def draft(self, gamma):
         if np.isscalar(gamma):

@@ -36,7 +36,7 @@ struct ModelRT {
     bool mfma_ok = false;
     int Rmax = 0;
     float *x = nullptr, *xg = nullptr, *ssq = nullptr, *q = nullptr, *ao = nullptr, *act = nullptr;
-    uint16_t *xgb = nullptr, *aob = nullptr, *actb = nullptr;
+    uint16_t *xgb = nullptr, *qb = nullptr, *aob = nullptr, *actb = nullptr;
     int32_t *row_pos = nullptr, *row_seq = nullptr;
     std::vector<void *> kpool, vpool;
     int32_t *block_table = nullptr;
@@ -225,6 +225,7 @@ int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights
     TRY(dalloc(c, &m.xgb, R * d));
     TRY(dalloc(c, &m.ssq, R * SSQ_STRIDE));
     TRY(dalloc(c, &m.q, R * qd));
+    TRY(dalloc(c, &m.qb, R * qd));
     TRY(dalloc(c, &m.ao, R * qd));
     TRY(dalloc(c, &m.aob, R * qd));
     TRY(dalloc(c, &m.act, R * s.d_ffn));
@@ -391,14 +392,14 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             a.w0 = m.wq[l]; a.w1 = m.wk[l]; a.w2 = m.wv[l];
             a.n0 = qd; a.n1 = a.n2 = kvd;
             a.ssq_in = m.ssq; a.ssq_in_slots = slots;
-            a.y = m.q; a.nq = s.n_q_heads; a.nkv = s.n_kv_heads; a.hd = s.head_dim;
+            a.y = m.q; a.yb = m.qb; a.nq = s.n_q_heads; a.nkv = s.n_kv_heads; a.hd = s.head_dim;
             a.rope_cos = m.rope_cos; a.rope_sin = m.rope_sin; a.row_pos = m.row_pos; a.row_seq = m.row_seq;
             a.kv = kv_of(c, m, l); a.kv_dtype = s.dtype;
             TRY(launch_proj(c, m, a, EPI_QKV, tiled ? m.t_qkv[l] : nullptr, qd + 2 * kvd, nullptr, nullptr));
         }
         {
             AttnArgs t{};
-            t.q = m.q; t.kv = kv_of(c, m, l); t.kv_dtype = s.dtype; t.R = R; t.rps = plan.rps; t.nq = s.n_q_heads;
+            t.q = m.q; t.qb = c->cfg.gemv_path == SPEC_PATH_WAVEDOT ? nullptr : m.qb; t.kv = kv_of(c, m, l); t.kv_dtype = s.dtype; t.R = R; t.rps = plan.rps; t.nq = s.n_q_heads;
             t.row_pos = m.row_pos; t.row_seq = m.row_seq; t.chunk = ATT_CHUNK; t.n_chunks = m.n_chunks;
             t.scale = 1.0f / std::sqrt((float)s.head_dim);
             t.part_m = m.part_m; t.part_l = m.part_l; t.part_o = m.part_o; t.o = m.ao; t.ob = m.aob; t.active = active;
@@ -694,29 +695,55 @@ int spec_debug_set_block_table(spec_ctx *c, const int32_t *table) {
     return SPEC_OK;
 }
 
-int spec_prefill(spec_ctx *c, const int32_t *host_tokens, int32_t n) {
-    if (!c || !host_tokens) return fail(c, SPEC_EINVAL, "prefill: null pointer");
+int spec_prefill_ragged(spec_ctx *c, const int32_t *host_tokens, int32_t n_max, const int32_t *lens) {
+    if (!c || !host_tokens || !lens) return fail(c, SPEC_EINVAL, "prefill: null pointer");
     const int B = c->cfg.batch;
-    if (n < 1 || n + c->cfg.gamma_max + 1 > c->cfg.max_seq) return fail(c, SPEC_ECAP, "prefill: prompt does not fit max_seq");
-    for (int64_t i = 0; i < (int64_t)B * n; ++i)
-        if (host_tokens[i] < 0 || host_tokens[i] >= c->tgt.s.vocab) return fail(c, SPEC_EINVAL, "prefill: token id out of range");
+    if (n_max < 1 || n_max + c->cfg.gamma_max + 1 > c->cfg.max_seq) return fail(c, SPEC_ECAP, "prefill: prompt does not fit max_seq");
+    for (int b = 0; b < B; ++b) {
+        if (lens[b] < 1 || lens[b] > n_max) return fail(c, SPEC_EINVAL, "prefill: length outside 1..n_max");
+        for (int i = 0; i < lens[b]; ++i) {
+            const int32_t t = host_tokens[(size_t)b * n_max + i];
+            if (t < 0 || t >= c->tgt.s.vocab) return fail(c, SPEC_EINVAL, "prefill: token id out of range");
+        }
+    }
     HIPCHK(c, hipStreamSynchronize(c->stream));
     std::vector<int32_t> toks((size_t)B * c->cfg.max_seq, 0);
-    for (int b = 0; b < B; ++b) std::memcpy(&toks[(size_t)b * c->cfg.max_seq], host_tokens + (size_t)b * n, sizeof(int32_t) * n);
+    for (int b = 0; b < B; ++b)
+        std::memcpy(&toks[(size_t)b * c->cfg.max_seq], host_tokens + (size_t)b * n_max, sizeof(int32_t) * lens[b]);
     HIPCHK(c, hipMemcpy(c->st.tokens, toks.data(), toks.size() * sizeof(int32_t), hipMemcpyHostToDevice));
-    std::vector<int32_t> lens(B, n);
-    HIPCHK(c, hipMemcpy(c->st.len, lens.data(), sizeof(int32_t) * B, hipMemcpyHostToDevice));
-    HIPCHK(c, hipMemcpy(c->st.prompt_len, lens.data(), sizeof(int32_t) * B, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(c->st.len, lens, sizeof(int32_t) * B, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(c->st.prompt_len, lens, sizeof(int32_t) * B, hipMemcpyHostToDevice));
     const int32_t ctl[4] = {-1, 0, 0, 0};
     HIPCHK(c, hipMemcpy(c->st.ctl, ctl, sizeof(ctl), hipMemcpyHostToDevice));
     std::vector<uint32_t> z(B, 0);
     HIPCHK(c, hipMemcpy(c->ticket, z.data(), sizeof(uint32_t) * B, hipMemcpyHostToDevice));
-    c->h_len.assign(B, n);
-    TRY(prefill_model(c, c->tgt, n - 1));
-    TRY(prefill_model(c, c->drf, n - 1));
+    c->h_len.assign(lens, lens + B);
+    // every sequence ingests positions 0 .. n_max-2; rows past a shorter sequence's end hold padding
+    // tokens whose cache entries are rewritten by the decode steps before anything reads them
+    TRY(prefill_model(c, c->tgt, n_max - 1));
+    TRY(prefill_model(c, c->drf, n_max - 1));
     HIPCHK(c, hipStreamSynchronize(c->stream));
     c->prefilled = true;
     c->phase = 1;
+    return SPEC_OK;
+}
+
+int spec_prefill(spec_ctx *c, const int32_t *host_tokens, int32_t n) {
+    if (!c) return SPEC_EINVAL;
+    std::vector<int32_t> lens((size_t)c->cfg.batch, n);
+    return spec_prefill_ragged(c, host_tokens, n, lens.data());
+}
+
+int spec_debug_set_step(spec_ctx *c, int32_t step, const int32_t *prompt_lens) {
+    if (!c || !prompt_lens) return fail(c, SPEC_EINVAL, "set_step: null pointer");
+    if (c->phase != 1) return fail(c, SPEC_ESTATE, "set_step: expected after prefill or accept");
+    if (step < 0) return fail(c, SPEC_EINVAL, "set_step: negative step");
+    for (int b = 0; b < c->cfg.batch; ++b)
+        if (prompt_lens[b] < 1 || prompt_lens[b] > c->h_len[b]) return fail(c, SPEC_EINVAL, "set_step: bad prompt length");
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    const int32_t before = step - 1;  // the draft phase increments the ordinal first
+    HIPCHK(c, hipMemcpy(c->st.ctl, &before, sizeof(int32_t), hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(c->st.prompt_len, prompt_lens, sizeof(int32_t) * c->cfg.batch, hipMemcpyHostToDevice));
     return SPEC_OK;
 }
 

@@ -224,6 +224,9 @@ __global__ __launch_bounds__(256) void gemv_wavedot_k(const GemvArgs a) {
                                 float *q = a.y + (size_t)r * a.nq * a.hd + (size_t)hh * a.hd + j;
                                 q[0] = y1;
                                 q[half] = y2;
+                                uint16_t *qb = a.yb + (size_t)r * a.nq * a.hd + (size_t)hh * a.hd + j;
+                                qb[0] = f32_to_bf16(y1);
+                                qb[half] = f32_to_bf16(y2);
                             } else {
                                 const bool is_k = hh < a.nq + a.nkv;
                                 const int kvh = hh - a.nq - (is_k ? 0 : a.nkv);

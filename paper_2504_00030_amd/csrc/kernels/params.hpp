@@ -100,6 +100,7 @@ struct EmbedArgs {
 
 struct AttnArgs {
     const float *q;       // [R][nq*hd], rotated
+    const uint16_t *qb;   // bf16 copy (matrix-core kernel); null forces the plain kernel
     KVCache kv;
     int32_t kv_dtype;
     int32_t R, rps, nq;

@@ -147,7 +147,9 @@ __global__ __launch_bounds__(64) void draft_sample_k(const DraftSampleArgs a) {
         double conf;
         if (a.cfg.forced) {
             const uint32_t g = (uint32_t)(len - a.st.prompt_len[b] + a.j - 1);
-            conf = 1.0 - philox_uniform(a.cfg.seed, g, 0u, PURPOSE_FORCED, (uint32_t)b);
+            const double al = (double)a.cfg.alpha[min((int)g, a.cfg.n_alpha - 1)];
+            conf = al + (0.5 - philox_uniform(a.cfg.seed, g, 0u, PURPOSE_FORCED, (uint32_t)b)) * 0.5;
+            conf = fmin(1.0, fmax(0.0, conf));
         } else {
             conf = 1.0 / rs.S;  // top probability of softmax(l / T_eff)
         }

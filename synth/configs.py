@@ -64,7 +64,12 @@ _T4 = ModelShape(40, 5120, 40, 40, 128, 13824, 32000, 10000.0, 1e-5, "bf16")
 _TS = ModelShape(3, 256, 8, 2, 32, 512, 1024, 500000.0, 1e-5, "bf16")
 _DS = ModelShape(2, 128, 4, 4, 32, 256, 1024, 500000.0, 1e-5, "bf16")
 
+_TH = ModelShape(2, 512, 4, 1, 128, 512, 1024, 10000.0, 1e-5, "bf16")
+_DH = ModelShape(2, 128, 2, 2, 64, 256, 1024, 10000.0, 1e-5, "bf16")
+
 PAIRS: Dict[str, PairConfig] = {
+    # head sizes 128 (target, 4 query heads on 1 kv head) and 64 (draft)
+    "small-bf16-hd128": PairConfig("small-bf16-hd128", _TH, _DH, "independent", 80, 64, 16),
     # small bf16 pair with grouped-query attention: exercises the 16-bit kernels at test speed
     "small-bf16": PairConfig("small-bf16", _TS, _DS, "independent", 48, 64, 16),
     # tiny fp32 pair; draft = first two target layers with the tied embedding / head

@@ -1,9 +1,17 @@
-"""Shared helpers of the GPU parity tests: run the HIP library and the CPU oracle on the same seeded
-inputs and compare them decision by decision."""
+"""Shared helpers of the GPU parity tests.
+
+The HIP library and the CPU oracle are driven in lock-step on the same seeded inputs.  After every
+speculative step the library's integers (drafted tokens, drafted count, accepted count, emitted
+token, next gamma) and logits are compared with the oracle's.  A decision may differ only where the
+oracle reports a margin below the float tolerance; in that case the step is counted as "skipped",
+and the library is restarted from the ORACLE's token sequence (spec_prefill_ragged +
+spec_debug_set_step), so that later steps are compared on identical prefixes again.  Nothing the
+library computes ever flows into the oracle.
+"""
 from __future__ import annotations
 
-from dataclasses import dataclass
-from typing import List, Optional
+from dataclasses import dataclass, field
+from typing import List
 
 import numpy as np
 
@@ -26,16 +34,19 @@ def to_gpu(W):
 
 @dataclass
 class Compare:
-    steps_compared: int = 0
-    steps_total: int = 0
+    steps_total: int = 0          # (sequence, step) pairs compared
+    steps_clean: int = 0          # ... with every decision identical
+    resyncs: int = 0
     decisions_compared: int = 0
-    diverged_at: Optional[str] = None      # description of the sub-margin decision that ended the comparison
-    max_logit_err: float = 0.0             # relative to max |logit|
-    failures: List[str] = None
+    decisions_skipped: int = 0    # differed below the margin threshold
+    max_logit_err: float = 0.0    # relative to max |logit|
+    failures: List[str] = field(default_factory=list)
+    skipped: List[str] = field(default_factory=list)
+    trace: List[dict] = field(default_factory=list)
 
     @property
     def coverage(self) -> float:
-        return self.steps_compared / max(1, self.steps_total)
+        return self.steps_clean / max(1, self.steps_total)
 
 
 def make_controllers(kind: str, n: int, gamma_max: int, which: str):
@@ -46,106 +57,121 @@ def make_controllers(kind: str, n: int, gamma_max: int, which: str):
         if kind.startswith("fixed"):
             g = int(kind[5:])
             out.append(pk.FixedGamma(g) if which == "gpu" else ogt.FixedGamma(g))
+        elif which == "gpu":
+            out.append(pk.GammaTune(eta=0.25, delta=1, gamma_min=1, gamma_max=gamma_max, gamma0=4))
         else:
-            if which == "gpu":
-                out.append(pk.GammaTune(eta=0.25, delta=1, gamma_min=1, gamma_max=gamma_max, gamma0=4))
-            else:
-                out.append(ogt.Controller(ogt.Params(0.25, 1, 1, gamma_max), 4))
+            out.append(ogt.Controller(ogt.Params(0.25, 1, 1, gamma_max), 4))
     return out
 
 
-def compare_run(cfg: synth.PairConfig, Wt_np, Wd_np, prompts, n_generate, gpu_tokens, gpu_trace, *, controller: str,
-                temperature: float, seed: int, accept_mode: int = 0, alpha=None, tau: float = 0.0) -> Compare:
-    """Replay the run on the oracle, sequence by sequence, and compare with what the GPU produced."""
+def _compare_step(res: Compare, tag: str, r, gamma: int, gk: int, gA: int, gy: int, gdrafted, ql, pl, dtype: str,
+                  temperature: float) -> bool:
+    """Compare one sequence's step; returns True when every decision matched."""
+    scale = max(float(np.abs(r.p_logits).max()), float(np.abs(np.stack(r.q_logits)).max()))
+    eps = TOL[dtype] * scale
+    k_logit = 4.0 * eps
+    k_prob = 8.0 * eps / (temperature if temperature > 0 else 1.0)
+    # logits of rows whose inputs (the drafted tokens before them) agree
+    n_agree = 0
+    while n_agree < min(r.k, gk) and gdrafted[n_agree] == r.drafted[n_agree]:
+        n_agree += 1
+    for i in range(min(r.k, gk, n_agree + 1)):
+        err = float(np.abs(ql[i] - r.q_logits[i]).max()) / scale
+        res.max_logit_err = max(res.max_logit_err, err)
+        if err > TOL[dtype]:
+            res.failures.append(f"{tag}: draft logits row {i} err {err:.3e}")
+    for i in range(min(r.k, gk, n_agree) + 1):
+        err = float(np.abs(pl[i] - r.p_logits[i]).max()) / scale
+        res.max_logit_err = max(res.max_logit_err, err)
+        if err > TOL[dtype]:
+            res.failures.append(f"{tag}: target logits row {i} err {err:.3e}")
+    # decisions, in the oracle's order; the first difference ends the step
+    for dcs in r.decisions:
+        kappa = k_logit if dcs.scale == "logit" else k_prob
+        if dcs.kind == "draft":
+            got = gdrafted[dcs.row - 1] if dcs.row - 1 < len(gdrafted) else None
+        elif dcs.kind == "stop":
+            if dcs.row < gk:
+                got = 0
+            elif dcs.row == gk:
+                got = 1 if gk < gamma else dcs.value  # reaching gamma ends drafting either way
+            else:
+                got = None
+        elif dcs.kind == "accept":
+            got = int(gA >= dcs.row)
+        else:  # resid / bonus
+            got = gy
+        res.decisions_compared += 1
+        if got is None or got != dcs.value:
+            if dcs.margin > kappa:
+                res.failures.append(f"{tag}: {dcs.kind} row {dcs.row}: gpu {got} != oracle {dcs.value} "
+                                    f"(margin {dcs.margin:.3e} > {kappa:.3e})")
+            else:
+                res.decisions_skipped += 1
+                res.skipped.append(f"{tag}: {dcs.kind} row {dcs.row} margin {dcs.margin:.3e}")
+            return False
+    if (gk, gA, gy) != (r.k, r.accepted, r.y):
+        res.failures.append(f"{tag}: (k,A,y) gpu {(gk, gA, gy)} != oracle {(r.k, r.accepted, r.y)}")
+        return False
+    return True
+
+
+def run_lockstep(eng, cfg: synth.PairConfig, Wt_np, Wd_np, prompts, n_generate, *, controller: str,
+                 temperature: float, seed: int, accept_mode: int = 0, alpha=None, tau: float = 0.0,
+                 max_failures: int = 5) -> Compare:
     dtype = cfg.target.dtype
-    res = Compare(failures=[])
+    res = Compare()
     B = prompts.shape[0]
-    for b in range(B):
-        pair = ospec.TransformerPair(oshape(cfg.target), Wt_np, oshape(cfg.draft), Wd_np)
-        ctrl = make_controllers(controller, 1, cfg.gamma_max, "oracle")[0]
-        scfg = ospec.StepConfig(temperature=temperature, seed=seed, accept_mode=accept_mode, tau=tau,
-                                alpha=None if alpha is None else [float(a) for a in alpha])
-        toks = [int(t) for t in prompts[b]]
-        n0 = len(toks)
-        s = 0
-        alive = True
-        res.steps_total += len(gpu_trace)
-        for rec in gpu_trace:
-            if not alive:
-                break
-            gamma = int(ctrl.gamma)
-            if int(rec["gamma"][b]) != gamma:
-                res.failures.append(f"seq {b} step {s}: gamma {int(rec['gamma'][b])} != oracle {gamma}")
-                break
-            gmax_step = int(rec["gamma"].max())
-            r = ospec.speculative_step(pair.draft_next, pair.target_rows, toks, gamma, s, b, scfg, len(toks) - n0,
-                                       keep_logits=True)
-            scale = max(float(np.abs(r.p_logits).max()), float(np.abs(np.stack(r.q_logits)).max()))
-            eps = TOL[dtype] * scale
-            k_logit = 4.0 * eps
-            k_prob = 8.0 * eps / (temperature if temperature > 0 else 1.0)
-            gk, gA, gy = int(rec["k"][b]), int(rec["A"][b]), int(rec["y"][b])
-            # logits of the rows both sides computed from the same prefix
-            if "q_logits" in rec:
-                ql = rec["q_logits"][b]
-                gdrafted = rec.get("drafted")
-                for i in range(min(r.k, gk)):
-                    # row i is comparable when the drafted tokens before it agree
-                    err = float(np.abs(ql[i] - r.q_logits[i]).max()) / scale
-                    res.max_logit_err = max(res.max_logit_err, err)
-                    if err > TOL[dtype]:
-                        res.failures.append(f"seq {b} step {s}: draft logits row {i} err {err:.3e}")
-                    if gdrafted is not None and int(gdrafted[b][i]) != r.drafted[i]:
-                        break
-            # decisions, in the oracle's order
-            gpu_drafted = None if "drafted" not in rec else [int(t) for t in rec["drafted"][b][:gk]]
-            ok_so_far = True
-            for dcs in r.decisions:
-                kappa = k_logit if dcs.scale == "logit" else k_prob
-                if dcs.kind == "draft":
-                    if gpu_drafted is None:
-                        continue
-                    got = gpu_drafted[dcs.row - 1] if dcs.row - 1 < len(gpu_drafted) else None
-                elif dcs.kind == "stop":
-                    if dcs.row < gk:
-                        got = 0
-                    elif dcs.row == gk:
-                        got = 1 if gk < gamma else dcs.value  # reaching gamma ends drafting either way
-                    else:
-                        got = None
-                elif dcs.kind == "accept":
-                    got = int(gA >= dcs.row)
-                else:  # resid / bonus
-                    got = gy
-                res.decisions_compared += 1
-                if got is None or got != dcs.value:
-                    if dcs.margin > kappa:
-                        res.failures.append(
-                            f"seq {b} step {s}: {dcs.kind} row {dcs.row}: gpu {got} != oracle {dcs.value} "
-                            f"(margin {dcs.margin:.3e} > {kappa:.3e})")
-                    else:
-                        res.diverged_at = f"seq {b} step {s} {dcs.kind} row {dcs.row} margin {dcs.margin:.3e}"
-                    ok_so_far = False
-                    break
-            if not ok_so_far:
-                alive = False
-                break
-            if "p_logits" in rec and gk == r.k and (gpu_drafted is None or gpu_drafted == r.drafted):
-                pl = rec["p_logits"][b][: r.k + 1]
-                err = float(np.abs(pl - r.p_logits).max()) / scale
-                res.max_logit_err = max(res.max_logit_err, err)
-                if err > TOL[dtype]:
-                    res.failures.append(f"seq {b} step {s}: target logits err {err:.3e}")
-            if (gk, gA, gy) != (r.k, r.accepted, r.y):
-                res.failures.append(f"seq {b} step {s}: (k,A,y) gpu {(gk, gA, gy)} != oracle {(r.k, r.accepted, r.y)}")
-                break
-            toks.extend(r.emitted)
-            ctrl.update(r.accepted, r.k)
-            s += 1
-            res.steps_compared += 1
-        if alive and not res.failures:
-            want = toks[: n0 + n_generate]
-            got = [int(t) for t in gpu_tokens[b][: len(want)]]
-            if got != want[: len(got)]:
+    n0 = prompts.shape[1]
+    pairs = [ospec.TransformerPair(oshape(cfg.target), Wt_np, oshape(cfg.draft), Wd_np) for _ in range(B)]
+    octl = make_controllers(controller, B, cfg.gamma_max, "oracle")
+    gctl = make_controllers(controller, B, cfg.gamma_max, "gpu")
+    scfg = ospec.StepConfig(temperature=temperature, seed=seed, accept_mode=accept_mode, tau=tau,
+                            alpha=None if alpha is None else [float(a) for a in alpha])
+    toks = [[int(t) for t in prompts[b]] for b in range(B)]
+    eng.prefill(prompts)
+    s = 0
+    while min(len(t) for t in toks) - n0 < n_generate and len(res.failures) < max_failures:
+        gammas = np.array([c.gamma for c in octl], dtype=np.int32)
+        ggam = [c.gamma for c in gctl]
+        if ggam != gammas.tolist():
+            res.failures.append(f"step {s}: gamma gpu {ggam} != oracle {gammas.tolist()}")
+            break
+        eng.draft(gammas if B > 1 else int(gammas[0]))
+        eng.verify(int(gammas.max()))
+        q = eng.debug_logits(0)
+        drafted = [eng.debug_drafted(b) for b in range(B)]
+        A, y, k = eng.accept()
+        p = eng.debug_logits(1)
+        res.trace.append({"gamma": gammas.copy(), "A": A.copy(), "y": y.copy(), "k": k.copy()})
+        resync = False
+        for b in range(B):
+            r = ospec.speculative_step(pairs[b].draft_next, pairs[b].target_rows, toks[b], int(gammas[b]), s, b, scfg,
+                                       len(toks[b]) - n0, keep_logits=True)
+            res.steps_total += 1
+            ok = _compare_step(res, f"seq {b} step {s}", r, int(gammas[b]), int(k[b]), int(A[b]), int(y[b]), drafted[b],
+                               q[b], p[b], dtype, temperature)
+            toks[b].extend(r.emitted)
+            octl[b].update(r.accepted, r.k)
+            if ok:
+                res.steps_clean += 1
+                gctl[b].update(int(A[b]), int(k[b]))
+            else:
+                resync = True
+        s += 1
+        if resync:
+            # restart the library from the oracle's sequences and controller states
+            res.resyncs += 1
+            eng.prefill_ragged(toks)
+            eng.set_step(s, [n0] * B)
+            for b in range(B):
+                if hasattr(gctl[b], "state"):
+                    gctl[b].state.gamma_bar = octl[b].gamma_bar
+                    gctl[b].state.gamma = octl[b].gamma
+    if not res.failures:
+        for b in range(B):
+            got = eng.read_tokens(b).tolist()
+            if got != toks[b]:
                 res.failures.append(f"seq {b}: final tokens differ")
+    res.tokens = [t[: n0 + n_generate] for t in toks]
     return res
