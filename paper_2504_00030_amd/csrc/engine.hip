@@ -150,9 +150,9 @@ int check_shape(spec_ctx *c, const spec_shape &s, const char *who) {
     if (s.d_model % vec || s.d_ffn % vec || (s.n_q_heads * s.head_dim) % vec) return bad("row length not 16-byte aligned");
     if (s.d_ffn % 2) return bad("d_ffn must be even");
     if (!(s.rms_eps > 0.f) || !(s.rope_theta > 0.f)) return bad("bad rms_eps / rope_theta");
-    {
-        const int rpw = gemv_wavedot_pick_rpw(EPI_RESID, s.d_model, s.d_ffn, 1, s.dtype);
-        if (((s.d_model + rpw - 1) / rpw + 3) / 4 > SSQ_STRIDE) return bad("d_model too large");
+    for (int R = 1; R <= 4; ++R) {
+        const int cols = gemv_wavedot_tile_cols(EPI_RESID, s.d_model, s.d_ffn, R, s.dtype);
+        if ((s.d_model + cols - 1) / cols > SSQ_STRIDE) return bad("d_model too large");
     }
     return SPEC_OK;
 }
@@ -334,21 +334,24 @@ int launch_proj(spec_ctx *c, ModelRT &m, GemvArgs a, int epi, const void *tiled,
     ProfScope ps_(c, m, epi);
     if (use_mfma(c, m, a.R)) {
         a.w0 = tiled; a.w1 = a.w2 = nullptr;
-        const int ng = gemv_mfma_groups_per_wg(epi, Ntot);
+        const int ng = gemv_mfma_groups_per_wg(epi, Ntot, a.K, a.R, 0);
         const int nb = (Ntot / 16 + ng - 1) / ng;
         if (epi == EPI_LOGITS) a.n_tiles = nb;
         if (blocks) *blocks = nb;
         if (tile_cols) *tile_cols = 16 * ng;
         if (epi == EPI_LOGITS && nb > m.tiles_cap) return fail(c, SPEC_EINVAL, "logits tiling exceeds the partial buffers");
         if (epi == EPI_RESID && nb > SSQ_STRIDE) return fail(c, SPEC_EINVAL, "too many statistics slots");
-        HIPCHK(c, launch_gemv_mfma(a, epi, c->stream));
+        HIPCHK(c, launch_gemv_mfma(a, epi, 0, c->stream));
         return SPEC_OK;
     }
-    a.rpw = gemv_wavedot_pick_rpw(epi, Ntot, a.K, a.R, m.s.dtype);
-    const int nb = ((Ntot + a.rpw - 1) / a.rpw + 3) / 4;
+    const bool split = gemv_wavedot_uses_split(epi, Ntot, a.K, a.R, m.s.dtype);
+    const int cols = gemv_wavedot_tile_cols(epi, Ntot, a.K, a.R, m.s.dtype);
+    a.rpw = split ? 0 : gemv_wavedot_pick_rpw(epi, Ntot, a.K, a.R, m.s.dtype);
+    const int nb = (Ntot + cols - 1) / cols;
     if (epi == EPI_LOGITS) a.n_tiles = nb;
     if (blocks) *blocks = nb;
-    if (tile_cols) *tile_cols = 4 * a.rpw;
+    if (tile_cols) *tile_cols = cols;
+    if (epi == EPI_RESID && nb > SSQ_STRIDE) return fail(c, SPEC_EINVAL, "too many statistics slots");
     if (epi == EPI_LOGITS && nb > m.tiles_cap) return fail(c, SPEC_EINVAL, "logits tiling exceeds the partial buffers");
     HIPCHK(c, launch_gemv_wavedot(a, epi, m.s.dtype, c->stream));
     return SPEC_OK;
@@ -934,12 +937,12 @@ int spec_k_gemv(const void *w, int32_t dtype, int32_t N, int32_t K, const float 
         int rc = SPEC_OK;
         if (launch_cast_to_bf16(x, xb, (int64_t)R * K, st) != hipSuccess) rc = SPEC_EHIP;
         a.xb = xb;
-        if (rc == SPEC_OK && launch_gemv_mfma(a, EPI_PLAIN, st) != hipSuccess) rc = SPEC_EHIP;
+        if (rc == SPEC_OK && launch_gemv_mfma(a, EPI_PLAIN, 0, st) != hipSuccess) rc = SPEC_EHIP;
         if (hipStreamSynchronize(st) != hipSuccess) rc = SPEC_EHIP;
         (void)hipFree(xb);
         return rc;
     }
-    a.rpw = gemv_wavedot_pick_rpw(EPI_PLAIN, N, K, R, dtype);
+    a.rpw = gemv_wavedot_uses_split(EPI_PLAIN, N, K, R, dtype) ? 0 : gemv_wavedot_pick_rpw(EPI_PLAIN, N, K, R, dtype);
     if (launch_gemv_wavedot(a, EPI_PLAIN, dtype, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return SPEC_EHIP;
     return SPEC_OK;
 }

@@ -7,6 +7,7 @@
 // This is the draft model's decode step and the small-gamma verify pass of a speculative
 // step (Background section: T_draft per drafted token, T_target per verification).
 #include "common.hpp"
+#include "epilogue.hpp"
 #include "kv.hpp"
 #include "params.hpp"
 
@@ -308,6 +309,138 @@ __global__ __launch_bounds__(256) void gemv_wavedot_k(const GemvArgs a) {
     }
 }
 
+// ---- split-K variant for one or two rows (draft decode) ---------------------------------------------
+// A workgroup of NW waves owns TW packed weight rows.  The waves form KS k-slices x (NW / KS) row
+// slots; a wave keeps its slice of the x rows in registers (read once), streams its slice of each of
+// its weight rows with one 16-byte load per lane and step, and leaves one partial dot product per
+// (row, slice) in LDS.  The slices are summed in slice order and the shared tile epilogue runs.
+constexpr int WS_STEPS = 4;  // k-steps (of 64 lanes x 16 bytes) a wave can hold of each x row
+
+template <typename WT, int RC, int EPI, int TW, int NW>
+__global__ __launch_bounds__(NW * 64) void gemv_wsplit_k(const GemvArgs a, const int KS) {
+    if (a.active != nullptr && *a.active == 0) return;
+    constexpr int NT = NW * 64;
+    constexpr int VEC = WVec<WT>::VEC;
+    constexpr int STEP = 64 * VEC;
+    constexpr int NR = TW >= 16 ? 8 : 4;  // rows streamed together by a wave
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int Ntot = total_rows(a, EPI);
+    const int K = a.K;
+    const int RS = NW / KS;              // row slots
+    const int wk = wave % KS, wr = wave / KS;
+    const int RPS = TW / RS;             // rows per slot (host guarantees TW % RS == 0)
+    const int steps = (K + STEP - 1) / STEP;
+    const int SPS = (steps + KS - 1) / KS;  // steps per slice, <= WS_STEPS
+    const int k0 = wk * SPS * STEP + lane * VEC;
+
+    __shared__ float part[TW * NW * RC];   // [row][slice][rc], slices < KS used
+    __shared__ float tile[RC * (TW + 1)];
+    __shared__ float s_scale[RC];
+
+    RowScales<NT> rs;
+    rs.begin(a, RC);
+
+    // this wave's slice of the x rows
+    float xs[RC][WS_STEPS][VEC];
+#pragma unroll
+    for (int rc = 0; rc < RC; ++rc) {
+        const float *xr = a.x + (size_t)(rc * a.x_mul + a.x_add) * K;
+#pragma unroll
+        for (int st = 0; st < WS_STEPS; ++st) {
+            const int k = k0 + st * STEP;
+            const bool in = st < SPS && k < K;
+#pragma unroll
+            for (int q = 0; q < VEC / 4; ++q) {
+                const float4 v = in ? *reinterpret_cast<const float4 *>(xr + k + 4 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
+                xs[rc][st][4 * q] = v.x; xs[rc][st][4 * q + 1] = v.y; xs[rc][st][4 * q + 2] = v.z; xs[rc][st][4 * q + 3] = v.w;
+            }
+        }
+    }
+
+    const int p_base = blockIdx.x * TW + wr * RPS;
+    for (int lr0 = 0; lr0 < RPS; lr0 += NR) {
+        const WT *wp[NR];
+#pragma unroll
+        for (int nr = 0; nr < NR; ++nr) wp[nr] = packed_row<WT, EPI>(a, min(p_base + min(lr0 + nr, RPS - 1), Ntot - 1), TW);
+        float acc[NR][RC];
+#pragma unroll
+        for (int nr = 0; nr < NR; ++nr)
+#pragma unroll
+            for (int rc = 0; rc < RC; ++rc) acc[nr][rc] = 0.f;
+#pragma unroll
+        for (int st = 0; st < WS_STEPS; ++st) {
+            const int k = k0 + st * STEP;
+            if (st < SPS && k < K) {
+                float wv[NR][VEC];
+#pragma unroll
+                for (int nr = 0; nr < NR; ++nr) WVec<WT>::load(wp[nr] + k, wv[nr]);
+#pragma unroll
+                for (int nr = 0; nr < NR; ++nr)
+#pragma unroll
+                    for (int rc = 0; rc < RC; ++rc)
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) acc[nr][rc] = fmaf(wv[nr][e], xs[rc][st][e], acc[nr][rc]);
+            }
+        }
+#pragma unroll
+        for (int nr = 0; nr < NR; ++nr)
+#pragma unroll
+            for (int rc = 0; rc < RC; ++rc) {
+                const float v = wave_sum(acc[nr][rc]);
+                if (lane == 0 && lr0 + nr < RPS) part[((wr * RPS + lr0 + nr) * NW + wk) * RC + rc] = v;
+            }
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < TW * RC; idx += NT) {
+        const int row = idx / RC, rc = idx % RC;
+        float s = 0.f;
+        for (int w = 0; w < KS; ++w) s += part[(row * NW + w) * RC + rc];
+        tile[rc * (TW + 1) + row] = s;
+    }
+    rs.finish(a, s_scale, RC);  // ends with a barrier
+    epilogue_tile<EPI, TW, NT>(a, tile, TW + 1, s_scale, RC, blockIdx.x, Ntot);
+}
+
+struct WsplitCfg { int tw, ks; bool ok; };
+
+// Tile width and k-slices for the split-K kernel (NW = 8 waves), or ok = false when the shape does not fit.
+static WsplitCfg wsplit_cfg(int epi, int Ntot, int K, int R, int w_dtype) {
+    WsplitCfg c{16, 8, false};
+    if (R > 2) return c;
+    const int step = 64 * (w_dtype == DT_BF16 ? 8 : 4);
+    const int steps = (K + step - 1) / step;
+    int ks = 8;
+    while (ks > 1 && ks > steps) ks >>= 1;     // never more slices than steps
+    if ((steps + ks - 1) / ks > WS_STEPS) return c;
+    int tw = 16;
+    if (epi == EPI_LOGITS) tw = 64;
+    else if (Ntot / 16 < 256) tw = 8;
+    const int rs = 8 / ks;
+    if (tw < rs) tw = rs < 8 ? 8 : rs;
+    if (tw % rs) return c;
+    c.tw = tw; c.ks = ks; c.ok = true;
+    return c;
+}
+
+bool gemv_wavedot_uses_split(int epi, int Ntot, int K, int R, int w_dtype) {
+    return wsplit_cfg(epi, Ntot, K, R, w_dtype).ok;
+}
+
+int gemv_wavedot_tile_cols(int epi, int Ntot, int K, int R, int w_dtype) {
+    const WsplitCfg c = wsplit_cfg(epi, Ntot, K, R, w_dtype);
+    if (c.ok) return c.tw;
+    return 4 * gemv_wavedot_pick_rpw(epi, Ntot, K, R, w_dtype);
+}
+
+template <typename WT, int RC, int EPI>
+static hipError_t launch_wsplit(const GemvArgs &a, int Ntot, const WsplitCfg &c, hipStream_t s) {
+    const int blocks = (Ntot + c.tw - 1) / c.tw;
+    if (c.tw == 8) hipLaunchKernelGGL((gemv_wsplit_k<WT, RC, EPI, 8, 8>), dim3(blocks), dim3(512), 0, s, a, c.ks);
+    else if (c.tw == 16) hipLaunchKernelGGL((gemv_wsplit_k<WT, RC, EPI, 16, 8>), dim3(blocks), dim3(512), 0, s, a, c.ks);
+    else hipLaunchKernelGGL((gemv_wsplit_k<WT, RC, EPI, 64, 8>), dim3(blocks), dim3(512), 0, s, a, c.ks);
+    return hipGetLastError();
+}
+
 // rows per wave: enough waves to fill the chip, long enough streams per wave
 int gemv_wavedot_pick_rpw(int epi, int Ntot, int K, int R, int w_dtype) {
     (void)K; (void)w_dtype;
@@ -333,6 +466,11 @@ static hipError_t launch_nr(const GemvArgs &a, int Ntot, hipStream_t s) {
 
 template <typename WT, int EPI>
 static hipError_t launch_rc(const GemvArgs &a, int Ntot, hipStream_t s) {
+    const WsplitCfg c = wsplit_cfg(EPI, Ntot, a.K, a.R, sizeof(WT) == 2 ? DT_BF16 : DT_F32);
+    if (c.ok && a.rpw == 0) {
+        if (a.R == 1) return launch_wsplit<WT, 1, EPI>(a, Ntot, c, s);
+        return launch_wsplit<WT, 2, EPI>(a, Ntot, c, s);
+    }
     if (a.R == 1) return launch_nr<WT, 1, EPI>(a, Ntot, s);
     if (a.R == 2) return launch_nr<WT, 2, EPI>(a, Ntot, s);
     return launch_nr<WT, 4, EPI>(a, Ntot, s);
@@ -357,8 +495,12 @@ static hipError_t launch_epi(const GemvArgs &a, int epi, hipStream_t s) {
 //   K % VEC == 0, rows 16-byte aligned, rpw even, rpw % 4 == 0 or rpw == 2,
 //   SWIGLU: n0 % (NR/2) == 0; QKV: (hd/2) % (NR/2) == 0; LOGITS: rpw * RC <= 64;
 //   RESID: R <= 128, gridDim.x <= ssq_stride; ssq_in_slots <= 512.
+// rpw == 0 selects the split-K kernel (shapes for which gemv_wavedot_uses_split() is true).
 hipError_t launch_gemv_wavedot(const GemvArgs &a, int epi, int w_dtype, hipStream_t s) {
-    if (a.R < 1 || a.rpw < 2) return hipErrorInvalidValue;
+    if (a.R < 1 || (a.rpw != 0 && a.rpw < 2)) return hipErrorInvalidValue;
+    if (a.rpw == 0 && !gemv_wavedot_uses_split(epi, epi == EPI_QKV ? (a.nq + 2 * a.nkv) * a.hd : (epi == EPI_SWIGLU ? 2 * a.n0 : a.n0),
+                                               a.K, a.R, w_dtype))
+        return hipErrorInvalidValue;
     if (w_dtype == DT_BF16) return launch_epi<bf16_t>(a, epi, s);
     return launch_epi<float>(a, epi, s);
 }
