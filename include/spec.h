@@ -193,6 +193,12 @@ const char *spec_last_error(const spec_ctx *ctx);
 int spec_k_gemv(const void *w, int32_t dtype, int32_t N, int32_t K, const float *x, int32_t R,
                 float *y, int32_t path, void *stream);
 
+/* The matrix-core kernel alone, asynchronous, no allocation: w_tiled from spec_k_retile, x_bf16 device bf16
+ * [R][K], y device fp32 [R][N].  cfg = 0 picks the launch shape from (N, K, R); cfg = 100 * groups + waves forces
+ * one of (1,16) (1,8) (1,4) (2,8) (2,4) (4,4) when groups * waves * ceil16(R)/16 <= 32 (kernel tuning). */
+int spec_k_gemv_tiled(const void *w_tiled, int32_t N, int32_t K, const void *x_bf16, int32_t R, float *y, int32_t cfg,
+                      void *stream);
+
 /* Re-tile a row-major bf16 matrix [N][K] into the streaming layout of the matrix-core kernel:
  * 16-row groups, each group a run of 1 KiB tiles (16 rows x 32 k) stored lane-major.  out: device,
  * N*K*2 bytes. */

@@ -27,7 +27,7 @@ EXPORTS = [
     "spec_init", "spec_prefill", "spec_prefill_ragged", "spec_debug_set_step", "spec_draft", "spec_draft_batch", "spec_verify", "spec_accept",
     "spec_set_forced_alpha", "spec_set_early_stop", "spec_read_tokens", "spec_debug_logits",
     "spec_debug_drafted", "spec_debug_fill_kv", "spec_debug_set_block_table", "spec_device_bytes", "spec_profile_kernel", "spec_profile_read", "spec_destroy",
-    "spec_strerror", "spec_last_error", "spec_k_gemv", "spec_k_retile", "spec_k_philox", "spec_k_accept",
+    "spec_strerror", "spec_last_error", "spec_k_gemv", "spec_k_gemv_tiled", "spec_k_retile", "spec_k_philox", "spec_k_accept",
     "gammatune_init", "gammatune_update",
 ]
 
@@ -107,6 +107,7 @@ def load() -> C.CDLL:
     lib.spec_last_error.restype = C.c_char_p
     lib.spec_k_gemv.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
                                 C.c_void_p]
+    lib.spec_k_gemv_tiled.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
     lib.spec_k_retile.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.spec_k_philox.argtypes = [C.c_uint64, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
     lib.spec_k_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_uint64,
@@ -337,6 +338,12 @@ def k_gemv(w, x, y, path=PATH_WAVEDOT, stream: int = 0, N=None, K=None):
     rc = load().spec_k_gemv(w.data_ptr(), dtype, N, K, x.data_ptr(), x.shape[0], y.data_ptr(), path, stream)
     if rc != 0:
         raise SpecError(rc, "spec_k_gemv")
+
+
+def k_gemv_tiled(w_tiled, N, K, x_bf16, y, cfg: int = 0, stream: int = 0):
+    rc = load().spec_k_gemv_tiled(w_tiled.data_ptr(), N, K, x_bf16.data_ptr(), x_bf16.shape[0], y.data_ptr(), cfg, stream)
+    if rc != 0:
+        raise SpecError(rc, "spec_k_gemv_tiled")
 
 
 def k_retile(w, out, stream: int = 0):

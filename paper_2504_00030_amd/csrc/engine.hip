@@ -320,7 +320,7 @@ struct ProfScope {
     }
 };
 
-constexpr int MFMA_MIN_ROWS = 3;  // fewer rows run as wave dot products on fp32 activations
+constexpr int MFMA_MIN_ROWS = 1;  // measured: the matrix-core kernel streams faster than wave dot products at every row count
 
 bool use_mfma(const spec_ctx *c, const ModelRT &m, int R) {
     if (!m.mfma_ok) return false;
@@ -944,6 +944,22 @@ int spec_k_gemv(const void *w, int32_t dtype, int32_t N, int32_t K, const float 
     }
     a.rpw = gemv_wavedot_uses_split(EPI_PLAIN, N, K, R, dtype) ? 0 : gemv_wavedot_pick_rpw(EPI_PLAIN, N, K, R, dtype);
     if (launch_gemv_wavedot(a, EPI_PLAIN, dtype, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return SPEC_EHIP;
+    return SPEC_OK;
+}
+
+int spec_k_gemv_tiled(const void *w_tiled, int32_t N, int32_t K, const void *x_bf16, int32_t R, float *y, int32_t cfg,
+                      void *stream) {
+    if (!w_tiled || !x_bf16 || !y || N < 16 || K < 32 || N % 16 || K % 32 || R < 1 || R > 128) return SPEC_EINVAL;
+    if (cfg != 0) {
+        const int ng = cfg / 100, nw = cfg % 100;
+        const int mb = R <= 16 ? 1 : (R <= 32 ? 2 : (R <= 64 ? 4 : 8));
+        const bool known = (ng == 1 && (nw == 16 || nw == 8 || nw == 4)) || (ng == 2 && (nw == 8 || nw == 4)) ||
+                           (ng == 4 && nw == 4);
+        if (!known || ng * nw * mb > 32) return SPEC_EINVAL;
+    }
+    GemvArgs a{};
+    a.w0 = w_tiled; a.n0 = N; a.K = K; a.R = R; a.xb = reinterpret_cast<const uint16_t *>(x_bf16); a.x_mul = 1; a.y = y;
+    if (launch_gemv_mfma(a, EPI_PLAIN, cfg, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return SPEC_EHIP;
     return SPEC_OK;
 }
 

@@ -132,13 +132,13 @@ struct MfmaCfg { int ng, nw; };
 
 static MfmaCfg pick_cfg(int n_groups, int KT, int MB, int forced) {
     if (forced > 0) return MfmaCfg{forced / 100, forced % 100};
-    const int budget = 32 / MB;
+    // measured on MI355X (plain epilogue, weights rotated through > 2 GiB): one group per workgroup with
+    // eight K slices streams fastest while x is a single 16-row block; with more row blocks the x operand
+    // traffic grows and tall matrices do better with more groups per workgroup (x fragments reused)
     MfmaCfg c;
-    if (n_groups >= 4096 && budget >= 16) c = MfmaCfg{4, 4};
-    else if (n_groups >= 1024 && budget >= 16) c = MfmaCfg{2, 8};
-    else if (n_groups >= 1024 && budget >= 8) c = MfmaCfg{2, 4};
-    else if (budget >= 16) c = MfmaCfg{1, 16};
-    else if (budget >= 8) c = MfmaCfg{1, 8};
+    if (MB == 1) c = MfmaCfg{1, 8};
+    else if (MB == 2) c = n_groups >= 1024 ? MfmaCfg{4, 4} : (n_groups >= 320 ? MfmaCfg{2, 4} : MfmaCfg{1, 8});
+    else if (MB == 4) c = n_groups >= 1024 ? MfmaCfg{2, 4} : MfmaCfg{1, 8};
     else c = MfmaCfg{1, 4};
     while (c.nw > 4 && KT / c.nw < 2) c.nw /= 2;  // keep at least two k-tiles per wave
     return c;

@@ -314,10 +314,11 @@ __global__ __launch_bounds__(256) void gemv_wavedot_k(const GemvArgs a) {
 // slots; a wave keeps its slice of the x rows in registers (read once), streams its slice of each of
 // its weight rows with one 16-byte load per lane and step, and leaves one partial dot product per
 // (row, slice) in LDS.  The slices are summed in slice order and the shared tile epilogue runs.
+constexpr int WS_MAX_WGS = 512;
 constexpr int WS_STEPS = 4;  // k-steps (of 64 lanes x 16 bytes) a wave can hold of each x row
 
 template <typename WT, int RC, int EPI, int TW, int NW>
-__global__ __launch_bounds__(NW * 64) void gemv_wsplit_k(const GemvArgs a, const int KS) {
+__global__ __launch_bounds__(NW * 64) void gemv_wsplit_k(const GemvArgs a, const int KS, const int n_tiles_total) {
     if (a.active != nullptr && *a.active == 0) return;
     constexpr int NT = NW * 64;
     constexpr int VEC = WVec<WT>::VEC;
@@ -357,7 +358,9 @@ __global__ __launch_bounds__(NW * 64) void gemv_wsplit_k(const GemvArgs a, const
         }
     }
 
-    const int p_base = blockIdx.x * TW + wr * RPS;
+  // a workgroup walks tiles blockIdx.x, blockIdx.x + gridDim.x, ...; its x slices stay in registers
+  for (int t = blockIdx.x; t < n_tiles_total; t += gridDim.x) {
+    const int p_base = t * TW + wr * RPS;
     for (int lr0 = 0; lr0 < RPS; lr0 += NR) {
         const WT *wp[NR];
 #pragma unroll
@@ -397,8 +400,11 @@ __global__ __launch_bounds__(NW * 64) void gemv_wsplit_k(const GemvArgs a, const
         for (int w = 0; w < KS; ++w) s += part[(row * NW + w) * RC + rc];
         tile[rc * (TW + 1) + row] = s;
     }
-    rs.finish(a, s_scale, RC);  // ends with a barrier
-    epilogue_tile<EPI, TW, NT>(a, tile, TW + 1, s_scale, RC, blockIdx.x, Ntot);
+    if (t == (int)blockIdx.x) rs.finish(a, s_scale, RC);  // ends with a barrier
+    else __syncthreads();
+    epilogue_tile<EPI, TW, NT>(a, tile, TW + 1, s_scale, RC, t, Ntot);
+    __syncthreads();  // part / tile are reused by the next tile
+  }
 }
 
 struct WsplitCfg { int tw, ks; bool ok; };
@@ -434,10 +440,12 @@ int gemv_wavedot_tile_cols(int epi, int Ntot, int K, int R, int w_dtype) {
 
 template <typename WT, int RC, int EPI>
 static hipError_t launch_wsplit(const GemvArgs &a, int Ntot, const WsplitCfg &c, hipStream_t s) {
-    const int blocks = (Ntot + c.tw - 1) / c.tw;
-    if (c.tw == 8) hipLaunchKernelGGL((gemv_wsplit_k<WT, RC, EPI, 8, 8>), dim3(blocks), dim3(512), 0, s, a, c.ks);
-    else if (c.tw == 16) hipLaunchKernelGGL((gemv_wsplit_k<WT, RC, EPI, 16, 8>), dim3(blocks), dim3(512), 0, s, a, c.ks);
-    else hipLaunchKernelGGL((gemv_wsplit_k<WT, RC, EPI, 64, 8>), dim3(blocks), dim3(512), 0, s, a, c.ks);
+    const int tiles = (Ntot + c.tw - 1) / c.tw;
+    // at most WS_MAX_WGS workgroups (two per CU): beyond that a workgroup loops over several tiles
+    const int blocks = tiles < WS_MAX_WGS ? tiles : WS_MAX_WGS;
+    if (c.tw == 8) hipLaunchKernelGGL((gemv_wsplit_k<WT, RC, EPI, 8, 8>), dim3(blocks), dim3(512), 0, s, a, c.ks, tiles);
+    else if (c.tw == 16) hipLaunchKernelGGL((gemv_wsplit_k<WT, RC, EPI, 16, 8>), dim3(blocks), dim3(512), 0, s, a, c.ks, tiles);
+    else hipLaunchKernelGGL((gemv_wsplit_k<WT, RC, EPI, 64, 8>), dim3(blocks), dim3(512), 0, s, a, c.ks, tiles);
     return hipGetLastError();
 }
 
