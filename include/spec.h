@@ -162,6 +162,14 @@ int spec_debug_drafted(spec_ctx *ctx, int32_t b, int32_t *host_out, int32_t cap,
  * the library from a token sequence produced elsewhere. */
 int spec_debug_set_step(spec_ctx *ctx, int32_t step, const int32_t *prompt_lens);
 
+/* Copy the first `bytes` bytes of an internal buffer of the draft (model 0) or target (model 1) to host
+ * memory, as left by the last forward pass: which = 0 residual stream, 1 rotated queries, 2 attention
+ * output, 3 SwiGLU output, 4 normed-input copy, 5 sum-of-squares slots, 6/7/8 attention chunk partials
+ * (max, sum, vectors), 9..12 the bf16 copies of attention output, normed input, SwiGLU output and queries,
+ * 100 + l / 200 + l the K / V page pool of layer l.  The caller must know the sizes;
+ * debugging aid only.  Synchronises. */
+int spec_debug_read(spec_ctx *ctx, int32_t model, int32_t which, void *host_out, int64_t bytes);
+
 /* Fill both KV caches with seeded values in [-1, 1) for positions 0..len-1 and set every sequence
  * length to len+1 with token 0 as the last token (verify-only sweeps).  Synchronises. */
 int spec_debug_fill_kv(spec_ctx *ctx, int32_t len, uint64_t seed);

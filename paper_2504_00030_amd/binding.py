@@ -26,7 +26,7 @@ GT_EXPAND_A, GT_LITERAL, GT_SHORT_TERM = 0, 1, 2
 EXPORTS = [
     "spec_init", "spec_prefill", "spec_prefill_ragged", "spec_debug_set_step", "spec_draft", "spec_draft_batch", "spec_verify", "spec_accept",
     "spec_set_forced_alpha", "spec_set_early_stop", "spec_read_tokens", "spec_debug_logits",
-    "spec_debug_drafted", "spec_debug_fill_kv", "spec_debug_set_block_table", "spec_device_bytes", "spec_profile_kernel", "spec_profile_read", "spec_destroy",
+    "spec_debug_drafted", "spec_debug_read", "spec_debug_fill_kv", "spec_debug_set_block_table", "spec_device_bytes", "spec_profile_kernel", "spec_profile_read", "spec_destroy",
     "spec_strerror", "spec_last_error", "spec_k_gemv", "spec_k_gemv_tiled", "spec_k_retile", "spec_k_philox", "spec_k_accept",
     "gammatune_init", "gammatune_update",
 ]
@@ -93,6 +93,7 @@ def load() -> C.CDLL:
     lib.spec_read_tokens.argtypes = [C.c_void_p, C.c_int32, i32p, C.c_int32, i32p]
     lib.spec_debug_logits.argtypes = [C.c_void_p, C.c_int32, f32p, C.c_int64, i32p]
     lib.spec_debug_drafted.argtypes = [C.c_void_p, C.c_int32, i32p, C.c_int32, i32p]
+    lib.spec_debug_read.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int64]
     lib.spec_debug_fill_kv.argtypes = [C.c_void_p, C.c_int32, C.c_uint64]
     lib.spec_debug_set_block_table.argtypes = [C.c_void_p, i32p]
     lib.spec_profile_kernel.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
@@ -284,6 +285,12 @@ class SpecEngine:
         self._chk(self._lib.spec_debug_drafted(self._ctx, b, out.ctypes.data_as(C.POINTER(C.c_int32)), self.gamma_max,
                                                C.byref(n)), "spec_debug_drafted")
         return out[: n.value].tolist()
+
+    def debug_read(self, model: int, which: int, n: int, dtype=np.float32) -> np.ndarray:
+        out = np.zeros(n, dtype=dtype)
+        self._chk(self._lib.spec_debug_read(self._ctx, model, which, out.ctypes.data_as(C.c_void_p), out.nbytes),
+                  "spec_debug_read")
+        return out
 
     def fill_kv(self, length: int, seed: int = 0):
         self._chk(self._lib.spec_debug_fill_kv(self._ctx, int(length), int(seed)), "spec_debug_fill_kv")

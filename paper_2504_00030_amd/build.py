@@ -12,6 +12,12 @@ import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
 
+if __package__:
+    from . import isa_guard
+else:  # run as a script
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    import isa_guard
+
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
@@ -28,6 +34,7 @@ HIP_SOURCES = [
     "kernels/misc.hip",
 ]
 C_SOURCES = ["gammatune.c"]
+MFMA_SOURCES = ["kernels/gemv_mfma.hip", "kernels/attention.hip"]  # scanned by isa_guard after compiling
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 HIP_FLAGS = [
@@ -58,12 +65,23 @@ def build(verbose: bool = True, jobs: int = 8) -> str:
         out = _run([HIPCC, *HIP_FLAGS, "-c", os.path.join(CSRC, src), "-o", _obj(src)])
         return src, out
 
+    def guard_hip(src):
+        # second, assembly-only compile of the matrix-core kernels, scanned by isa_guard
+        asm = _obj(src)[:-2] + ".s"
+        _run([HIPCC, *HIP_FLAGS, "--cuda-device-only", "-S", os.path.join(CSRC, src), "-o", asm])
+        with open(asm) as f:
+            bad = isa_guard.scan(f.read())
+        if bad:
+            raise RuntimeError(f"{src}: " + "\n".join(bad[:10]))
+        return src + " (matrix-instruction guard)", ""
+
     def compile_c(src):
         out = _run(["gcc", *C_FLAGS, "-c", os.path.join(CSRC, src), "-o", _obj(src)])
         return src, out
 
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         futs = [ex.submit(compile_hip, s) for s in hip_sources] + [ex.submit(compile_c, s) for s in C_SOURCES]
+        futs += [ex.submit(guard_hip, s) for s in hip_sources if s in MFMA_SOURCES]
         for f in futs:
             src, out = f.result()
             if verbose:

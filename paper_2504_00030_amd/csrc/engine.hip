@@ -43,14 +43,15 @@ struct ModelRT {
     int pages_per_seq = 0, n_pages = 0;
     float *rope_cos = nullptr, *rope_sin = nullptr;
     float *part_m = nullptr, *part_l = nullptr, *part_o = nullptr;
+    uint32_t *attn_cnt = nullptr;
     int n_chunks = 0;
     // logits and their tile partials
     float *logits = nullptr;
     int logit_rows = 0;
-    float *pm = nullptr;
-    double *ps = nullptr;
-    int32_t *pa = nullptr;
-    int tiles_cap = 0;
+    float *pm = nullptr, *pm2 = nullptr;
+    double *ps = nullptr, *ps2 = nullptr;
+    int32_t *pa = nullptr, *pa2 = nullptr;
+    int tiles_cap = 0, tiles2_cap = 0;
 };
 
 }  // namespace
@@ -273,6 +274,7 @@ int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights
     TRY(dalloc(c, &m.part_m, pn));
     TRY(dalloc(c, &m.part_l, pn));
     TRY(dalloc(c, &m.part_o, pn * s.head_dim));
+    TRY(dalloc(c, &m.attn_cnt, (size_t)c->cfg.batch * s.n_kv_heads));
 
     m.logit_rows = logit_rows;
     TRY(dalloc(c, &m.logits, (size_t)logit_rows * s.vocab));
@@ -280,6 +282,10 @@ int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights
     TRY(dalloc(c, &m.pm, (size_t)logit_rows * m.tiles_cap));
     TRY(dalloc(c, &m.ps, (size_t)logit_rows * m.tiles_cap));
     TRY(dalloc(c, &m.pa, (size_t)logit_rows * m.tiles_cap));
+    m.tiles2_cap = (m.tiles_cap + 63) / 64;
+    TRY(dalloc(c, &m.pm2, (size_t)logit_rows * m.tiles2_cap));
+    TRY(dalloc(c, &m.ps2, (size_t)logit_rows * m.tiles2_cap));
+    TRY(dalloc(c, &m.pa2, (size_t)logit_rows * m.tiles2_cap));
     return SPEC_OK;
 }
 
@@ -406,6 +412,11 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             t.row_pos = m.row_pos; t.row_seq = m.row_seq; t.chunk = ATT_CHUNK; t.n_chunks = m.n_chunks;
             t.scale = 1.0f / std::sqrt((float)s.head_dim);
             t.part_m = m.part_m; t.part_l = m.part_l; t.part_o = m.part_o; t.o = m.ao; t.ob = m.aob; t.active = active;
+            t.cnt = m.attn_cnt;
+            if (attention_uses_mfma(t, s.head_dim)) {
+                t.chunk = attention_mfma_chunk(c->cfg.max_seq);
+                t.n_chunks = (c->cfg.max_seq + t.chunk - 1) / t.chunk;
+            }
             HIPCHK(c, launch_attention(t, s.head_dim, st));
         }
         {   // output projection + residual
@@ -441,6 +452,8 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
         TRY(launch_proj(c, m, a, EPI_LOGITS, tiled ? m.t_lm : nullptr, s.vocab, &nb, &tile));
         *lp.tile = tile;
         *lp.ntiles = nb;
+        HIPCHK(c, launch_merge_partials(m.pm, m.ps, m.pa, nb, c->scfg.inv_t, m.pm2, m.ps2, m.pa2, lp.rows, lp.y_mul, lp.y_add,
+                                        active, st));
     }
     return SPEC_OK;
 }
@@ -469,6 +482,7 @@ int enqueue_draft(spec_ctx *c, int gamma) {
         a.st = c->st; a.cfg = c->scfg; a.j = j; a.gamma_max = c->cfg.gamma_max; a.logits = c->drf.logits;
         a.vocab = c->drf.s.vocab; a.pm = c->drf.pm; a.ps = c->drf.ps; a.pa = c->drf.pa;
         a.n_tiles = c->d_ntiles; a.tile = c->d_tile;
+        a.pm2 = c->drf.pm2; a.ps2 = c->drf.ps2; a.pa2 = c->drf.pa2; a.n2 = (c->d_ntiles + 63) / 64;
         a.q_logit = c->q_logit; a.q_max = c->q_max; a.q_sum = c->q_sum;
         HIPCHK(c, launch_draft_sample(a, c->stream));
     }
@@ -491,6 +505,7 @@ int enqueue_accept(spec_ctx *c, int gamma) {
     a.st = c->st; a.cfg = c->scfg; a.gamma = gamma; a.gamma_max = c->cfg.gamma_max; a.vocab = c->tgt.s.vocab;
     a.p_logits = c->tgt.logits; a.pm = c->tgt.pm; a.ps = c->tgt.ps; a.pa = c->tgt.pa;
     a.n_tiles = c->t_ntiles; a.tile = c->t_tile;
+    a.pm2 = c->tgt.pm2; a.ps2 = c->tgt.ps2; a.pa2 = c->tgt.pa2; a.n2 = (c->t_ntiles + 63) / 64;
     a.q_logits = c->drf.logits; a.q_logit = c->q_logit; a.q_max = c->q_max; a.q_sum = c->q_sum;
     a.row_max = c->row_max; a.row_sum = c->row_sum; a.row_arg = c->row_arg; a.resid_row = c->resid_row;
     a.resid_part = c->resid_part; a.n_resid_chunks = RESID_CHUNKS; a.ticket = c->ticket;
@@ -864,6 +879,34 @@ int spec_debug_drafted(spec_ctx *c, int32_t b, int32_t *host_out, int32_t cap, i
     return SPEC_OK;
 }
 
+int spec_debug_read(spec_ctx *c, int32_t model, int32_t which, void *host_out, int64_t bytes) {
+    if (!c || !host_out || bytes < 0) return SPEC_EINVAL;
+    ModelRT &m = model ? c->tgt : c->drf;
+    const void *src = nullptr;
+    switch (which) {
+        case 0: src = m.x; break;
+        case 1: src = m.q; break;
+        case 2: src = m.ao; break;
+        case 3: src = m.act; break;
+        case 4: src = m.xg; break;
+        case 5: src = m.ssq; break;
+        case 6: src = m.part_m; break;
+        case 7: src = m.part_l; break;
+        case 8: src = m.part_o; break;
+        case 9: src = m.aob; break;
+        case 10: src = m.xgb; break;
+        case 11: src = m.actb; break;
+        case 12: src = m.qb; break;
+        default:
+            if (which >= 100 && which < 100 + m.s.n_layers) src = m.kpool[which - 100];
+            else if (which >= 200 && which < 200 + m.s.n_layers) src = m.vpool[which - 200];
+    }
+    if (!src) return fail(c, SPEC_EINVAL, "debug_read: unknown buffer");
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    HIPCHK(c, hipMemcpy(host_out, src, (size_t)bytes, hipMemcpyDeviceToHost));
+    return SPEC_OK;
+}
+
 int spec_debug_fill_kv(spec_ctx *c, int32_t len, uint64_t seed) {
     if (!c) return SPEC_EINVAL;
     if (len < 0 || len + 1 + c->cfg.gamma_max + 1 > c->cfg.max_seq) return fail(c, SPEC_ECAP, "fill_kv: len does not fit max_seq");
@@ -994,6 +1037,8 @@ int spec_k_accept(const float *p_logits, const float *q_logits, const int32_t *d
                  o_pm = take(rows_p * n_tiles * 4), o_qm = take(rows_q * n_tiles * 4), o_pa = take(rows_p * n_tiles * 4),
                  o_qa = take(rows_q * n_tiles * 4), o_ql = take(rows_q * 4), o_qmax = take(rows_q * 4),
                  o_rarg = take(rows_p * 4), o_tok = take((rows_p + 1) * 4), o_state = take(64 * 4);
+    const int n2 = (n_tiles + 63) / 64;
+    const size_t o_ps2 = take(rows_p * n2 * 8), o_pm2 = take(rows_p * n2 * 4), o_pa2 = take(rows_p * n2 * 4);
     uint8_t *buf = nullptr;
     if (hipMalloc(reinterpret_cast<void **>(&buf), off) != hipSuccess) return SPEC_ENOMEM;
     int rc = SPEC_OK;
@@ -1012,6 +1057,10 @@ int spec_k_accept(const float *p_logits, const float *q_logits, const int32_t *d
     int32_t *pa = reinterpret_cast<int32_t *>(buf + o_pa), *qa = reinterpret_cast<int32_t *>(buf + o_qa);
     ok(launch_row_partials(p_logits, k + 1, vocab, tile, inv_t, pm, ps, pa, st));
     ok(launch_row_partials(q_logits, k, vocab, tile, inv_t, qm, qs, qa, st));
+    float *pm2 = reinterpret_cast<float *>(buf + o_pm2);
+    double *ps2 = reinterpret_cast<double *>(buf + o_ps2);
+    int32_t *pa2 = reinterpret_cast<int32_t *>(buf + o_pa2);
+    ok(launch_merge_partials(pm, ps, pa, n_tiles, inv_t, pm2, ps2, pa2, k + 1, 1, 0, nullptr, st));
     float *ql = reinterpret_cast<float *>(buf + o_ql), *qmax = reinterpret_cast<float *>(buf + o_qmax);
     double *qsum = reinterpret_cast<double *>(buf + o_qsum);
     ok(launch_gather_qstats(q_logits, drafted, k, vocab, qm, qs, qa, n_tiles, inv_t, ql, qmax, qsum, st));
@@ -1021,7 +1070,7 @@ int spec_k_accept(const float *p_logits, const float *q_logits, const int32_t *d
     a.cfg.temperature = temperature; a.cfg.inv_t = inv_t; a.cfg.seed = seed; a.cfg.forced = 0; a.cfg.tau = 0.f;
     a.cfg.alpha = nullptr; a.cfg.n_alpha = 0;
     a.gamma = k; a.gamma_max = k; a.vocab = vocab; a.p_logits = p_logits; a.pm = pm; a.ps = ps; a.pa = pa;
-    a.n_tiles = n_tiles; a.tile = tile; a.q_logits = q_logits; a.q_logit = ql; a.q_max = qmax; a.q_sum = qsum;
+    a.n_tiles = n_tiles; a.tile = tile; a.pm2 = pm2; a.ps2 = ps2; a.pa2 = pa2; a.n2 = n2; a.q_logits = q_logits; a.q_logit = ql; a.q_max = qmax; a.q_sum = qsum;
     a.row_max = reinterpret_cast<double *>(buf + o_rmax); a.row_sum = reinterpret_cast<double *>(buf + o_rsum);
     a.row_arg = reinterpret_cast<int32_t *>(buf + o_rarg); a.resid_row = state + 8;
     a.resid_part = reinterpret_cast<double *>(buf + o_part); a.n_resid_chunks = RESID_CHUNKS;

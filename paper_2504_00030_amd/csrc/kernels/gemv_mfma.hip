@@ -29,7 +29,10 @@ __global__ __launch_bounds__(NW * 64) void gemv_mfma_k(const GemvArgs a) {
     constexpr int TS = NG * 16 + 1;     // row stride of the reduced tile
     constexpr int U = NG >= 4 ? 2 : (NG == 2 ? 4 : 8);  // k-tiles whose loads are issued together
     static_assert(NW * MB * NG <= 32, "partial tiles must fit 32 KiB of LDS");
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // the wave index is made a scalar so that every branch around a matrix instruction is a scalar
+    // branch: v_mfma ignores the execution mask, and a short masked block whose skip branch the compiler
+    // drops would run it on undefined operands
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     int Ntot = a.n0;
     if (EPI == EPI_QKV) Ntot = (a.nq + 2 * a.nkv) * a.hd;
     if (EPI == EPI_SWIGLU) Ntot = 2 * a.n0;

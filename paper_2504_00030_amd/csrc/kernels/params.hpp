@@ -113,6 +113,7 @@ struct AttnArgs {
     float *o;                // [R][nq*hd]
     uint16_t *ob;            // bf16 copy
     const int32_t *active;
+    uint32_t *cnt;           // [B][n_kv] arrival counters of the matrix-core kernel (zero between launches)
 };
 
 // Sampling configuration shared by the sampler kernels.
@@ -135,6 +136,8 @@ struct DraftSampleArgs {
     int32_t vocab;
     const float *pm; const double *ps; const int32_t *pa;  // partials [B*gamma_max][n_tiles]
     int32_t n_tiles, tile;
+    const float *pm2; const double *ps2; const int32_t *pa2;  // level 2: one per 64 tiles, [..][n2]
+    int32_t n2;
     // per drafted token: logit of the chosen token, row max, row sum  -> [B][gamma_max]
     float *q_logit, *q_max;
     double *q_sum;
@@ -149,6 +152,8 @@ struct AcceptArgs {
     const float *p_logits;  // [B][gamma+1][V]
     const float *pm; const double *ps; const int32_t *pa;  // target partials [B*(gamma+1)][n_tiles]
     int32_t n_tiles, tile;
+    const float *pm2; const double *ps2; const int32_t *pa2;  // level 2: one per 64 tiles, [..][n2]
+    int32_t n2;
     const float *q_logits;  // [B][gamma_max][V]
     const float *q_logit, *q_max; const double *q_sum;     // [B][gamma_max]
     // scratch of the accept phase
@@ -172,10 +177,15 @@ bool gemv_wavedot_uses_split(int epi, int Ntot, int K, int R, int w_dtype);
 int gemv_wavedot_tile_cols(int epi, int Ntot, int K, int R, int w_dtype);
 int gemv_wavedot_pick_rpw(int epi, int N, int K, int R, int w_dtype);
 hipError_t launch_attention(const AttnArgs &a, int hd, hipStream_t s);
+int attention_mfma_chunk(int max_seq);
+bool attention_uses_mfma(const AttnArgs &a, int hd);
 hipError_t launch_draft_sample(const DraftSampleArgs &a, hipStream_t s);
 hipError_t launch_accept(const AcceptArgs &a, hipStream_t s);
 hipError_t launch_row_partials(const float *logits, int rows, int vocab, int tile, float inv_t, float *pm, double *ps,
                                int32_t *pa, hipStream_t s);
+hipError_t launch_merge_partials(const float *pm, const double *ps, const int32_t *pa, int n1, float inv_t, float *pm2,
+                                 double *ps2, int32_t *pa2, int rows, int y_mul, int y_add, const int32_t *active,
+                                 hipStream_t s);
 hipError_t launch_gather_qstats(const float *q_logits, const int32_t *drafted, int rows, int vocab, const float *pm,
                                 const double *ps, const int32_t *pa, int n_tiles, float inv_t, float *q_logit,
                                 float *q_max, double *q_sum, hipStream_t s);

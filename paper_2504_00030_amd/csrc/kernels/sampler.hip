@@ -27,12 +27,28 @@ struct RowStats {
     int arg;
 };
 
-// Statistics of one logits row from its tile partials, computed by one wave.
-__device__ RowStats wave_row_stats(const float *pm, const double *ps, const int32_t *pa, int n_tiles, double inv_t,
-                                   int lane) {
+// Softmax partials of one logits row on two levels: level 1 has one (max, sum exp, argmax) per tile of
+// `tile` vocabulary entries (left by the logits kernel), level 2 one per 64 consecutive level-1 tiles
+// (left by merge_partials_k).
+struct PartRow {
+    const float *pm1; const double *ps1; const int32_t *pa1; int n1, tile;
+    const float *pm2; const double *ps2; const int32_t *pa2; int n2;
+};
+
+__device__ __forceinline__ PartRow part_row(const float *pm, const double *ps, const int32_t *pa, int n1, int tile,
+                                            const float *pm2, const double *ps2, const int32_t *pa2, int n2, size_t row) {
+    PartRow p;
+    p.pm1 = pm + row * n1; p.ps1 = ps + row * n1; p.pa1 = pa + row * n1; p.n1 = n1; p.tile = tile;
+    p.pm2 = pm2 + row * n2; p.ps2 = ps2 + row * n2; p.pa2 = pa2 + row * n2; p.n2 = n2;
+    return p;
+}
+
+// One wave reduces n partials (max with lowest-index argmax, then sum of rescaled sums).
+__device__ RowStats wave_reduce_partials(const float *pm, const double *ps, const int32_t *pa, int n, double inv_t,
+                                         int lane) {
     float m = -INFINITY;
     int arg = 0x7fffffff;
-    for (int t = lane; t < n_tiles; t += 64) {
+    for (int t = lane; t < n; t += 64) {
         const float v = pm[t];
         const int ai = pa[t];
         if (v > m || (v == m && ai < arg)) { m = v; arg = ai; }
@@ -44,53 +60,70 @@ __device__ RowStats wave_row_stats(const float *pm, const double *ps, const int3
         if (om > m || (om == m && oa < arg)) { m = om; arg = oa; }
     }
     double s = 0.0;
-    for (int t = lane; t < n_tiles; t += 64) s += ps[t] * exp((double)(pm[t] - m) * inv_t);
+    for (int t = lane; t < n; t += 64) s += ps[t] * exp((double)(pm[t] - m) * inv_t);
     s = wave_sum(s);
     RowStats r;
-    r.M = (double)m; r.S = s; r.arg = arg;
+    r.M = (double)m; r.S = s; r.arg = arg;  // arg stays 0x7fffffff when no entry compares (empty or all-NaN input)
     return r;
 }
 
-// Index-order inverse CDF over one row, by one wave: first j with cum_j > target, where the weights are
-// w_j = exp((l_j - M) * inv_t).  Tiles are walked through their partial sums, the crossing tile element
-// by element.  If rounding leaves no crossing the last index is returned.
-__device__ int wave_sample_row(const float *logits, int vocab, const float *pm, const double *ps, int n_tiles, int tile,
-                               double M, double inv_t, double target, int lane) {
-    // contiguous run of tiles per lane keeps index order
-    const int tpl = (n_tiles + 63) / 64;
-    const int tb = lane * tpl, te = min(tb + tpl, n_tiles);
+// Statistics of one logits row from its level-2 partials, computed by one wave.
+__device__ __forceinline__ RowStats wave_row_stats(const PartRow &p, double inv_t, int lane) {
+    return wave_reduce_partials(p.pm2, p.ps2, p.pa2, p.n2, inv_t, lane);
+}
+
+// First index i in [0, n) whose inclusive running sum base + c_0 + .. + c_i exceeds target, where
+// c_i = ps[i] * exp((pm[i] - M) * inv_t); lanes own contiguous runs so the order is index order.
+// Returns the index (or n - 1 when rounding leaves no crossing) and the running sum before it.
+__device__ __forceinline__ int wave_find_partial(const float *pm, const double *ps, int n, double M, double inv_t,
+                                                 double base, double target, int lane, double *before) {
+    const int per = (n + 63) / 64;
+    const int b0 = lane * per, b1 = min(b0 + per, n);
     double seg = 0.0;
-    for (int t = tb; t < te; ++t) seg += ps[t] * exp(((double)pm[t] - M) * inv_t);
-    const double incl = wave_scan_incl(seg, lane);
-    const unsigned long long hit = __ballot(incl > target && tb < te);
-    int src = hit ? __ffsll((long long)hit) - 1 : -1;
-    int t_star;
-    double base;
-    if (src < 0) {  // no crossing: last tile
-        t_star = n_tiles - 1;
-        base = 0.0;  // unused: the fallback below picks the last element
-    } else {
-        // the owning lane walks its tiles
+    for (int i = b0; i < b1; ++i) seg += ps[i] * exp(((double)pm[i] - M) * inv_t);
+    const double incl = base + wave_scan_incl(seg, lane);
+    const unsigned long long hit = __ballot(incl > target && b0 < b1);
+    int idx = n - 1;
+    double bef = 0.0;
+    if (hit) {
+        const int src = __ffsll((long long)hit) - 1;
         double cum = incl - seg;
-        int ts = te - 1;
-        double tbse = cum;
-        bool found = false;
-        for (int t = tb; t < te; ++t) {
-            const double c = ps[t] * exp(((double)pm[t] - M) * inv_t);
-            if (!found && cum + c > target) { ts = t; tbse = cum; found = true; }
+        int is = b1 - 1;
+        double ib = cum;
+        bool f = false;
+        for (int i = b0; i < b1; ++i) {
+            const double c = ps[i] * exp(((double)pm[i] - M) * inv_t);
+            if (!f) {
+                ib = cum;  // stays at "before the last entry of the run" when rounding hides the crossing
+                if (cum + c > target) { is = i; f = true; }
+            }
             cum += c;
         }
-        if (!found) {  // rounding between the scan and the walk: last tile of the run
-            double c2 = incl - seg;
-            for (int t = tb; t < te - 1; ++t) c2 += ps[t] * exp(((double)pm[t] - M) * inv_t);
-            tbse = c2;
-        }
-        t_star = __shfl(ts, src, WAVE);
-        base = __shfl(tbse, src, WAVE);
+        idx = __shfl(is, src, WAVE);
+        bef = __shfl(ib, src, WAVE);
+    } else {
+        // running sum before the last entry
+        const double tot = __shfl(incl, 63, WAVE);
+        bef = tot - ps[n - 1] * exp(((double)pm[n - 1] - M) * inv_t);
     }
+    *before = bef;
+    return idx;
+}
+
+// Index-order inverse CDF over one row, by one wave: first j with cum_j > target, where the weights are
+// w_j = exp((l_j - M) * inv_t).  The crossing is located on level 2, then among the 64 level-1 tiles
+// below it, then element by element inside that tile.  If rounding leaves no crossing the last index
+// of the innermost range is returned.
+__device__ int wave_sample_row(const float *logits, int vocab, const PartRow &p, double M, double inv_t, double target,
+                               int lane) {
+    double base2 = 0.0;
+    const int j2 = wave_find_partial(p.pm2, p.ps2, p.n2, M, inv_t, 0.0, target, lane, &base2);
+    const int t_lo = j2 * 64, t_n = min(64, p.n1 - t_lo);
+    double base1 = 0.0;
+    const int t_star = t_lo + wave_find_partial(p.pm1 + t_lo, p.ps1 + t_lo, t_n, M, inv_t, base2, target, lane, &base1);
     // inside the tile: contiguous elements per lane
-    const int e0 = t_star * tile;
-    const int len = min(tile, vocab - e0);
+    const int e0 = t_star * p.tile;
+    const int len = min(p.tile, vocab - e0);
     const int epl = (len + 63) / 64;
     const int eb = lane * epl, ee = min(eb + epl, len);
     double w[8];
@@ -100,13 +133,12 @@ __device__ int wave_sample_row(const float *logits, int vocab, const float *pm, 
         w[i] = e < ee ? exp(((double)logits[e0 + e] - M) * inv_t) : 0.0;
         sseg += w[i];
     }
-    const double eincl = wave_scan_incl(sseg, lane);
-    const bool cross = src >= 0 && eb < ee && base + eincl > target;
-    const unsigned long long ehit = __ballot(cross);
-    if (!ehit) return src < 0 ? vocab - 1 : e0 + len - 1;
+    const double eincl = base1 + wave_scan_incl(sseg, lane);
+    const unsigned long long ehit = __ballot(eb < ee && eincl > target);
+    if (!ehit) return e0 + len - 1;
     const int el = __ffsll((long long)ehit) - 1;
     int tok = e0 + ee - 1;
-    double cum = base + eincl - sseg;
+    double cum = eincl - sseg;
     bool f = false;
     for (int i = 0; i < 8; ++i) {
         const int e = eb + i;
@@ -118,17 +150,40 @@ __device__ int wave_sample_row(const float *logits, int vocab, const float *pm, 
     return __shfl(tok, el, WAVE);
 }
 
+// Level-2 partials: one wave merges 64 consecutive level-1 partials of one row.
+__global__ __launch_bounds__(64) void merge_partials_k(const float *pm, const double *ps, const int32_t *pa, int n1,
+                                                       float inv_t, float *pm2, double *ps2, int32_t *pa2, int n2,
+                                                       int y_mul, int y_add, const int32_t *active) {
+    if (active != nullptr && *active == 0) return;
+    const int j = blockIdx.x, lane = threadIdx.x;
+    const size_t row = (size_t)blockIdx.y * y_mul + y_add;
+    const int t0 = j * 64, n = min(64, n1 - t0);
+    const RowStats r = wave_reduce_partials(pm + row * n1 + t0, ps + row * n1 + t0, pa + row * n1 + t0, n, (double)inv_t, lane);
+    if (lane == 0) {
+        pm2[row * n2 + j] = (float)r.M;
+        ps2[row * n2 + j] = r.S;
+        pa2[row * n2 + j] = r.arg;
+    }
+}
+
+hipError_t launch_merge_partials(const float *pm, const double *ps, const int32_t *pa, int n1, float inv_t, float *pm2,
+                                 double *ps2, int32_t *pa2, int rows, int y_mul, int y_add, const int32_t *active,
+                                 hipStream_t s) {
+    const int n2 = (n1 + 63) / 64;
+    hipLaunchKernelGGL(merge_partials_k, dim3(n2, rows), dim3(64), 0, s, pm, ps, pa, n1, inv_t, pm2, ps2, pa2, n2, y_mul,
+                       y_add, active);
+    return hipGetLastError();
+}
+
 // ---- draft sampling ------------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void draft_sample_k(const DraftSampleArgs a) {
     const int b = blockIdx.x, lane = threadIdx.x;
     if (a.st.k[b] != 0) return;  // this sequence stopped drafting earlier in the step
     const int row = b * a.gamma_max + (a.j - 1);
-    const float *pm = a.pm + (size_t)row * a.n_tiles;
-    const double *ps = a.ps + (size_t)row * a.n_tiles;
-    const int32_t *pa = a.pa + (size_t)row * a.n_tiles;
+    const PartRow pr = part_row(a.pm, a.ps, a.pa, a.n_tiles, a.tile, a.pm2, a.ps2, a.pa2, a.n2, (size_t)row);
     const float *logits = a.logits + (size_t)row * a.vocab;
     const double inv_t = (double)a.cfg.inv_t;
-    const RowStats rs = wave_row_stats(pm, ps, pa, a.n_tiles, inv_t, lane);
+    const RowStats rs = wave_row_stats(pr, inv_t, lane);
     const int len = a.st.len[b];
     const uint32_t step = (uint32_t)a.st.ctl[0];
     int x;
@@ -136,8 +191,9 @@ __global__ __launch_bounds__(64) void draft_sample_k(const DraftSampleArgs a) {
         x = rs.arg;
     } else {
         const double u = philox_uniform(a.cfg.seed, step, (uint32_t)a.j, PURPOSE_DRAFT, (uint32_t)b);
-        x = wave_sample_row(logits, a.vocab, pm, ps, a.n_tiles, a.tile, rs.M, inv_t, u * rs.S, lane);
+        x = wave_sample_row(logits, a.vocab, pr, rs.M, inv_t, u * rs.S, lane);
     }
+    x = min(max(x, 0), a.vocab - 1);  // a row of non-finite logits has no argmax: stay inside the vocabulary
     if (lane == 0) {
         const int pos = len + a.j - 1;
         if (pos < a.st.max_seq) a.st.tokens[(size_t)b * a.st.max_seq + pos] = x;
@@ -172,6 +228,7 @@ constexpr int ACC_THREADS = 1024;
 constexpr int ACC_ROWS_MAX = 65;
 
 __device__ __forceinline__ void commit_step(const AcceptArgs &a, int b, int A, int y) {
+    y = min(max(y, 0), a.vocab - 1);
     const int len = a.st.len[b];
     const int pos = len + A;
     if (pos < a.st.max_seq) a.st.tokens[(size_t)b * a.st.max_seq + pos] = y;
@@ -194,8 +251,8 @@ __global__ __launch_bounds__(ACC_THREADS) void accept_scan_k(const AcceptArgs a)
 
     for (int i = wave; i <= k; i += ACC_THREADS / 64) {  // target rows 1..k+1 (0-based i)
         const size_t row = (size_t)b * rows + i;
-        const RowStats rs = wave_row_stats(a.pm + row * a.n_tiles, a.ps + row * a.n_tiles, a.pa + row * a.n_tiles,
-                                           a.n_tiles, inv_t, lane);
+        const RowStats rs = wave_row_stats(part_row(a.pm, a.ps, a.pa, a.n_tiles, a.tile, a.pm2, a.ps2, a.pa2, a.n2, row),
+                                           inv_t, lane);
         if (lane == 0) {
             sM[i] = rs.M; sS[i] = rs.S; sArg[i] = rs.arg;
             a.row_max[row] = rs.M; a.row_sum[row] = rs.S; a.row_arg[row] = rs.arg;
@@ -249,8 +306,9 @@ __global__ __launch_bounds__(ACC_THREADS) void accept_scan_k(const AcceptArgs a)
         const int i = k;  // 0-based bonus row
         const size_t row = (size_t)b * rows + i;
         const double u = philox_uniform(a.cfg.seed, step, (uint32_t)(k + 1), PURPOSE_BONUS, (uint32_t)b);
-        const int y = wave_sample_row(a.p_logits + row * a.vocab, a.vocab, a.pm + row * a.n_tiles,
-                                      a.ps + row * a.n_tiles, a.n_tiles, a.tile, sM[i], inv_t, u * sS[i], lane);
+        const int y = wave_sample_row(a.p_logits + row * a.vocab, a.vocab,
+                                      part_row(a.pm, a.ps, a.pa, a.n_tiles, a.tile, a.pm2, a.ps2, a.pa2, a.n2, row), sM[i],
+                                      inv_t, u * sS[i], lane);
         if (lane == 0) a.y_dev[b] = y;
     }
 }
@@ -361,8 +419,9 @@ __global__ __launch_bounds__(RES_THREADS) void residual_k(const AcceptArgs a) {
     if (!(s_tot > 0.0)) {
         // no residual mass (p == q up to rounding): draw from p with the same uniform
         if (wave == 0) {
-            const int y = wave_sample_row(lp, a.vocab, a.pm + prow * a.n_tiles, a.ps + prow * a.n_tiles, a.n_tiles,
-                                          a.tile, Mp, inv_t, u * Sp, lane);
+            const int y = wave_sample_row(lp, a.vocab,
+                                          part_row(a.pm, a.ps, a.pa, a.n_tiles, a.tile, a.pm2, a.ps2, a.pa2, a.n2, prow),
+                                          Mp, inv_t, u * Sp, lane);
             if (lane == 0) {
                 a.ticket[b] = 0;
                 commit_step(a, b, a.A_dev[b], y);
@@ -465,8 +524,8 @@ __global__ __launch_bounds__(64) void gather_qstats_k(const float *q_logits, con
                                                       const float *pm, const double *ps, const int32_t *pa, int n_tiles,
                                                       float inv_t, float *q_logit, float *q_max, double *q_sum) {
     const int row = blockIdx.x, lane = threadIdx.x;
-    const RowStats rs = wave_row_stats(pm + (size_t)row * n_tiles, ps + (size_t)row * n_tiles,
-                                       pa + (size_t)row * n_tiles, n_tiles, (double)inv_t, lane);
+    const RowStats rs = wave_reduce_partials(pm + (size_t)row * n_tiles, ps + (size_t)row * n_tiles,
+                                             pa + (size_t)row * n_tiles, n_tiles, (double)inv_t, lane);
     if (lane == 0) {
         q_logit[row] = q_logits[(size_t)row * vocab + drafted[row]];
         q_max[row] = (float)rs.M;

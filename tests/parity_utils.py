@@ -68,6 +68,9 @@ def _compare_step(res: Compare, tag: str, r, gamma: int, gk: int, gA: int, gy: i
                   temperature: float) -> bool:
     """Compare one sequence's step; returns True when every decision matched."""
     scale = max(float(np.abs(r.p_logits).max()), float(np.abs(np.stack(r.q_logits)).max()))
+    if not (np.isfinite(ql[: max(gk, 1)]).all() and np.isfinite(pl[: gk + 1]).all()):
+        res.failures.append(f"{tag}: non-finite logits from the library")
+        return False
     eps = TOL[dtype] * scale
     k_logit = 4.0 * eps
     k_prob = 8.0 * eps / (temperature if temperature > 0 else 1.0)
@@ -78,12 +81,12 @@ def _compare_step(res: Compare, tag: str, r, gamma: int, gk: int, gA: int, gy: i
     for i in range(min(r.k, gk, n_agree + 1)):
         err = float(np.abs(ql[i] - r.q_logits[i]).max()) / scale
         res.max_logit_err = max(res.max_logit_err, err)
-        if err > TOL[dtype]:
+        if not err <= TOL[dtype]:
             res.failures.append(f"{tag}: draft logits row {i} err {err:.3e}")
     for i in range(min(r.k, gk, n_agree) + 1):
         err = float(np.abs(pl[i] - r.p_logits[i]).max()) / scale
         res.max_logit_err = max(res.max_logit_err, err)
-        if err > TOL[dtype]:
+        if not err <= TOL[dtype]:
             res.failures.append(f"{tag}: target logits row {i} err {err:.3e}")
     # decisions, in the oracle's order; the first difference ends the step
     for dcs in r.decisions:
