@@ -47,6 +47,7 @@ def parse():
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-roofline", action="store_true")
     ap.add_argument("--gemv-path", type=int, default=0)
+    ap.add_argument("--attn-chunk", type=int, default=0)
     return ap.parse_args()
 
 
@@ -144,7 +145,7 @@ def main():
     def engine(use_graphs):
         e = pk.SpecEngine(cfg.target, Wt, cfg.draft, Wd, batch=1, max_seq=max_seq, gamma_max=cfg.gamma_max,
                           temperature=args.temperature, seed=0, accept_mode=pk.ACCEPT_FORCED, use_graphs=use_graphs,
-                          gemv_path=args.gemv_path)
+                          gemv_path=args.gemv_path, attn_chunk=args.attn_chunk)
         e.set_forced_alpha(alpha)
         if tau > 0:
             e.set_early_stop(tau)

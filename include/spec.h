@@ -83,6 +83,7 @@ typedef struct {
     int32_t  accept_mode;  /* SPEC_ACCEPT_NATURAL or SPEC_ACCEPT_FORCED */
     int32_t  gemv_path;    /* SPEC_PATH_AUTO, or force one kernel family (bf16 models; fp32 models always use WAVEDOT) */
     int32_t  use_graphs;   /* 1: replay one captured HIP graph per gamma; 0: launch kernel by kernel */
+    int32_t  attn_chunk;   /* KV positions per attention workgroup (bf16 models): 0 = automatic, else 64, 128, 256 or 512 */
     void    *hip_stream;   /* hipStream_t to enqueue on (borrowed); NULL = a stream the context creates and owns */
 } spec_config;
 

@@ -49,7 +49,7 @@ class SpecWeights(C.Structure):
 class SpecConfig(C.Structure):
     _fields_ = [("batch", C.c_int32), ("max_seq", C.c_int32), ("page_tokens", C.c_int32), ("gamma_max", C.c_int32),
                 ("temperature", C.c_float), ("seed", C.c_uint64), ("accept_mode", C.c_int32), ("gemv_path", C.c_int32),
-                ("use_graphs", C.c_int32), ("hip_stream", C.c_void_p)]
+                ("use_graphs", C.c_int32), ("attn_chunk", C.c_int32), ("hip_stream", C.c_void_p)]
 
 
 class GtParams(C.Structure):
@@ -186,13 +186,13 @@ class SpecEngine:
 
     def __init__(self, target_shape, target_w: Dict, draft_shape, draft_w: Dict, *, batch=1, max_seq=512, gamma_max=8,
                  temperature=0.0, seed=0, accept_mode=ACCEPT_NATURAL, page_tokens=64, gemv_path=PATH_AUTO,
-                 use_graphs=False, stream: int = 0):
+                 use_graphs=False, attn_chunk=0, stream: int = 0):
         self._lib = load()
         self._keep = [target_w, draft_w]
         ts, ds = _shape_struct(target_shape), _shape_struct(draft_shape)
         tw, dw = _weights_struct(target_w, self._keep), _weights_struct(draft_w, self._keep)
         cfg = SpecConfig(batch, max_seq, page_tokens, gamma_max, temperature, seed, accept_mode, gemv_path,
-                         1 if use_graphs else 0, stream)
+                         1 if use_graphs else 0, attn_chunk, stream)
         self.batch, self.max_seq, self.gamma_max, self.vocab = batch, max_seq, gamma_max, target_shape.vocab
         self._ctx = C.c_void_p()
         rc = self._lib.spec_init(C.byref(ts), C.byref(tw), C.byref(ds), C.byref(dw), C.byref(cfg), C.byref(self._ctx))

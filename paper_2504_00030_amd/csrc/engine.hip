@@ -43,7 +43,6 @@ struct ModelRT {
     int pages_per_seq = 0, n_pages = 0;
     float *rope_cos = nullptr, *rope_sin = nullptr;
     float *part_m = nullptr, *part_l = nullptr, *part_o = nullptr;
-    uint32_t *attn_cnt = nullptr;
     int n_chunks = 0;
     // logits and their tile partials
     float *logits = nullptr;
@@ -274,7 +273,6 @@ int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights
     TRY(dalloc(c, &m.part_m, pn));
     TRY(dalloc(c, &m.part_l, pn));
     TRY(dalloc(c, &m.part_o, pn * s.head_dim));
-    TRY(dalloc(c, &m.attn_cnt, (size_t)c->cfg.batch * s.n_kv_heads));
 
     m.logit_rows = logit_rows;
     TRY(dalloc(c, &m.logits, (size_t)logit_rows * s.vocab));
@@ -412,10 +410,11 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             t.row_pos = m.row_pos; t.row_seq = m.row_seq; t.chunk = ATT_CHUNK; t.n_chunks = m.n_chunks;
             t.scale = 1.0f / std::sqrt((float)s.head_dim);
             t.part_m = m.part_m; t.part_l = m.part_l; t.part_o = m.part_o; t.o = m.ao; t.ob = m.aob; t.active = active;
-            t.cnt = m.attn_cnt;
             if (attention_uses_mfma(t, s.head_dim)) {
-                t.chunk = attention_mfma_chunk(c->cfg.max_seq);
-                t.n_chunks = (c->cfg.max_seq + t.chunk - 1) / t.chunk;
+                const int chunk = attention_mfma_chunk(c->cfg.max_seq, c->cfg.attn_chunk);
+                const int nch = (c->cfg.max_seq + chunk - 1) / chunk;
+                if (nch <= ATT_NC_MAX) { t.chunk = chunk; t.n_chunks = nch; }
+                else t.qb = nullptr;  // capacity beyond the merge of the matrix-core kernel: plain kernel
             }
             HIPCHK(c, launch_attention(t, s.head_dim, st));
         }
@@ -612,6 +611,8 @@ int spec_init(const spec_shape *t, const spec_weights *tw, const spec_shape *d, 
     if (g.gamma_max < 1 || g.gamma_max > 64) return bail(fail(c, SPEC_EINVAL, "gamma_max outside 1..64"));
     if (g.page_tokens < 8 || (g.page_tokens & (g.page_tokens - 1)))
         return bail(fail(c, SPEC_EINVAL, "page_tokens must be a power of two >= 8"));
+    if (g.attn_chunk != 0 && g.attn_chunk != 64 && g.attn_chunk != 128 && g.attn_chunk != 256 && g.attn_chunk != 512)
+        return bail(fail(c, SPEC_EINVAL, "attn_chunk must be 0, 64, 128, 256 or 512"));
     if (g.max_seq < g.gamma_max + 2) return bail(fail(c, SPEC_EINVAL, "max_seq too small"));
     if (!(g.temperature >= 0.f)) return bail(fail(c, SPEC_EINVAL, "temperature < 0"));
     if (g.accept_mode != SPEC_ACCEPT_NATURAL && g.accept_mode != SPEC_ACCEPT_FORCED)

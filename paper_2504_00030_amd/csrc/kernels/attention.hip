@@ -93,45 +93,64 @@ __global__ __launch_bounds__(128) void attn_combine_k(const AttnArgs a) {
 }
 
 // ---- matrix-core version for 16-bit caches --------------------------------------------------------
-// One workgroup per (chunk of 64 * spw positions, kv head, sequence); wave w owns the 16-position slabs
-// w, w + 4, ... of the chunk.  Per 16-query tile a wave forms S^T = K Q^T with
-// v_mfma_f32_16x16x32_bf16 (K rows and bf16 query rows are loaded straight into the operand layout),
-// takes the softmax over its slabs, and multiplies by V with v_mfma_f32_16x16x16_bf16: the S^T result
-// registers already are the A operand (query = lane % 16, four positions per lane), and the transposed
-// V pages give the B operand with one 8-byte load.  The four wave partials are merged through LDS into
-// one (max, sum, vector) partial per chunk; the workgroup that finishes last for its (sequence, kv head)
-// merges the chunk partials, in chunk order, into the attention output.
+// One workgroup per (chunk of 64 * SPW positions, kv head, sequence); wave w owns the 16-position slabs
+// w, w + 4, ... of the chunk.  A wave first issues every load of its slabs (K rows and transposed V
+// columns, straight into the operand layouts; positions past the last visible one are clamped, so the
+// loads and the matrix instructions need no branch), then per 16-query tile forms S^T = K Q^T with
+// v_mfma_f32_16x16x32_bf16, takes the softmax over its slabs, and multiplies by V with
+// v_mfma_f32_16x16x16_bf16: the S^T result registers already are the A operand (query = lane % 16, four
+// positions per lane).  The four wave partials are merged through LDS into one (max, sum, vector)
+// partial per chunk, and attn_mfma_merge_k merges the chunk partials into the attention output (a
+// kernel boundary is the cheapest way to order the partials across the chip's eight L2 caches).  A
+// sequence that fits one chunk skips the partials.
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
-constexpr int ATT_SPW_MAX = 8;  // slabs per wave -> chunks of up to 512 positions
+constexpr int ATT_SPW_MAX = 8;   // slabs per wave -> chunks of up to 512 positions
 
-template <int HD>
+template <int HD, int SPW>
 __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
     if (a.active != nullptr && *a.active == 0) return;
     constexpr int ES = HD / 32;  // k-steps of the score product
     constexpr int ET = HD / 16;  // 16-channel tiles of the output
+    constexpr int CT = 64 * SPW;
     const int c = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-    // wave index and last position are scalars: branches around matrix instructions must be scalar
-    // branches, since v_mfma ignores the execution mask
+    // wave index and last position are scalars, so that branches on them are scalar branches
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l16 = lane & 15, g = lane >> 4;
     const int G = a.nq / a.kv.n_kv;
     const int QN = G * a.rps;
     const int r_first = b * a.rps;
-    const int CT = a.chunk, spw = a.chunk >> 6;
     const int t0 = c * CT;
     const int last_pos = __builtin_amdgcn_readfirstlane(a.row_pos[r_first + a.rps - 1]);
     if (t0 > last_pos) return;
+    const int n_live = last_pos / CT + 1;
     const bf16_t *kp = reinterpret_cast<const bf16_t *>(a.kv.k);
     const bf16_t *vp = reinterpret_cast<const bf16_t *>(a.kv.v);
 
     __shared__ float sO[4][16][HD + 1];
     __shared__ float sM[4][16], sL[4][16];
-    __shared__ int s_last;
+
+    // K fragment: position tw + l16, channels 32 s + 8 g .. + 8; V fragment: channel 16 et + l16, positions
+    // tw + 4 g .. + 4 (contiguous in the transposed page)
+    u32x4_t kf[SPW][ES];
+    u32x2_t vf[SPW][ET];
+#pragma unroll
+    for (int sl = 0; sl < SPW; ++sl) {
+        const int tw = t0 + 16 * (wave + 4 * sl);
+        const int pk = min(tw + l16, last_pos);
+        const size_t kb = kv_index_k(a.kv, b, pk, kvh, 8 * g);
+#pragma unroll
+        for (int s = 0; s < ES; ++s) kf[sl][s] = *reinterpret_cast<const u32x4_t *>(kp + kb + 32 * s);
+        const int pv = min(tw + 4 * g, last_pos & ~3);
+        const size_t vb = kv_index_v(a.kv, b, pv, kvh, l16);
+#pragma unroll
+        for (int et = 0; et < ET; ++et)
+            vf[sl][et] = *reinterpret_cast<const u32x2_t *>(vp + vb + (size_t)(16 * et) * a.kv.page_tokens);
+    }
 
     const int QT = (QN + 15) / 16;
     for (int qt = 0; qt < QT; ++qt) {
@@ -146,60 +165,46 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
 #pragma unroll
             for (int s = 0; s < ES; ++s) qf[s] = *reinterpret_cast<const u32x4_t *>(qp + 32 * s);
         }
-        // pass 1: scores of every slab of this wave; S[sl][v] = (position tw + 4 g + v, query l16)
-        f32x4_t S[ATT_SPW_MAX];
+        // scores of every slab of this wave; S[sl][v] = (position tw + 4 g + v, query l16)
+        f32x4_t S[SPW];
         float m = -INFINITY;
 #pragma unroll
-        for (int sl = 0; sl < ATT_SPW_MAX; ++sl) {
-            S[sl] = f32x4_t{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        for (int sl = 0; sl < SPW; ++sl) {
             const int tw = t0 + 16 * (wave + 4 * sl);
-            if (sl < spw && tw <= last_pos) {
-                const int pos = min(tw + l16, last_pos);
-                const size_t kb = kv_index_k(a.kv, b, pos, kvh, 0);
-                f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+            f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int s = 0; s < ES; ++s) {
-                    const u32x4_t kf = *reinterpret_cast<const u32x4_t *>(kp + kb + 32 * s + 8 * g);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kf),
-                                                                  __builtin_bit_cast(bf16x8_t, qf[s]), acc, 0, 0, 0);
-                }
+            for (int s = 0; s < ES; ++s)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kf[sl][s]),
+                                                              __builtin_bit_cast(bf16x8_t, qf[s]), acc, 0, 0, 0);
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const bool vis = (tw + 4 * g + v) <= qpos;
-                    S[sl][v] = vis ? acc[v] * a.scale : -INFINITY;
-                    m = fmaxf(m, S[sl][v]);
-                }
+            for (int v = 0; v < 4; ++v) {
+                const bool vis = (tw + 4 * g + v) <= qpos;
+                S[sl][v] = vis ? acc[v] * a.scale : -INFINITY;
+                m = fmaxf(m, S[sl][v]);
             }
         }
         m = fmaxf(m, __shfl_xor(m, 16, WAVE));
         m = fmaxf(m, __shfl_xor(m, 32, WAVE));
-        // pass 2: probabilities and the weighted values
+        // probabilities and the weighted values
         float l = 0.f;
         f32x4_t O[ET];
 #pragma unroll
         for (int et = 0; et < ET; ++et) O[et] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int sl = 0; sl < ATT_SPW_MAX; ++sl) {
-            const int tw = t0 + 16 * (wave + 4 * sl);
-            if (sl < spw && tw <= last_pos) {
-                float p[4];
+        for (int sl = 0; sl < SPW; ++sl) {
+            float p[4];
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    p[v] = m == -INFINITY ? 0.f : __expf(S[sl][v] - m);
-                    l += p[v];
-                }
-                u32x2_t pw;
-                pw.x = pack_bf16x2(p[0], p[1]);
-                pw.y = pack_bf16x2(p[2], p[3]);
-                // V fragment: channel 16 et + l16, positions tw + 4 g .. + 4 (contiguous in the transposed page)
-                const int pos = min(tw + 4 * g, last_pos & ~3);
-#pragma unroll
-                for (int et = 0; et < ET; ++et) {
-                    const u32x2_t vf = *reinterpret_cast<const u32x2_t *>(vp + kv_index_v(a.kv, b, pos, kvh, 16 * et + l16));
-                    O[et] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, pw),
-                                                                      __builtin_bit_cast(s16x4_t, vf), O[et], 0, 0, 0);
-                }
+            for (int v = 0; v < 4; ++v) {
+                p[v] = m == -INFINITY ? 0.f : __expf(S[sl][v] - m);
+                l += p[v];
             }
+            u32x2_t pw;
+            pw.x = pack_bf16x2(p[0], p[1]);
+            pw.y = pack_bf16x2(p[2], p[3]);
+#pragma unroll
+            for (int et = 0; et < ET; ++et)
+                O[et] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, pw),
+                                                                  __builtin_bit_cast(s16x4_t, vf[sl][et]), O[et], 0, 0, 0);
         }
         l += __shfl_xor(l, 16, WAVE);
         l += __shfl_xor(l, 32, WAVE);
@@ -224,59 +229,85 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
                 L += f * sL[w][q];
             }
             const int rr = r_first + qj % a.rps, hh = kvh * G + qj / a.rps;
-            const size_t pi = ((size_t)rr * a.nq + hh) * a.n_chunks + c;
-            a.part_o[pi * HD + e] = acc;
-            if (e == 0) { a.part_m[pi] = M; a.part_l[pi] = L; }
+            if (n_live == 1) {
+                const float v = acc / L;
+                const size_t o = ((size_t)rr * a.nq + hh) * HD + e;
+                a.o[o] = v;
+                a.ob[o] = f32_to_bf16(v);
+            } else {
+                const size_t pi = ((size_t)rr * a.nq + hh) * a.n_chunks + c;
+                a.part_o[pi * HD + e] = acc;
+                if (e == 0) { a.part_m[pi] = M; a.part_l[pi] = L; }
+            }
         }
         __syncthreads();
     }
-
-    // the last workgroup of this (sequence, kv head) merges the chunk partials; every thread publishes
-    // its own partial stores before the arrival is counted
-    const int n_live = last_pos / CT + 1;
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const uint32_t t = atomicAdd(&a.cnt[b * a.kv.n_kv + kvh], 1u);
-        s_last = (t == (uint32_t)(n_live - 1));
-        if (s_last) a.cnt[b * a.kv.n_kv + kvh] = 0;
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    const volatile float *pm = a.part_m, *pl = a.part_l, *po = a.part_o;
-    for (int idx = threadIdx.x; idx < QN * HD; idx += 256) {
-        const int qj = idx / HD, e = idx % HD;
-        const int rr = r_first + qj % a.rps, hh = kvh * G + qj / a.rps;
-        const int nc = a.row_pos[rr] / CT + 1;  // chunks that hold a position this row may see
-        const size_t pb = ((size_t)rr * a.nq + hh) * a.n_chunks;
-        float M = -INFINITY;
-        for (int cc = 0; cc < nc; ++cc) M = fmaxf(M, pm[pb + cc]);
-        float L = 0.f, acc = 0.f;
-        for (int cc = 0; cc < nc; ++cc) {
-            const float f = __expf(pm[pb + cc] - M);
-            L += pl[pb + cc] * f;
-            acc += po[(pb + cc) * HD + e] * f;
-        }
-        const float v = acc / L;
-        const size_t o = ((size_t)rr * a.nq + hh) * HD + e;
-        a.o[o] = v;
-        a.ob[o] = f32_to_bf16(v);
-    }
 }
 
-// Chunk size (a multiple of 64 positions) of the matrix-core kernel for a given capacity: at most eight
-// chunks per sequence while the capacity allows it.
-int attention_mfma_chunk(int max_seq) {
-    int spw = (max_seq + 64 * 8 - 1) / (64 * 8);
-    if (spw < 1) spw = 1;
-    if (spw > ATT_SPW_MAX) spw = ATT_SPW_MAX;
+// Merge of the chunk partials of the matrix-core kernel: o = sum_c w_c o_c with
+// w_c = exp(m_c - M) / sum_c exp(m_c - M) l_c, in chunk order.  One thread per (row, head, four channels);
+// rows of a sequence that fits one chunk were already written by attn_mfma_k.
+template <int HD>
+__global__ __launch_bounds__(256) void attn_mfma_merge_k(const AttnArgs a) {
+    if (a.active != nullptr && *a.active == 0) return;
+    constexpr int E4 = HD / 4;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= a.R * a.nq * E4) return;
+    const int e = (idx % E4) * 4, hh = (idx / E4) % a.nq, rr = idx / (E4 * a.nq);
+    const int b = rr / a.rps;
+    const int last_pos = a.row_pos[b * a.rps + a.rps - 1];
+    if (last_pos / a.chunk == 0) return;
+    const int nc = a.row_pos[rr] / a.chunk + 1;  // chunks that hold a position this row may see
+    const size_t pb = ((size_t)rr * a.nq + hh) * a.n_chunks;
+    float M = -INFINITY;
+    for (int cc = 0; cc < nc; ++cc) M = fmaxf(M, a.part_m[pb + cc]);
+    float L = 0.f;
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    for (int cc = 0; cc < nc; ++cc) {
+        const float f = __expf(a.part_m[pb + cc] - M);
+        const f32x4_t po = *reinterpret_cast<const f32x4_t *>(a.part_o + (pb + cc) * HD + e);
+        L += a.part_l[pb + cc] * f;
+        acc[0] += po[0] * f; acc[1] += po[1] * f; acc[2] += po[2] * f; acc[3] += po[3] * f;
+    }
+    const float inv = 1.f / L;
+    acc[0] *= inv; acc[1] *= inv; acc[2] *= inv; acc[3] *= inv;
+    const size_t o = ((size_t)rr * a.nq + hh) * HD + e;
+    *reinterpret_cast<f32x4_t *>(a.o + o) = acc;
+    u32x2_t ob;
+    ob.x = pack_bf16x2(acc[0], acc[1]);
+    ob.y = pack_bf16x2(acc[2], acc[3]);
+    *reinterpret_cast<u32x2_t *>(a.ob + o) = ob;
+}
+
+// Chunk size of the matrix-core kernel for a given capacity: 64 * 2^k positions, the smallest that keeps
+// a sequence within 16 chunks (more, shorter chunks mean more workgroups but a longer merge).
+int attention_mfma_chunk(int max_seq, int wanted) {
+    if (wanted == 64 || wanted == 128 || wanted == 256 || wanted == 512) {
+        if ((max_seq + wanted - 1) / wanted <= ATT_NC_MAX) return wanted;
+    }
+    int spw = 1;
+    while (spw < ATT_SPW_MAX && (max_seq + 64 * spw - 1) / (64 * spw) > 16) spw *= 2;
     return 64 * spw;
 }
 
 bool attention_uses_mfma(const AttnArgs &a, int hd) {
-    return a.kv_dtype == DT_BF16 && a.qb != nullptr && a.cnt != nullptr && a.kv.page_tokens % 4 == 0 &&
+    return a.kv_dtype == DT_BF16 && a.qb != nullptr && a.kv.page_tokens % 4 == 0 &&
            (hd == 32 || hd == 64 || hd == 128);
+}
+
+template <int HD>
+static hipError_t launch_attn_mfma(const AttnArgs &a, dim3 grid, hipStream_t s) {
+    switch (a.chunk / 64) {
+        case 1: hipLaunchKernelGGL((attn_mfma_k<HD, 1>), grid, dim3(256), 0, s, a); break;
+        case 2: hipLaunchKernelGGL((attn_mfma_k<HD, 2>), grid, dim3(256), 0, s, a); break;
+        case 4: hipLaunchKernelGGL((attn_mfma_k<HD, 4>), grid, dim3(256), 0, s, a); break;
+        default: hipLaunchKernelGGL((attn_mfma_k<HD, 8>), grid, dim3(256), 0, s, a); break;
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess || a.n_chunks == 1) return e;
+    const int items = a.R * a.nq * (HD / 4);
+    hipLaunchKernelGGL(attn_mfma_merge_k<HD>, dim3((items + 255) / 256), dim3(256), 0, s, a);
+    return hipGetLastError();
 }
 
 // a.chunk / a.n_chunks: 64 and ceil(max_seq / 64) for the plain kernel, attention_mfma_chunk() and the
@@ -284,12 +315,13 @@ bool attention_uses_mfma(const AttnArgs &a, int hd) {
 hipError_t launch_attention(const AttnArgs &a, int hd, hipStream_t s) {
     const int B = a.R / a.rps;
     if (attention_uses_mfma(a, hd)) {
-        if (a.chunk % 64 || a.chunk < 64 || a.chunk > 64 * ATT_SPW_MAX) return hipErrorInvalidValue;
+        const int spw = a.chunk / 64;
+        if (a.chunk % 64 || (spw != 1 && spw != 2 && spw != 4 && spw != 8) || a.n_chunks > ATT_NC_MAX)
+            return hipErrorInvalidValue;
         const dim3 grid(a.n_chunks, a.kv.n_kv, B);
-        if (hd == 32) hipLaunchKernelGGL(attn_mfma_k<32>, grid, dim3(256), 0, s, a);
-        else if (hd == 64) hipLaunchKernelGGL(attn_mfma_k<64>, grid, dim3(256), 0, s, a);
-        else hipLaunchKernelGGL(attn_mfma_k<128>, grid, dim3(256), 0, s, a);
-        return hipGetLastError();
+        if (hd == 32) return launch_attn_mfma<32>(a, grid, s);
+        if (hd == 64) return launch_attn_mfma<64>(a, grid, s);
+        return launch_attn_mfma<128>(a, grid, s);
     }
     if (a.rps > ATT_RPS_MAX || a.chunk != ATT_CT) return hipErrorInvalidValue;
     hipLaunchKernelGGL(attn_simple_k, dim3(a.n_chunks, a.nq, B), dim3(256), 0, s, a);

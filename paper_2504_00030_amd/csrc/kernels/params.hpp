@@ -113,7 +113,6 @@ struct AttnArgs {
     float *o;                // [R][nq*hd]
     uint16_t *ob;            // bf16 copy
     const int32_t *active;
-    uint32_t *cnt;           // [B][n_kv] arrival counters of the matrix-core kernel (zero between launches)
 };
 
 // Sampling configuration shared by the sampler kernels.
@@ -177,7 +176,8 @@ bool gemv_wavedot_uses_split(int epi, int Ntot, int K, int R, int w_dtype);
 int gemv_wavedot_tile_cols(int epi, int Ntot, int K, int R, int w_dtype);
 int gemv_wavedot_pick_rpw(int epi, int N, int K, int R, int w_dtype);
 hipError_t launch_attention(const AttnArgs &a, int hd, hipStream_t s);
-int attention_mfma_chunk(int max_seq);
+constexpr int ATT_NC_MAX = 32;  // chunks per sequence the matrix-core attention kernel can merge
+int attention_mfma_chunk(int max_seq, int wanted);  // wanted: 0 = automatic, else 64 / 128 / 256 / 512
 bool attention_uses_mfma(const AttnArgs &a, int hd);
 hipError_t launch_draft_sample(const DraftSampleArgs &a, hipStream_t s);
 hipError_t launch_accept(const AcceptArgs &a, hipStream_t s);

@@ -82,7 +82,7 @@ def test_gemv_mfma_matches_fp64_matmul(R, N, K):
 
 def _run_pair(cfg, *, controller, temperature, seed=0, n_generate=None, prompt_len=None, batch=1, accept_mode=0,
               alpha=None, tau=0.0, norm_jitter=0.0, use_graphs=False, page_tokens=64, weights_seed=0, block_table=None,
-              gemv_path=0):
+              gemv_path=0, attn_chunk=0):
     pk = _pk()
     n_generate = n_generate or cfg.n_generate
     prompt_len = prompt_len or cfg.prompt_len
@@ -94,7 +94,8 @@ def _run_pair(cfg, *, controller, temperature, seed=0, n_generate=None, prompt_l
     eng = pk.SpecEngine(cfg.target, Wt_g, cfg.draft, Wd_g, batch=batch,
                         max_seq=prompt_len + (n_generate + 2 * cfg.gamma_max + 4) * (4 if batch > 1 else 1),
                         gamma_max=cfg.gamma_max, temperature=temperature, seed=seed, accept_mode=accept_mode,
-                        page_tokens=page_tokens, use_graphs=use_graphs, gemv_path=gemv_path)
+                        page_tokens=page_tokens, use_graphs=use_graphs, gemv_path=gemv_path,
+                        attn_chunk=attn_chunk)
     if block_table is not None:
         eng.set_block_table(block_table(eng))
     if alpha is not None:
@@ -189,6 +190,17 @@ def test_small_bf16_pair_end_to_end(path, temperature):
 def test_small_bf16_pair_head_sizes_64_and_128():
     cfg = synth.pair("small-bf16-hd128")
     c, toks, trace = _run_pair(cfg, controller="gammatune", temperature=1.0, seed=3, norm_jitter=0.05, n_generate=96)
+    _assert_clean(c, full_coverage=False)
+    assert c.max_logit_err <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("attn_chunk", [64, 128, 256, 512])
+@pytest.mark.parametrize("pair", ["small-bf16", "small-bf16-hd128"])
+def test_small_bf16_pair_attention_chunk_sizes(pair, attn_chunk):
+    # prompt of 300 tokens: several chunks at 64 / 128 / 256 (merged by the last workgroup), a single one at 512
+    cfg = synth.pair(pair)
+    c, toks, trace = _run_pair(cfg, controller="gammatune", temperature=1.0, seed=5, prompt_len=300, n_generate=40,
+                               attn_chunk=attn_chunk, page_tokens=16)
     _assert_clean(c, full_coverage=False)
     assert c.max_logit_err <= TOL["bf16"]
 
