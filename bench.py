@@ -206,6 +206,7 @@ def main():
                          f"V{cfg.target.vocab}, draft {cfg.draft.n_layers}L d{cfg.draft.d_model}; batch 1, prompt {n_prompt}, "
                          f"generate {n_gen}; {args.controller} gamma in [1,{cfg.gamma_max}] gamma0 {args.gamma0}, "
                          f"T={args.temperature}, forced alpha {args.alpha}, tau {tau}; seeded random-init weights"),
+            "step": f"one generation of {n_gen} tokens (prefill excluded)",
             "graphs": not args.no_graphs, "spec_steps": stats["spec_steps"], "tokens_per_spec_step": tokens_per_step,
             "mean_gamma": mean_gamma, "mean_accepted": stats["accepted"] / max(stats["spec_steps"], 1),
             "mean_drafted": stats["drafted"] / max(stats["spec_steps"], 1),

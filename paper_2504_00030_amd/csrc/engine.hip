@@ -303,10 +303,13 @@ KVCache kv_of(const spec_ctx *c, const ModelRT &m, int l) {
 }
 
 // Bracket the next launch with an event pair when its kernel class is being timed.
+// Event pair around the launches of one kernel class.  With `in_dispatch` the launcher hands the pair to
+// the dispatch itself (kernel start / end); otherwise the pair is recorded on the stream around the launch.
 struct ProfScope {
     spec_ctx *c;
-    bool on;
-    ProfScope(spec_ctx *c_, const ModelRT &m, int epi) : c(c_), on(false) {
+    bool on, in_dispatch;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    ProfScope(spec_ctx *c_, const ModelRT &m, int epi, bool in_dispatch_) : c(c_), on(false), in_dispatch(in_dispatch_) {
         if (c->prof_epi != epi || c->capturing) return;
         if ((c->prof_model == 1) != (&m == &c->tgt)) return;
         if (c->prof_used + 2 > c->prof_events.size()) {
@@ -315,11 +318,12 @@ struct ProfScope {
             c->prof_events.push_back(a);
             c->prof_events.push_back(b);
         }
-        on = hipEventRecord(c->prof_events[c->prof_used], c->stream) == hipSuccess;
+        on = in_dispatch || hipEventRecord(c->prof_events[c->prof_used], c->stream) == hipSuccess;
+        if (on && in_dispatch) { ev0 = c->prof_events[c->prof_used]; ev1 = c->prof_events[c->prof_used + 1]; }
     }
     ~ProfScope() {
         if (!on) return;
-        (void)hipEventRecord(c->prof_events[c->prof_used + 1], c->stream);
+        if (!in_dispatch) (void)hipEventRecord(c->prof_events[c->prof_used + 1], c->stream);
         c->prof_used += 2;
     }
 };
@@ -335,7 +339,7 @@ bool use_mfma(const spec_ctx *c, const ModelRT &m, int R) {
 // copy of the same matrices.  Returns the number of workgroups through *blocks.
 int launch_proj(spec_ctx *c, ModelRT &m, GemvArgs a, int epi, const void *tiled, int Ntot, int *blocks,
                 int *tile_cols) {
-    ProfScope ps_(c, m, epi);
+    ProfScope ps_(c, m, epi, use_mfma(c, m, a.R));
     if (use_mfma(c, m, a.R)) {
         a.w0 = tiled; a.w1 = a.w2 = nullptr;
         const int ng = gemv_mfma_groups_per_wg(epi, Ntot, a.K, a.R, 0);
@@ -345,7 +349,7 @@ int launch_proj(spec_ctx *c, ModelRT &m, GemvArgs a, int epi, const void *tiled,
         if (tile_cols) *tile_cols = 16 * ng;
         if (epi == EPI_LOGITS && nb > m.tiles_cap) return fail(c, SPEC_EINVAL, "logits tiling exceeds the partial buffers");
         if (epi == EPI_RESID && nb > SSQ_STRIDE) return fail(c, SPEC_EINVAL, "too many statistics slots");
-        HIPCHK(c, launch_gemv_mfma(a, epi, 0, c->stream));
+        HIPCHK(c, launch_gemv_mfma(a, epi, 0, ps_.ev0, ps_.ev1, c->stream));
         return SPEC_OK;
     }
     const bool split = gemv_wavedot_uses_split(epi, Ntot, a.K, a.R, m.s.dtype);
@@ -981,7 +985,7 @@ int spec_k_gemv(const void *w, int32_t dtype, int32_t N, int32_t K, const float 
         int rc = SPEC_OK;
         if (launch_cast_to_bf16(x, xb, (int64_t)R * K, st) != hipSuccess) rc = SPEC_EHIP;
         a.xb = xb;
-        if (rc == SPEC_OK && launch_gemv_mfma(a, EPI_PLAIN, 0, st) != hipSuccess) rc = SPEC_EHIP;
+        if (rc == SPEC_OK && launch_gemv_mfma(a, EPI_PLAIN, 0, nullptr, nullptr, st) != hipSuccess) rc = SPEC_EHIP;
         if (hipStreamSynchronize(st) != hipSuccess) rc = SPEC_EHIP;
         (void)hipFree(xb);
         return rc;
@@ -1003,7 +1007,7 @@ int spec_k_gemv_tiled(const void *w_tiled, int32_t N, int32_t K, const void *x_b
     }
     GemvArgs a{};
     a.w0 = w_tiled; a.n0 = N; a.K = K; a.R = R; a.xb = reinterpret_cast<const uint16_t *>(x_bf16); a.x_mul = 1; a.y = y;
-    if (launch_gemv_mfma(a, EPI_PLAIN, cfg, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return SPEC_EHIP;
+    if (launch_gemv_mfma(a, EPI_PLAIN, cfg, nullptr, nullptr, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return SPEC_EHIP;
     return SPEC_OK;
 }
 

@@ -9,6 +9,8 @@
 // repeat bit for bit), and the epilogue (RoPE + KV write, residual + next-norm statistics, SwiGLU,
 // logits + softmax partials) runs on the reduced tile.  The pass stays HBM-bound: one MFMA per KiB
 // of weights per 16 rows.
+#include <hip/hip_ext.h>
+
 #include "common.hpp"
 #include "epilogue.hpp"
 #include "kv.hpp"
@@ -153,10 +155,17 @@ int gemv_mfma_groups_per_wg(int epi, int Ntot, int K, int R, int forced) {
     return pick_cfg(Ntot / 16, K / 32, MB, forced).ng;
 }
 
+// Events of an optional timed launch: recorded by the dispatch itself (start and end of the kernel,
+// nothing of the launch path in between).
+struct LaunchEvents { hipEvent_t start, stop; };
+
 template <int EPI, int NG, int MB, int NW>
-static hipError_t launch_one(const GemvArgs &a, int blocks, hipStream_t s) {
+static hipError_t launch_one(const GemvArgs &a, int blocks, LaunchEvents ev, hipStream_t s) {
     if constexpr (NW * MB * NG <= 32) {
-        hipLaunchKernelGGL((gemv_mfma_k<EPI, NG, MB, NW>), dim3(blocks), dim3(NW * 64), 0, s, a);
+        if (ev.start != nullptr)
+            hipExtLaunchKernelGGL((gemv_mfma_k<EPI, NG, MB, NW>), dim3(blocks), dim3(NW * 64), 0, s, ev.start, ev.stop, 0, a);
+        else
+            hipLaunchKernelGGL((gemv_mfma_k<EPI, NG, MB, NW>), dim3(blocks), dim3(NW * 64), 0, s, a);
         return hipGetLastError();
     } else {
         return hipErrorInvalidValue;
@@ -164,29 +173,29 @@ static hipError_t launch_one(const GemvArgs &a, int blocks, hipStream_t s) {
 }
 
 template <int EPI, int NG, int NW>
-static hipError_t launch_mb(const GemvArgs &a, int MB, int blocks, hipStream_t s) {
+static hipError_t launch_mb(const GemvArgs &a, int MB, int blocks, LaunchEvents ev, hipStream_t s) {
     switch (MB) {
-        case 1: return launch_one<EPI, NG, 1, NW>(a, blocks, s);
-        case 2: return launch_one<EPI, NG, 2, NW>(a, blocks, s);
-        case 4: return launch_one<EPI, NG, 4, NW>(a, blocks, s);
-        default: return launch_one<EPI, NG, 8, NW>(a, blocks, s);
+        case 1: return launch_one<EPI, NG, 1, NW>(a, blocks, ev, s);
+        case 2: return launch_one<EPI, NG, 2, NW>(a, blocks, ev, s);
+        case 4: return launch_one<EPI, NG, 4, NW>(a, blocks, ev, s);
+        default: return launch_one<EPI, NG, 8, NW>(a, blocks, ev, s);
     }
 }
 
 template <int EPI>
-static hipError_t launch_cfg(const GemvArgs &a, int Ntot, int forced, hipStream_t s) {
+static hipError_t launch_cfg(const GemvArgs &a, int Ntot, int forced, LaunchEvents ev, hipStream_t s) {
     const int MB = a.R <= 16 ? 1 : (a.R <= 32 ? 2 : (a.R <= 64 ? 4 : 8));
     const int n_groups = Ntot / 16;
     const MfmaCfg c = pick_cfg(n_groups, a.K / 32, MB, forced);
     const int blocks = (n_groups + c.ng - 1) / c.ng;
     const int key = c.ng * 100 + c.nw;
     switch (key) {
-        case 116: return launch_mb<EPI, 1, 16>(a, MB, blocks, s);
-        case 108: return launch_mb<EPI, 1, 8>(a, MB, blocks, s);
-        case 104: return launch_mb<EPI, 1, 4>(a, MB, blocks, s);
-        case 208: return launch_mb<EPI, 2, 8>(a, MB, blocks, s);
-        case 204: return launch_mb<EPI, 2, 4>(a, MB, blocks, s);
-        case 404: return launch_mb<EPI, 4, 4>(a, MB, blocks, s);
+        case 116: return launch_mb<EPI, 1, 16>(a, MB, blocks, ev, s);
+        case 108: return launch_mb<EPI, 1, 8>(a, MB, blocks, ev, s);
+        case 104: return launch_mb<EPI, 1, 4>(a, MB, blocks, ev, s);
+        case 208: return launch_mb<EPI, 2, 8>(a, MB, blocks, ev, s);
+        case 204: return launch_mb<EPI, 2, 4>(a, MB, blocks, ev, s);
+        case 404: return launch_mb<EPI, 4, 4>(a, MB, blocks, ev, s);
     }
     return hipErrorInvalidValue;
 }
@@ -194,18 +203,20 @@ static hipError_t launch_cfg(const GemvArgs &a, int Ntot, int forced, hipStream_
 // Host-side contract: w0 is the re-tiled matrix (for QKV / SWIGLU the fused, pair-interleaved one),
 // Ntot % 16 == 0, K % 32 == 0, xb holds bf16 rows of length K, 1 <= R <= 128;
 // RESID: gridDim.x <= ssq_stride; LOGITS: n_tiles == gridDim.x.  `forced` = NG * 100 + NW overrides the
-// shape heuristic (0 = automatic).
-hipError_t launch_gemv_mfma(const GemvArgs &a, int epi, int forced, hipStream_t s) {
+// shape heuristic (0 = automatic).  With ev_start / ev_stop non-null the dispatch records them at the
+// kernel's start and end.
+hipError_t launch_gemv_mfma(const GemvArgs &a, int epi, int forced, hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t s) {
+    const LaunchEvents ev{ev_start, ev_stop};
     int Ntot = a.n0;
     if (epi == EPI_QKV) Ntot = (a.nq + 2 * a.nkv) * a.hd;
     if (epi == EPI_SWIGLU) Ntot = 2 * a.n0;
     if (a.R < 1 || a.R > 128 || Ntot % 16 || a.K % 32 || a.xb == nullptr) return hipErrorInvalidValue;
     switch (epi) {
-        case EPI_PLAIN: return launch_cfg<EPI_PLAIN>(a, Ntot, forced, s);
-        case EPI_QKV: return launch_cfg<EPI_QKV>(a, Ntot, forced, s);
-        case EPI_RESID: return launch_cfg<EPI_RESID>(a, Ntot, forced, s);
-        case EPI_SWIGLU: return launch_cfg<EPI_SWIGLU>(a, Ntot, forced, s);
-        case EPI_LOGITS: return launch_cfg<EPI_LOGITS>(a, Ntot, forced, s);
+        case EPI_PLAIN: return launch_cfg<EPI_PLAIN>(a, Ntot, forced, ev, s);
+        case EPI_QKV: return launch_cfg<EPI_QKV>(a, Ntot, forced, ev, s);
+        case EPI_RESID: return launch_cfg<EPI_RESID>(a, Ntot, forced, ev, s);
+        case EPI_SWIGLU: return launch_cfg<EPI_SWIGLU>(a, Ntot, forced, ev, s);
+        case EPI_LOGITS: return launch_cfg<EPI_LOGITS>(a, Ntot, forced, ev, s);
     }
     return hipErrorInvalidValue;
 }

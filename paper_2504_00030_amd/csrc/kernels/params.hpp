@@ -170,7 +170,8 @@ struct AcceptArgs {
 hipError_t launch_begin_draft(const State &st, const int32_t *gamma_plan, hipStream_t s);
 hipError_t launch_embed(const EmbedArgs &a, hipStream_t s);
 hipError_t launch_gemv_wavedot(const GemvArgs &a, int epi, int w_dtype, hipStream_t s);
-hipError_t launch_gemv_mfma(const GemvArgs &a, int epi, int forced_cfg, hipStream_t s);
+hipError_t launch_gemv_mfma(const GemvArgs &a, int epi, int forced_cfg, hipEvent_t ev_start, hipEvent_t ev_stop,
+                            hipStream_t s);
 int gemv_mfma_groups_per_wg(int epi, int Ntot, int K, int R, int forced_cfg);  // 16-row groups per workgroup
 bool gemv_wavedot_uses_split(int epi, int Ntot, int K, int R, int w_dtype);
 int gemv_wavedot_tile_cols(int epi, int Ntot, int K, int R, int w_dtype);
