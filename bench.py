@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--skip-roofline", action="store_true")
     ap.add_argument("--gemv-path", type=int, default=0)
     ap.add_argument("--attn-chunk", type=int, default=0)
+    ap.add_argument("--roofline-only", action="store_true",
+                    help="skip the timed generations: prefill, the event-timed decode leg and the reference copy only "
+                         "(a short run for profiler counter passes)")
     return ap.parse_args()
 
 
@@ -113,6 +116,35 @@ def cpu_baseline(cfg, Wt, Wd, tokens_per_step, mean_gamma):
     }
 
 
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "gemv_gate_up_8b_pmc.json")
+KERNEL_SOURCES = ["gemv_mfma.hip", "epilogue.hpp", "common.hpp", "params.hpp", "kv.hpp"]
+COPY_BYTES = 1 << 30
+
+
+def kernel_source_digest():
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2504_00030_amd", "csrc", "kernels", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def measured_traffic(pair):
+    """HBM bytes per launch of the roofline kernel from stored profiler counters (FETCH_SIZE and WRITE_SIZE, KiB per
+    dispatch), each scaled by what the same counter read for the plain copy of COPY_BYTES in the same run.  None when
+    no counters are stored, or when the kernel's sources changed after they were taken."""
+    if pair != "8b" or not os.path.exists(TRAFFIC_FILE):
+        return None
+    with open(TRAFFIC_FILE) as f:
+        t = json.load(f)
+    if t.get("source_sha256") != kernel_source_digest():
+        return None
+    fetch = t["kernel_fetch_kib"] * 1024.0 * (t["copy_bytes"] / (t["copy_fetch_kib"] * 1024.0))
+    write = t["kernel_write_kib"] * 1024.0 * (t["copy_bytes"] / (t["copy_write_kib"] * 1024.0))
+    return fetch + write
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -151,8 +183,10 @@ def main():
             e.set_early_stop(tau)
         return e
 
+    if args.roofline_only:
+        args.warmup = args.steps = 0
     eng = engine(not args.no_graphs)
-    stats = None
+    stats = dict(generated=0, spec_steps=0, accepted=0, drafted=0, gamma_sum=0)
     t_prefill = 0.0
     for _ in range(args.warmup):
         eng.prefill(prompts)
@@ -180,14 +214,21 @@ def main():
         e2.prefill(prompts)
         e2.profile_kernel(1, 3)  # target model, gate/up projection + SwiGLU
         c2 = make_controller(pk, args, cfg.gamma_max)
-        decode_loop(e2, c2, min(n_gen, 128))
+        decode_loop(e2, c2, min(n_gen, 32 if args.roofline_only else 128))
         n_launch, ms = e2.profile_read()
         e2.close()
+        # reference traffic for profiler byte counters: one plain copy of known size
+        src = torch.empty(COPY_BYTES, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        pk.k_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
         bytes_per_launch = 2 * cfg.target.d_ffn * cfg.target.d_model * (2 if cfg.target.dtype == "bf16" else 4)
         avg_ms = ms / max(n_launch, 1)
         achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "target gate/up projection + SwiGLU",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.pair), "kernel": "target gate/up projection + SwiGLU",
                     "launches": n_launch, "avg_us": avg_ms * 1e3, "bytes_per_launch": bytes_per_launch}
 
     tokens_per_step = stats["generated"] / max(stats["spec_steps"], 1)

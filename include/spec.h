@@ -213,6 +213,10 @@ int spec_k_gemv_tiled(const void *w_tiled, int32_t N, int32_t K, const void *x_b
  * N*K*2 bytes. */
 int spec_k_retile(const void *w, int32_t N, int32_t K, void *out, void *stream);
 
+/* dst[0..bytes) = src[0..bytes): a plain device-to-device copy kernel, 16 bytes per lane (bytes % 16 == 0, both
+ * device, 16-byte aligned, not overlapping).  Measurement aid: the known traffic that scales profiler byte counters. */
+int spec_k_copy(void *dst, const void *src, int64_t bytes, void *stream);
+
 /* out[i] = Philox4x32-10(counter = ctr[i][0..3], key = seed); ctr, out: device uint32 [n][4]. */
 int spec_k_philox(uint64_t seed, const uint32_t *ctr, int32_t n, uint32_t *out, void *stream);
 

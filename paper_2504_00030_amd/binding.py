@@ -27,7 +27,7 @@ EXPORTS = [
     "spec_init", "spec_prefill", "spec_prefill_ragged", "spec_debug_set_step", "spec_draft", "spec_draft_batch", "spec_verify", "spec_accept",
     "spec_set_forced_alpha", "spec_set_early_stop", "spec_read_tokens", "spec_debug_logits",
     "spec_debug_drafted", "spec_debug_read", "spec_debug_fill_kv", "spec_debug_set_block_table", "spec_device_bytes", "spec_profile_kernel", "spec_profile_read", "spec_destroy",
-    "spec_strerror", "spec_last_error", "spec_k_gemv", "spec_k_gemv_tiled", "spec_k_retile", "spec_k_philox", "spec_k_accept",
+    "spec_strerror", "spec_last_error", "spec_k_gemv", "spec_k_gemv_tiled", "spec_k_retile", "spec_k_copy", "spec_k_philox", "spec_k_accept",
     "gammatune_init", "gammatune_update",
 ]
 
@@ -110,6 +110,7 @@ def load() -> C.CDLL:
                                 C.c_void_p]
     lib.spec_k_gemv_tiled.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
     lib.spec_k_retile.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.spec_k_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     lib.spec_k_philox.argtypes = [C.c_uint64, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
     lib.spec_k_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_uint64,
                                   C.c_int32, C.c_void_p, C.c_void_p]
@@ -357,6 +358,12 @@ def k_retile(w, out, stream: int = 0):
     rc = load().spec_k_retile(w.data_ptr(), w.shape[0], w.shape[1], out.data_ptr(), stream)
     if rc != 0:
         raise SpecError(rc, "spec_k_retile")
+
+
+def k_copy(dst, src, stream: int = 0):
+    rc = load().spec_k_copy(dst.data_ptr(), src.data_ptr(), src.numel() * src.element_size(), stream)
+    if rc != 0:
+        raise SpecError(rc, "spec_k_copy")
 
 
 def k_philox(seed: int, ctr, out, stream: int = 0):

@@ -1019,6 +1019,12 @@ int spec_k_retile(const void *w, int32_t N, int32_t K, void *out, void *stream) 
     return SPEC_OK;
 }
 
+int spec_k_copy(void *dst, const void *src, int64_t bytes, void *stream) {
+    if (!dst || !src || bytes < 0 || bytes % 16) return SPEC_EINVAL;
+    if (launch_copy(src, dst, bytes, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return SPEC_EHIP;
+    return SPEC_OK;
+}
+
 int spec_k_philox(uint64_t seed, const uint32_t *ctr, int32_t n, uint32_t *out, void *stream) {
     if (!ctr || !out || n < 0) return SPEC_EINVAL;
     if (launch_philox(seed, ctr, n, out, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return SPEC_EHIP;
