@@ -198,15 +198,17 @@ const char *spec_last_error(const spec_ctx *ctx);
 
 /* y[r][n] = sum_k x[r][k] * W[n][k].  W: device, row-major [N][K], dtype SPEC_F32 or SPEC_BF16
  * (for path SPEC_PATH_MFMA: the re-tiled copy produced by spec_k_retile, bf16 only, N % 16 == 0,
- * K % 32 == 0).  x: device fp32 [R][K]; y: device fp32 [R][N]; 1 <= R <= 128.  Asynchronous on `stream`. */
+ * K % 32 == 0).  x: device fp32 [R][K] (the matrix-core path multiplies by its two-term bf16 split, about 16
+ * significant bits); y: device fp32 [R][N]; 1 <= R <= 128.  Asynchronous on `stream`. */
 int spec_k_gemv(const void *w, int32_t dtype, int32_t N, int32_t K, const float *x, int32_t R,
                 float *y, int32_t path, void *stream);
 
 /* The matrix-core kernel alone, asynchronous, no allocation: w_tiled from spec_k_retile, x_bf16 device bf16
- * [R][K], y device fp32 [R][N].  cfg = 0 picks the launch shape from (N, K, R); cfg = 100 * groups + waves forces
+ * [R][K], x_lo_bf16 an optional second bf16 term of x (same shape, same allocation as x_bf16; NULL: none; the
+ * kernel multiplies by x_bf16 + x_lo_bf16), y device fp32 [R][N].  cfg = 0 picks the launch shape from (N, K, R); cfg = 100 * groups + waves forces
  * one of (1,16) (1,8) (1,4) (2,8) (2,4) (4,4) when groups * waves * ceil16(R)/16 <= 32 (kernel tuning). */
-int spec_k_gemv_tiled(const void *w_tiled, int32_t N, int32_t K, const void *x_bf16, int32_t R, float *y, int32_t cfg,
-                      void *stream);
+int spec_k_gemv_tiled(const void *w_tiled, int32_t N, int32_t K, const void *x_bf16, const void *x_lo_bf16, int32_t R,
+                      float *y, int32_t cfg, void *stream);
 
 /* Re-tile a row-major bf16 matrix [N][K] into the streaming layout of the matrix-core kernel:
  * 16-row groups, each group a run of 1 KiB tiles (16 rows x 32 k) stored lane-major.  out: device,

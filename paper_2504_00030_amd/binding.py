@@ -108,7 +108,8 @@ def load() -> C.CDLL:
     lib.spec_last_error.restype = C.c_char_p
     lib.spec_k_gemv.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
                                 C.c_void_p]
-    lib.spec_k_gemv_tiled.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
+    lib.spec_k_gemv_tiled.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
+                                      C.c_void_p]
     lib.spec_k_retile.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.spec_k_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     lib.spec_k_philox.argtypes = [C.c_uint64, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
@@ -348,8 +349,10 @@ def k_gemv(w, x, y, path=PATH_WAVEDOT, stream: int = 0, N=None, K=None):
         raise SpecError(rc, "spec_k_gemv")
 
 
-def k_gemv_tiled(w_tiled, N, K, x_bf16, y, cfg: int = 0, stream: int = 0):
-    rc = load().spec_k_gemv_tiled(w_tiled.data_ptr(), N, K, x_bf16.data_ptr(), x_bf16.shape[0], y.data_ptr(), cfg, stream)
+def k_gemv_tiled(w_tiled, N, K, x_bf16, y, cfg: int = 0, stream: int = 0, x_lo=None):
+    """x_bf16: [R][K] bf16, or [2][R][K] with x_lo = x_bf16[1] (both terms in one allocation)."""
+    rc = load().spec_k_gemv_tiled(w_tiled.data_ptr(), N, K, x_bf16.data_ptr(), None if x_lo is None else x_lo.data_ptr(),
+                                  y.shape[0], y.data_ptr(), cfg, stream)
     if rc != 0:
         raise SpecError(rc, "spec_k_gemv_tiled")
 

@@ -222,14 +222,14 @@ int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights
     const size_t R = (size_t)Rmax;
     TRY(dalloc(c, &m.x, R * d));
     TRY(dalloc(c, &m.xg, R * d));
-    TRY(dalloc(c, &m.xgb, R * d));
+    TRY(dalloc(c, &m.xgb, 2 * R * d));  // hi half, then the remainder half
     TRY(dalloc(c, &m.ssq, R * SSQ_STRIDE));
     TRY(dalloc(c, &m.q, R * qd));
-    TRY(dalloc(c, &m.qb, R * qd));
+    TRY(dalloc(c, &m.qb, 2 * R * qd));
     TRY(dalloc(c, &m.ao, R * qd));
-    TRY(dalloc(c, &m.aob, R * qd));
+    TRY(dalloc(c, &m.aob, 2 * R * qd));
     TRY(dalloc(c, &m.act, R * s.d_ffn));
-    TRY(dalloc(c, &m.actb, R * s.d_ffn));
+    TRY(dalloc(c, &m.actb, 2 * R * s.d_ffn));
     TRY(dalloc(c, &m.row_pos, R));
     TRY(dalloc(c, &m.row_seq, R));
 
@@ -384,14 +384,17 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
 
     EmbedArgs e{};
     e.st = c->st; e.plan = plan; e.R = R; e.embed = m.embed; e.dtype = s.dtype; e.d = d; e.vocab = s.vocab;
-    e.g_next = m.attn_norm[0]; e.x = m.x; e.xg = m.xg; e.xgb = m.xgb; e.ssq_out = m.ssq; e.ssq_stride = SSQ_STRIDE;
+    // bf16 activation buffers hold a hi half and, Rmax rows later, the remainder half (matrix-core path)
+    const int64_t RM = m.mfma_ok ? (int64_t)m.Rmax : 0;
+    const int64_t xgb_lo = RM * s.d_model, qb_lo = RM * s.n_q_heads * s.head_dim, aob_lo = qb_lo, actb_lo = RM * s.d_ffn;
+    e.g_next = m.attn_norm[0]; e.x = m.x; e.xg = m.xg; e.xgb = m.xgb; e.xgb_lo = xgb_lo; e.ssq_out = m.ssq; e.ssq_stride = SSQ_STRIDE;
     e.row_pos = m.row_pos; e.row_seq = m.row_seq;
     HIPCHK(c, launch_embed(e, st));
     int slots = 1;
 
-    auto base = [&](int K, const float *x, const uint16_t *xb) {
+    auto base = [&](int K, const float *x, const uint16_t *xb, int64_t xb_lo) {
         GemvArgs a{};
-        a.K = K; a.R = R; a.x = x; a.xb = xb; a.x_mul = 1; a.x_add = 0; a.eps = s.rms_eps; a.active = active;
+        a.K = K; a.R = R; a.x = x; a.xb = xb; a.xb_lo = xb_lo; a.x_mul = 1; a.x_add = 0; a.eps = s.rms_eps; a.active = active;
         a.ssq_stride = SSQ_STRIDE;
         return a;
     };
@@ -399,11 +402,11 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
     const bool tiled = m.mfma_ok;
     for (int l = 0; l < s.n_layers; ++l) {
         {   // fused QKV projection + RoPE + KV write
-            GemvArgs a = base(d, m.xg, m.xgb);
+            GemvArgs a = base(d, m.xg, m.xgb, xgb_lo);
             a.w0 = m.wq[l]; a.w1 = m.wk[l]; a.w2 = m.wv[l];
             a.n0 = qd; a.n1 = a.n2 = kvd;
             a.ssq_in = m.ssq; a.ssq_in_slots = slots;
-            a.y = m.q; a.yb = m.qb; a.nq = s.n_q_heads; a.nkv = s.n_kv_heads; a.hd = s.head_dim;
+            a.y = m.q; a.yb = m.qb; a.yb_lo = qb_lo; a.nq = s.n_q_heads; a.nkv = s.n_kv_heads; a.hd = s.head_dim;
             a.rope_cos = m.rope_cos; a.rope_sin = m.rope_sin; a.row_pos = m.row_pos; a.row_seq = m.row_seq;
             a.kv = kv_of(c, m, l); a.kv_dtype = s.dtype;
             TRY(launch_proj(c, m, a, EPI_QKV, tiled ? m.t_qkv[l] : nullptr, qd + 2 * kvd, nullptr, nullptr));
@@ -414,6 +417,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             t.row_pos = m.row_pos; t.row_seq = m.row_seq; t.chunk = ATT_CHUNK; t.n_chunks = m.n_chunks;
             t.scale = 1.0f / std::sqrt((float)s.head_dim);
             t.part_m = m.part_m; t.part_l = m.part_l; t.part_o = m.part_o; t.o = m.ao; t.ob = m.aob; t.active = active;
+            t.qb_lo = qb_lo; t.ob_lo = aob_lo;
             if (attention_uses_mfma(t, s.head_dim)) {
                 const int chunk = attention_mfma_chunk(c->cfg.max_seq, c->cfg.attn_chunk);
                 const int nch = (c->cfg.max_seq + chunk - 1) / chunk;
@@ -423,28 +427,28 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             HIPCHK(c, launch_attention(t, s.head_dim, st));
         }
         {   // output projection + residual
-            GemvArgs a = base(qd, m.ao, m.aob);
+            GemvArgs a = base(qd, m.ao, m.aob, aob_lo);
             a.w0 = m.wo[l]; a.n0 = d;
-            a.xres = m.x; a.g_next = m.ffn_norm[l]; a.xg = m.xg; a.xgb = m.xgb; a.ssq_out = m.ssq;
+            a.xres = m.x; a.g_next = m.ffn_norm[l]; a.xg = m.xg; a.xgb = m.xgb; a.xgb_lo = xgb_lo; a.ssq_out = m.ssq;
             TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wo[l] : nullptr, d, &slots, nullptr));
         }
         {   // gate / up projections + SwiGLU
-            GemvArgs a = base(d, m.xg, m.xgb);
+            GemvArgs a = base(d, m.xg, m.xgb, xgb_lo);
             a.w0 = m.wg[l]; a.w1 = m.wu[l]; a.n0 = ffn;
             a.ssq_in = m.ssq; a.ssq_in_slots = slots;
-            a.y = m.act; a.yb = m.actb;
+            a.y = m.act; a.yb = m.actb; a.yb_lo = actb_lo;
             TRY(launch_proj(c, m, a, EPI_SWIGLU, tiled ? m.t_gu[l] : nullptr, 2 * ffn, nullptr, nullptr));
         }
         {   // down projection + residual
-            GemvArgs a = base(ffn, m.act, m.actb);
+            GemvArgs a = base(ffn, m.act, m.actb, actb_lo);
             a.w0 = m.wd[l]; a.n0 = d;
             a.xres = m.x; a.g_next = (l + 1 < s.n_layers) ? m.attn_norm[l + 1] : m.final_norm;
-            a.xg = m.xg; a.xgb = m.xgb; a.ssq_out = m.ssq;
+            a.xg = m.xg; a.xgb = m.xgb; a.xgb_lo = xgb_lo; a.ssq_out = m.ssq;
             TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wd[l] : nullptr, d, &slots, nullptr));
         }
     }
     if (lp.want) {
-        GemvArgs a = base(d, m.xg, m.xgb);
+        GemvArgs a = base(d, m.xg, m.xgb, xgb_lo);
         a.R = lp.rows;
         a.x_mul = lp.x_mul; a.x_add = lp.x_add;
         a.w0 = m.lm_head; a.n0 = s.vocab;
@@ -977,14 +981,14 @@ int spec_k_gemv(const void *w, int32_t dtype, int32_t N, int32_t K, const float 
     GemvArgs a{};
     a.w0 = w; a.n0 = N; a.K = K; a.R = R; a.x = x; a.x_mul = 1; a.y = y;
     if (path == SPEC_PATH_MFMA) {
-        // x is rounded to bf16 into a scratch copy: the matrix-core kernel reads 16-bit rows
+        // x is split into two bf16 terms in a scratch copy: the matrix-core kernel reads 16-bit rows
         if (dtype != SPEC_BF16 || N % 16 || K % 32) return SPEC_EINVAL;
         const hipStream_t st = reinterpret_cast<hipStream_t>(stream);
         uint16_t *xb = nullptr;
-        if (hipMalloc(reinterpret_cast<void **>(&xb), (size_t)R * K * 2) != hipSuccess) return SPEC_ENOMEM;
+        if (hipMalloc(reinterpret_cast<void **>(&xb), (size_t)R * K * 4) != hipSuccess) return SPEC_ENOMEM;
         int rc = SPEC_OK;
-        if (launch_cast_to_bf16(x, xb, (int64_t)R * K, st) != hipSuccess) rc = SPEC_EHIP;
-        a.xb = xb;
+        if (launch_cast_to_bf16(x, xb, (int64_t)R * K, (int64_t)R * K, st) != hipSuccess) rc = SPEC_EHIP;
+        a.xb = xb; a.xb_lo = (int64_t)R * K;
         if (rc == SPEC_OK && launch_gemv_mfma(a, EPI_PLAIN, 0, nullptr, nullptr, st) != hipSuccess) rc = SPEC_EHIP;
         if (hipStreamSynchronize(st) != hipSuccess) rc = SPEC_EHIP;
         (void)hipFree(xb);
@@ -995,8 +999,8 @@ int spec_k_gemv(const void *w, int32_t dtype, int32_t N, int32_t K, const float 
     return SPEC_OK;
 }
 
-int spec_k_gemv_tiled(const void *w_tiled, int32_t N, int32_t K, const void *x_bf16, int32_t R, float *y, int32_t cfg,
-                      void *stream) {
+int spec_k_gemv_tiled(const void *w_tiled, int32_t N, int32_t K, const void *x_bf16, const void *x_lo_bf16, int32_t R,
+                      float *y, int32_t cfg, void *stream) {
     if (!w_tiled || !x_bf16 || !y || N < 16 || K < 32 || N % 16 || K % 32 || R < 1 || R > 128) return SPEC_EINVAL;
     if (cfg != 0) {
         const int ng = cfg / 100, nw = cfg % 100;
@@ -1007,6 +1011,7 @@ int spec_k_gemv_tiled(const void *w_tiled, int32_t N, int32_t K, const void *x_b
     }
     GemvArgs a{};
     a.w0 = w_tiled; a.n0 = N; a.K = K; a.R = R; a.xb = reinterpret_cast<const uint16_t *>(x_bf16); a.x_mul = 1; a.y = y;
+    if (x_lo_bf16) a.xb_lo = reinterpret_cast<const uint16_t *>(x_lo_bf16) - a.xb;
     if (launch_gemv_mfma(a, EPI_PLAIN, cfg, nullptr, nullptr, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return SPEC_EHIP;
     return SPEC_OK;
 }

@@ -152,18 +152,22 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
             vf[sl][et] = *reinterpret_cast<const u32x2_t *>(vp + vb + (size_t)(16 * et) * a.kv.page_tokens);
     }
 
+    const bool has_qlo = a.qb_lo != 0;
     const int QT = (QN + 15) / 16;
     for (int qt = 0; qt < QT; ++qt) {
-        // query handled by this lane in the score product (column l16 of S^T)
+        // query handled by this lane in the score product (column l16 of S^T); q enters as hi + lo bf16 terms
         const int qi = min(qt * 16 + l16, QN - 1);
         const int gq = qi / a.rps, i = qi % a.rps;
         const int r = r_first + i, h = kvh * G + gq;
         const int qpos = a.row_pos[r];
-        u32x4_t qf[ES];
+        u32x4_t qf[ES], ql[ES];
         {
             const bf16_t *qp = a.qb + ((size_t)r * a.nq + h) * HD + 8 * g;
 #pragma unroll
-            for (int s = 0; s < ES; ++s) qf[s] = *reinterpret_cast<const u32x4_t *>(qp + 32 * s);
+            for (int s = 0; s < ES; ++s) {
+                qf[s] = *reinterpret_cast<const u32x4_t *>(qp + 32 * s);
+                ql[s] = has_qlo ? *reinterpret_cast<const u32x4_t *>(qp + a.qb_lo + 32 * s) : u32x4_t{0u, 0u, 0u, 0u};
+            }
         }
         // scores of every slab of this wave; S[sl][v] = (position tw + 4 g + v, query l16)
         f32x4_t S[SPW];
@@ -173,9 +177,12 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
             const int tw = t0 + 16 * (wave + 4 * sl);
             f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < ES; ++s)
+            for (int s = 0; s < ES; ++s) {
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kf[sl][s]),
                                                               __builtin_bit_cast(bf16x8_t, qf[s]), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kf[sl][s]),
+                                                              __builtin_bit_cast(bf16x8_t, ql[s]), acc, 0, 0, 0);
+            }
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const bool vis = (tw + 4 * g + v) <= qpos;
@@ -198,13 +205,19 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
                 p[v] = m == -INFINITY ? 0.f : __expf(S[sl][v] - m);
                 l += p[v];
             }
-            u32x2_t pw;
+            // probabilities as hi + lo bf16 terms as well
+            u32x2_t pw, pl;
             pw.x = pack_bf16x2(p[0], p[1]);
             pw.y = pack_bf16x2(p[2], p[3]);
+            pl.x = pack_bf16x2(p[0] - bf16_lo(pw.x), p[1] - bf16_hi(pw.x));
+            pl.y = pack_bf16x2(p[2] - bf16_lo(pw.y), p[3] - bf16_hi(pw.y));
 #pragma unroll
-            for (int et = 0; et < ET; ++et)
+            for (int et = 0; et < ET; ++et) {
                 O[et] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, pw),
                                                                   __builtin_bit_cast(s16x4_t, vf[sl][et]), O[et], 0, 0, 0);
+                O[et] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, pl),
+                                                                  __builtin_bit_cast(s16x4_t, vf[sl][et]), O[et], 0, 0, 0);
+            }
         }
         l += __shfl_xor(l, 16, WAVE);
         l += __shfl_xor(l, 32, WAVE);
@@ -233,7 +246,7 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
                 const float v = acc / L;
                 const size_t o = ((size_t)rr * a.nq + hh) * HD + e;
                 a.o[o] = v;
-                a.ob[o] = f32_to_bf16(v);
+                store_split_bf16(a.ob, o, a.ob_lo, v);
             } else {
                 const size_t pi = ((size_t)rr * a.nq + hh) * a.n_chunks + c;
                 a.part_o[pi * HD + e] = acc;
@@ -277,6 +290,12 @@ __global__ __launch_bounds__(256) void attn_mfma_merge_k(const AttnArgs a) {
     ob.x = pack_bf16x2(acc[0], acc[1]);
     ob.y = pack_bf16x2(acc[2], acc[3]);
     *reinterpret_cast<u32x2_t *>(a.ob + o) = ob;
+    if (a.ob_lo) {
+        u32x2_t lo;
+        lo.x = pack_bf16x2(acc[0] - bf16_lo(ob.x), acc[1] - bf16_hi(ob.x));
+        lo.y = pack_bf16x2(acc[2] - bf16_lo(ob.y), acc[3] - bf16_hi(ob.y));
+        *reinterpret_cast<u32x2_t *>(a.ob + o + a.ob_lo) = lo;
+    }
 }
 
 // Chunk size of the matrix-core kernel for a given capacity: 64 * 2^k positions, the smallest that keeps

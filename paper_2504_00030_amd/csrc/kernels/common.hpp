@@ -24,6 +24,15 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
 }
 
+// Activations feed the matrix cores as two bf16 terms, v ~= hi + lo (about 16 significant bits): the second
+// matrix instruction per tile is free in a weight-streaming kernel and keeps deep models inside the logit
+// tolerance.  `lo_off` is the element offset from a buffer's hi half to its lo half (0: no lo half).
+__device__ __forceinline__ void store_split_bf16(bf16_t *p, size_t o, int64_t lo_off, float v) {
+    const bf16_t hi = f32_to_bf16(v);
+    p[o] = hi;
+    if (lo_off) p[o + lo_off] = f32_to_bf16(v - bf16_to_f32(hi));
+}
+
 template <typename T> __device__ __forceinline__ T wave_sum(T v) {
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, WAVE);

@@ -63,7 +63,7 @@ __device__ __forceinline__ void epilogue_tile(const GemvArgs &a, const float *ti
                 const float xn = a.xres[o] + tile[r * TS + c] * scale[r];
                 a.xres[o] = xn;
                 a.xg[o] = xn * gn;
-                a.xgb[o] = f32_to_bf16(xn * gn);
+                store_split_bf16(a.xgb, o, a.xgb_lo, xn * gn);
                 sq = xn * xn;
             }
 #pragma unroll
@@ -81,7 +81,7 @@ __device__ __forceinline__ void epilogue_tile(const GemvArgs &a, const float *ti
                 const float v = gt / (1.f + __expf(-gt)) * up;
                 const size_t o = (size_t)r * a.n0 + j;
                 a.y[o] = v;
-                a.yb[o] = f32_to_bf16(v);
+                store_split_bf16(a.yb, o, a.yb_lo, v);
             }
         }
     } else if constexpr (EPI == EPI_QKV) {
@@ -107,8 +107,8 @@ __device__ __forceinline__ void epilogue_tile(const GemvArgs &a, const float *ti
                 const size_t o = (size_t)r * a.nq * a.hd + (size_t)hh * a.hd + j;
                 a.y[o] = y1;
                 a.y[o + half] = y2;
-                a.yb[o] = f32_to_bf16(y1);
-                a.yb[o + half] = f32_to_bf16(y2);
+                store_split_bf16(a.yb, o, a.yb_lo, y1);
+                store_split_bf16(a.yb, o + half, a.yb_lo, y2);
             } else {
                 const bool is_k = hh < a.nq + a.nkv;
                 const int kvh = hh - a.nq - (is_k ? 0 : a.nkv);

@@ -29,7 +29,11 @@ __global__ __launch_bounds__(NW * 64) void gemv_mfma_k(const GemvArgs a) {
     constexpr int NT = NW * 64;
     constexpr int FR = MB * NG * 256;   // floats of one wave's partial tile
     constexpr int TS = NG * 16 + 1;     // row stride of the reduced tile
-    constexpr int U = NG >= 4 ? 2 : (NG == 2 ? 4 : 8);  // k-tiles whose loads are issued together
+    // k-tiles whose loads are issued together: bounded by the registers of the weight tiles (NG per k-tile) and
+    // of the x fragments (hi and lo terms of half a batch for each of the MB row blocks)
+    constexpr int UB = NG >= 4 ? 2 : (NG == 2 ? 4 : 8);
+    constexpr int UA = 40 / (NG + MB) >= 8 ? 8 : (40 / (NG + MB) >= 4 ? 4 : (40 / (NG + MB) >= 2 ? 2 : 1));
+    constexpr int U = UA < UB ? UA : UB;
     static_assert(NW * MB * NG <= 32, "partial tiles must fit 32 KiB of LDS");
     // the wave index is made a scalar so that every branch around a matrix instruction is a scalar
     // branch: v_mfma ignores the execution mask, and a short masked block whose skip branch the compiler
@@ -58,41 +62,83 @@ __global__ __launch_bounds__(NW * 64) void gemv_mfma_k(const GemvArgs a) {
         const int g = min(g0 + ng, n_groups - 1);
         bp[ng] = reinterpret_cast<const u32x4_t *>(a.w0) + ((size_t)g * KT + kt_begin) * 64 + lane;
     }
+    // x fragments: lane l holds row 16 mb + l % 16.  Rows at or beyond R produce output rows nobody reads, so
+    // their lanes skip the loads
     const u32x4_t *ap[MB];
+    bool row_ok[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
-        const int r = min(mb * 16 + (lane & 15), R - 1);
-        const size_t xr = (size_t)(r * a.x_mul + a.x_add);
+        const int r = mb * 16 + (lane & 15);
+        row_ok[mb] = r < R;
+        const size_t xr = (size_t)(min(r, R - 1) * a.x_mul + a.x_add);
         ap[mb] = reinterpret_cast<const u32x4_t *>(a.xb + xr * K + (size_t)kt_begin * 32 + (lane >> 4) * 8);
     }
+    const bool has_lo = a.xb_lo != 0;  // x = hi + lo bf16 terms: a second matrix instruction per tile (kernel argument: scalar)
     f32x4_t acc[NG][MB];
 #pragma unroll
     for (int ng = 0; ng < NG; ++ng)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) acc[ng][mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
+    // One batch = U k-tiles.  The x fragments (short latency: L2) are fetched for half a batch at a time, the
+    // first half before the weight loads and the second after the first half's matrix instructions, so that
+    // they take half the registers; the weight loads (HBM) of the whole batch are in flight together.
+    constexpr int UH = U >= 2 ? U / 2 : 1;
     for (int kt = kt_begin; kt < kt_end; kt += U) {
-        u32x4_t bw[U][NG], aw[U][MB];
+        u32x4_t bw[U][NG], aw[UH][MB], al[UH][MB];
+        auto load_x = [&](int h) {
+#pragma unroll
+            for (int i = 0; i < UH; ++i) {
+                const int u = h * UH + i;
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    aw[i][mb] = u32x4_t{0u, 0u, 0u, 0u};
+                    al[i][mb] = u32x4_t{0u, 0u, 0u, 0u};
+                }
+                if (kt + u < kt_end) {
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        if (row_ok[mb]) {
+                            aw[i][mb] = ap[mb][4 * u];
+                            if (has_lo)
+                                al[i][mb] = *reinterpret_cast<const u32x4_t *>(
+                                    reinterpret_cast<const uint16_t *>(ap[mb] + 4 * u) + a.xb_lo);
+                        }
+                    }
+                }
+            }
+        };
+        auto multiply = [&](int h) {
+#pragma unroll
+            for (int i = 0; i < UH; ++i) {
+                const int u = h * UH + i;
+                if (kt + u < kt_end) {
+#pragma unroll
+                    for (int ng = 0; ng < NG; ++ng)
+#pragma unroll
+                        for (int mb = 0; mb < MB; ++mb) {
+                            acc[ng][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                __builtin_bit_cast(bf16x8_t, aw[i][mb]), __builtin_bit_cast(bf16x8_t, bw[u][ng]), acc[ng][mb],
+                                0, 0, 0);
+                            acc[ng][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                __builtin_bit_cast(bf16x8_t, al[i][mb]), __builtin_bit_cast(bf16x8_t, bw[u][ng]), acc[ng][mb],
+                                0, 0, 0);
+                        }
+                }
+            }
+        };
+        load_x(0);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (kt + u < kt_end) {
 #pragma unroll
                 for (int ng = 0; ng < NG; ++ng) bw[u][ng] = __builtin_nontemporal_load(bp[ng] + 64 * u);
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb) aw[u][mb] = ap[mb][4 * u];
             }
         }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (kt + u < kt_end) {
-#pragma unroll
-                for (int ng = 0; ng < NG; ++ng)
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
-                        acc[ng][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            __builtin_bit_cast(bf16x8_t, aw[u][mb]), __builtin_bit_cast(bf16x8_t, bw[u][ng]), acc[ng][mb], 0,
-                            0, 0);
-            }
+        multiply(0);
+        if (U >= 2) {
+            load_x(1);
+            multiply(1);
         }
 #pragma unroll
         for (int ng = 0; ng < NG; ++ng) bp[ng] += 64 * U;

@@ -58,7 +58,7 @@ __global__ __launch_bounds__(256) void embed_k(const EmbedArgs a) {
         const size_t o = (size_t)r * a.d + c;
         a.x[o] = v;
         a.xg[o] = v * g;
-        a.xgb[o] = f32_to_bf16(v * g);
+        store_split_bf16(a.xgb, o, a.xgb_lo, v * g);
         ss += v * v;
     }
     __shared__ float red[4];
@@ -158,14 +158,15 @@ __global__ void cast_to_f32_k(const void *src, int dtype, float *dst, int64_t n)
                               : reinterpret_cast<const float *>(src)[i];
 }
 
-__global__ void cast_to_bf16_k(const float *src, uint16_t *dst, int64_t n) {
+// dst[i] = bf16(src[i]); with lo_off != 0 also dst[lo_off + i] = bf16(src[i] - dst[i])
+__global__ void cast_to_bf16_k(const float *src, uint16_t *dst, int64_t lo_off, int64_t n) {
     const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-    if (i < n) dst[i] = f32_to_bf16(src[i]);
+    if (i < n) store_split_bf16(dst, (size_t)i, lo_off, src[i]);
 }
 
-hipError_t launch_cast_to_bf16(const float *src, uint16_t *dst, int64_t n, hipStream_t s) {
+hipError_t launch_cast_to_bf16(const float *src, uint16_t *dst, int64_t lo_off, int64_t n, hipStream_t s) {
     if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(cast_to_bf16_k, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, src, dst, n);
+    hipLaunchKernelGGL(cast_to_bf16_k, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, src, dst, lo_off, n);
     return hipGetLastError();
 }
 

@@ -46,6 +46,7 @@ struct GemvArgs {
     int32_t R;                // rows of x in this launch
     const float *x;           // fp32 [.][K] (already multiplied by the norm weight when normed)
     const uint16_t *xb;       // bf16 copy of x for the matrix-core path
+    int64_t xb_lo;            // element offset from xb to the bf16 remainder x - bf16(x) (0: none)
     int32_t x_mul, x_add;     // logical row r reads x row r * x_mul + x_add
     const float *ssq_in;      // [row][ssq_stride] partial sums of squares of the un-normed input, or null
     int32_t ssq_in_slots, ssq_stride;
@@ -60,9 +61,11 @@ struct GemvArgs {
     const float *g_next;      // [N] weight of the norm that consumes the new residual (null -> ones)
     float *xg;                // [R][N] xres * g_next (fp32)
     uint16_t *xgb;            // same, bf16
+    int64_t xgb_lo;           // offset to its remainder half (0: none)
     float *ssq_out;           // [R][ssq_stride] one slot per workgroup
     // SWIGLU / QKV second outputs
-    uint16_t *yb;             // bf16 copy of y (SWIGLU act)
+    uint16_t *yb;             // bf16 copy of y (SWIGLU act, QKV q)
+    int64_t yb_lo;            // offset to its remainder half (0: none)
     // QKV
     int32_t nq, nkv, hd;
     const float *rope_cos, *rope_sin;  // [max_seq][hd/2]
@@ -93,6 +96,7 @@ struct EmbedArgs {
     const float *g_next;
     float *x, *xg;
     uint16_t *xgb;
+    int64_t xgb_lo;
     float *ssq_out;
     int32_t ssq_stride;
     int32_t *row_pos, *row_seq;
@@ -101,6 +105,7 @@ struct EmbedArgs {
 struct AttnArgs {
     const float *q;       // [R][nq*hd], rotated
     const uint16_t *qb;   // bf16 copy (matrix-core kernel); null forces the plain kernel
+    int64_t qb_lo, ob_lo; // offsets to the remainder halves of qb / ob (0: none)
     KVCache kv;
     int32_t kv_dtype;
     int32_t R, rps, nq;
@@ -194,7 +199,7 @@ hipError_t launch_retile(const RetileArgs &a, void *out, hipStream_t s);
 hipError_t launch_philox(uint64_t seed, const uint32_t *ctr, int n, uint32_t *out, hipStream_t s);
 hipError_t launch_fill_uniform(void *dst, int64_t n, int dtype, uint64_t seed, hipStream_t s);
 hipError_t launch_copy(const void *src, void *dst, int64_t bytes, hipStream_t s);
-hipError_t launch_cast_to_bf16(const float *src, uint16_t *dst, int64_t n, hipStream_t s);
+hipError_t launch_cast_to_bf16(const float *src, uint16_t *dst, int64_t lo_off, int64_t n, hipStream_t s);
 hipError_t launch_cast_to_f32(const void *src, int dtype, float *dst, int64_t n, hipStream_t s);
 
 }  // namespace sd
