@@ -1012,8 +1012,8 @@ int spec_k_gemv_tiled(const void *w_tiled, int32_t N, int32_t K, const void *x_b
     GemvArgs a{};
     a.w0 = w_tiled; a.n0 = N; a.K = K; a.R = R; a.xb = reinterpret_cast<const uint16_t *>(x_bf16); a.x_mul = 1; a.y = y;
     if (x_lo_bf16) a.xb_lo = reinterpret_cast<const uint16_t *>(x_lo_bf16) - a.xb;
-    if (launch_gemv_mfma(a, EPI_PLAIN, cfg, nullptr, nullptr, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return SPEC_EHIP;
-    return SPEC_OK;
+    const hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    return launch_gemv_mfma(a, EPI_PLAIN, cfg, nullptr, nullptr, st) == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 
 int spec_k_retile(const void *w, int32_t N, int32_t K, void *out, void *stream) {

@@ -38,13 +38,12 @@ __device__ __forceinline__ const WT *packed_row(const GemvArgs &a, int p, int TW
     }
 }
 
-// tile: LDS, element (r, c) at tile[r * TS + c]; scale: LDS [R]; t: tile index (blockIdx.x);
-// NT: threads in the workgroup; Ntot: total packed rows of the fused matrix.
+// tile: LDS, element (r, c) at tile[r * TS + c]; scale: LDS [R]; t: tile index; NT: threads that share the
+// tile (whole waves), tid: this thread's index among them; Ntot: total packed rows of the fused matrix.
 template <int EPI, int TW, int NT>
 __device__ __forceinline__ void epilogue_tile(const GemvArgs &a, const float *tile, int TS, const float *scale, int R,
-                                              int t, int Ntot) {
+                                              int t, int Ntot, int tid) {
     static_assert(TW >= 8 && TW <= 64 && (TW & (TW - 1)) == 0, "tile width");
-    const int tid = threadIdx.x;
     const int n_base = t * TW;
     if constexpr (EPI == EPI_PLAIN) {
         for (int idx = tid; idx < R * TW; idx += NT) {

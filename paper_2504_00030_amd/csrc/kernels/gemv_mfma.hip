@@ -63,17 +63,23 @@ __global__ __launch_bounds__(NW * 64) void gemv_mfma_k(const GemvArgs a) {
         bp[ng] = reinterpret_cast<const u32x4_t *>(a.w0) + ((size_t)g * KT + kt_begin) * 64 + lane;
     }
     // x fragments: lane l holds row 16 mb + l % 16.  Rows at or beyond R produce output rows nobody reads, so
-    // their lanes skip the loads
+    // their lanes skip the loads.  x enters as two bf16 terms, x = hi + lo.  With at most 8 rows both terms share
+    // one fragment (hi rows in 0..7, lo rows in 8..15: one load and one matrix instruction per tile, the two
+    // halves of the result are added in the reduction); otherwise the lo term takes a second fragment.
+    const bool has_lo = a.xb_lo != 0;            // kernel arguments: scalar conditions
+    const bool fold = has_lo && MB == 1 && R <= 8;
+    const bool two_terms = has_lo && !fold;
     const u32x4_t *ap[MB];
     bool row_ok[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
-        const int r = mb * 16 + (lane & 15);
+        int r = mb * 16 + (lane & 15);
+        size_t off = 0;
+        if (fold && r >= 8) { r -= 8; off = (size_t)a.xb_lo; }
         row_ok[mb] = r < R;
         const size_t xr = (size_t)(min(r, R - 1) * a.x_mul + a.x_add);
-        ap[mb] = reinterpret_cast<const u32x4_t *>(a.xb + xr * K + (size_t)kt_begin * 32 + (lane >> 4) * 8);
+        ap[mb] = reinterpret_cast<const u32x4_t *>(a.xb + off + xr * K + (size_t)kt_begin * 32 + (lane >> 4) * 8);
     }
-    const bool has_lo = a.xb_lo != 0;  // x = hi + lo bf16 terms: a second matrix instruction per tile (kernel argument: scalar)
     f32x4_t acc[NG][MB];
 #pragma unroll
     for (int ng = 0; ng < NG; ++ng)
@@ -100,7 +106,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_mfma_k(const GemvArgs a) {
                     for (int mb = 0; mb < MB; ++mb) {
                         if (row_ok[mb]) {
                             aw[i][mb] = ap[mb][4 * u];
-                            if (has_lo)
+                            if (two_terms)
                                 al[i][mb] = *reinterpret_cast<const u32x4_t *>(
                                     reinterpret_cast<const uint16_t *>(ap[mb] + 4 * u) + a.xb_lo);
                         }
@@ -120,9 +126,10 @@ __global__ __launch_bounds__(NW * 64) void gemv_mfma_k(const GemvArgs a) {
                             acc[ng][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                                 __builtin_bit_cast(bf16x8_t, aw[i][mb]), __builtin_bit_cast(bf16x8_t, bw[u][ng]), acc[ng][mb],
                                 0, 0, 0);
-                            acc[ng][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                __builtin_bit_cast(bf16x8_t, al[i][mb]), __builtin_bit_cast(bf16x8_t, bw[u][ng]), acc[ng][mb],
-                                0, 0, 0);
+                            if (two_terms)
+                                acc[ng][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                    __builtin_bit_cast(bf16x8_t, al[i][mb]), __builtin_bit_cast(bf16x8_t, bw[u][ng]),
+                                    acc[ng][mb], 0, 0, 0);
                         }
                 }
             }
@@ -161,6 +168,14 @@ __global__ __launch_bounds__(NW * 64) void gemv_mfma_k(const GemvArgs a) {
 #pragma unroll
         for (int w = 1; w < NW; ++w) s += part[w * FR + idx];
         const int l = idx & 63, v = (idx >> 6) & 3, t = idx >> 8;
+        if (fold) {
+            // rows 8..15 hold the lo term of rows 0..7: lane l + 32 of the same register
+            if (l >= 32) continue;
+            float s2 = part[idx + 32];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) s2 += part[w * FR + idx + 32];
+            s += s2;
+        }
         const int mb = t / NG, ng = t % NG;
         tile[(mb * 16 + (l >> 4) * 4 + v) * TS + ng * 16 + (l & 15)] = s;
     }
@@ -170,9 +185,9 @@ __global__ __launch_bounds__(NW * 64) void gemv_mfma_k(const GemvArgs a) {
         // pairs live inside each 16-row group
 #pragma unroll
         for (int ng = 0; ng < NG; ++ng)
-            if (g0 + ng < n_groups) epilogue_tile<EPI, 16, NT>(a, tile + ng * 16, TS, s_scale, R, g0 + ng, Ntot);
+            if (g0 + ng < n_groups) epilogue_tile<EPI, 16, NT>(a, tile + ng * 16, TS, s_scale, R, g0 + ng, Ntot, threadIdx.x);
     } else {
-        epilogue_tile<EPI, NG * 16, NT>(a, tile, TS, s_scale, R, blockIdx.x, Ntot);
+        epilogue_tile<EPI, NG * 16, NT>(a, tile, TS, s_scale, R, blockIdx.x, Ntot, threadIdx.x);
     }
 }
 

@@ -402,7 +402,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_wsplit_k(const GemvArgs a, const
     }
     if (t == (int)blockIdx.x) rs.finish(a, s_scale, RC);  // ends with a barrier
     else __syncthreads();
-    epilogue_tile<EPI, TW, NT>(a, tile, TW + 1, s_scale, RC, t, Ntot);
+    epilogue_tile<EPI, TW, NT>(a, tile, TW + 1, s_scale, RC, t, Ntot, threadIdx.x);
     __syncthreads();  // part / tile are reused by the next tile
   }
 }
