@@ -154,18 +154,18 @@ __device__ __forceinline__ void epilogue_tile(const GemvArgs &a, const float *ti
 constexpr int SC_ROWS = 5;
 constexpr int SC_REGS = 4;
 
-template <int NT>
+template <int NT, int ROWS = SC_ROWS>
 struct RowScales {
-    float v[SC_ROWS][SC_REGS];
+    float v[ROWS][SC_REGS];
     bool early;
 
     __device__ __forceinline__ void begin(const GemvArgs &a, int R) {
         constexpr int NW = NT / 64;
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-        early = a.ssq_in != nullptr && R <= NW * SC_ROWS && a.ssq_in_slots <= 64 * SC_REGS;
+        early = a.ssq_in != nullptr && R <= NW * ROWS && a.ssq_in_slots <= 64 * SC_REGS;
         if (!early) return;
 #pragma unroll
-        for (int i = 0; i < SC_ROWS; ++i) {
+        for (int i = 0; i < ROWS; ++i) {
             const int r = wave + NW * i;
             const int xr = min(r, R - 1) * a.x_mul + a.x_add;
 #pragma unroll
@@ -184,7 +184,7 @@ struct RowScales {
             for (int r = threadIdx.x; r < R; r += NT) scale[r] = 1.f;
         } else if (early) {
 #pragma unroll
-            for (int i = 0; i < SC_ROWS; ++i) {
+            for (int i = 0; i < ROWS; ++i) {
                 const int r = wave + NW * i;
                 float s = 0.f;
 #pragma unroll

@@ -191,6 +191,120 @@ __global__ __launch_bounds__(NW * 64) void gemv_mfma_k(const GemvArgs a) {
     }
 }
 
+// ---- persistent variant for one 16-row block of x -------------------------------------------------
+// One workgroup of 16 waves per compute unit walks the groups b, b + G, b + 2G, ...  Wave w multiplies the
+// k-tiles w, w + 16, w + 32, ... of every group (the workgroup's 16 loads of one step are 16 consecutive KiB),
+// so its x fragments do not depend on the group: they are loaded once and stay in registers.  That removes the
+// x traffic of the kernel above, where every workgroup re-reads its x rows (measured: it costs about as much as
+// a quarter of the weight stream at 9 rows with both bf16 terms).  After the matrix instructions of a group the
+// wave issues the first loads of the next group, which are then in flight while the workgroup sums the partial
+// tiles and runs the epilogue; the barriers wait on LDS only, not on those loads.
+//   KTW: k-tiles per wave (K = 512 KTW); TERMS: 1 = x as one fragment (single bf16 term, or both terms folded
+//   into rows 0-7 / 8-15 for up to 8 rows), 2 = hi and lo fragments.
+constexpr int PW = 16;  // waves
+
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+template <int EPI, int KTW, int TERMS>
+__global__ __launch_bounds__(PW * 64) void gemv_persist_k(const GemvArgs a) {
+    if (a.active != nullptr && *a.active == 0) return;
+    constexpr int NT = PW * 64;
+    // tiles per burst of loads: 8 KiB per wave, 4 where 64 registers already hold x fragments
+    constexpr int UB = KTW * TERMS >= 16 ? 4 : (KTW < 8 ? KTW : 8);
+    constexpr int NB = KTW / UB;           // bursts per group
+    static_assert(KTW % UB == 0, "bursts tile the wave's k-tiles");
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    int Ntot = a.n0;
+    if (EPI == EPI_QKV) Ntot = (a.nq + 2 * a.nkv) * a.hd;
+    if (EPI == EPI_SWIGLU) Ntot = 2 * a.n0;
+    const int n_groups = Ntot >> 4;
+    const int G = gridDim.x, b = blockIdx.x;
+    const int n_my = (n_groups - b + G - 1) / G;  // host: G <= n_groups
+    const int K = a.K, KT = K >> 5;               // host: KT == PW * KTW
+    const int R = a.R;
+
+    __shared__ float part[PW * 256];
+    __shared__ float tile[16 * 17];
+    __shared__ float s_scale[16];
+
+    RowScales<NT, 1> rs;  // 16 waves, at most 16 rows: one row per wave
+    rs.begin(a, R);
+
+    // x fragments, once
+    const bool fold = TERMS == 1 && a.xb_lo != 0;  // host: then R <= 8
+    u32x4_t xh[KTW], xl[TERMS == 2 ? KTW : 1];
+    {
+        int r = lane & 15;
+        size_t off = 0;
+        if (fold && r >= 8) { r -= 8; off = (size_t)a.xb_lo; }
+        const bool row_ok = r < R;
+        const size_t xr = (size_t)(min(r, R - 1) * a.x_mul + a.x_add);
+        const uint16_t *xp = a.xb + off + xr * K + (size_t)wave * 32 + (lane >> 4) * 8;
+#pragma unroll
+        for (int j = 0; j < KTW; ++j) {
+            xh[j] = u32x4_t{0u, 0u, 0u, 0u};
+            if (TERMS == 2) xl[j] = u32x4_t{0u, 0u, 0u, 0u};
+            if (row_ok) {
+                xh[j] = *reinterpret_cast<const u32x4_t *>(xp + (size_t)j * PW * 32);
+                if (TERMS == 2) xl[j] = *reinterpret_cast<const u32x4_t *>(xp + a.xb_lo + (size_t)j * PW * 32);
+            }
+        }
+    }
+    // weight tiles: group g, k-tile (wave + 16 j) at ((g KT + wave + 16 j) 64 + lane) 16 bytes
+    const u32x4_t *wp = reinterpret_cast<const u32x4_t *>(a.w0) + ((size_t)b * KT + wave) * 64 + lane;
+    const size_t gstride = (size_t)G * KT * 64;  // in 16-byte units, between two groups of this workgroup
+    u32x4_t bw[UB];
+#pragma unroll
+    for (int u = 0; u < UB; ++u) bw[u] = __builtin_nontemporal_load(wp + (size_t)u * PW * 64);
+
+    for (int i = 0; i < n_my; ++i) {
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xh[nb * UB + u]),
+                                                              __builtin_bit_cast(bf16x8_t, bw[u]), acc, 0, 0, 0);
+                if (TERMS == 2)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xl[nb * UB + u]),
+                                                                  __builtin_bit_cast(bf16x8_t, bw[u]), acc, 0, 0, 0);
+            }
+            // next burst: the rest of this group, or the head of the next one
+            if (nb + 1 < NB) {
+#pragma unroll
+                for (int u = 0; u < UB; ++u) bw[u] = __builtin_nontemporal_load(wp + (size_t)((nb + 1) * UB + u) * PW * 64);
+            } else if (i + 1 < n_my) {
+#pragma unroll
+                for (int u = 0; u < UB; ++u) bw[u] = __builtin_nontemporal_load(wp + gstride + (size_t)u * PW * 64);
+            }
+        }
+        wp += gstride;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) part[wave * 256 + v * 64 + lane] = acc[v];
+        if (i == 0) rs.finish(a, s_scale, R);  // row scales, once (ends with a full barrier)
+        lds_barrier();
+        // sum the K slices in wave order; register (v, lane) is x row 4 (lane / 16) + v, column lane % 16
+        if (threadIdx.x < 256) {
+            const int idx = threadIdx.x, l = idx & 63, v = idx >> 6;
+            if (!fold || l < 32) {
+                float s = part[idx];
+#pragma unroll
+                for (int w = 1; w < PW; ++w) s += part[w * 256 + idx];
+                if (fold) {
+                    // rows 8..15 hold the lo term of rows 0..7: lane l + 32 of the same register
+                    float s2 = part[idx + 32];
+#pragma unroll
+                    for (int w = 1; w < PW; ++w) s2 += part[w * 256 + idx + 32];
+                    s += s2;
+                }
+                tile[((l >> 4) * 4 + v) * 17 + (l & 15)] = s;
+            }
+        }
+        lds_barrier();
+        epilogue_tile<EPI, 16, NT>(a, tile, 17, s_scale, R, b + i * G, Ntot, threadIdx.x);
+    }
+}
+
 // ---- launch configuration ---------------------------------------------------------------------------
 // (NG, NW) by matrix shape and row blocks: enough waves to fill 256 CUs with loads in flight, at least a
 // few k-tiles per wave, and NW * MB * NG <= 32 (LDS budget of the partial tiles).
@@ -243,10 +357,43 @@ static hipError_t launch_mb(const GemvArgs &a, int MB, int blocks, LaunchEvents 
     }
 }
 
+// The persistent kernel serves one 16-row block of x whose fragments fit the registers of a 16-wave workgroup:
+// K = 512 KTW with KTW x (1 or 2 fragments) <= 16.
+static int persist_terms(const GemvArgs &a) { return (a.xb_lo != 0 && a.R > 8) ? 2 : 1; }
+static bool persist_fits(const GemvArgs &a) {
+    if (a.R > 16 || a.K % 512) return false;
+    const int ktw = a.K / 512;
+    if (ktw != 4 && ktw != 8 && ktw != 16) return false;
+    return ktw * persist_terms(a) <= 16;
+}
+
+template <int EPI, int KTW, int TERMS>
+static hipError_t launch_persist_one(const GemvArgs &a, int n_groups, LaunchEvents ev, hipStream_t s) {
+    const int G = n_groups < 256 ? n_groups : 256;  // one workgroup per compute unit
+    if (ev.start != nullptr)
+        hipExtLaunchKernelGGL((gemv_persist_k<EPI, KTW, TERMS>), dim3(G), dim3(PW * 64), 0, s, ev.start, ev.stop, 0, a);
+    else
+        hipLaunchKernelGGL((gemv_persist_k<EPI, KTW, TERMS>), dim3(G), dim3(PW * 64), 0, s, a);
+    return hipGetLastError();
+}
+
+template <int EPI>
+static hipError_t launch_persist(const GemvArgs &a, int n_groups, LaunchEvents ev, hipStream_t s) {
+    const int ktw = a.K / 512;
+    if (persist_terms(a) == 2) {
+        if (ktw == 4) return launch_persist_one<EPI, 4, 2>(a, n_groups, ev, s);
+        return launch_persist_one<EPI, 8, 2>(a, n_groups, ev, s);
+    }
+    if (ktw == 4) return launch_persist_one<EPI, 4, 1>(a, n_groups, ev, s);
+    if (ktw == 8) return launch_persist_one<EPI, 8, 1>(a, n_groups, ev, s);
+    return launch_persist_one<EPI, 16, 1>(a, n_groups, ev, s);
+}
+
 template <int EPI>
 static hipError_t launch_cfg(const GemvArgs &a, int Ntot, int forced, LaunchEvents ev, hipStream_t s) {
     const int MB = a.R <= 16 ? 1 : (a.R <= 32 ? 2 : (a.R <= 64 ? 4 : 8));
     const int n_groups = Ntot / 16;
+    if (forced == 0 && persist_fits(a)) return launch_persist<EPI>(a, n_groups, ev, s);
     const MfmaCfg c = pick_cfg(n_groups, a.K / 32, MB, forced);
     const int blocks = (n_groups + c.ng - 1) / c.ng;
     const int key = c.ng * 100 + c.nw;
