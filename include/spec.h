@@ -175,6 +175,12 @@ int spec_debug_read(spec_ctx *ctx, int32_t model, int32_t which, void *host_out,
  * length to len+1 with token 0 as the last token (verify-only sweeps).  Synchronises. */
 int spec_debug_fill_kv(spec_ctx *ctx, int32_t len, uint64_t seed);
 
+/* Overwrite positions pos0 .. pos0+n-1 of one sequence in the KV cache of one layer (model 0 = draft, 1 = target)
+ * with caller data: k_host, v_host host fp32 [n][n_kv_heads][head_dim], rounded to the cache type.  Lets a parity
+ * test give the library and its reference the same synthetic cache without a prefill.  Synchronises. */
+int spec_debug_write_kv(spec_ctx *ctx, int32_t model, int32_t layer, int32_t seq, int32_t pos0, int32_t n,
+                        const float *k_host, const float *v_host);
+
 /* Replace the logical-to-physical KV page map of both models: host int32 [batch][max_seq/page_tokens],
  * a permutation of 0..batch*pages-1.  Must be called before spec_prefill. */
 int spec_debug_set_block_table(spec_ctx *ctx, const int32_t *table);

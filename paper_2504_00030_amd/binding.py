@@ -26,7 +26,7 @@ GT_EXPAND_A, GT_LITERAL, GT_SHORT_TERM = 0, 1, 2
 EXPORTS = [
     "spec_init", "spec_prefill", "spec_prefill_ragged", "spec_debug_set_step", "spec_draft", "spec_draft_batch", "spec_verify", "spec_accept",
     "spec_set_forced_alpha", "spec_set_early_stop", "spec_read_tokens", "spec_debug_logits",
-    "spec_debug_drafted", "spec_debug_read", "spec_debug_fill_kv", "spec_debug_set_block_table", "spec_device_bytes", "spec_profile_kernel", "spec_profile_read", "spec_destroy",
+    "spec_debug_drafted", "spec_debug_read", "spec_debug_fill_kv", "spec_debug_write_kv", "spec_debug_set_block_table", "spec_device_bytes", "spec_profile_kernel", "spec_profile_read", "spec_destroy",
     "spec_strerror", "spec_last_error", "spec_k_gemv", "spec_k_gemv_tiled", "spec_k_retile", "spec_k_copy", "spec_k_philox", "spec_k_accept",
     "gammatune_init", "gammatune_update",
 ]
@@ -95,6 +95,8 @@ def load() -> C.CDLL:
     lib.spec_debug_drafted.argtypes = [C.c_void_p, C.c_int32, i32p, C.c_int32, i32p]
     lib.spec_debug_read.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int64]
     lib.spec_debug_fill_kv.argtypes = [C.c_void_p, C.c_int32, C.c_uint64]
+    lib.spec_debug_write_kv.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                        C.c_void_p]
     lib.spec_debug_set_block_table.argtypes = [C.c_void_p, i32p]
     lib.spec_profile_kernel.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     lib.spec_profile_read.argtypes = [C.c_void_p, i32p, C.POINTER(C.c_double)]
@@ -296,6 +298,13 @@ class SpecEngine:
 
     def fill_kv(self, length: int, seed: int = 0):
         self._chk(self._lib.spec_debug_fill_kv(self._ctx, int(length), int(seed)), "spec_debug_fill_kv")
+
+    def write_kv(self, model: int, layer: int, seq: int, pos0: int, k, v):
+        """k, v: numpy float32 [n][n_kv_heads][head_dim]."""
+        k = np.ascontiguousarray(k, dtype=np.float32)
+        v = np.ascontiguousarray(v, dtype=np.float32)
+        self._chk(self._lib.spec_debug_write_kv(self._ctx, model, layer, seq, pos0, k.shape[0], k.ctypes.data, v.ctypes.data),
+                  "spec_debug_write_kv")
 
     def profile_kernel(self, model: int, kind: int):
         self._chk(self._lib.spec_profile_kernel(self._ctx, model, kind), "spec_profile_kernel")

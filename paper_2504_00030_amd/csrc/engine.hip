@@ -945,6 +945,28 @@ int spec_debug_fill_kv(spec_ctx *c, int32_t len, uint64_t seed) {
     return SPEC_OK;
 }
 
+int spec_debug_write_kv(spec_ctx *c, int32_t model, int32_t layer, int32_t seq, int32_t pos0, int32_t n,
+                        const float *k_host, const float *v_host) {
+    if (!c || !k_host || !v_host) return SPEC_EINVAL;
+    ModelRT &m = model ? c->tgt : c->drf;
+    if (layer < 0 || layer >= m.s.n_layers || seq < 0 || seq >= c->cfg.batch || pos0 < 0 || n < 1 ||
+        pos0 + n > c->cfg.max_seq)
+        return fail(c, SPEC_EINVAL, "write_kv: layer, sequence or positions out of range");
+    const size_t count = (size_t)n * m.s.n_kv_heads * m.s.head_dim;
+    float *dk = nullptr, *dv = nullptr;
+    if (hipMalloc(reinterpret_cast<void **>(&dk), count * 4) != hipSuccess) return fail(c, SPEC_ENOMEM, "write_kv: staging");
+    if (hipMalloc(reinterpret_cast<void **>(&dv), count * 4) != hipSuccess) { (void)hipFree(dk); return fail(c, SPEC_ENOMEM, "write_kv: staging"); }
+    int rc = SPEC_OK;
+    if (hipMemcpy(dk, k_host, count * 4, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(dv, v_host, count * 4, hipMemcpyHostToDevice) != hipSuccess ||
+        launch_kv_write(kv_of(c, m, layer), m.s.dtype, seq, pos0, n, dk, dv, c->stream) != hipSuccess ||
+        hipStreamSynchronize(c->stream) != hipSuccess)
+        rc = fail(c, SPEC_EHIP, "write_kv: copy or launch failed");
+    (void)hipFree(dk);
+    (void)hipFree(dv);
+    return rc;
+}
+
 int spec_profile_kernel(spec_ctx *c, int32_t model, int32_t kind) {
     if (!c) return SPEC_EINVAL;
     if (model != 0 && model != 1) return fail(c, SPEC_EINVAL, "profile: model must be 0 (draft) or 1 (target)");

@@ -1,6 +1,7 @@
 // Small kernels around the projections: step bookkeeping, token embedding, weight re-tiling,
 // seeded fills, and a Philox probe for parity tests.
 #include "common.hpp"
+#include "kv.hpp"
 #include "params.hpp"
 
 namespace sd {
@@ -173,6 +174,26 @@ hipError_t launch_cast_to_bf16(const float *src, uint16_t *dst, int64_t lo_off, 
 hipError_t launch_cast_to_f32(const void *src, int dtype, float *dst, int64_t n, hipStream_t s) {
     if (n <= 0) return hipSuccess;
     hipLaunchKernelGGL(cast_to_f32_k, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, src, dtype, dst, n);
+    return hipGetLastError();
+}
+
+// Write caller-supplied K / V rows [n][n_kv][hd] (fp32) of one sequence into the paged cache at positions pos0...
+__global__ __launch_bounds__(256) void kv_write_k(KVCache kv, int kv_dtype, int seq, int pos0, int n, const float *k,
+                                                   const float *v) {
+    const int64_t total = (int64_t)n * kv.n_kv * kv.hd;
+    for (int64_t i = blockIdx.x * (int64_t)256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int j = (int)(i % kv.hd);
+        const int h = (int)((i / kv.hd) % kv.n_kv);
+        const int t = (int)(i / ((int64_t)kv.hd * kv.n_kv));
+        kv_store(kv, kv_dtype, true, seq, pos0 + t, h, j, k[i]);
+        kv_store(kv, kv_dtype, false, seq, pos0 + t, h, j, v[i]);
+    }
+}
+
+hipError_t launch_kv_write(const KVCache &kv, int kv_dtype, int seq, int pos0, int n, const float *k, const float *v,
+                           hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(kv_write_k, dim3(1024), dim3(256), 0, s, kv, kv_dtype, seq, pos0, n, k, v);
     return hipGetLastError();
 }
 

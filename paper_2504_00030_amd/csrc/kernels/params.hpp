@@ -198,6 +198,8 @@ hipError_t launch_gather_qstats(const float *q_logits, const int32_t *drafted, i
 hipError_t launch_retile(const RetileArgs &a, void *out, hipStream_t s);
 hipError_t launch_philox(uint64_t seed, const uint32_t *ctr, int n, uint32_t *out, hipStream_t s);
 hipError_t launch_fill_uniform(void *dst, int64_t n, int dtype, uint64_t seed, hipStream_t s);
+hipError_t launch_kv_write(const KVCache &kv, int kv_dtype, int seq, int pos0, int n, const float *k, const float *v,
+                           hipStream_t s);
 hipError_t launch_copy(const void *src, void *dst, int64_t bytes, hipStream_t s);
 hipError_t launch_cast_to_bf16(const float *src, uint16_t *dst, int64_t lo_off, int64_t n, hipStream_t s);
 hipError_t launch_cast_to_f32(const void *src, int dtype, float *dst, int64_t n, hipStream_t s);

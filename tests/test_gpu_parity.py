@@ -214,8 +214,8 @@ def test_small_bf16_pair_head_sizes_batch2_gamma16():
     _assert_clean(c, full_coverage=False)
 
 
-@pytest.mark.parametrize("pair_name", ["1b", "7b", "8b", "13b"])
-def test_full_width_pairs_at_reduced_depth(pair_name):
+@pytest.mark.parametrize("pair_name,batch", [("1b", 1), ("7b", 1), ("8b", 1), ("13b", 1), ("8b", 4)])
+def test_full_width_pairs_at_reduced_depth(pair_name, batch):
     """The benchmark's launch configuration (graphs, GammaTune+, T = 0.7, forced piecewise landscape, capacity of
     the 8B run so that attention uses the same chunking) at the full widths of the large pairs, two target layers
     and one draft layer deep: every kernel runs at its real shape, and the oracle still finishes in seconds.
@@ -228,21 +228,19 @@ def test_full_width_pairs_at_reduced_depth(pair_name):
     widen = lambda W: {k: ([om.as_f64(a) for a in v] if isinstance(v, list) else om.as_f64(v))
                        for k, v in synth.to_numpy_weights(W).items()}
     Wt_np, Wd_np = widen(Wt), widen(Wd)
-    prompts = synth.make_prompts(1, 200, cfg.target.vocab, 7)
+    prompts = synth.make_prompts(batch, 200, cfg.target.vocab, 7)
     alpha = synth.alpha_piecewise(64, 8)
     tau = float(np.float32(0.4))
-    eng = pk.SpecEngine(cfg.target, Wt, cfg.draft, Wd, batch=1, max_seq=1024 + 512 + 2 * 16 + 8, gamma_max=cfg.gamma_max,
+    eng = pk.SpecEngine(cfg.target, Wt, cfg.draft, Wd, batch=batch, max_seq=1024 + 512 + 2 * 16 + 8, gamma_max=cfg.gamma_max,
                         temperature=0.7, seed=0, accept_mode=pk.ACCEPT_FORCED, use_graphs=True)
     eng.set_forced_alpha(alpha)
     eng.set_early_stop(tau)
     c = run_lockstep(eng, cfg, Wt_np, Wd_np, prompts, 24, controller="gammatune", temperature=0.7, seed=0,
                      accept_mode=1, alpha=alpha, tau=tau)
     eng.close()
-    # with a 32000..128256-token vocabulary and near-flat random-init distributions almost every sampled index sits
-    # closer to a CDF edge than the bf16 margin, so no coverage is demanded: every step must agree in its logits
-    # (the harness restarts the library from the oracle's tokens after each sub-margin difference), and no
-    # decision may differ above the margin
-    _assert_clean(c, full_coverage=False, min_coverage=0.0)
+    # near-flat random-init distributions over 32000..128256 tokens put many sampled indices close to a CDF edge;
+    # with the activations carried as two bf16 terms the logits agree to a few 1e-4 and most steps still match
+    _assert_clean(c, full_coverage=False, min_coverage=0.7)
     assert c.steps_total >= 8
     assert c.max_logit_err <= TOL["bf16"]
 
@@ -270,6 +268,90 @@ def test_8b_pair_at_full_depth_and_width():
     _assert_clean(c, full_coverage=False, min_coverage=0.0)
     assert c.steps_total >= 3
     assert c.max_logit_err <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("temperature", [0.0, 0.7, 1.0])
+@pytest.mark.parametrize("vocab", [32000, 1000])
+def test_standalone_accept_kernel_on_table_models(vocab, temperature):
+    """The fused accept / resample phase alone (sampler of the verify-only sweep): draft logits N(0, std 2), target
+    logits = draft + N(0, std 1) so that both accepts and rejections occur; table models, 40 steps of k = 1..8."""
+    from oracle import spec as ospec
+    pk = _pk()
+    rng = np.random.default_rng(vocab + int(temperature * 10))
+    agree = 0
+    total = 0
+    eps = 1e-6  # fp32 logits in, fp64 arithmetic on both sides: margins far above this are demanded
+    for step in range(40):
+        k = 1 + step % 8
+        ql = (rng.standard_normal((k, vocab)) * 2.0).astype(np.float32)
+        pl = (np.concatenate([ql, ql[-1:]], 0) + rng.standard_normal((k + 1, vocab)).astype(np.float32)).astype(np.float32)
+        draft_next = lambda toks: ql[len(toks) - 1]
+        target_rows = lambda toks, kk: pl[: kk + 1]
+        cfg = ospec.StepConfig(temperature=temperature, seed=11, accept_mode=0, tau=0.0, alpha=None)
+        r = ospec.speculative_step(draft_next, target_rows, [0], k, step, 0, cfg, 0)
+        out = torch.zeros(2, dtype=torch.int32, device="cuda")
+        pk.k_accept(torch.from_numpy(pl).cuda(), torch.from_numpy(ql).cuda(),
+                    torch.tensor(r.drafted, dtype=torch.int32, device="cuda"), temperature, 11, step, out)
+        torch.cuda.synchronize()
+        A, y = (int(v) for v in out.cpu())
+        after_draft = [d for d in r.decisions if d.kind != "draft"]
+        if min((d.margin for d in after_draft), default=1.0) > eps:
+            assert (A, y) == (r.accepted, r.y), f"step {step}: gpu {(A, y)} oracle {(r.accepted, r.y)}"
+            agree += 1
+        total += 1
+    assert agree >= total * 0.9
+
+
+@pytest.mark.parametrize("batch,kv_len", [(1, 512), (1, 2048), (4, 512), (4, 1024)])
+def test_13b_verify_sweep_with_synthetic_cache(batch, kv_len):
+    """Verification passes of 2, 4, 8 and 16 rows against a seeded synthetic KV cache (no prefill), 13B-shaped target
+    at full width and two layers, one-layer draft; every sequence of a batch has its own cache contents."""
+    from oracle import model as om
+    from oracle import spec as ospec
+    from parity_utils import Compare, _compare_step, oshape
+    pk = _pk()
+    cfg = synth.shrink(synth.pair("13b"), 2, 1)
+    Wt, Wd = synth.make_pair_weights(cfg, 0, device="cuda")
+    torch.cuda.synchronize()
+    widen = lambda W: {k: ([om.as_f64(a) for a in v] if isinstance(v, list) else om.as_f64(v))
+                       for k, v in synth.to_numpy_weights(W).items()}
+    Wt_np, Wd_np = widen(Wt), widen(Wd)
+    res = Compare()
+    for gamma in (1, 3, 7, 15):
+        eng = pk.SpecEngine(cfg.target, Wt, cfg.draft, Wd, batch=batch, max_seq=kv_len + 64, gamma_max=16,
+                            temperature=1.0, seed=9)
+        eng.fill_kv(kv_len)
+        pairs = []
+        for b in range(batch):
+            pair = ospec.TransformerPair(oshape(cfg.target), Wt_np, oshape(cfg.draft), Wd_np)
+            for model, ms, cache in ((1, cfg.target, pair._ct), (0, cfg.draft, pair._cd)):
+                for l in range(ms.n_layers):
+                    k, v = synth.make_kv(kv_len, ms.n_kv_heads, ms.head_dim, 1000 * b + 10 * l + model)
+                    eng.write_kv(model, l, b, 0, k, v)
+                    # the first draft pass of a step always feeds the last two tokens, so the draft's cache entry
+                    # at position kv_len - 1 is recomputed from its token on both sides
+                    n_keep = kv_len if model == 1 else kv_len - 1
+                    cache.k[l], cache.v[l] = k[:n_keep].astype(np.float64), v[:n_keep].astype(np.float64)
+                cache.length = kv_len if model == 1 else kv_len - 1
+            pair._tt, pair._td = [0] * kv_len, [0] * (kv_len - 1)
+            pairs.append(pair)
+        eng.draft(gamma)
+        eng.verify(gamma)
+        q = eng.debug_logits(0)
+        drafted = [eng.debug_drafted(b) for b in range(batch)]
+        A, y, k = eng.accept()
+        p = eng.debug_logits(1)
+        eng.close()
+        scfg = ospec.StepConfig(temperature=1.0, seed=9, accept_mode=0, tau=0.0, alpha=None)
+        for b in range(batch):
+            r = ospec.speculative_step(pairs[b].draft_next, pairs[b].target_rows, [0] * (kv_len + 1), gamma, 0, b, scfg, 0,
+                                       keep_logits=True)
+            res.steps_total += 1
+            if _compare_step(res, f"gamma {gamma} seq {b}", r, gamma, int(k[b]), int(A[b]), int(y[b]), drafted[b], q[b],
+                             p[b], "bf16", 1.0):
+                res.steps_clean += 1
+    _assert_clean(res, full_coverage=False, min_coverage=0.0)
+    assert res.max_logit_err <= TOL["bf16"]
 
 
 def test_plain_copy_kernel():
