@@ -531,7 +531,7 @@ template <typename F> int capture(spec_ctx *c, F body, hipGraphExec_t *out) {
     hipGraph_t g = nullptr;
     const hipError_t e = hipStreamEndCapture(c->stream, &g);
     if (rc != SPEC_OK) {
-        if (g) hipGraphDestroy(g);
+        if (g) (void)hipGraphDestroy(g);
         return rc;
     }
     if (e != hipSuccess) return fail(c, SPEC_EHIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
@@ -577,14 +577,14 @@ int64_t spec_device_bytes(const spec_ctx *ctx) { return ctx ? ctx->dev_bytes : 0
 
 void spec_destroy(spec_ctx *c) {
     if (!c) return;
-    hipStreamSynchronize(c->stream);
-    for (auto &kv : c->g_draft) hipGraphExecDestroy(kv.second);
-    for (auto &kv : c->g_verify) hipGraphExecDestroy(kv.second);
-    for (auto g : c->graphs) hipGraphDestroy(g);
-    for (void *p : c->dev_allocs) hipFree(p);
-    for (void *p : c->host_allocs) hipHostFree(p);
-    for (hipEvent_t e : c->prof_events) hipEventDestroy(e);
-    if (c->own_stream) hipStreamDestroy(c->stream);
+    (void)hipStreamSynchronize(c->stream);
+    for (auto &kv : c->g_draft) (void)hipGraphExecDestroy(kv.second);
+    for (auto &kv : c->g_verify) (void)hipGraphExecDestroy(kv.second);
+    for (auto g : c->graphs) (void)hipGraphDestroy(g);
+    for (void *p : c->dev_allocs) (void)hipFree(p);
+    for (void *p : c->host_allocs) (void)hipHostFree(p);
+    for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
+    if (c->own_stream) (void)hipStreamDestroy(c->stream);
     delete c;
 }
 
@@ -690,8 +690,8 @@ int spec_set_forced_alpha(spec_ctx *c, const float *alpha, int32_t n) {
     c->scfg.alpha = p;
     c->scfg.n_alpha = n;
     // kernel arguments are baked into captured graphs
-    for (auto &kv : c->g_draft) hipGraphExecDestroy(kv.second);
-    for (auto &kv : c->g_verify) hipGraphExecDestroy(kv.second);
+    for (auto &kv : c->g_draft) (void)hipGraphExecDestroy(kv.second);
+    for (auto &kv : c->g_verify) (void)hipGraphExecDestroy(kv.second);
     c->g_draft.clear();
     c->g_verify.clear();
     return SPEC_OK;
@@ -702,7 +702,7 @@ int spec_set_early_stop(spec_ctx *c, float tau) {
     if (!(tau == tau)) return fail(c, SPEC_EINVAL, "tau is NaN");
     HIPCHK(c, hipStreamSynchronize(c->stream));
     c->scfg.tau = tau > 0.f ? tau : 0.f;
-    for (auto &kv : c->g_draft) hipGraphExecDestroy(kv.second);
+    for (auto &kv : c->g_draft) (void)hipGraphExecDestroy(kv.second);
     c->g_draft.clear();
     return SPEC_OK;
 }
@@ -1117,7 +1117,7 @@ int spec_k_accept(const float *p_logits, const float *q_logits, const int32_t *d
     ok(launch_accept(a, st));
     ok(hipMemcpyAsync(result, state + 12, sizeof(int32_t) * 2, hipMemcpyDeviceToDevice, st));
     ok(hipStreamSynchronize(st));
-    hipFree(buf);
+    (void)hipFree(buf);
     return rc;
 }
 

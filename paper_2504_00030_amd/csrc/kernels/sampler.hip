@@ -247,7 +247,7 @@ __global__ __launch_bounds__(ACC_THREADS) void accept_scan_k(const AcceptArgs a)
     const double inv_t = (double)a.cfg.inv_t;
     __shared__ double sM[ACC_ROWS_MAX], sS[ACC_ROWS_MAX];
     __shared__ int sArg[ACC_ROWS_MAX];
-    __shared__ int sA, sBonus;
+    __shared__ int sBonus;
 
     for (int i = wave; i <= k; i += ACC_THREADS / 64) {  // target rows 1..k+1 (0-based i)
         const size_t row = (size_t)b * rows + i;
@@ -287,7 +287,6 @@ __global__ __launch_bounds__(ACC_THREADS) void accept_scan_k(const AcceptArgs a)
         const unsigned long long fail = __ballot(!ok);
         const int A = fail ? __ffsll((long long)fail) - 1 : k;
         if (lane == 0) {
-            sA = A;
             a.A_dev[b] = A;
             int resid = 0, bonus = 0;
             if (greedy) {
