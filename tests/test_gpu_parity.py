@@ -372,6 +372,17 @@ def test_small_bf16_pair_batch_forced_early_stop_graphs():
     assert max(int(r["gamma"].max()) for r in trace) >= 3
 
 
+@pytest.mark.parametrize("batch,gamma", [(8, 15), (64, 1), (42, 2)])
+def test_small_bf16_pair_at_the_row_limit(batch, gamma):
+    """128 rows per verification pass (the library's limit) and a ragged 126: eight 16-row blocks of x."""
+    from dataclasses import replace
+    cfg = replace(synth.pair("small-bf16"), gamma_max=gamma)
+    c, toks, trace = _run_pair(cfg, controller=f"fixed{gamma}", temperature=1.0, seed=8, batch=batch, n_generate=12,
+                               prompt_len=20)
+    _assert_clean(c, full_coverage=False)
+    assert c.max_logit_err <= TOL["bf16"]
+
+
 def test_prompt_of_one_token_and_gamma_one():
     cfg = synth.pair("tiny")
     c, toks, _ = _run_pair(cfg, controller="fixed1", temperature=1.0, seed=8, prompt_len=1, n_generate=12)
