@@ -125,9 +125,6 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
     const int QN = G * a.rps;
     const int r_first = b * a.rps;
     const int t0 = c * CT;
-    const int last_pos = __builtin_amdgcn_readfirstlane(a.row_pos[r_first + a.rps - 1]);
-    if (t0 > last_pos) return;
-    const int n_live = last_pos / CT + 1;
     const bf16_t *kp = reinterpret_cast<const bf16_t *>(a.kv.k);
     const bf16_t *vp = reinterpret_cast<const bf16_t *>(a.kv.v);
 
@@ -135,22 +132,28 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
     __shared__ float sM[4][16], sL[4][16];
 
     // K fragment: position tw + l16, channels 32 s + 8 g .. + 8; V fragment: channel 16 et + l16, positions
-    // tw + 4 g .. + 4 (contiguous in the transposed page)
+    // tw + 4 g .. + 4 (contiguous in the transposed page).  Positions are clamped to the cache capacity only, not to
+    // the sequence length: the loads then depend on nothing but the block table and start at once; whatever finite
+    // values lie beyond the last visible position meet a zero probability.
+    const int cap = a.kv.pages_per_seq * a.kv.page_tokens;
     u32x4_t kf[SPW][ES];
     u32x2_t vf[SPW][ET];
 #pragma unroll
     for (int sl = 0; sl < SPW; ++sl) {
         const int tw = t0 + 16 * (wave + 4 * sl);
-        const int pk = min(tw + l16, last_pos);
+        const int pk = min(tw + l16, cap - 1);
         const size_t kb = kv_index_k(a.kv, b, pk, kvh, 8 * g);
 #pragma unroll
         for (int s = 0; s < ES; ++s) kf[sl][s] = *reinterpret_cast<const u32x4_t *>(kp + kb + 32 * s);
-        const int pv = min(tw + 4 * g, last_pos & ~3);
+        const int pv = min(tw + 4 * g, cap - 4);
         const size_t vb = kv_index_v(a.kv, b, pv, kvh, l16);
 #pragma unroll
         for (int et = 0; et < ET; ++et)
             vf[sl][et] = *reinterpret_cast<const u32x2_t *>(vp + vb + (size_t)(16 * et) * a.kv.page_tokens);
     }
+    const int last_pos = __builtin_amdgcn_readfirstlane(a.row_pos[r_first + a.rps - 1]);
+    if (t0 > last_pos) return;
+    const int n_live = last_pos / CT + 1;
 
     const bool has_qlo = a.qb_lo != 0;
     const int QT = (QN + 15) / 16;
@@ -259,8 +262,11 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
 
 // Merge of the chunk partials of the matrix-core kernel: o = sum_c w_c o_c with
 // w_c = exp(m_c - M) / sum_c exp(m_c - M) l_c, in chunk order.  One thread per (row, head, four channels);
-// rows of a sequence that fits one chunk were already written by attn_mfma_k.
-template <int HD>
+// rows of a sequence that fits one chunk were already written by attn_mfma_k.  The partials of all n_chunks
+// chunks (NCB at most) are fetched at once, before the row's position says how many of them count, so that
+// the kernel is one round of loads deep; chunks beyond the row's position hold stale finite numbers and are
+// masked out.
+template <int HD, int NCB>
 __global__ __launch_bounds__(256) void attn_mfma_merge_k(const AttnArgs a) {
     if (a.active != nullptr && *a.active == 0) return;
     constexpr int E4 = HD / 4;
@@ -268,19 +274,33 @@ __global__ __launch_bounds__(256) void attn_mfma_merge_k(const AttnArgs a) {
     if (idx >= a.R * a.nq * E4) return;
     const int e = (idx % E4) * 4, hh = (idx / E4) % a.nq, rr = idx / (E4 * a.nq);
     const int b = rr / a.rps;
+    const size_t pb = ((size_t)rr * a.nq + hh) * a.n_chunks;
+    float pm[NCB], pl[NCB];
+    f32x4_t po[NCB];
+#pragma unroll
+    for (int cc = 0; cc < NCB; ++cc) {
+        pm[cc] = -INFINITY; pl[cc] = 0.f; po[cc] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        if (cc < a.n_chunks) {
+            pm[cc] = a.part_m[pb + cc];
+            pl[cc] = a.part_l[pb + cc];
+            po[cc] = *reinterpret_cast<const f32x4_t *>(a.part_o + (pb + cc) * HD + e);
+        }
+    }
     const int last_pos = a.row_pos[b * a.rps + a.rps - 1];
     if (last_pos / a.chunk == 0) return;
     const int nc = a.row_pos[rr] / a.chunk + 1;  // chunks that hold a position this row may see
-    const size_t pb = ((size_t)rr * a.nq + hh) * a.n_chunks;
     float M = -INFINITY;
-    for (int cc = 0; cc < nc; ++cc) M = fmaxf(M, a.part_m[pb + cc]);
+#pragma unroll
+    for (int cc = 0; cc < NCB; ++cc) M = cc < nc ? fmaxf(M, pm[cc]) : M;
     float L = 0.f;
     f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-    for (int cc = 0; cc < nc; ++cc) {
-        const float f = __expf(a.part_m[pb + cc] - M);
-        const f32x4_t po = *reinterpret_cast<const f32x4_t *>(a.part_o + (pb + cc) * HD + e);
-        L += a.part_l[pb + cc] * f;
-        acc[0] += po[0] * f; acc[1] += po[1] * f; acc[2] += po[2] * f; acc[3] += po[3] * f;
+#pragma unroll
+    for (int cc = 0; cc < NCB; ++cc) {
+        if (cc < nc) {
+            const float f = __expf(pm[cc] - M);
+            L += pl[cc] * f;
+            acc[0] += po[cc][0] * f; acc[1] += po[cc][1] * f; acc[2] += po[cc][2] * f; acc[3] += po[cc][3] * f;
+        }
     }
     const float inv = 1.f / L;
     acc[0] *= inv; acc[1] *= inv; acc[2] *= inv; acc[3] *= inv;
@@ -325,7 +345,8 @@ static hipError_t launch_attn_mfma(const AttnArgs &a, dim3 grid, hipStream_t s) 
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.n_chunks == 1) return e;
     const int items = a.R * a.nq * (HD / 4);
-    hipLaunchKernelGGL(attn_mfma_merge_k<HD>, dim3((items + 255) / 256), dim3(256), 0, s, a);
+    if (a.n_chunks <= 16) hipLaunchKernelGGL((attn_mfma_merge_k<HD, 16>), dim3((items + 255) / 256), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((attn_mfma_merge_k<HD, ATT_NC_MAX>), dim3((items + 255) / 256), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
