@@ -48,26 +48,34 @@ def parse():
     ap.add_argument("--skip-roofline", action="store_true")
     ap.add_argument("--gemv-path", type=int, default=0)
     ap.add_argument("--attn-chunk", type=int, default=0)
+    ap.add_argument("--batch", type=int, default=1, help="sequences decoded in lock-step, one controller each "
+                                                         "(the headline metric is batch 1)")
     ap.add_argument("--roofline-only", action="store_true",
                     help="skip the timed generations: prefill, the event-timed decode leg and the reference copy only "
                          "(a short run for profiler counter passes)")
     return ap.parse_args()
 
 
-def decode_loop(eng, ctrl, n_generate):
-    gen, steps, acc, drafted, gsum = 0, 0, 0, 0, 0
-    while gen < n_generate:
-        g = ctrl.gamma
-        eng.draft(g)
-        eng.verify(g)
+def decode_loop(eng, ctrls, n_generate):
+    """Speculative steps until every sequence has n_generate new tokens; `ctrls`: one controller per sequence.
+    Counts tokens up to n_generate per sequence."""
+    B = len(ctrls)
+    gen = [0] * B
+    steps, acc, drafted, gsum = 0, 0, 0, 0
+    while min(gen) < n_generate:
+        gs = [c.gamma for c in ctrls]
+        eng.draft(gs[0] if B == 1 else np.array(gs, dtype=np.int32))
+        eng.verify(max(gs))
         A, y, k = eng.accept()
-        ctrl.update(int(A[0]), int(k[0]))
-        gen += int(A[0]) + 1
+        for b in range(B):
+            ctrls[b].update(int(A[b]), int(k[b]))
+            gen[b] += int(A[b]) + 1
+            acc += int(A[b])
+            drafted += int(k[b])
+            gsum += gs[b]
         steps += 1
-        acc += int(A[0])
-        drafted += int(k[0])
-        gsum += g
-    return dict(generated=gen, spec_steps=steps, accepted=acc, drafted=drafted, gamma_sum=gsum)
+    return dict(generated=sum(min(g, n_generate) for g in gen), spec_steps=steps, accepted=acc, drafted=drafted,
+                gamma_sum=gsum, seq_steps=steps * B)
 
 
 def make_controller(pk, args, gamma_max):
@@ -117,7 +125,7 @@ def cpu_baseline(cfg, Wt, Wd, tokens_per_step, mean_gamma):
 
 
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "gemv_gate_up_8b_pmc.json")
-KERNEL_SOURCES = ["gemv_mfma.hip", "epilogue.hpp", "common.hpp", "params.hpp", "kv.hpp"]
+KERNEL_SOURCES = ["gemv_mfma.hip", "epilogue.hpp", "common.hpp", "kv.hpp"]  # the files that hold the kernel's code
 COPY_BYTES = 1 << 30
 
 
@@ -171,11 +179,13 @@ def main():
     else:
         alpha = synth.alpha_constant(float(args.alpha), 4)
     tau = float(np.float32(0.4)) if args.controller == "gammatune+" else 0.0
-    max_seq = n_prompt + n_gen + 2 * cfg.gamma_max + 8
-    prompts = synth.make_prompts(1, n_prompt, cfg.target.vocab, 7)
+    # with several sequences the fast ones run on until the slowest has n_gen tokens
+    max_seq = n_prompt + n_gen * (1 if args.batch == 1 else 3) + 2 * cfg.gamma_max + 8
+    B = args.batch
+    prompts = synth.make_prompts(B, n_prompt, cfg.target.vocab, 7)
 
     def engine(use_graphs):
-        e = pk.SpecEngine(cfg.target, Wt, cfg.draft, Wd, batch=1, max_seq=max_seq, gamma_max=cfg.gamma_max,
+        e = pk.SpecEngine(cfg.target, Wt, cfg.draft, Wd, batch=B, max_seq=max_seq, gamma_max=cfg.gamma_max,
                           temperature=args.temperature, seed=0, accept_mode=pk.ACCEPT_FORCED, use_graphs=use_graphs,
                           gemv_path=args.gemv_path, attn_chunk=args.attn_chunk)
         e.set_forced_alpha(alpha)
@@ -190,7 +200,7 @@ def main():
     t_prefill = 0.0
     for _ in range(args.warmup):
         eng.prefill(prompts)
-        decode_loop(eng, make_controller(pk, args, cfg.gamma_max), n_gen)
+        decode_loop(eng, [make_controller(pk, args, cfg.gamma_max) for _ in range(B)], n_gen)
     total = 0.0
     for _ in range(args.steps):
         torch.cuda.synchronize()
@@ -198,14 +208,14 @@ def main():
         eng.prefill(prompts)
         torch.cuda.synchronize()
         t_prefill += time.perf_counter() - tp
-        ctrl = make_controller(pk, args, cfg.gamma_max)
+        ctrl = [make_controller(pk, args, cfg.gamma_max) for _ in range(B)]
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         stats = decode_loop(eng, ctrl, n_gen)
         torch.cuda.synchronize()
         total += time.perf_counter() - t1
     steps = max(args.steps, 1)
-    tok_s = steps * n_gen / total if total > 0 else 0.0
+    tok_s = steps * B * n_gen / total if total > 0 else 0.0
     eng.close()
 
     roofline = None
@@ -213,7 +223,7 @@ def main():
         e2 = engine(False)
         e2.prefill(prompts)
         e2.profile_kernel(1, 3)  # target model, gate/up projection + SwiGLU
-        c2 = make_controller(pk, args, cfg.gamma_max)
+        c2 = [make_controller(pk, args, cfg.gamma_max) for _ in range(B)]
         decode_loop(e2, c2, min(n_gen, 32 if args.roofline_only else 128))
         n_launch, ms = e2.profile_read()
         e2.close()
@@ -231,26 +241,28 @@ def main():
                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.pair), "kernel": "target gate/up projection + SwiGLU",
                     "launches": n_launch, "avg_us": avg_ms * 1e3, "bytes_per_launch": bytes_per_launch}
 
-    tokens_per_step = stats["generated"] / max(stats["spec_steps"], 1)
-    mean_gamma = stats["gamma_sum"] / max(stats["spec_steps"], 1)
+    seq_steps = max(stats.get("seq_steps", stats["spec_steps"]), 1)  # (sequence, speculative step) pairs
+    tokens_per_step = stats["generated"] / seq_steps
+    mean_gamma = stats["gamma_sum"] / seq_steps
     cpu = None
     if not args.skip_cpu:
         cpu = cpu_baseline(cfg, Wt, Wd, tokens_per_step, mean_gamma)
 
     line = {
-        "metric": "generated tokens/s (8B-shaped pair, bs1); verify-pass HBM GB/s % of peak" if args.pair == "8b" else f"generated tokens/s ({args.pair} pair, bs1)",
+        "metric": ("generated tokens/s (8B-shaped pair, bs1); verify-pass HBM GB/s % of peak" if (args.pair == "8b" and B == 1)
+                   else f"generated tokens/s ({args.pair} pair, bs{B})"),
         "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": 1e3 * total / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.target.dtype, "data": "synthetic",
         "config": {
             "workload": (f"{args.pair}: target {cfg.target.n_layers}L d{cfg.target.d_model} ffn{cfg.target.d_ffn} "
-                         f"V{cfg.target.vocab}, draft {cfg.draft.n_layers}L d{cfg.draft.d_model}; batch 1, prompt {n_prompt}, "
+                         f"V{cfg.target.vocab}, draft {cfg.draft.n_layers}L d{cfg.draft.d_model}; batch {B}, prompt {n_prompt}, "
                          f"generate {n_gen}; {args.controller} gamma in [1,{cfg.gamma_max}] gamma0 {args.gamma0}, "
                          f"T={args.temperature}, forced alpha {args.alpha}, tau {tau}; seeded random-init weights"),
             "step": f"one generation of {n_gen} tokens (prefill excluded)",
             "graphs": not args.no_graphs, "spec_steps": stats["spec_steps"], "tokens_per_spec_step": tokens_per_step,
-            "mean_gamma": mean_gamma, "mean_accepted": stats["accepted"] / max(stats["spec_steps"], 1),
-            "mean_drafted": stats["drafted"] / max(stats["spec_steps"], 1),
+            "mean_gamma": mean_gamma, "mean_accepted": stats["accepted"] / seq_steps,
+            "mean_drafted": stats["drafted"] / seq_steps,
             "prefill_ms": 1e3 * t_prefill / steps, "weights_s": t_weights,
         },
         "roofline": roofline, "cpu_baseline": cpu,
