@@ -48,6 +48,7 @@ def parse():
     ap.add_argument("--skip-roofline", action="store_true")
     ap.add_argument("--gemv-path", type=int, default=0)
     ap.add_argument("--attn-chunk", type=int, default=0)
+    ap.add_argument("--host-loop", action="store_true", help="drive the steps from Python instead of spec_generate")
     ap.add_argument("--batch", type=int, default=1, help="sequences decoded in lock-step, one controller each "
                                                          "(the headline metric is batch 1)")
     ap.add_argument("--roofline-only", action="store_true",
@@ -58,7 +59,12 @@ def parse():
 
 def decode_loop(eng, ctrls, n_generate):
     """Speculative steps until every sequence has n_generate new tokens; `ctrls`: one controller per sequence.
-    Counts tokens up to n_generate per sequence."""
+    Counts tokens up to n_generate per sequence.  The loop itself runs in the library (spec_generate)."""
+    return eng.run(n_generate, ctrls)
+
+
+def decode_loop_host(eng, ctrls, n_generate):
+    """The same loop driven from Python through spec_draft / spec_verify / spec_accept / gammatune_update."""
     B = len(ctrls)
     gen = [0] * B
     steps, acc, drafted, gsum = 0, 0, 0, 0
@@ -155,6 +161,8 @@ def measured_traffic(pair):
 
 def main():
     args = parse()
+    if args.host_loop:
+        globals()["decode_loop"] = decode_loop_host
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)

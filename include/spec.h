@@ -31,6 +31,8 @@
 
 #include <stdint.h>
 
+#include "gammatune.h"
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -109,7 +111,8 @@ int spec_prefill_ragged(spec_ctx *ctx, const int32_t *host_tokens, int32_t n_max
  * Philox(seed; counter = (step, i, DRAFT, b)) (argmax if T == 0), appends it to the
  * sequence, and keeps the draft logits row for the accept phase.  With early stopping
  * enabled drafting of a sequence ends after the first x_i whose confidence is below tau;
- * that x_i is kept.  1 <= gamma <= gamma_max.  SPEC_ECAP if len + gamma + 1 > max_seq. */
+ * that x_i is kept; the call then launches pass by pass and waits for each pass's verdict (a few words
+ * in pinned memory) before it launches the next, so it returns when the last pass has been enqueued.  1 <= gamma <= gamma_max.  SPEC_ECAP if len + gamma + 1 > max_seq. */
 int spec_draft(spec_ctx *ctx, int32_t gamma);
 
 /* Same with one planned gamma per sequence (host int32 [batch]); the launch uses the
@@ -143,6 +146,22 @@ int spec_set_forced_alpha(spec_ctx *ctx, const float *alpha, int32_t n);
 /* GammaTune+ threshold: stop drafting when the draft's top probability
  * max softmax(logits / T_eff), T_eff = T > 0 ? T : 1, is below tau.  tau <= 0 disables. */
 int spec_set_early_stop(spec_ctx *ctx, float tau);
+
+/* Totals of a spec_generate() call over all sequences and steps. */
+typedef struct {
+    int64_t steps;      /* speculative steps (draft + verify + accept) */
+    int64_t generated;  /* tokens emitted, counted up to n_generate per sequence */
+    int64_t accepted;   /* accepted draft tokens */
+    int64_t drafted;    /* drafted tokens */
+    int64_t gamma_sum;  /* planned gammas, one per (sequence, step) */
+} spec_gen_stats;
+
+/* The decode loop in native code: speculative steps until every sequence has n_generate tokens more than when the
+ * call began.  controllers: host array of `batch` GammaTune states, updated in place with gammatune_update(A, k)
+ * after every step, or NULL for the fixed speculation length fixed_gamma.  Must follow spec_prefill() or
+ * spec_accept().  Equivalent to calling spec_draft_batch / spec_verify / spec_accept / gammatune_update from the
+ * host in a loop; stats may be NULL.  SPEC_ECAP when a step would exceed max_seq. */
+int spec_generate(spec_ctx *ctx, gt_state *controllers, int32_t fixed_gamma, int32_t n_generate, spec_gen_stats *stats);
 
 /* Copy the tokens of sequence b (prompt + generated so far) to host_out (host int32, capacity cap);
  * *n receives the length.  Synchronises. */

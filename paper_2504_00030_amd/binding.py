@@ -25,7 +25,7 @@ GT_EXPAND_A, GT_LITERAL, GT_SHORT_TERM = 0, 1, 2
 # every symbol include/spec.h and include/gammatune.h declare
 EXPORTS = [
     "spec_init", "spec_prefill", "spec_prefill_ragged", "spec_debug_set_step", "spec_draft", "spec_draft_batch", "spec_verify", "spec_accept",
-    "spec_set_forced_alpha", "spec_set_early_stop", "spec_read_tokens", "spec_debug_logits",
+    "spec_set_forced_alpha", "spec_set_early_stop", "spec_generate", "spec_read_tokens", "spec_debug_logits",
     "spec_debug_drafted", "spec_debug_read", "spec_debug_fill_kv", "spec_debug_write_kv", "spec_debug_set_block_table", "spec_device_bytes", "spec_profile_kernel", "spec_profile_read", "spec_destroy",
     "spec_strerror", "spec_last_error", "spec_k_gemv", "spec_k_gemv_tiled", "spec_k_retile", "spec_k_copy", "spec_k_philox", "spec_k_accept",
     "gammatune_init", "gammatune_update",
@@ -50,6 +50,10 @@ class SpecConfig(C.Structure):
     _fields_ = [("batch", C.c_int32), ("max_seq", C.c_int32), ("page_tokens", C.c_int32), ("gamma_max", C.c_int32),
                 ("temperature", C.c_float), ("seed", C.c_uint64), ("accept_mode", C.c_int32), ("gemv_path", C.c_int32),
                 ("use_graphs", C.c_int32), ("attn_chunk", C.c_int32), ("hip_stream", C.c_void_p)]
+
+
+class SpecGenStats(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("steps", "generated", "accepted", "drafted", "gamma_sum")]
 
 
 class GtParams(C.Structure):
@@ -100,6 +104,7 @@ def load() -> C.CDLL:
     lib.spec_debug_set_block_table.argtypes = [C.c_void_p, i32p]
     lib.spec_profile_kernel.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     lib.spec_profile_read.argtypes = [C.c_void_p, i32p, C.POINTER(C.c_double)]
+    lib.spec_generate.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.POINTER(SpecGenStats)]
     lib.spec_device_bytes.argtypes = [C.c_void_p]
     lib.spec_device_bytes.restype = C.c_int64
     lib.spec_destroy.argtypes = [C.c_void_p]
@@ -317,6 +322,21 @@ class SpecEngine:
 
     def device_bytes(self) -> int:
         return int(self._lib.spec_device_bytes(self._ctx))
+
+    def run(self, n_generate: int, controllers: List) -> dict:
+        """spec_generate: the decode loop in native code (after prefill).  controllers: one GammaTune per sequence
+        (their states are updated), or FixedGamma objects of one common gamma."""
+        st = SpecGenStats()
+        if all(isinstance(c, GammaTune) for c in controllers):
+            arr = (GtState * self.batch)(*[c.state for c in controllers])
+            rc = self._lib.spec_generate(self._ctx, arr, 0, int(n_generate), C.byref(st))
+            for c, s_ in zip(controllers, arr):
+                c.state.gamma_bar, c.state.gamma = s_.gamma_bar, s_.gamma
+        else:
+            rc = self._lib.spec_generate(self._ctx, None, int(controllers[0].gamma), int(n_generate), C.byref(st))
+        self._chk(rc, "spec_generate")
+        return dict(generated=int(st.generated), spec_steps=int(st.steps), accepted=int(st.accepted), drafted=int(st.drafted),
+                    gamma_sum=int(st.gamma_sum), seq_steps=int(st.steps) * self.batch)
 
     def generate(self, prompts: np.ndarray, n_generate: int, controllers: List, keep_logits: bool = False):
         """Host loop of speculative decoding: draft -> verify -> accept -> controller update, until every

@@ -3,12 +3,15 @@
 // speculative step (Background section): gamma draft decode steps, one target verification pass
 // over gamma+1 rows, and the accept / resample step.
 #include "spec.h"
+#include "gammatune.h"
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <chrono>
 #include <map>
 #include <string>
 #include <vector>
@@ -68,6 +71,8 @@ struct spec_ctx {
     std::vector<int32_t> h_len;
     int32_t *h_gamma_plan = nullptr;  // pinned, read by the device
     int32_t *h_out = nullptr;         // pinned [3][B]: A, y, k
+    int32_t *h_pass = nullptr, *d_pass = nullptr;  // pinned [2]: draft passes sampled, sequences still drafting
+    int32_t passes_launched = 0;      // draft sample kernels enqueued since the last reset of ctl[3]
     int32_t *d_gamma_plan = nullptr, *d_out = nullptr;
     // sampling
     SampleCfg scfg{};
@@ -84,7 +89,7 @@ struct spec_ctx {
     int phase = 0;
     int cur_gamma = 0;
     bool prefilled = false;
-    std::map<int, hipGraphExec_t> g_draft, g_verify;
+    std::map<int, hipGraphExec_t> g_draft, g_verify, g_pass;  // whole draft phase per gamma, verify per gamma, draft pass j
     std::vector<hipGraph_t> graphs;
     // optional timing of one kernel class with event pairs (direct launches only)
     int prof_epi = -1, prof_model = 0;
@@ -465,34 +470,54 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
     return SPEC_OK;
 }
 
-int enqueue_draft(spec_ctx *c, int gamma) {
-    HIPCHK(c, launch_begin_draft(c->st, c->d_gamma_plan, c->stream));
+// One draft pass: forward of the draft model and the sampler; pass 1 also opens the step.
+int enqueue_draft_pass(spec_ctx *c, int j) {
+    if (j == 1) HIPCHK(c, launch_begin_draft(c->st, c->d_gamma_plan, c->stream));
     const int B = c->cfg.batch;
-    for (int j = 1; j <= gamma; ++j) {
-        RowPlan plan{};
-        LogitsPlan lp{};
-        lp.want = true;
-        lp.rows = B;
-        lp.tile = &c->d_tile;
-        lp.ntiles = &c->d_ntiles;
-        lp.y_mul = c->cfg.gamma_max;
-        lp.y_add = j - 1;
-        if (j == 1) {
-            plan.mode = ROWS_DRAFT_FIRST; plan.rps = 2; plan.arg = 0;
-            lp.x_mul = 2; lp.x_add = 1;
-        } else {
-            plan.mode = ROWS_DRAFT_NEXT; plan.rps = 1; plan.arg = j;
-            lp.x_mul = 1; lp.x_add = 0;
-        }
-        TRY(forward(c, c->drf, plan, lp, true));
-        DraftSampleArgs a{};
-        a.st = c->st; a.cfg = c->scfg; a.j = j; a.gamma_max = c->cfg.gamma_max; a.logits = c->drf.logits;
-        a.vocab = c->drf.s.vocab; a.pm = c->drf.pm; a.ps = c->drf.ps; a.pa = c->drf.pa;
-        a.n_tiles = c->d_ntiles; a.tile = c->d_tile;
-        a.pm2 = c->drf.pm2; a.ps2 = c->drf.ps2; a.pa2 = c->drf.pa2; a.n2 = (c->d_ntiles + 63) / 64;
-        a.q_logit = c->q_logit; a.q_max = c->q_max; a.q_sum = c->q_sum;
-        HIPCHK(c, launch_draft_sample(a, c->stream));
+    RowPlan plan{};
+    LogitsPlan lp{};
+    lp.want = true;
+    lp.rows = B;
+    lp.tile = &c->d_tile;
+    lp.ntiles = &c->d_ntiles;
+    lp.y_mul = c->cfg.gamma_max;
+    lp.y_add = j - 1;
+    if (j == 1) {
+        plan.mode = ROWS_DRAFT_FIRST; plan.rps = 2; plan.arg = 0;
+        lp.x_mul = 2; lp.x_add = 1;
+    } else {
+        plan.mode = ROWS_DRAFT_NEXT; plan.rps = 1; plan.arg = j;
+        lp.x_mul = 1; lp.x_add = 0;
     }
+    TRY(forward(c, c->drf, plan, lp, true));
+    DraftSampleArgs a{};
+    a.st = c->st; a.cfg = c->scfg; a.j = j; a.gamma_max = c->cfg.gamma_max; a.logits = c->drf.logits;
+    a.vocab = c->drf.s.vocab; a.pm = c->drf.pm; a.ps = c->drf.ps; a.pa = c->drf.pa;
+    a.n_tiles = c->d_ntiles; a.tile = c->d_tile;
+    a.pm2 = c->drf.pm2; a.ps2 = c->drf.ps2; a.pa2 = c->drf.pa2; a.n2 = (c->d_ntiles + 63) / 64;
+    a.host_pass = c->d_pass;
+    a.q_logit = c->q_logit; a.q_max = c->q_max; a.q_sum = c->q_sum;
+    HIPCHK(c, launch_draft_sample(a, c->stream));
+    return SPEC_OK;
+}
+
+int enqueue_draft(spec_ctx *c, int gamma) {
+    for (int j = 1; j <= gamma; ++j) TRY(enqueue_draft_pass(c, j));
+    return SPEC_OK;
+}
+
+// Wait until the device has sampled `n` draft passes since the last reset; *active = sequences still drafting.
+int wait_draft_pass(spec_ctx *c, int n, int *active) {
+    const auto t0 = std::chrono::steady_clock::now();
+    for (uint64_t spins = 0;; ++spins) {
+        if (__atomic_load_n(&c->h_pass[0], __ATOMIC_ACQUIRE) >= n) break;
+        if ((spins & 0xffff) == 0xffff &&
+            std::chrono::steady_clock::now() - t0 > std::chrono::seconds(20)) {
+            const hipError_t e = hipStreamQuery(c->stream);
+            return fail(c, SPEC_EHIP, std::string("draft pass did not report within 20 s: ") + hipGetErrorString(e));
+        }
+    }
+    *active = __atomic_load_n(&c->h_pass[1], __ATOMIC_RELAXED);
     return SPEC_OK;
 }
 
@@ -580,6 +605,7 @@ void spec_destroy(spec_ctx *c) {
     (void)hipStreamSynchronize(c->stream);
     for (auto &kv : c->g_draft) (void)hipGraphExecDestroy(kv.second);
     for (auto &kv : c->g_verify) (void)hipGraphExecDestroy(kv.second);
+    for (auto &kv : c->g_pass) (void)hipGraphExecDestroy(kv.second);
     for (auto g : c->graphs) (void)hipGraphDestroy(g);
     for (void *p : c->dev_allocs) (void)hipFree(p);
     for (void *p : c->host_allocs) (void)hipHostFree(p);
@@ -647,17 +673,19 @@ int spec_init(const spec_shape *t, const spec_weights *tw, const spec_shape *d, 
     c->h_len.assign(B, 0);
 
     void *hp = nullptr;
-    if (hipHostMalloc(&hp, sizeof(int32_t) * 4 * B, hipHostMallocMapped) != hipSuccess)
+    if (hipHostMalloc(&hp, sizeof(int32_t) * (4 * B + 2), hipHostMallocMapped) != hipSuccess)
         return bail(fail(c, SPEC_ENOMEM, "hipHostMalloc failed"));
     c->host_allocs.push_back(hp);
-    std::memset(hp, 0, sizeof(int32_t) * 4 * B);
+    std::memset(hp, 0, sizeof(int32_t) * (4 * B + 2));
     c->h_gamma_plan = reinterpret_cast<int32_t *>(hp);
     c->h_out = c->h_gamma_plan + B;
+    c->h_pass = c->h_gamma_plan + 4 * B;
     void *dp = nullptr;
     if (hipHostGetDevicePointer(&dp, hp, 0) != hipSuccess)
         return bail(fail(c, SPEC_EHIP, "hipHostGetDevicePointer failed"));
     c->d_gamma_plan = reinterpret_cast<int32_t *>(dp);
     c->d_out = c->d_gamma_plan + B;
+    c->d_pass = c->d_gamma_plan + 4 * B;
 
     c->scfg.temperature = g.temperature;
     c->scfg.inv_t = g.temperature > 0.f ? 1.0f / g.temperature : 1.0f;
@@ -692,8 +720,10 @@ int spec_set_forced_alpha(spec_ctx *c, const float *alpha, int32_t n) {
     // kernel arguments are baked into captured graphs
     for (auto &kv : c->g_draft) (void)hipGraphExecDestroy(kv.second);
     for (auto &kv : c->g_verify) (void)hipGraphExecDestroy(kv.second);
+    for (auto &kv : c->g_pass) (void)hipGraphExecDestroy(kv.second);
     c->g_draft.clear();
     c->g_verify.clear();
+    c->g_pass.clear();
     return SPEC_OK;
 }
 
@@ -704,6 +734,8 @@ int spec_set_early_stop(spec_ctx *c, float tau) {
     c->scfg.tau = tau > 0.f ? tau : 0.f;
     for (auto &kv : c->g_draft) (void)hipGraphExecDestroy(kv.second);
     c->g_draft.clear();
+    for (auto &kv : c->g_pass) (void)hipGraphExecDestroy(kv.second);
+    c->g_pass.clear();
     return SPEC_OK;
 }
 
@@ -742,6 +774,9 @@ int spec_prefill_ragged(spec_ctx *c, const int32_t *host_tokens, int32_t n_max, 
     HIPCHK(c, hipMemcpy(c->st.prompt_len, lens, sizeof(int32_t) * B, hipMemcpyHostToDevice));
     const int32_t ctl[4] = {-1, 0, 0, 0};
     HIPCHK(c, hipMemcpy(c->st.ctl, ctl, sizeof(ctl), hipMemcpyHostToDevice));
+    c->passes_launched = 0;
+    c->h_pass[0] = 0;
+    c->h_pass[1] = 0;
     std::vector<uint32_t> z(B, 0);
     HIPCHK(c, hipMemcpy(c->ticket, z.data(), sizeof(uint32_t) * B, hipMemcpyHostToDevice));
     c->h_len.assign(lens, lens + B);
@@ -786,7 +821,28 @@ int spec_draft_batch(spec_ctx *c, const int32_t *gammas) {
     for (int b = 0; b < B; ++b)
         if (c->h_len[b] + gmax + 1 > c->cfg.max_seq) return fail(c, SPEC_ECAP, "draft: len + gamma + 1 > max_seq");
     for (int b = 0; b < B; ++b) c->h_gamma_plan[b] = gammas[b];
-    if (c->cfg.use_graphs) {
+    if (c->scfg.tau > 0.f && gmax > 1) {
+        // early stopping: pass by pass, and the next pass only while a sequence still drafts
+        for (int j = 1; j <= gmax; ++j) {
+            if (j > 1) {
+                int active = 0;
+                TRY(wait_draft_pass(c, c->passes_launched, &active));
+                if (active == 0) break;
+            }
+            if (c->cfg.use_graphs) {
+                auto it = c->g_pass.find(j);
+                if (it == c->g_pass.end()) {
+                    hipGraphExec_t ex = nullptr;
+                    TRY(capture(c, [&] { return enqueue_draft_pass(c, j); }, &ex));
+                    it = c->g_pass.emplace(j, ex).first;
+                }
+                HIPCHK(c, hipGraphLaunch(it->second, c->stream));
+            } else {
+                TRY(enqueue_draft_pass(c, j));
+            }
+            c->passes_launched += 1;
+        }
+    } else if (c->cfg.use_graphs) {
         auto it = c->g_draft.find(gmax);
         if (it == c->g_draft.end()) {
             hipGraphExec_t ex = nullptr;
@@ -794,8 +850,10 @@ int spec_draft_batch(spec_ctx *c, const int32_t *gammas) {
             it = c->g_draft.emplace(gmax, ex).first;
         }
         HIPCHK(c, hipGraphLaunch(it->second, c->stream));
+        c->passes_launched += gmax;
     } else {
         TRY(enqueue_draft(c, gmax));
+        c->passes_launched += gmax;
     }
     c->cur_gamma = gmax;
     c->phase = 2;
@@ -841,6 +899,37 @@ int spec_accept(spec_ctx *c, int32_t *n_accepted, int32_t *next_token, int32_t *
         c->h_len[b] += A + 1;
     }
     c->phase = 1;
+    return SPEC_OK;
+}
+
+int spec_generate(spec_ctx *c, gt_state *controllers, int32_t fixed_gamma, int32_t n_generate, spec_gen_stats *stats) {
+    if (!c) return SPEC_EINVAL;
+    if (n_generate < 0) return fail(c, SPEC_EINVAL, "generate: n_generate < 0");
+    if (!controllers && (fixed_gamma < 1 || fixed_gamma > c->cfg.gamma_max))
+        return fail(c, SPEC_EINVAL, "generate: fixed gamma outside 1..gamma_max");
+    const int B = c->cfg.batch;
+    std::vector<int32_t> gam(B), A(B), y(B), k(B), gen(B, 0);
+    spec_gen_stats st{};
+    for (;;) {
+        int least = gen[0];
+        for (int b = 1; b < B; ++b) least = std::min(least, gen[b]);
+        if (least >= n_generate) break;
+        for (int b = 0; b < B; ++b) gam[b] = controllers ? controllers[b].gamma : fixed_gamma;
+        TRY(spec_draft_batch(c, gam.data()));
+        TRY(spec_verify(c, c->cur_gamma));
+        TRY(spec_accept(c, A.data(), y.data(), k.data()));
+        for (int b = 0; b < B; ++b) {
+            if (controllers && gammatune_update(&controllers[b], A[b], k[b]) < 0)
+                return fail(c, SPEC_EINVAL, "generate: controller state rejected by gammatune_update");
+            gen[b] += A[b] + 1;
+            st.accepted += A[b];
+            st.drafted += k[b];
+            st.gamma_sum += gam[b];
+        }
+        st.steps += 1;
+    }
+    for (int b = 0; b < B; ++b) st.generated += std::min(gen[b], n_generate);
+    if (stats) *stats = st;
     return SPEC_OK;
 }
 
@@ -936,6 +1025,9 @@ int spec_debug_fill_kv(spec_ctx *c, int32_t len, uint64_t seed) {
     HIPCHK(c, hipMemcpy(c->st.prompt_len, lens.data(), sizeof(int32_t) * B, hipMemcpyHostToDevice));
     const int32_t ctl[4] = {-1, 0, 0, 0};
     HIPCHK(c, hipMemcpy(c->st.ctl, ctl, sizeof(ctl), hipMemcpyHostToDevice));
+    c->passes_launched = 0;
+    c->h_pass[0] = 0;
+    c->h_pass[1] = 0;
     std::vector<uint32_t> z(B, 0);
     HIPCHK(c, hipMemcpy(c->ticket, z.data(), sizeof(uint32_t) * B, hipMemcpyHostToDevice));
     HIPCHK(c, hipStreamSynchronize(c->stream));

@@ -14,7 +14,8 @@ struct State {
     int32_t *prompt_len;  // [B]
     int32_t *gamma_b;     // [B] planned gamma of the current step
     int32_t *k;           // [B] tokens drafted in the current step; 0 while the sequence is still drafting
-    int32_t *ctl;         // [0] speculative-step ordinal, [1] sequences still drafting
+    int32_t *ctl;         // [0] speculative-step ordinal, [1] sequences still drafting, [2] arrivals of the draft
+                          // sampler's workgroups, [3] draft passes sampled since the last reset
     int32_t *tokens;      // [B][max_seq]
     int32_t max_seq;
     int32_t batch;
@@ -142,6 +143,7 @@ struct DraftSampleArgs {
     int32_t n_tiles, tile;
     const float *pm2; const double *ps2; const int32_t *pa2;  // level 2: one per 64 tiles, [..][n2]
     int32_t n2;
+    int32_t *host_pass;   // pinned host memory, or null: [0] = ctl[3] after this pass, [1] = sequences still drafting
     // per drafted token: logit of the chosen token, row max, row sum  -> [B][gamma_max]
     float *q_logit, *q_max;
     double *q_sum;

@@ -178,41 +178,57 @@ hipError_t launch_merge_partials(const float *pm, const double *ps, const int32_
 // ---- draft sampling ------------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void draft_sample_k(const DraftSampleArgs a) {
     const int b = blockIdx.x, lane = threadIdx.x;
-    if (a.st.k[b] != 0) return;  // this sequence stopped drafting earlier in the step
-    const int row = b * a.gamma_max + (a.j - 1);
-    const PartRow pr = part_row(a.pm, a.ps, a.pa, a.n_tiles, a.tile, a.pm2, a.ps2, a.pa2, a.n2, (size_t)row);
-    const float *logits = a.logits + (size_t)row * a.vocab;
-    const double inv_t = (double)a.cfg.inv_t;
-    const RowStats rs = wave_row_stats(pr, inv_t, lane);
-    const int len = a.st.len[b];
-    const uint32_t step = (uint32_t)a.st.ctl[0];
-    int x;
-    if (a.cfg.temperature == 0.f) {
-        x = rs.arg;
-    } else {
-        const double u = philox_uniform(a.cfg.seed, step, (uint32_t)a.j, PURPOSE_DRAFT, (uint32_t)b);
-        x = wave_sample_row(logits, a.vocab, pr, rs.M, inv_t, u * rs.S, lane);
-    }
-    x = min(max(x, 0), a.vocab - 1);  // a row of non-finite logits has no argmax: stay inside the vocabulary
-    if (lane == 0) {
-        const int pos = len + a.j - 1;
-        if (pos < a.st.max_seq) a.st.tokens[(size_t)b * a.st.max_seq + pos] = x;
-        a.q_logit[row] = logits[x];
-        a.q_max[row] = (float)rs.M;
-        a.q_sum[row] = rs.S;
-        double conf;
-        if (a.cfg.forced) {
-            const uint32_t g = (uint32_t)(len - a.st.prompt_len[b] + a.j - 1);
-            const double al = (double)a.cfg.alpha[min((int)g, a.cfg.n_alpha - 1)];
-            conf = al + (0.5 - philox_uniform(a.cfg.seed, g, 0u, PURPOSE_FORCED, (uint32_t)b)) * 0.5;
-            conf = fmin(1.0, fmax(0.0, conf));
+    if (a.st.k[b] == 0) {  // else this sequence stopped drafting earlier in the step
+        const int row = b * a.gamma_max + (a.j - 1);
+        const PartRow pr = part_row(a.pm, a.ps, a.pa, a.n_tiles, a.tile, a.pm2, a.ps2, a.pa2, a.n2, (size_t)row);
+        const float *logits = a.logits + (size_t)row * a.vocab;
+        const double inv_t = (double)a.cfg.inv_t;
+        const RowStats rs = wave_row_stats(pr, inv_t, lane);
+        const int len = a.st.len[b];
+        const uint32_t step = (uint32_t)a.st.ctl[0];
+        int x;
+        if (a.cfg.temperature == 0.f) {
+            x = rs.arg;
         } else {
-            conf = 1.0 / rs.S;  // top probability of softmax(l / T_eff)
+            const double u = philox_uniform(a.cfg.seed, step, (uint32_t)a.j, PURPOSE_DRAFT, (uint32_t)b);
+            x = wave_sample_row(logits, a.vocab, pr, rs.M, inv_t, u * rs.S, lane);
         }
-        const bool stop = (a.cfg.tau > 0.f && conf < (double)a.cfg.tau) || a.j >= a.st.gamma_b[b];
-        if (stop) {
-            a.st.k[b] = a.j;
-            atomicSub(&a.st.ctl[1], 1);
+        x = min(max(x, 0), a.vocab - 1);  // a row of non-finite logits has no argmax: stay inside the vocabulary
+        if (lane == 0) {
+            const int pos = len + a.j - 1;
+            if (pos < a.st.max_seq) a.st.tokens[(size_t)b * a.st.max_seq + pos] = x;
+            a.q_logit[row] = logits[x];
+            a.q_max[row] = (float)rs.M;
+            a.q_sum[row] = rs.S;
+            double conf;
+            if (a.cfg.forced) {
+                const uint32_t g = (uint32_t)(len - a.st.prompt_len[b] + a.j - 1);
+                const double al = (double)a.cfg.alpha[min((int)g, a.cfg.n_alpha - 1)];
+                conf = al + (0.5 - philox_uniform(a.cfg.seed, g, 0u, PURPOSE_FORCED, (uint32_t)b)) * 0.5;
+                conf = fmin(1.0, fmax(0.0, conf));
+            } else {
+                conf = 1.0 / rs.S;  // top probability of softmax(l / T_eff)
+            }
+            const bool stop = (a.cfg.tau > 0.f && conf < (double)a.cfg.tau) || a.j >= a.st.gamma_b[b];
+            if (stop) {
+                a.st.k[b] = a.j;
+                atomicSub(&a.st.ctl[1], 1);
+            }
+        }
+    }
+    // the workgroup that arrives last tells the host how many sequences still draft, so that the host launches
+    // the next draft pass only when one is needed (a pass whose kernels all return at once still costs its launches)
+    if (a.host_pass != nullptr && lane == 0) {
+        __threadfence();
+        if (atomicAdd(&a.st.ctl[2], 1) == a.st.batch - 1) {
+            a.st.ctl[2] = 0;
+            const int active = atomicAdd(&a.st.ctl[1], 0);
+            const int n = a.st.ctl[3] + 1;
+            a.st.ctl[3] = n;
+            volatile int32_t *hp = a.host_pass;
+            hp[1] = active;
+            __threadfence_system();
+            hp[0] = n;
         }
     }
 }

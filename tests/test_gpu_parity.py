@@ -383,6 +383,39 @@ def test_small_bf16_pair_at_the_row_limit(batch, gamma):
     assert c.max_logit_err <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("batch", [1, 3])
+def test_native_generate_loop_equals_host_loop(batch):
+    """spec_generate (loop in the library) against the same loop driven call by call: identical tokens, identical
+    controller states and totals.  The host-driven loop is what every lock-step parity test above exercises."""
+    pk = _pk()
+    cfg = synth.pair("small-bf16")
+    Wt, Wd = synth.make_pair_weights(cfg, 0, norm_jitter=0.05)
+    Wt_g, Wd_g = to_gpu(Wt), to_gpu(Wd)
+    prompts = synth.make_prompts(batch, 24, cfg.target.vocab, 3)
+    alpha = synth.alpha_piecewise(256, 16)
+    out = []
+    for native in (False, True):
+        eng = pk.SpecEngine(cfg.target, Wt_g, cfg.draft, Wd_g, batch=batch, max_seq=24 + 3 * 60 + 40, gamma_max=cfg.gamma_max,
+                            temperature=0.7, seed=4, accept_mode=pk.ACCEPT_FORCED, use_graphs=True)
+        eng.set_forced_alpha(alpha)
+        eng.set_early_stop(float(np.float32(0.4)))
+        ctl = [pk.GammaTune(eta=0.25, delta=1, gamma_min=1, gamma_max=cfg.gamma_max, gamma0=4) for _ in range(batch)]
+        if native:
+            eng.prefill(prompts)
+            stats = eng.run(60, ctl)
+            toks = np.stack([eng.read_tokens(b)[: 24 + 60] for b in range(batch)])
+        else:
+            toks, trace = eng.generate(prompts, 60, ctl)
+            stats = dict(spec_steps=len(trace), accepted=int(sum(r["A"].sum() for r in trace)),
+                         drafted=int(sum(r["k"].sum() for r in trace)))
+        out.append((toks, [(c.gamma, c.gamma_bar) for c in ctl], stats))
+        eng.close()
+    assert np.array_equal(out[0][0], out[1][0])
+    assert out[0][1] == out[1][1]
+    for key in ("spec_steps", "accepted", "drafted"):
+        assert out[0][2][key] == out[1][2][key]
+
+
 def test_prompt_of_one_token_and_gamma_one():
     cfg = synth.pair("tiny")
     c, toks, _ = _run_pair(cfg, controller="fixed1", temperature=1.0, seed=8, prompt_len=1, n_generate=12)
