@@ -1,5 +1,5 @@
 // Host engine behind the C ABI of include/spec.h: owns the paged KV caches, the activation and
-// logits buffers and the per-gamma HIP graphs, and strings the kernels into the three phases of a
+// logits buffers and the HIP graphs (one per draft pass index, one per verification length), and strings the kernels into the three phases of a
 // speculative step (Background section): gamma draft decode steps, one target verification pass
 // over gamma+1 rows, and the accept / resample step.
 #include "spec.h"
@@ -307,7 +307,6 @@ KVCache kv_of(const spec_ctx *c, const ModelRT &m, int l) {
     return kv;
 }
 
-// Bracket the next launch with an event pair when its kernel class is being timed.
 // Event pair around the launches of one kernel class.  With `in_dispatch` the launcher hands the pair to
 // the dispatch itself (kernel start / end); otherwise the pair is recorded on the stream around the launch.
 struct ProfScope {

@@ -1,14 +1,17 @@
-// Weight-streaming projections on the matrix cores for 3..128 rows (the verification pass of a
-// speculative step over gamma+1 rows per sequence, and prompt ingestion).
+// Weight-streaming projections on the matrix cores, 1..128 rows of x (draft decode, the verification
+// pass of a speculative step over gamma+1 rows per sequence, and prompt ingestion).
 //
 // Weights are read from a re-tiled copy: 16-row groups, each a contiguous run of 1 KiB tiles
 // (16 rows x 32 k) stored lane-major, so that a wave's 16-byte-per-lane load of one tile is one
-// contiguous KiB and IS the B operand of v_mfma_f32_16x16x32_bf16.  The x rows (bf16) are the A
-// operand, fetched from L2 with the same 16-byte pattern.  The NW waves of a workgroup split K,
-// leave their partial tiles in LDS, the partials are summed in wave order (fixed order: results
-// repeat bit for bit), and the epilogue (RoPE + KV write, residual + next-norm statistics, SwiGLU,
-// logits + softmax partials) runs on the reduced tile.  The pass stays HBM-bound: one MFMA per KiB
-// of weights per 16 rows.
+// contiguous KiB and IS the B operand of v_mfma_f32_16x16x32_bf16.  The x rows are the A operand, as
+// two bf16 terms (x = hi + lo, about 16 significant bits; one bf16 term left a 32-layer model outside the
+// logit tolerance).  The waves of a workgroup split K, leave their partial tiles in LDS, the partials
+// are summed in wave order (fixed order: results repeat bit for bit), and the epilogue (RoPE + KV
+// write, residual + next-norm statistics, SwiGLU, logits + softmax partials) runs on the reduced tile.
+// Both kernels stay HBM-bound: one or two matrix instructions per KiB of weights per 16 rows.
+//
+//   gemv_mfma_k     one workgroup per NG groups, any row count: x fragments re-read per workgroup
+//   gemv_persist_k  up to 16 rows: 16-wave workgroups walk the groups with the x fragments resident
 #include <hip/hip_ext.h>
 
 #include "common.hpp"
