@@ -136,11 +136,16 @@ COPY_BYTES = 1 << 30
 
 
 def kernel_source_digest():
+    """Digest of the roofline kernel's code: its source files with comments and white space removed."""
     import hashlib
+    import re
     h = hashlib.sha256()
     for name in KERNEL_SOURCES:
-        with open(os.path.join(ROOT, "paper_2504_00030_amd", "csrc", "kernels", name), "rb") as f:
-            h.update(f.read())
+        with open(os.path.join(ROOT, "paper_2504_00030_amd", "csrc", "kernels", name), "r") as f:
+            text = f.read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        text = re.sub(r"//[^\n]*", "", text)
+        h.update("".join(text.split()).encode())
     return h.hexdigest()
 
 
