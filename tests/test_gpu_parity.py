@@ -416,6 +416,42 @@ def test_native_generate_loop_equals_host_loop(batch):
         assert out[0][2][key] == out[1][2][key]
 
 
+@pytest.mark.parametrize("case", range(12))
+def test_random_small_shapes(case):
+    """Seeded random model shapes, batch sizes, page sizes, prompt lengths and controllers: head sizes 32 / 64 / 128,
+    grouped and multi-head attention, d_model different from n_q_heads * head_dim, vocabularies that are and are
+    not multiples of 16 (the latter take the wave-dot kernels), prompts that end inside and on page and attention
+    chunk boundaries."""
+    rng = np.random.default_rng(1000 + case)
+    hd = int(rng.choice([32, 64, 128]))
+    n_kv = int(rng.choice([1, 2, 4]))
+    n_q = n_kv * int(rng.choice([1, 2, 4]))
+    d = int(rng.choice([128, 256, 384]))
+    ffn = int(rng.choice([256, 352, 512]))
+    vocab = int(rng.choice([512, 1000, 1008, 2048]))
+    dtype = "bf16" if case % 4 != 3 else "fp32"
+    target = synth.ModelShape(int(rng.integers(1, 4)), d, n_q, n_kv, hd, ffn, vocab, 10000.0, 1e-5, dtype)
+    dhd = int(rng.choice([32, 64]))
+    draft = synth.ModelShape(int(rng.integers(1, 3)), int(rng.choice([128, 256])), int(rng.choice([2, 4])),
+                             int(rng.choice([1, 2])), dhd, int(rng.choice([256, 384])), vocab, 10000.0, 1e-5, dtype)
+    gamma_max = int(rng.choice([4, 8, 16]))
+    batch = int(rng.choice([1, 1, 2, 3, 5]))
+    if batch * (gamma_max + 1) > 128:
+        batch = 1
+    cfg = synth.PairConfig(f"random-{case}", target, draft, "independent", int(rng.choice([1, 7, 16, 63, 64, 65, 130])),
+                           int(rng.integers(10, 40)), gamma_max, batch)
+    temperature = float(rng.choice([0.0, 0.7, 1.0]))
+    forced = bool(rng.integers(0, 2))
+    alpha = synth.alpha_piecewise(256, 8) if forced else None
+    tau = float(np.float32(0.4)) if (forced and rng.integers(0, 2)) else 0.0
+    controller = str(rng.choice(["gammatune", f"fixed{int(rng.integers(1, gamma_max + 1))}"]))
+    c, toks, trace = _run_pair(cfg, controller=controller, temperature=temperature, seed=case, batch=batch,
+                               accept_mode=1 if forced else 0, alpha=alpha, tau=tau, norm_jitter=0.05,
+                               use_graphs=bool(rng.integers(0, 2)), page_tokens=int(rng.choice([8, 16, 64])))
+    _assert_clean(c, full_coverage=False, min_coverage=0.5)
+    assert c.max_logit_err <= TOL[dtype]
+
+
 def test_prompt_of_one_token_and_gamma_one():
     cfg = synth.pair("tiny")
     c, toks, _ = _run_pair(cfg, controller="fixed1", temperature=1.0, seed=8, prompt_len=1, n_generate=12)
