@@ -147,6 +147,109 @@ __device__ __forceinline__ void epilogue_tile(const GemvArgs &a, const float *ti
     }
 }
 
+// Operands of a residual / QKV epilogue that do not depend on the projection's result, fetched by the
+// persistent kernel before the matrix instructions of the group so that the epilogue itself is free of loads.
+// One thread per output element of a 16-column tile (residual: R x 16, QKV: R x 8 pairs).
+struct EpiPre {
+    float xres, gn;        // RESID: residual element, weight of the next norm
+    float cs, sn;          // QKV: rotary cosine / sine of this row's position and this pair's frequency
+    int pos, seq, page;    // QKV: row position, sequence, physical KV page (fetched once per kernel)
+};
+
+template <int EPI>
+__device__ __forceinline__ void epi_prefetch_rows(const GemvArgs &a, int R, int tid, EpiPre &p) {
+    if constexpr (EPI == EPI_QKV) {
+        const int r = tid >> 3;
+        p.pos = 0; p.seq = 0; p.page = 0;
+        if (r < R) {
+            p.pos = a.row_pos[r];
+            p.seq = a.row_seq[r];
+            p.page = kv_page(a.kv, p.seq, p.pos);
+        }
+    }
+}
+
+template <int EPI>
+__device__ __forceinline__ void epi_prefetch_group(const GemvArgs &a, int R, int t, int Ntot, int tid, EpiPre &p) {
+    if constexpr (EPI == EPI_RESID) {
+        const int r = tid >> 4, n = t * 16 + (tid & 15);
+        p.xres = 0.f; p.gn = 1.f;
+        if (r < R && n < Ntot) {
+            p.xres = a.xres[(size_t)r * a.n0 + n];
+            if (a.g_next != nullptr) p.gn = a.g_next[n];
+        }
+    } else if constexpr (EPI == EPI_QKV) {
+        const int r = tid >> 3, half = a.hd >> 1;
+        const int P = t * 8 + (tid & 7);
+        p.cs = 1.f; p.sn = 0.f;
+        if (r < R && P < (Ntot >> 1) && P / half < a.nq + a.nkv) {
+            p.cs = a.rope_cos[(size_t)p.pos * half + P % half];
+            p.sn = a.rope_sin[(size_t)p.pos * half + P % half];
+        }
+    }
+}
+
+// The residual and QKV epilogues of epilogue_tile for a 16-column tile and at least 16 R threads, on prefetched
+// operands: the same arithmetic in the same order.
+template <int EPI>
+__device__ __forceinline__ void epilogue_tile_pre(const GemvArgs &a, const float *tile, int TS, const float *scale, int R,
+                                                  int t, int Ntot, int tid, const EpiPre &p) {
+    if constexpr (EPI == EPI_RESID) {
+        if (tid >= ((R * 16 + 63) & ~63)) return;  // whole waves: the shuffles below need their 16-lane groups
+        const int r = tid >> 4, c = tid & 15;
+        const int n = t * 16 + c;
+        float sq = 0.f;
+        if (r < R && n < Ntot) {
+            const size_t o = (size_t)r * a.n0 + n;
+            const float xn = p.xres + tile[r * TS + c] * scale[r];
+            a.xres[o] = xn;
+            a.xg[o] = xn * p.gn;
+            store_split_bf16(a.xgb, o, a.xgb_lo, xn * p.gn);
+            sq = xn * xn;
+        }
+#pragma unroll
+        for (int m = 8; m >= 1; m >>= 1) sq += __shfl_xor(sq, m, WAVE);
+        if (c == 0 && r < R) a.ssq_out[(size_t)r * a.ssq_stride + t] = sq;
+    } else if constexpr (EPI == EPI_QKV) {
+        const int r = tid >> 3, pj = tid & 7;
+        if (r >= R) return;
+        const int half = a.hd >> 1;
+        const int P = t * 8 + pj;
+        if (P >= (Ntot >> 1)) return;
+        int hh = P / half;
+        const int j = P % half;
+        float y1 = tile[r * TS + pj] * scale[r];
+        float y2 = tile[r * TS + 8 + pj] * scale[r];
+        if (hh < a.nq + a.nkv) {
+            const float r1 = y1 * p.cs - y2 * p.sn;
+            const float r2 = y2 * p.cs + y1 * p.sn;
+            y1 = r1; y2 = r2;
+        }
+        if (hh < a.nq) {
+            const size_t o = (size_t)r * a.nq * a.hd + (size_t)hh * a.hd + j;
+            a.y[o] = y1;
+            a.y[o + half] = y2;
+            store_split_bf16(a.yb, o, a.yb_lo, y1);
+            store_split_bf16(a.yb, o + half, a.yb_lo, y2);
+        } else {
+            const bool is_k = hh < a.nq + a.nkv;
+            const int kvh = hh - a.nq - (is_k ? 0 : a.nkv);
+            const int in_page = p.pos & (a.kv.page_tokens - 1);
+            const size_t base = kv_head_base(a.kv, p.page, kvh);
+            const size_t e1 = is_k ? base + (size_t)in_page * a.kv.hd + j : base + (size_t)j * a.kv.page_tokens + in_page;
+            const size_t e2 = is_k ? e1 + half : e1 + (size_t)half * a.kv.page_tokens;
+            void *pool = is_k ? a.kv.k : a.kv.v;
+            if (a.kv_dtype == DT_BF16) {
+                reinterpret_cast<bf16_t *>(pool)[e1] = f32_to_bf16(y1);
+                reinterpret_cast<bf16_t *>(pool)[e2] = f32_to_bf16(y2);
+            } else {
+                reinterpret_cast<float *>(pool)[e1] = y1;
+                reinterpret_cast<float *>(pool)[e2] = y2;
+            }
+        }
+    }
+}
+
 // Row scales rsqrt(mean(x^2) + eps) from the sum-of-squares slots of the producer (1 when the input is
 // not normed).  One wave per row, lanes over slots.  The slot loads are issued by begin() before the
 // weight stream starts and consumed by finish() after it, so their latency is hidden; shapes that do not

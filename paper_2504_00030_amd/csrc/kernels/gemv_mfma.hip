@@ -260,7 +260,14 @@ __global__ __launch_bounds__(PW * 64) void gemv_persist_k(const GemvArgs a) {
 #pragma unroll
     for (int u = 0; u < UB; ++u) bw[u] = __builtin_nontemporal_load(wp + (size_t)u * PW * 64);
 
+    // what the residual / QKV epilogues read besides the tile is fetched ahead of the matrix instructions (these
+    // loads are older than the next group's weight loads, so waiting for them does not drain the stream)
+    constexpr bool PRE = EPI == EPI_RESID || EPI == EPI_QKV;
+    EpiPre pre{};
+    if constexpr (PRE) epi_prefetch_rows<EPI>(a, R, threadIdx.x, pre);
+
     for (int i = 0; i < n_my; ++i) {
+        if constexpr (PRE) epi_prefetch_group<EPI>(a, R, b + i * G, Ntot, threadIdx.x, pre);
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
@@ -304,7 +311,8 @@ __global__ __launch_bounds__(PW * 64) void gemv_persist_k(const GemvArgs a) {
             }
         }
         lds_barrier();
-        epilogue_tile<EPI, 16, NT>(a, tile, 17, s_scale, R, b + i * G, Ntot, threadIdx.x);
+        if constexpr (PRE) epilogue_tile_pre<EPI>(a, tile, 17, s_scale, R, b + i * G, Ntot, threadIdx.x, pre);
+        else epilogue_tile<EPI, 16, NT>(a, tile, 17, s_scale, R, b + i * G, Ntot, threadIdx.x);
     }
 }
 
