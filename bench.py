@@ -29,6 +29,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix-core peak of the chip
 
 
 def parse():
@@ -51,6 +52,8 @@ def parse():
     ap.add_argument("--host-loop", action="store_true", help="drive the steps from Python instead of spec_generate")
     ap.add_argument("--batch", type=int, default=1, help="sequences decoded in lock-step, one controller each "
                                                          "(the headline metric is batch 1)")
+    ap.add_argument("--prefill-only", action="store_true",
+                    help="time --steps prompt ingestions (after --warmup untimed ones) and print the prefill object alone")
     ap.add_argument("--roofline-only", action="store_true",
                     help="skip the timed generations: prefill, the event-timed decode leg and the reference copy only "
                          "(a short run for profiler counter passes)")
@@ -206,6 +209,35 @@ def main():
             e.set_early_stop(tau)
         return e
 
+    def prefill_report(seconds):
+        """Prompt ingestion: every sequence's first n_prompt - 1 tokens through both models (the last prompt token
+        enters with the first speculative step).  `achieved` counts the projections' useful flops, 2 x rows x
+        weights; the kernel multiplies each weight by both bf16 terms of the activation, twice that many
+        matrix-instruction flops.  Attention, embedding and the epilogues are inside the time, not the flops."""
+        rows = B * (n_prompt - 1)
+        def proj_weights(m):
+            qd, kvd = m.n_q_heads * m.head_dim, m.n_kv_heads * m.head_dim
+            return m.n_layers * (m.d_model * (qd + 2 * kvd) + qd * m.d_model + 3 * m.d_model * m.d_ffn)
+        flops = 2.0 * rows * (proj_weights(cfg.target) + proj_weights(cfg.draft))
+        tf = flops / seconds / 1e12 if seconds > 0 else 0.0
+        return {"ms": 1e3 * seconds, "rows": rows, "tokens_per_s": rows / seconds if seconds > 0 else 0.0,
+                "bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": tf / MFMA_BF16_PEAK_TFLOPS, "matrix_instruction_flops_per_useful_flop": 2}
+
+    if args.prefill_only:
+        eng = engine(not args.no_graphs)
+        for _ in range(args.warmup):
+            eng.prefill(prompts)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            eng.prefill(prompts)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / max(args.steps, 1)
+        eng.close()
+        print(json.dumps({"prefill": prefill_report(dt), "steps": args.steps, "warmup": args.warmup,
+                          "config": {"workload": f"{args.pair}: batch {B}, prompt {n_prompt}"}}))
+        return
     if args.roofline_only:
         args.warmup = args.steps = 0
     eng = engine(not args.no_graphs)
@@ -279,6 +311,7 @@ def main():
             "prefill_ms": 1e3 * t_prefill / steps, "weights_s": t_weights,
         },
         "roofline": roofline, "cpu_baseline": cpu,
+        "prefill": prefill_report(t_prefill / steps) if args.steps > 0 else None,
     }
     print(json.dumps(line))
 

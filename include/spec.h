@@ -235,6 +235,13 @@ int spec_k_gemv(const void *w, int32_t dtype, int32_t N, int32_t K, const float 
 int spec_k_gemv_tiled(const void *w_tiled, int32_t N, int32_t K, const void *x_bf16, const void *x_lo_bf16, int32_t R,
                       float *y, int32_t cfg, void *stream);
 
+/* The prompt-ingestion kernel alone (a dense contraction on the matrix cores, for many rows), asynchronous, no
+ * allocation: y[r][n] = sum_k x[r][k] * W[n][k] with w_tiled from spec_k_retile (N % 16 == 0, K % 32 == 0), x device
+ * fp32 [R][K] (multiplied as its two-term bf16 split, about 16 significant bits), y device fp32 [R][N], any R >= 1.
+ * cfg = 0 picks the block shape from (N, R); 408 / 404 force blocks of 128 rows of x by 256 / 128 rows of W. */
+int spec_k_gemm_tiled(const void *w_tiled, int32_t N, int32_t K, const float *x, int32_t R, float *y, int32_t cfg,
+                      void *stream);
+
 /* Re-tile a row-major bf16 matrix [N][K] into the streaming layout of the matrix-core kernel:
  * 16-row groups, each group a run of 1 KiB tiles (16 rows x 32 k) stored lane-major.  out: device,
  * N*K*2 bytes. */

@@ -29,12 +29,13 @@ HIP_SOURCES = [
     "engine.hip",
     "kernels/gemv_wavedot.hip",
     "kernels/gemv_mfma.hip",
+    "kernels/gemm_mfma.hip",
     "kernels/attention.hip",
     "kernels/sampler.hip",
     "kernels/misc.hip",
 ]
 C_SOURCES = ["gammatune.c"]
-MFMA_SOURCES = ["kernels/gemv_mfma.hip", "kernels/attention.hip"]  # scanned by isa_guard after compiling
+MFMA_SOURCES = ["kernels/gemv_mfma.hip", "kernels/gemm_mfma.hip", "kernels/attention.hip"]  # scanned by isa_guard after compiling
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 HIP_FLAGS = [

@@ -25,7 +25,8 @@ namespace {
 constexpr int SSQ_STRIDE = 512;
 constexpr int ATT_CHUNK = 64;
 constexpr int RESID_CHUNKS = 64;
-constexpr int PREFILL_ROWS = 32;
+constexpr int PREFILL_ROWS = 32;        // rows per sequence of one ingestion launch on the weight-streaming kernels
+constexpr int PREFILL_GEMM_ROWS = 1024;  // rows (all sequences) of one ingestion launch on the dense-contraction kernels
 
 struct ModelRT {
     spec_shape s{};
@@ -38,7 +39,7 @@ struct ModelRT {
     void *t_lm = nullptr;
     bool mfma_ok = false;
     int Rmax = 0;
-    float *x = nullptr, *xg = nullptr, *ssq = nullptr, *q = nullptr, *ao = nullptr, *act = nullptr;
+    float *x = nullptr, *xg = nullptr, *ssq = nullptr, *row_scale = nullptr, *q = nullptr, *ao = nullptr, *act = nullptr;
     uint16_t *xgb = nullptr, *qb = nullptr, *aob = nullptr, *actb = nullptr;
     int32_t *row_pos = nullptr, *row_seq = nullptr;
     std::vector<void *> kpool, vpool;
@@ -178,6 +179,25 @@ int check_weights(spec_ctx *c, const spec_shape &s, const spec_weights *w, const
     return SPEC_OK;
 }
 
+// Whether the projections of a model run on the matrix-core kernels (re-tiled bf16 weights).
+bool model_on_matrix_cores(const spec_config &g, const spec_shape &s) {
+    const int d = s.d_model, qd = s.n_q_heads * s.head_dim;
+    return s.dtype == SPEC_BF16 && g.gemv_path != SPEC_PATH_WAVEDOT && d % 32 == 0 && qd % 32 == 0 && s.d_ffn % 32 == 0 &&
+           s.vocab % 16 == 0 && (s.head_dim / 2) % 8 == 0 && d % 16 == 0;
+}
+
+// Rows of one prompt-ingestion launch (all sequences together).  A model on the matrix cores whose attention
+// also runs on them ingests through the dense-contraction kernels, PREFILL_GEMM_ROWS rows at a time; otherwise
+// PREFILL_ROWS per sequence (the plain attention kernel holds at most 128 rows of a sequence).
+int ingest_rows(const spec_config &g, const spec_shape &s) {
+    const int hd = s.head_dim;
+    const int chunk = attention_mfma_chunk(g.max_seq, g.attn_chunk);
+    const bool attn_mc = g.page_tokens % 4 == 0 && (hd == 32 || hd == 64 || hd == 128) &&
+                         (g.max_seq + chunk - 1) / chunk <= ATT_NC_MAX;
+    if (model_on_matrix_cores(g, s) && attn_mc && s.d_model / 16 <= SSQ_STRIDE) return std::max(PREFILL_GEMM_ROWS, g.batch);
+    return std::min(128, g.batch * PREFILL_ROWS);
+}
+
 int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights *w, int Rmax, int logit_rows) {
     m.s = s;
     m.Rmax = Rmax;
@@ -201,8 +221,7 @@ int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights
 
     // re-tiled copies for the matrix-core kernels
     const int kvd = s.n_kv_heads * s.head_dim;
-    m.mfma_ok = s.dtype == SPEC_BF16 && c->cfg.gemv_path != SPEC_PATH_WAVEDOT && d % 32 == 0 && qd % 32 == 0 &&
-                s.d_ffn % 32 == 0 && s.vocab % 16 == 0 && (s.head_dim / 2) % 8 == 0 && d % 16 == 0;
+    m.mfma_ok = model_on_matrix_cores(c->cfg, s);
     if (m.mfma_ok) {
         auto retile = [&](int mode, const void *w0, const void *w1, const void *w2, int Ntot, int K, void **out) {
             uint16_t *buf = nullptr;
@@ -229,6 +248,7 @@ int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights
     TRY(dalloc(c, &m.xg, R * d));
     TRY(dalloc(c, &m.xgb, 2 * R * d));  // hi half, then the remainder half
     TRY(dalloc(c, &m.ssq, R * SSQ_STRIDE));
+    TRY(dalloc(c, &m.row_scale, R));
     TRY(dalloc(c, &m.q, R * qd));
     TRY(dalloc(c, &m.qb, 2 * R * qd));
     TRY(dalloc(c, &m.ao, R * qd));
@@ -342,8 +362,17 @@ bool use_mfma(const spec_ctx *c, const ModelRT &m, int R) {
 // Launch one fused projection on whichever kernel family serves R rows; `tiled` is the re-tiled
 // copy of the same matrices.  Returns the number of workgroups through *blocks.
 int launch_proj(spec_ctx *c, ModelRT &m, GemvArgs a, int epi, const void *tiled, int Ntot, int *blocks,
-                int *tile_cols) {
+                int *tile_cols, bool ingest = false) {
     ProfScope ps_(c, m, epi, use_mfma(c, m, a.R));
+    if (ingest && m.mfma_ok && gemm_mfma_serves(epi, Ntot, a.K, a.R)) {
+        // prompt ingestion over many rows: the dense-contraction kernel; statistics slots are per 16-row group
+        a.w0 = tiled; a.w1 = a.w2 = nullptr;
+        if (blocks) *blocks = Ntot / 16;
+        if (tile_cols) *tile_cols = 16;
+        if (epi == EPI_RESID && Ntot / 16 > SSQ_STRIDE) return fail(c, SPEC_EINVAL, "too many statistics slots");
+        HIPCHK(c, launch_gemm_mfma(a, epi, 0, m.row_scale, ps_.ev0, ps_.ev1, c->stream));
+        return SPEC_OK;
+    }
     if (use_mfma(c, m, a.R)) {
         a.w0 = tiled; a.w1 = a.w2 = nullptr;
         const int ng = gemv_mfma_groups_per_wg(epi, Ntot, a.K, a.R, 0);
@@ -404,6 +433,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
     };
     const int kvd = s.n_kv_heads * s.head_dim;
     const bool tiled = m.mfma_ok;
+    const bool ingest = plan.mode == ROWS_PREFILL;
     for (int l = 0; l < s.n_layers; ++l) {
         {   // fused QKV projection + RoPE + KV write
             GemvArgs a = base(d, m.xg, m.xgb, xgb_lo);
@@ -413,7 +443,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             a.y = m.q; a.yb = m.qb; a.yb_lo = qb_lo; a.nq = s.n_q_heads; a.nkv = s.n_kv_heads; a.hd = s.head_dim;
             a.rope_cos = m.rope_cos; a.rope_sin = m.rope_sin; a.row_pos = m.row_pos; a.row_seq = m.row_seq;
             a.kv = kv_of(c, m, l); a.kv_dtype = s.dtype;
-            TRY(launch_proj(c, m, a, EPI_QKV, tiled ? m.t_qkv[l] : nullptr, qd + 2 * kvd, nullptr, nullptr));
+            TRY(launch_proj(c, m, a, EPI_QKV, tiled ? m.t_qkv[l] : nullptr, qd + 2 * kvd, nullptr, nullptr, ingest));
         }
         {
             AttnArgs t{};
@@ -434,21 +464,21 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             GemvArgs a = base(qd, m.ao, m.aob, aob_lo);
             a.w0 = m.wo[l]; a.n0 = d;
             a.xres = m.x; a.g_next = m.ffn_norm[l]; a.xg = m.xg; a.xgb = m.xgb; a.xgb_lo = xgb_lo; a.ssq_out = m.ssq;
-            TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wo[l] : nullptr, d, &slots, nullptr));
+            TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wo[l] : nullptr, d, &slots, nullptr, ingest));
         }
         {   // gate / up projections + SwiGLU
             GemvArgs a = base(d, m.xg, m.xgb, xgb_lo);
             a.w0 = m.wg[l]; a.w1 = m.wu[l]; a.n0 = ffn;
             a.ssq_in = m.ssq; a.ssq_in_slots = slots;
             a.y = m.act; a.yb = m.actb; a.yb_lo = actb_lo;
-            TRY(launch_proj(c, m, a, EPI_SWIGLU, tiled ? m.t_gu[l] : nullptr, 2 * ffn, nullptr, nullptr));
+            TRY(launch_proj(c, m, a, EPI_SWIGLU, tiled ? m.t_gu[l] : nullptr, 2 * ffn, nullptr, nullptr, ingest));
         }
         {   // down projection + residual
             GemvArgs a = base(ffn, m.act, m.actb, actb_lo);
             a.w0 = m.wd[l]; a.n0 = d;
             a.xres = m.x; a.g_next = (l + 1 < s.n_layers) ? m.attn_norm[l + 1] : m.final_norm;
             a.xg = m.xg; a.xgb = m.xgb; a.xgb_lo = xgb_lo; a.ssq_out = m.ssq;
-            TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wd[l] : nullptr, d, &slots, nullptr));
+            TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wd[l] : nullptr, d, &slots, nullptr, ingest));
         }
     }
     if (lp.want) {
@@ -566,7 +596,7 @@ template <typename F> int capture(spec_ctx *c, F body, hipGraphExec_t *out) {
 
 int prefill_model(spec_ctx *c, ModelRT &m, int n_ingest) {
     const int B = c->cfg.batch;
-    const int chunk = std::max(1, std::min(PREFILL_ROWS, m.Rmax / B));
+    const int chunk = std::max(1, ingest_rows(c->cfg, m.s) / B);
     for (int p0 = 0; p0 < n_ingest; p0 += chunk) {
         RowPlan plan{};
         plan.mode = ROWS_PREFILL;
@@ -653,8 +683,8 @@ int spec_init(const spec_shape *t, const spec_weights *tw, const spec_shape *d, 
     if (g.batch * (g.gamma_max + 1) > 128) return bail(fail(c, SPEC_EINVAL, "batch * (gamma_max + 1) > 128 rows"));
 
     const int B = g.batch;
-    const int rows_t = std::max(B * (g.gamma_max + 1), std::min(128, B * PREFILL_ROWS));
-    const int rows_d = std::max(2 * B, std::min(128, B * PREFILL_ROWS));
+    const int rows_t = std::max(B * (g.gamma_max + 1), ingest_rows(c->cfg, *t));
+    const int rows_d = std::max(2 * B, ingest_rows(c->cfg, *d));
     if ((rc = build_model(c, c->tgt, *t, tw, rows_t, B * (g.gamma_max + 1)))) return bail(rc);
     if ((rc = build_model(c, c->drf, *d, dw, rows_d, B * g.gamma_max))) return bail(rc);
 
@@ -1127,6 +1157,16 @@ int spec_k_gemv_tiled(const void *w_tiled, int32_t N, int32_t K, const void *x_b
     if (x_lo_bf16) a.xb_lo = reinterpret_cast<const uint16_t *>(x_lo_bf16) - a.xb;
     const hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     return launch_gemv_mfma(a, EPI_PLAIN, cfg, nullptr, nullptr, st) == hipSuccess ? SPEC_OK : SPEC_EHIP;
+}
+
+int spec_k_gemm_tiled(const void *w_tiled, int32_t N, int32_t K, const float *x, int32_t R, float *y, int32_t cfg,
+                      void *stream) {
+    if (!w_tiled || !x || !y || N < 16 || K < 32 || N % 16 || K % 32 || R < 1) return SPEC_EINVAL;
+    if (cfg != 0 && cfg != 408 && cfg != 404) return SPEC_EINVAL;
+    GemvArgs a{};
+    a.w0 = w_tiled; a.n0 = N; a.K = K; a.R = R; a.x = x; a.x_mul = 1; a.y = y;
+    const hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    return launch_gemm_mfma(a, EPI_PLAIN, cfg, nullptr, nullptr, nullptr, st) == hipSuccess ? SPEC_OK : SPEC_EHIP;
 }
 
 int spec_k_retile(const void *w, int32_t N, int32_t K, void *out, void *stream) {

@@ -110,6 +110,7 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
 constexpr int ATT_SPW_MAX = 8;   // slabs per wave -> chunks of up to 512 positions
+constexpr int ATT_TILES_PER_WG = 8;  // 16-query tiles a workgroup works through (decode and verification: all of them)
 
 template <int HD, int SPW>
 __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
@@ -117,7 +118,10 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
     constexpr int ES = HD / 32;  // k-steps of the score product
     constexpr int ET = HD / 16;  // 16-channel tiles of the output
     constexpr int CT = 64 * SPW;
-    const int c = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    // grid.z = sequences x query splits: with many rows per sequence (prompt ingestion) the 16-query tiles of a
+    // sequence are shared out over several workgroups, each of which loads the chunk for itself
+    const int QS = gridDim.z / (a.R / a.rps);
+    const int c = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z / QS, qs = blockIdx.z % QS;
     // wave index and last position are scalars, so that branches on them are scalar branches
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l16 = lane & 15, g = lane >> 4;
@@ -156,13 +160,15 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
     const int n_live = last_pos / CT + 1;
 
     const bool has_qlo = a.qb_lo != 0;
-    const int QT = (QN + 15) / 16;
-    for (int qt = 0; qt < QT; ++qt) {
+    const int QT = (QN + 15) / 16, TPW = (QT + QS - 1) / QS;
+    for (int qt = qs * TPW; qt < min(QT, (qs + 1) * TPW); ++qt) {
         // query handled by this lane in the score product (column l16 of S^T); q enters as hi + lo bf16 terms
         const int qi = min(qt * 16 + l16, QN - 1);
         const int gq = qi / a.rps, i = qi % a.rps;
         const int r = r_first + i, h = kvh * G + gq;
         const int qpos = a.row_pos[r];
+        // a tile none of whose queries sees this chunk leaves no partial: the merge never reads one there
+        if (t0 > __builtin_amdgcn_readfirstlane(wave_max(qpos))) continue;
         u32x4_t qf[ES], ql[ES];
         {
             const bf16_t *qp = a.qb + ((size_t)r * a.nq + h) * HD + 8 * g;
@@ -358,7 +364,8 @@ hipError_t launch_attention(const AttnArgs &a, int hd, hipStream_t s) {
         const int spw = a.chunk / 64;
         if (a.chunk % 64 || (spw != 1 && spw != 2 && spw != 4 && spw != 8) || a.n_chunks > ATT_NC_MAX)
             return hipErrorInvalidValue;
-        const dim3 grid(a.n_chunks, a.kv.n_kv, B);
+        const int QT = (a.nq / a.kv.n_kv * a.rps + 15) / 16;
+        const dim3 grid(a.n_chunks, a.kv.n_kv, B * ((QT + ATT_TILES_PER_WG - 1) / ATT_TILES_PER_WG));
         if (hd == 32) return launch_attn_mfma<32>(a, grid, s);
         if (hd == 64) return launch_attn_mfma<64>(a, grid, s);
         return launch_attn_mfma<128>(a, grid, s);

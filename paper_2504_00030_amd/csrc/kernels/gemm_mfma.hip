@@ -1,0 +1,402 @@
+// Prompt ingestion: the same fused projections as the decode kernels, for hundreds of rows of x, where the
+// work is a dense contraction bound by the matrix cores rather than by the weight stream.
+//
+// One workgroup of four waves (2 x 2) computes a block of 32 WM rows of x by 32 WN rows of W.  Per k-tile
+// (32 columns) a stage in LDS holds the operands of the whole block in the register layout of
+// v_mfma_f32_16x16x32_bf16:
+//   * W tiles come from the re-tiled weights, where a 16-row x 32-column tile is one contiguous KiB that
+//     already has that layout: global_load_lds_dwordx4 moves it into LDS without passing through registers;
+//   * x is read as fp32 rows (fully coalesced 128-byte lines), split in registers into two bf16 terms
+//     (x = hi + lo, the same split as the decode kernels make) and written as hi and lo fragments.
+// Two stages alternate: the loads of k-tile kt + 1 are issued before the matrix instructions of k-tile kt, and
+// two workgroups share a compute unit, so that one multiplies while the other converts and waits.  The block
+// index is mapped so that the workgroups an XCD runs at the same time share their W block (one L2 per XCD).
+// The epilogues are the decode kernels' own (RoPE + KV write, residual + next-norm statistics, SwiGLU): each
+// wave passes its 32 WM x 16 result tiles through LDS, one 16-row group of W at a time.
+#include <hip/hip_ext.h>
+
+#include "common.hpp"
+#include "epilogue.hpp"
+#include "kv.hpp"
+#include "params.hpp"
+
+namespace sd {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+namespace {
+
+// 64 lanes x 16 bytes from global memory into LDS: lane l's bytes land at lds + 16 l.
+__device__ __forceinline__ void dma_tile(const void *g, void *lds) {
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)g,
+                                     (void __attribute__((address_space(3))) *)lds, 16, 0, 0);
+}
+
+// every vector-memory load of this wave, the LDS-bound ones included, has landed
+__device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// x = hi + lo with both terms rounded to nearest even (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ void split4(const f32x4_t v, u32x2_t &hi, u32x2_t &lo) {
+    const f32x2_t a = {v[0], v[1]}, b = {v[2], v[3]};
+    const bf16x2_t ha = __builtin_convertvector(a, bf16x2_t), hb = __builtin_convertvector(b, bf16x2_t);
+    const bf16x2_t la = __builtin_convertvector(a - __builtin_convertvector(ha, f32x2_t), bf16x2_t);
+    const bf16x2_t lb = __builtin_convertvector(b - __builtin_convertvector(hb, f32x2_t), bf16x2_t);
+    hi.x = __builtin_bit_cast(uint32_t, ha);
+    hi.y = __builtin_bit_cast(uint32_t, hb);
+    lo.x = __builtin_bit_cast(uint32_t, la);
+    lo.y = __builtin_bit_cast(uint32_t, lb);
+}
+
+}  // namespace
+
+constexpr int GEMM_THREADS = 256;
+constexpr int GEMM_TS = 36;                      // row stride (floats) of a wave's result tile in the epilogue
+
+// DEEP: the four-slot W ring with fragments double-buffered in registers (loads two to three iterations ahead);
+// otherwise two alternating stages with loads one iteration ahead, which leaves room for two workgroups of the
+// widest block per compute unit.
+template <int WM, int WN, bool DEEP>
+struct GemmShape {
+    static constexpr int BMB = 2 * WM;              // 16-row blocks of x per workgroup
+    static constexpr int BNG = 2 * WN;              // 16-row groups of W per workgroup
+    static constexpr int XS = BMB * 2 * 1024;       // bytes of the x fragments of a stage (hi and lo)
+    static constexpr int WS = BNG * 1024;           // bytes of the W tiles of a stage
+    static constexpr int XI = BMB / 2;              // x loads per thread and stage
+    static constexpr int GROUP = BNG / 4 + XI;      // vector-memory loads a wave issues per stage
+    static constexpr int WSLOTS = DEEP ? 4 : 2;
+    static constexpr int RING = 2 * XS + WSLOTS * WS;
+    static constexpr int EPI_BYTES = 4 * (WM * 16 * GEMM_TS + WM * 16) * 4;  // four waves: result tile + row scales
+    static constexpr int LDS = RING > EPI_BYTES ? RING : EPI_BYTES;
+    static constexpr int WAVES_PER_SIMD = 2 * LDS <= 160 * 1024 ? 2 : 1;
+};
+
+// The workgroup meets once this wave's LDS traffic is done and all but its N newest vector-memory loads
+// have landed.  (__syncthreads would drain every load and with it the prefetch.)
+template <int N> __device__ __forceinline__ void stage_barrier() {
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+template <int WM, int WN> struct GemmFrags { u32x4_t ah[WM], al[WM], bw[WN]; };
+
+// scale[r] = rsqrt(mean(x_r^2) + eps) from the statistics slots of the producer: one wave per row.
+__global__ __launch_bounds__(256) void row_scale_k(const float *ssq, int slots, int stride, int R, int K, float eps,
+                                                   float *scale) {
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (r >= R) return;
+    float s = 0.f;
+    for (int q = lane; q < slots; q += 64) s += ssq[(size_t)r * stride + q];
+    s = wave_sum(s);
+    if (lane == 0) scale[r] = rsqrtf(s / (float)K + eps);
+}
+
+// Arguments as for the decode kernels, except: x is a.x (fp32, row-major, row length K, x_mul = 1, x_add = 0) and the
+// row scales come ready-made in a.row_scale (null: ones).  grid.x = 8 * ceil(n_blocks / 8) * m_blocks.
+//
+// Timeline of the main loop (iteration t multiplies k-tile t from fragments already in registers):
+//   barrier            stage t + 1 is complete in LDS; nobody reads stages <= t any more
+//   convert x(t + 2)   from the registers loaded two iterations ago, into the x slot stage t has left
+//   issue   t + 4      W tiles by DMA into the W slot stage t has left, x rows into the registers just freed
+//   read    t + 1      fragments for the next iteration
+//   multiply t
+// so every global load has two to three iterations to arrive.  Stages past the last k-tile repeat it into slots
+// nobody reads again, which keeps the loop and its wait counts uniform.
+template <int EPI, int WM, int WN, bool DEEP>
+__global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_SIMD)) void gemm_mfma_k(const GemvArgs a,
+                                                                                                    const int m_blocks) {
+    using S = GemmShape<WM, WN, DEEP>;
+    constexpr int XI = S::XI;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    // the wave index is a scalar: every branch around a matrix instruction must be a scalar branch
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    int Ntot = a.n0;
+    if (EPI == EPI_QKV) Ntot = (a.nq + 2 * a.nkv) * a.hd;
+    if (EPI == EPI_SWIGLU) Ntot = 2 * a.n0;
+    const int n_groups = Ntot >> 4;
+    const int n_blocks = (n_groups + S::BNG - 1) / S::BNG;
+    // consecutive workgroup ids go round the XCDs: the m_blocks row blocks of one W block stay on one XCD
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const int nb = (j / m_blocks) * 8 + xcd, mb = j % m_blocks;
+    if (nb >= n_blocks) return;
+    const int g0 = nb * S::BNG, m0 = mb * S::BMB * 16;
+    const int K = a.K, KT = K >> 5, R = a.R;
+    char *const xs = smem;               // [2][XS]
+    char *const ws = smem + 2 * S::XS;   // [WSLOTS][WS]
+
+    // ---- load plan -------------------------------------------------------------------------------------
+    // W: wave w moves the tiles w, w + 4, ... of the stage
+    const char *wsrc[S::BNG / 4];
+#pragma unroll
+    for (int i = 0; i < S::BNG / 4; ++i) {
+        const int g = min(g0 + wave + 4 * i, n_groups - 1);
+        wsrc[i] = reinterpret_cast<const char *>(a.w0) + (size_t)g * KT * 1024 + lane * 16;
+    }
+    // x: load i of this thread covers row 8 (wave + 4 i) + lane / 8 of the block, floats 4 (lane % 8) ..+4 of the
+    // k-tile; they belong to fragment row % 16, k-chunk (lane % 8) / 2, elements 4 ((lane % 8) % 2) ..+4
+    const float *xsrc[XI];
+    int xdst[XI];
+#pragma unroll
+    for (int i = 0; i < XI; ++i) {
+        const int rl = 8 * (wave + 4 * i) + (lane >> 3), p = lane & 7;
+        xsrc[i] = a.x + (size_t)min(m0 + rl, R - 1) * K + 4 * p;
+        xdst[i] = (rl >> 4) * 2048 + (((p >> 1) * 16 + (rl & 15)) * 16) + (p & 1) * 8;
+    }
+
+    f32x4_t acc[WM][WN];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int n = 0; n < WN; ++n) acc[i][n] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    auto issue = [&](int stage, f32x4_t(&xr)[XI]) {
+        const int kt = min(stage, KT - 1);
+        char *wslot = ws + (stage & (S::WSLOTS - 1)) * S::WS;
+#pragma unroll
+        for (int i = 0; i < S::BNG / 4; ++i) dma_tile(wsrc[i] + (size_t)kt * 1024, wslot + (wave + 4 * i) * 1024);
+#pragma unroll
+        for (int i = 0; i < XI; ++i) xr[i] = *reinterpret_cast<const f32x4_t *>(xsrc[i] + (size_t)kt * 32);
+    };
+    auto convert = [&](const f32x4_t(&xr)[XI], char *xslot) {
+#pragma unroll
+        for (int i = 0; i < XI; ++i) {
+            u32x2_t hi, lo;
+            split4(xr[i], hi, lo);
+            *reinterpret_cast<u32x2_t *>(xslot + xdst[i]) = hi;
+            *reinterpret_cast<u32x2_t *>(xslot + xdst[i] + 1024) = lo;
+        }
+    };
+    auto read = [&](int stage, GemmFrags<WM, WN> &f) {
+        const char *xslot = xs + (stage & 1) * S::XS + lane * 16;
+        const char *wslot = ws + (stage & (S::WSLOTS - 1)) * S::WS + lane * 16;
+#pragma unroll
+        for (int i = 0; i < WM; ++i) {
+            f.ah[i] = *reinterpret_cast<const u32x4_t *>(xslot + (wm * WM + i) * 2048);
+            f.al[i] = *reinterpret_cast<const u32x4_t *>(xslot + (wm * WM + i) * 2048 + 1024);
+        }
+#pragma unroll
+        for (int n = 0; n < WN; ++n) f.bw[n] = *reinterpret_cast<const u32x4_t *>(wslot + (wn * WN + n) * 1024);
+    };
+    auto multiply = [&](const GemmFrags<WM, WN> &f) {
+#pragma unroll
+        for (int i = 0; i < WM; ++i) {
+#pragma unroll
+            for (int n = 0; n < WN; ++n) {
+                acc[i][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, f.ah[i]),
+                                                                    __builtin_bit_cast(bf16x8_t, f.bw[n]), acc[i][n], 0, 0, 0);
+                acc[i][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, f.al[i]),
+                                                                    __builtin_bit_cast(bf16x8_t, f.bw[n]), acc[i][n], 0, 0, 0);
+            }
+        }
+    };
+
+    f32x4_t xr0[XI], xr1[XI];
+    GemmFrags<WM, WN> fa, fb;
+    if constexpr (DEEP) {
+        issue(0, xr0);
+        issue(1, xr1);
+        convert(xr0, xs);
+        issue(2, xr0);
+        stage_barrier<2 * S::GROUP>();  // stage 0 complete
+        convert(xr1, xs + S::XS);
+        issue(3, xr1);
+        read(0, fa);
+        for (int t = 0; t + 1 < KT; t += 2) {  // two iterations per trip: registers and slots alternate
+            stage_barrier<2 * S::GROUP>();
+            convert(xr0, xs);
+            issue(t + 4, xr0);
+            read(t + 1, fb);
+            multiply(fa);
+            stage_barrier<2 * S::GROUP>();
+            convert(xr1, xs + S::XS);
+            issue(t + 5, xr1);
+            read(t + 2, fa);
+            multiply(fb);
+        }
+        if (KT & 1) multiply(fa);  // the last k-tile of an odd count was read by the trip before
+    } else {
+        // iteration t: issue t + 1, read and multiply t, convert x(t + 1), meet
+        issue(0, xr0);
+        convert(xr0, xs);
+        stage_barrier<0>();
+        for (int t = 0; t < KT; ++t) {
+            issue(t + 1, xr0);
+            read(t, fa);
+            multiply(fa);
+            convert(xr0, xs + ((t + 1) & 1) * S::XS);
+            stage_barrier<0>();
+        }
+    }
+    stage_barrier<0>();        // every load has landed before the ring is reused
+
+    // ---- epilogue: this wave's rows m0 + 16 WM wm ..+16 WM, two groups of W (32 columns) at a time ----------
+    constexpr int TS = GEMM_TS;
+    float *tile = reinterpret_cast<float *>(smem) + wave * (WM * 16 * TS + WM * 16);
+    float *scale = tile + WM * 16 * TS;
+    const int row0 = m0 + wm * WM * 16;
+    const int Rw = max(0, min(WM * 16, R - row0));
+    for (int r = lane; r < WM * 16; r += 64) scale[r] = (a.row_scale != nullptr && r < Rw) ? a.row_scale[row0 + r] : 1.f;
+    GemvArgs b = a;  // the same arguments, seen from this wave's first row
+    {
+        const size_t ro = (size_t)row0;
+        if constexpr (EPI == EPI_PLAIN) {
+            b.y += ro * a.n0;
+        } else if constexpr (EPI == EPI_RESID) {
+            b.xres += ro * a.n0; b.xg += ro * a.n0; b.xgb += ro * a.n0; b.ssq_out += ro * a.ssq_stride;
+        } else if constexpr (EPI == EPI_SWIGLU) {
+            b.y += ro * a.n0; b.yb += ro * a.n0;
+        } else if constexpr (EPI == EPI_QKV) {
+            b.y += ro * a.nq * a.hd; b.yb += ro * a.nq * a.hd; b.row_pos += row0; b.row_seq += row0;
+        }
+    }
+    // the tile and the scales are private to the wave: LDS serves a wave's accesses in order, so a wave-level
+    // wait orders its writes before its reads
+    auto wave_sync = [] { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); };
+    constexpr int RI = WM;  // residual epilogue: row steps (8 rows each) of half a pass
+#pragma unroll
+    for (int p = 0; p < WN / 2; ++p) {
+        const int g = g0 + wn * WN + 2 * p;  // first group of the pass
+        // residual: a lane owns four columns of one row per row step; the residual values of half the rows are
+        // fetched before the tile is staged, those of the other half while the first is worked through
+        const int rsub = lane >> 3, c4 = (lane & 7) * 4;
+        const int gl = g + (c4 >> 4);
+        const bool col_ok = gl < n_groups;
+        const int n = g * 16 + c4;
+        f32x4_t xo[RI], gn = {1.f, 1.f, 1.f, 1.f};
+        auto fetch = [&](int half) {
+#pragma unroll
+            for (int it = 0; it < RI; ++it) {
+                const int r = (half * RI + it) * 8 + rsub;
+                xo[it] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                if (col_ok && r < Rw) xo[it] = *reinterpret_cast<const f32x4_t *>(b.xres + (size_t)r * a.n0 + n);
+            }
+        };
+        if constexpr (EPI == EPI_RESID) {
+            if (col_ok && a.g_next != nullptr) gn = *reinterpret_cast<const f32x4_t *>(a.g_next + n);
+            fetch(0);
+        }
+        wave_sync();  // the previous pass has read the tile
+        // register v of lane l is x row 4 (l / 16) + v, W row l % 16
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    tile[(i * 16 + (lane >> 4) * 4 + v) * TS + h * 16 + (lane & 15)] = acc[i][2 * p + h][v];
+        wave_sync();
+        if constexpr (EPI == EPI_RESID) {
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                if (half == 1) fetch(1);
+#pragma unroll
+                for (int it = 0; it < RI; ++it) {
+                    const int r = (half * RI + it) * 8 + rsub;
+                    const bool ok = col_ok && r < Rw;
+                    const f32x4_t y = *reinterpret_cast<const f32x4_t *>(tile + r * TS + c4);
+                    const float sc = scale[r];
+                    f32x4_t xn, xg;
+                    float sq = 0.f;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        xn[e] = xo[it][e] + y[e] * sc;
+                        xg[e] = xn[e] * gn[e];
+                        sq += xn[e] * xn[e];
+                    }
+                    if (ok) {
+                        const size_t o = (size_t)r * a.n0 + n;
+                        *reinterpret_cast<f32x4_t *>(b.xres + o) = xn;
+                        *reinterpret_cast<f32x4_t *>(b.xg + o) = xg;
+                        u32x2_t hi, lo;
+                        split4(xg, hi, lo);
+                        *reinterpret_cast<u32x2_t *>(b.xgb + o) = hi;
+                        if (a.xgb_lo) *reinterpret_cast<u32x2_t *>(b.xgb + o + a.xgb_lo) = lo;
+                    }
+                    sq += __shfl_xor(sq, 1, WAVE);
+                    sq += __shfl_xor(sq, 2, WAVE);
+                    if (ok && (lane & 3) == 0) b.ssq_out[(size_t)r * a.ssq_stride + gl] = sq;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                if (g + h < n_groups && Rw > 0) epilogue_tile<EPI, 16, 64>(b, tile + h * 16, TS, scale, Rw, g + h, Ntot, lane);
+        }
+    }
+}
+
+template <int EPI, int WM, int WN, bool DEEP>
+static hipError_t launch_gemm_one(const GemvArgs &a, int Ntot, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s) {
+    using S = GemmShape<WM, WN, DEEP>;
+    const int n_blocks = (Ntot / 16 + S::BNG - 1) / S::BNG;
+    const int m_blocks = (a.R + S::BMB * 16 - 1) / (S::BMB * 16);
+    const int grid = ((n_blocks + 7) / 8) * 8 * m_blocks;
+    static bool attr_set = false;  // per instantiation
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_mfma_k<EPI, WM, WN, DEEP>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    if (ev0 != nullptr)
+        hipExtLaunchKernelGGL((gemm_mfma_k<EPI, WM, WN, DEEP>), dim3(grid), dim3(GEMM_THREADS), S::LDS, s, ev0, ev1, 0, a, m_blocks);
+    else
+        hipLaunchKernelGGL((gemm_mfma_k<EPI, WM, WN, DEEP>), dim3(grid), dim3(GEMM_THREADS), S::LDS, s, a, m_blocks);
+    return hipGetLastError();
+}
+
+template <int EPI>
+static hipError_t launch_gemm_cfg(const GemvArgs &a, int Ntot, int forced, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s) {
+    int cfg = forced;
+    if (cfg == 0) {
+        // both shapes are bound by what a compute unit can fetch from L2 per matrix instruction: the wide block
+        // needs a third less, the narrow one fills the chip when the wide one would leave compute units idle
+        const int m_blocks = (a.R + 127) / 128;
+        cfg = ((Ntot + 255) / 256) * m_blocks > 256 ? 408 : 404;
+    }
+    switch (cfg) {
+        case 408: return launch_gemm_one<EPI, 4, 8, false>(a, Ntot, ev0, ev1, s);
+        case 404: return launch_gemm_one<EPI, 4, 4, true>(a, Ntot, ev0, ev1, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+bool gemm_mfma_serves(int epi, int Ntot, int K, int R) {
+    return epi != EPI_LOGITS && R >= GEMM_MIN_ROWS && Ntot % 16 == 0 && K % 32 == 0;
+}
+
+// Host-side contract: w0 is the re-tiled matrix, Ntot % 16 == 0, K % 32 == 0, a.x holds R fp32 rows of length K
+// (x_mul = 1, x_add = 0), any R >= 1; RESID writes Ntot / 16 statistics slots per row (<= ssq_stride).  With
+// statistics of the input (a.ssq_in) the row scales are first reduced into scale_buf (device, R floats).
+// `forced` = 100 WM + WN selects the block shape (0 = automatic).
+hipError_t launch_gemm_mfma(const GemvArgs &a0, int epi, int forced, float *scale_buf, hipEvent_t ev_start,
+                            hipEvent_t ev_stop, hipStream_t s) {
+    GemvArgs a = a0;
+    int Ntot = a.n0;
+    if (epi == EPI_QKV) Ntot = (a.nq + 2 * a.nkv) * a.hd;
+    if (epi == EPI_SWIGLU) Ntot = 2 * a.n0;
+    if (a.R < 1 || Ntot % 16 || a.K % 32 || a.x == nullptr || a.x_mul != 1 || a.x_add != 0) return hipErrorInvalidValue;
+    if (epi == EPI_RESID && Ntot / 16 > a.ssq_stride) return hipErrorInvalidValue;
+    a.row_scale = nullptr;
+    if (a.ssq_in != nullptr) {
+        if (scale_buf == nullptr) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(row_scale_k, dim3((a.R + 3) / 4), dim3(256), 0, s, a.ssq_in, a.ssq_in_slots, a.ssq_stride, a.R,
+                           a.K, a.eps, scale_buf);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        a.row_scale = scale_buf;
+    }
+    switch (epi) {
+        case EPI_PLAIN: return launch_gemm_cfg<EPI_PLAIN>(a, Ntot, forced, ev_start, ev_stop, s);
+        case EPI_QKV: return launch_gemm_cfg<EPI_QKV>(a, Ntot, forced, ev_start, ev_stop, s);
+        case EPI_RESID: return launch_gemm_cfg<EPI_RESID>(a, Ntot, forced, ev_start, ev_stop, s);
+        case EPI_SWIGLU: return launch_gemm_cfg<EPI_SWIGLU>(a, Ntot, forced, ev_start, ev_stop, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace sd

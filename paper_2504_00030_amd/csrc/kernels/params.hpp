@@ -52,6 +52,7 @@ struct GemvArgs {
     const float *ssq_in;      // [row][ssq_stride] partial sums of squares of the un-normed input, or null
     int32_t ssq_in_slots, ssq_stride;
     float eps;
+    const float *row_scale;   // dense-contraction kernel only: ready-made row scales [R] (null: ones)
     int32_t rpw;              // W rows per wave (wave-dot) / 16-row groups per workgroup (matrix-core)
     const int32_t *active;    // when non-null and *active == 0 the kernel does nothing (drafting has stopped)
     // ---- epilogue ----
@@ -180,6 +181,11 @@ hipError_t launch_gemv_wavedot(const GemvArgs &a, int epi, int w_dtype, hipStrea
 hipError_t launch_gemv_mfma(const GemvArgs &a, int epi, int forced_cfg, hipEvent_t ev_start, hipEvent_t ev_stop,
                             hipStream_t s);
 int gemv_mfma_groups_per_wg(int epi, int Ntot, int K, int R, int forced_cfg);  // 16-row groups per workgroup
+// Prompt ingestion: the dense-contraction kernel for many rows (x read as fp32 rows, a.x).
+constexpr int GEMM_MIN_ROWS = 64;  // below this the weight-streaming kernels are the faster ones
+bool gemm_mfma_serves(int epi, int Ntot, int K, int R);
+hipError_t launch_gemm_mfma(const GemvArgs &a, int epi, int forced_cfg, float *scale_buf, hipEvent_t ev_start,
+                            hipEvent_t ev_stop, hipStream_t s);
 bool gemv_wavedot_uses_split(int epi, int Ntot, int K, int R, int w_dtype);
 int gemv_wavedot_tile_cols(int epi, int Ntot, int K, int R, int w_dtype);
 int gemv_wavedot_pick_rpw(int epi, int N, int K, int R, int w_dtype);

@@ -81,6 +81,27 @@ def test_gemv_mfma_matches_fp64_matmul(R, N, K):
     assert np.abs(got - want).max() <= tol
 
 
+@pytest.mark.parametrize("cfg", [0, 404, 408])
+@pytest.mark.parametrize("R", [1, 63, 64, 129, 200, 1023])
+@pytest.mark.parametrize("N,K", [(4096, 4096), (2064, 768), (48, 4096), (272, 96), (16384, 2048), (16, 32)])
+def test_gemm_mfma_matches_fp64_matmul(N, K, R, cfg):
+    # the prompt-ingestion kernel: row counts around its 128-row blocks, group counts off its 128 / 256-row blocks
+    pk = _pk()
+    g = torch.Generator().manual_seed(N * 5 + K + R)
+    w = (torch.randn(N, K, generator=g) * 0.02).to(torch.bfloat16)
+    x = torch.randn(R, K, generator=g)
+    want = (x.double() @ w.double().t()).numpy()
+    wt = torch.empty_like(w, device="cuda")
+    pk.k_retile(w.cuda().contiguous(), wt)
+    y = torch.full((R, N), float("nan"), device="cuda")
+    pk.k_gemm_tiled(wt, N, K, x.cuda().contiguous(), y, cfg)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy()
+    tol = 2e-6 * np.sqrt(K) * np.abs(want).max() + 1e-7
+    assert np.isfinite(got).all()
+    assert np.abs(got - want).max() <= tol
+
+
 def _run_pair(cfg, *, controller, temperature, seed=0, n_generate=None, prompt_len=None, batch=1, accept_mode=0,
               alpha=None, tau=0.0, norm_jitter=0.0, use_graphs=False, page_tokens=64, weights_seed=0, block_table=None,
               gemv_path=0, attn_chunk=0):
@@ -206,6 +227,19 @@ def test_small_bf16_pair_attention_chunk_sizes(pair, attn_chunk):
     assert c.max_logit_err <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("pair,batch,prompt_len", [("small-bf16", 1, 1100), ("small-bf16-hd128", 1, 1060),
+                                                   ("small-bf16", 3, 400), ("small-bf16-hd128", 2, 66)])
+def test_long_prompts_through_the_ingestion_kernels(pair, batch, prompt_len):
+    # prompts long enough for the dense-contraction kernels: two launches (1024 rows, then 75 rows on the same
+    # kernels or 35 rows on the weight-streaming ones), three sequences sharing a launch (341 rows each, then 58),
+    # and the smallest row count the kernels take; every later step attends to the cache they wrote
+    cfg = synth.pair(pair)
+    c, toks, trace = _run_pair(cfg, controller="gammatune", temperature=1.0, seed=11, prompt_len=prompt_len, n_generate=24,
+                               norm_jitter=0.05)
+    _assert_clean(c, full_coverage=False)
+    assert c.max_logit_err <= TOL["bf16"]
+
+
 def test_small_bf16_pair_head_sizes_batch2_gamma16():
     # 30-row last prefill chunk with K = 128 on the draft: the shape whose matrix instructions once ran
     # under an empty execution mask (non-finite logits, then an out-of-range argmax index)
@@ -246,8 +280,9 @@ def test_full_width_pairs_at_reduced_depth(pair_name, batch):
 
 
 def test_8b_pair_at_full_depth_and_width():
-    """The headline pair at its full size (32 / 16 layers): a 12-token prompt and a few speculative steps against
-    the fp64 oracle (about 75 GB of host memory for the widened weights, well under a minute on the GPU host).
+    """The headline pair at its full size (32 / 16 layers): an 80-token prompt (ingested by the dense-contraction
+    kernels) and a few speculative steps against the fp64 oracle (about 75 GB of host memory for the widened weights,
+    about a minute on the GPU host).
     Rounding accumulates with depth; this is the case that needs the activations as two bf16 terms."""
     from oracle import model as om
     pk = _pk()
@@ -257,7 +292,7 @@ def test_8b_pair_at_full_depth_and_width():
     widen = lambda W: {k: ([om.as_f64(a) for a in v] if isinstance(v, list) else om.as_f64(v))
                        for k, v in synth.to_numpy_weights(W).items()}
     Wt_np, Wd_np = widen(Wt), widen(Wd)
-    prompts = synth.make_prompts(1, 12, cfg.target.vocab, 7)
+    prompts = synth.make_prompts(1, 80, cfg.target.vocab, 7)
     alpha = synth.alpha_constant(0.9, 4)
     eng = pk.SpecEngine(cfg.target, Wt, cfg.draft, Wd, batch=1, max_seq=256, gamma_max=cfg.gamma_max, temperature=0.7,
                         seed=0, accept_mode=pk.ACCEPT_FORCED, use_graphs=True)
