@@ -1,18 +1,22 @@
 // Prompt ingestion: the same fused projections as the decode kernels, for hundreds of rows of x, where the
-// work is a dense contraction bound by the matrix cores rather than by the weight stream.
+// work is a dense contraction on the matrix cores rather than a weight stream.
 //
 // One workgroup of four waves (2 x 2) computes a block of 32 WM rows of x by 32 WN rows of W.  Per k-tile
 // (32 columns) a stage in LDS holds the operands of the whole block in the register layout of
 // v_mfma_f32_16x16x32_bf16:
 //   * W tiles come from the re-tiled weights, where a 16-row x 32-column tile is one contiguous KiB that
-//     already has that layout: global_load_lds_dwordx4 moves it into LDS without passing through registers;
-//   * x is read as fp32 rows (fully coalesced 128-byte lines), split in registers into two bf16 terms
-//     (x = hi + lo, the same split as the decode kernels make) and written as hi and lo fragments.
-// Two stages alternate: the loads of k-tile kt + 1 are issued before the matrix instructions of k-tile kt, and
-// two workgroups share a compute unit, so that one multiplies while the other converts and waits.  The block
-// index is mapped so that the workgroups an XCD runs at the same time share their W block (one L2 per XCD).
-// The epilogues are the decode kernels' own (RoPE + KV write, residual + next-norm statistics, SwiGLU): each
-// wave passes its 32 WM x 16 result tiles through LDS, one 16-row group of W at a time.
+//     already has that layout;
+//   * x is read as fp32 rows, split in registers into two bf16 terms (x = hi + lo, the same split as the
+//     decode kernels make) and written as hi and lo fragments.
+// Both pass through registers on their way to LDS: the compiler then counts every load exactly and waits for
+// the oldest ones only.  (A direct global-to-LDS copy of the W tiles saves the registers, but the compiler
+// drains every outstanding load before any LDS access that might alias such a copy, and with it the
+// prefetch; measured, that cost more than half of the kernel's time.)  Loads run one (wide block) or two
+// (narrow block) iterations ahead of the matrix instructions, two workgroups share a compute unit, and the
+// block index is mapped so that the workgroups an XCD runs at the same time share their W block (one L2 per
+// XCD).  The epilogues are the decode kernels' own arithmetic (RoPE + KV write, residual + next-norm
+// statistics, SwiGLU): each wave passes its 32 WM x 32 result tiles through LDS, two 16-row groups of W at a
+// time.
 #include <hip/hip_ext.h>
 
 #include "common.hpp"
@@ -31,15 +35,6 @@ typedef float f32x2_t __attribute__((ext_vector_type(2)));
 
 namespace {
 
-// 64 lanes x 16 bytes from global memory into LDS: lane l's bytes land at lds + 16 l.
-__device__ __forceinline__ void dma_tile(const void *g, void *lds) {
-    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)g,
-                                     (void __attribute__((address_space(3))) *)lds, 16, 0, 0);
-}
-
-// every vector-memory load of this wave, the LDS-bound ones included, has landed
-__device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
 // x = hi + lo with both terms rounded to nearest even (v_cvt_pk_bf16_f32)
 __device__ __forceinline__ void split4(const f32x4_t v, u32x2_t &hi, u32x2_t &lo) {
     const f32x2_t a = {v[0], v[1]}, b = {v[2], v[3]};
@@ -57,9 +52,9 @@ __device__ __forceinline__ void split4(const f32x4_t v, u32x2_t &hi, u32x2_t &lo
 constexpr int GEMM_THREADS = 256;
 constexpr int GEMM_TS = 36;                      // row stride (floats) of a wave's result tile in the epilogue
 
-// DEEP: the four-slot W ring with fragments double-buffered in registers (loads two to three iterations ahead);
-// otherwise two alternating stages with loads one iteration ahead, which leaves room for two workgroups of the
-// widest block per compute unit.
+// DEEP: loads two iterations ahead and the fragments of the next iteration read while this one multiplies (both
+// double-buffered in registers); otherwise loads one iteration ahead and fragments read where they are used,
+// which fits the registers of the wide block.
 template <int WM, int WN, bool DEEP>
 struct GemmShape {
     static constexpr int BMB = 2 * WM;              // 16-row blocks of x per workgroup
@@ -67,19 +62,16 @@ struct GemmShape {
     static constexpr int XS = BMB * 2 * 1024;       // bytes of the x fragments of a stage (hi and lo)
     static constexpr int WS = BNG * 1024;           // bytes of the W tiles of a stage
     static constexpr int XI = BMB / 2;              // x loads per thread and stage
-    static constexpr int GROUP = BNG / 4 + XI;      // vector-memory loads a wave issues per stage
-    static constexpr int WSLOTS = DEEP ? 4 : 2;
-    static constexpr int RING = 2 * XS + WSLOTS * WS;
+    static constexpr int WI = BNG / 4;              // W loads per thread and stage
+    static constexpr int RING = 2 * (XS + WS);      // two stages alternate
     static constexpr int EPI_BYTES = 4 * (WM * 16 * GEMM_TS + WM * 16) * 4;  // four waves: result tile + row scales
     static constexpr int LDS = RING > EPI_BYTES ? RING : EPI_BYTES;
     static constexpr int WAVES_PER_SIMD = 2 * LDS <= 160 * 1024 ? 2 : 1;
 };
 
-// The workgroup meets once this wave's LDS traffic is done and all but its N newest vector-memory loads
-// have landed.  (__syncthreads would drain every load and with it the prefetch.)
-template <int N> __device__ __forceinline__ void stage_barrier() {
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
-}
+// The workgroup meets once this wave's LDS traffic is done.  (__syncthreads would also drain every global
+// load and with it the prefetch.)
+__device__ __forceinline__ void stage_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 template <int WM, int WN> struct GemmFrags { u32x4_t ah[WM], al[WM], bw[WN]; };
 
@@ -97,14 +89,13 @@ __global__ __launch_bounds__(256) void row_scale_k(const float *ssq, int slots, 
 // Arguments as for the decode kernels, except: x is a.x (fp32, row-major, row length K, x_mul = 1, x_add = 0) and the
 // row scales come ready-made in a.row_scale (null: ones).  grid.x = 8 * ceil(n_blocks / 8) * m_blocks.
 //
-// Timeline of the main loop (iteration t multiplies k-tile t from fragments already in registers):
-//   barrier            stage t + 1 is complete in LDS; nobody reads stages <= t any more
-//   convert x(t + 2)   from the registers loaded two iterations ago, into the x slot stage t has left
-//   issue   t + 4      W tiles by DMA into the W slot stage t has left, x rows into the registers just freed
+// Timeline of the deep main loop (iteration t multiplies k-tile t from fragments already in registers):
+//   barrier            stage t + 1 is complete in LDS; nobody reads stage t any more
+//   stash   t + 2      from the registers loaded two iterations ago into the slot stage t has left (x is split here)
+//   issue   t + 4      global loads into the registers just freed
 //   read    t + 1      fragments for the next iteration
 //   multiply t
-// so every global load has two to three iterations to arrive.  Stages past the last k-tile repeat it into slots
-// nobody reads again, which keeps the loop and its wait counts uniform.
+// Stages past the last k-tile repeat it into slots nobody reads again, which keeps the loop uniform.
 template <int EPI, int WM, int WN, bool DEEP>
 __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_SIMD)) void gemm_mfma_k(const GemvArgs a,
                                                                                                     const int m_blocks) {
@@ -126,7 +117,7 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
     const int g0 = nb * S::BNG, m0 = mb * S::BMB * 16;
     const int K = a.K, KT = K >> 5, R = a.R;
     char *const xs = smem;               // [2][XS]
-    char *const ws = smem + 2 * S::XS;   // [WSLOTS][WS]
+    char *const ws = smem + 2 * S::XS;   // [2][WS]
 
     // ---- load plan -------------------------------------------------------------------------------------
     // W: wave w moves the tiles w, w + 4, ... of the stage
@@ -136,15 +127,19 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
         const int g = min(g0 + wave + 4 * i, n_groups - 1);
         wsrc[i] = reinterpret_cast<const char *>(a.w0) + (size_t)g * KT * 1024 + lane * 16;
     }
-    // x: load i of this thread covers row 8 (wave + 4 i) + lane / 8 of the block, floats 4 (lane % 8) ..+4 of the
-    // k-tile; they belong to fragment row % 16, k-chunk (lane % 8) / 2, elements 4 ((lane % 8) % 2) ..+4
+    // x: the block's fragments are filled in units of 512 contiguous bytes (16 rows x two k-chunks of 8 columns), one
+    // unit per wave-wide load, so that the LDS writes of a wave touch every bank once: unit q = XI wave + i is row
+    // block q / 2, k-chunks 2 (q % 2) and 2 (q % 2) + 1; lane l holds row l / 2 % 16, k-chunk l / 32 of the pair,
+    // elements 4 (l % 2) ..+4, and its eight bytes (per term) land at 8 l of the unit.  Two consecutive loads of a
+    // wave read the two halves of the same 128-byte lines.
     const float *xsrc[XI];
     int xdst[XI];
 #pragma unroll
     for (int i = 0; i < XI; ++i) {
-        const int rl = 8 * (wave + 4 * i) + (lane >> 3), p = lane & 7;
-        xsrc[i] = a.x + (size_t)min(m0 + rl, R - 1) * K + 4 * p;
-        xdst[i] = (rl >> 4) * 2048 + (((p >> 1) * 16 + (rl & 15)) * 16) + (p & 1) * 8;
+        const int q = XI * wave + i, rb = q >> 1, c = 2 * (q & 1) + (lane >> 5);
+        const int row = m0 + rb * 16 + ((lane >> 1) & 15);
+        xsrc[i] = a.x + (size_t)min(row, R - 1) * K + 8 * c + 4 * (lane & 1);
+        xdst[i] = rb * 2048 + (q & 1) * 512 + lane * 8;
     }
 
     f32x4_t acc[WM][WN];
@@ -153,26 +148,29 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
 #pragma unroll
         for (int n = 0; n < WN; ++n) acc[i][n] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    auto issue = [&](int stage, f32x4_t(&xr)[XI]) {
+    struct Staged { f32x4_t x[XI]; u32x4_t w[S::WI]; };
+    auto issue = [&](int stage, Staged &r) {
         const int kt = min(stage, KT - 1);
-        char *wslot = ws + (stage & (S::WSLOTS - 1)) * S::WS;
 #pragma unroll
-        for (int i = 0; i < S::BNG / 4; ++i) dma_tile(wsrc[i] + (size_t)kt * 1024, wslot + (wave + 4 * i) * 1024);
+        for (int i = 0; i < S::WI; ++i) r.w[i] = *reinterpret_cast<const u32x4_t *>(wsrc[i] + (size_t)kt * 1024);
 #pragma unroll
-        for (int i = 0; i < XI; ++i) xr[i] = *reinterpret_cast<const f32x4_t *>(xsrc[i] + (size_t)kt * 32);
+        for (int i = 0; i < XI; ++i) r.x[i] = *reinterpret_cast<const f32x4_t *>(xsrc[i] + (size_t)kt * 32);
     };
-    auto convert = [&](const f32x4_t(&xr)[XI], char *xslot) {
+    auto stash = [&](const Staged &r, int slot) {
+        char *xslot = xs + slot * S::XS, *wslot = ws + slot * S::WS;
 #pragma unroll
         for (int i = 0; i < XI; ++i) {
             u32x2_t hi, lo;
-            split4(xr[i], hi, lo);
+            split4(r.x[i], hi, lo);
             *reinterpret_cast<u32x2_t *>(xslot + xdst[i]) = hi;
             *reinterpret_cast<u32x2_t *>(xslot + xdst[i] + 1024) = lo;
         }
+#pragma unroll
+        for (int i = 0; i < S::WI; ++i) *reinterpret_cast<u32x4_t *>(wslot + (wave + 4 * i) * 1024 + lane * 16) = r.w[i];
     };
     auto read = [&](int stage, GemmFrags<WM, WN> &f) {
         const char *xslot = xs + (stage & 1) * S::XS + lane * 16;
-        const char *wslot = ws + (stage & (S::WSLOTS - 1)) * S::WS + lane * 16;
+        const char *wslot = ws + (stage & 1) * S::WS + lane * 16;
 #pragma unroll
         for (int i = 0; i < WM; ++i) {
             f.ah[i] = *reinterpret_cast<const u32x4_t *>(xslot + (wm * WM + i) * 2048);
@@ -194,44 +192,44 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
         }
     };
 
-    f32x4_t xr0[XI], xr1[XI];
+    Staged r0, r1;
     GemmFrags<WM, WN> fa, fb;
     if constexpr (DEEP) {
-        issue(0, xr0);
-        issue(1, xr1);
-        convert(xr0, xs);
-        issue(2, xr0);
-        stage_barrier<2 * S::GROUP>();  // stage 0 complete
-        convert(xr1, xs + S::XS);
-        issue(3, xr1);
+        issue(0, r0);
+        issue(1, r1);
+        stash(r0, 0);
+        issue(2, r0);
+        stage_barrier();  // stage 0 complete
+        stash(r1, 1);
+        issue(3, r1);
         read(0, fa);
         for (int t = 0; t + 1 < KT; t += 2) {  // two iterations per trip: registers and slots alternate
-            stage_barrier<2 * S::GROUP>();
-            convert(xr0, xs);
-            issue(t + 4, xr0);
+            stage_barrier();
+            stash(r0, 0);
+            issue(t + 4, r0);
             read(t + 1, fb);
             multiply(fa);
-            stage_barrier<2 * S::GROUP>();
-            convert(xr1, xs + S::XS);
-            issue(t + 5, xr1);
+            stage_barrier();
+            stash(r1, 1);
+            issue(t + 5, r1);
             read(t + 2, fa);
             multiply(fb);
         }
         if (KT & 1) multiply(fa);  // the last k-tile of an odd count was read by the trip before
     } else {
-        // iteration t: issue t + 1, read and multiply t, convert x(t + 1), meet
-        issue(0, xr0);
-        convert(xr0, xs);
-        stage_barrier<0>();
+        // iteration t: issue t + 1, read and multiply t, stash t + 1, meet
+        issue(0, r0);
+        stash(r0, 0);
+        stage_barrier();
         for (int t = 0; t < KT; ++t) {
-            issue(t + 1, xr0);
+            issue(t + 1, r0);
             read(t, fa);
             multiply(fa);
-            convert(xr0, xs + ((t + 1) & 1) * S::XS);
-            stage_barrier<0>();
+            stash(r0, (t + 1) & 1);
+            stage_barrier();
         }
     }
-    stage_barrier<0>();        // every load has landed before the ring is reused
+    __syncthreads();  // every load has landed and every wave has left the stages before they are reused
 
     // ---- epilogue: this wave's rows m0 + 16 WM wm ..+16 WM, two groups of W (32 columns) at a time ----------
     constexpr int TS = GEMM_TS;
