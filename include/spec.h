@@ -76,7 +76,8 @@ typedef struct {
 } spec_weights;
 
 typedef struct {
-    int32_t  batch;        /* sequences decoded in lock-step, >= 1 */
+    int32_t  batch;        /* sequences decoded in lock-step, 1..64; batch * (gamma_max + 1) rows make one verification
+                              pass: at most 128, or 1024 when the target is a bf16 model on the matrix-core kernels */
     int32_t  max_seq;      /* capacity in tokens per sequence (prompt + generated + gamma_max + 1) */
     int32_t  page_tokens;  /* tokens per KV page, a power of two >= 8; 0 -> 64 */
     int32_t  gamma_max;    /* largest gamma ever passed to spec_draft, 1..64 */

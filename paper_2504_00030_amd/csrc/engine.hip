@@ -26,6 +26,7 @@ constexpr int SSQ_STRIDE = 512;
 constexpr int ATT_CHUNK = 64;
 constexpr int RESID_CHUNKS = 64;
 constexpr int PREFILL_ROWS = 32;        // rows per sequence of one ingestion launch on the weight-streaming kernels
+constexpr int64_t DENSE_MIN_ROWS_X_N = 640 * 1024;  // rows x output columns from which the dense kernel is the faster one
 constexpr int PREFILL_GEMM_ROWS = 1024;  // rows (all sequences) of one ingestion launch on the dense-contraction kernels
 
 struct ModelRT {
@@ -362,13 +363,21 @@ bool use_mfma(const spec_ctx *c, const ModelRT &m, int R) {
 // Launch one fused projection on whichever kernel family serves R rows; `tiled` is the re-tiled
 // copy of the same matrices.  Returns the number of workgroups through *blocks.
 int launch_proj(spec_ctx *c, ModelRT &m, GemvArgs a, int epi, const void *tiled, int Ntot, int *blocks,
-                int *tile_cols, bool ingest = false) {
+                int *tile_cols) {
     ProfScope ps_(c, m, epi, use_mfma(c, m, a.R));
-    if (ingest && m.mfma_ok && gemm_mfma_serves(epi, Ntot, a.K, a.R)) {
-        // prompt ingestion over many rows: the dense-contraction kernel; statistics slots are per 16-row group
+    // Many rows (prompt ingestion, verification of a large batch): the dense-contraction kernel.  Its time hardly
+    // depends on the row count (about 0.6 us per k-tile while its blocks fit the chip once), the weight-streaming
+    // kernel's grows with rows x N (about 3e-8 us per row, output column and k): measured on the 8B shapes the
+    // dense kernel wins from N * R ~ 640 k up; beyond 128 rows it is the only one.
+    const bool dense = m.mfma_ok && gemm_mfma_serves(epi, Ntot, a.K, a.R) && a.x_mul == 1 && a.x_add == 0 &&
+                       (a.R > 128 || (int64_t)Ntot * a.R >= DENSE_MIN_ROWS_X_N);
+    if (dense) {
+        // statistics slots and softmax partials are per 16-row group of W
         a.w0 = tiled; a.w1 = a.w2 = nullptr;
+        if (epi == EPI_LOGITS) a.n_tiles = Ntot / 16;
         if (blocks) *blocks = Ntot / 16;
         if (tile_cols) *tile_cols = 16;
+        if (epi == EPI_LOGITS && Ntot / 16 > m.tiles_cap) return fail(c, SPEC_EINVAL, "logits tiling exceeds the partial buffers");
         if (epi == EPI_RESID && Ntot / 16 > SSQ_STRIDE) return fail(c, SPEC_EINVAL, "too many statistics slots");
         HIPCHK(c, launch_gemm_mfma(a, epi, 0, m.row_scale, ps_.ev0, ps_.ev1, c->stream));
         return SPEC_OK;
@@ -433,7 +442,6 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
     };
     const int kvd = s.n_kv_heads * s.head_dim;
     const bool tiled = m.mfma_ok;
-    const bool ingest = plan.mode == ROWS_PREFILL;
     for (int l = 0; l < s.n_layers; ++l) {
         {   // fused QKV projection + RoPE + KV write
             GemvArgs a = base(d, m.xg, m.xgb, xgb_lo);
@@ -443,7 +451,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             a.y = m.q; a.yb = m.qb; a.yb_lo = qb_lo; a.nq = s.n_q_heads; a.nkv = s.n_kv_heads; a.hd = s.head_dim;
             a.rope_cos = m.rope_cos; a.rope_sin = m.rope_sin; a.row_pos = m.row_pos; a.row_seq = m.row_seq;
             a.kv = kv_of(c, m, l); a.kv_dtype = s.dtype;
-            TRY(launch_proj(c, m, a, EPI_QKV, tiled ? m.t_qkv[l] : nullptr, qd + 2 * kvd, nullptr, nullptr, ingest));
+            TRY(launch_proj(c, m, a, EPI_QKV, tiled ? m.t_qkv[l] : nullptr, qd + 2 * kvd, nullptr, nullptr));
         }
         {
             AttnArgs t{};
@@ -464,21 +472,21 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             GemvArgs a = base(qd, m.ao, m.aob, aob_lo);
             a.w0 = m.wo[l]; a.n0 = d;
             a.xres = m.x; a.g_next = m.ffn_norm[l]; a.xg = m.xg; a.xgb = m.xgb; a.xgb_lo = xgb_lo; a.ssq_out = m.ssq;
-            TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wo[l] : nullptr, d, &slots, nullptr, ingest));
+            TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wo[l] : nullptr, d, &slots, nullptr));
         }
         {   // gate / up projections + SwiGLU
             GemvArgs a = base(d, m.xg, m.xgb, xgb_lo);
             a.w0 = m.wg[l]; a.w1 = m.wu[l]; a.n0 = ffn;
             a.ssq_in = m.ssq; a.ssq_in_slots = slots;
             a.y = m.act; a.yb = m.actb; a.yb_lo = actb_lo;
-            TRY(launch_proj(c, m, a, EPI_SWIGLU, tiled ? m.t_gu[l] : nullptr, 2 * ffn, nullptr, nullptr, ingest));
+            TRY(launch_proj(c, m, a, EPI_SWIGLU, tiled ? m.t_gu[l] : nullptr, 2 * ffn, nullptr, nullptr));
         }
         {   // down projection + residual
             GemvArgs a = base(ffn, m.act, m.actb, actb_lo);
             a.w0 = m.wd[l]; a.n0 = d;
             a.xres = m.x; a.g_next = (l + 1 < s.n_layers) ? m.attn_norm[l + 1] : m.final_norm;
             a.xg = m.xg; a.xgb = m.xgb; a.xgb_lo = xgb_lo; a.ssq_out = m.ssq;
-            TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wd[l] : nullptr, d, &slots, nullptr, ingest));
+            TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wd[l] : nullptr, d, &slots, nullptr));
         }
     }
     if (lp.want) {
@@ -680,7 +688,13 @@ int spec_init(const spec_shape *t, const spec_weights *tw, const spec_shape *d, 
     if (!(g.temperature >= 0.f)) return bail(fail(c, SPEC_EINVAL, "temperature < 0"));
     if (g.accept_mode != SPEC_ACCEPT_NATURAL && g.accept_mode != SPEC_ACCEPT_FORCED)
         return bail(fail(c, SPEC_EINVAL, "unknown accept_mode"));
-    if (g.batch * (g.gamma_max + 1) > 128) return bail(fail(c, SPEC_EINVAL, "batch * (gamma_max + 1) > 128 rows"));
+    {   // rows of a verification pass: 128 on the weight-streaming kernels; up to the ingestion launch size when
+        // the target also runs on the dense-contraction kernels.  The first draft pass has two rows per sequence.
+        const int rows = g.batch * (g.gamma_max + 1);
+        const int cap = ingest_rows(c->cfg, *t) >= PREFILL_GEMM_ROWS ? PREFILL_GEMM_ROWS : 128;
+        if (rows > cap) return bail(fail(c, SPEC_EINVAL, "batch * (gamma_max + 1) exceeds the rows of one pass (128, or 1024 for a bf16 target on the matrix cores)"));
+        if (2 * g.batch > 128) return bail(fail(c, SPEC_EINVAL, "batch > 64"));
+    }
 
     const int B = g.batch;
     const int rows_t = std::max(B * (g.gamma_max + 1), ingest_rows(c->cfg, *t));

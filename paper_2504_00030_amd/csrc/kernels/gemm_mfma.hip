@@ -101,6 +101,7 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
                                                                                                     const int m_blocks) {
     using S = GemmShape<WM, WN, DEEP>;
     constexpr int XI = S::XI;
+    if (a.active != nullptr && *a.active == 0) return;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     // the wave index is a scalar: every branch around a matrix instruction must be a scalar branch
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -249,6 +250,10 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
             b.y += ro * a.n0; b.yb += ro * a.n0;
         } else if constexpr (EPI == EPI_QKV) {
             b.y += ro * a.nq * a.hd; b.yb += ro * a.nq * a.hd; b.row_pos += row0; b.row_seq += row0;
+        } else if constexpr (EPI == EPI_LOGITS) {
+            // logical row r writes output row r * y_mul + y_add: one softmax partial per row and 16-column tile
+            const size_t orow = ro * a.y_mul;
+            b.y += orow * a.y_stride; b.pm += orow * a.n_tiles; b.ps += orow * a.n_tiles; b.pa += orow * a.n_tiles;
         }
     }
     // the tile and the scales are private to the wave: LDS serves a wave's accesses in order, so a wave-level
@@ -364,11 +369,13 @@ static hipError_t launch_gemm_cfg(const GemvArgs &a, int Ntot, int forced, hipEv
 }
 
 bool gemm_mfma_serves(int epi, int Ntot, int K, int R) {
-    return epi != EPI_LOGITS && R >= GEMM_MIN_ROWS && Ntot % 16 == 0 && K % 32 == 0;
+    (void)epi;
+    return R >= GEMM_MIN_ROWS && Ntot % 16 == 0 && K % 32 == 0;
 }
 
 // Host-side contract: w0 is the re-tiled matrix, Ntot % 16 == 0, K % 32 == 0, a.x holds R fp32 rows of length K
-// (x_mul = 1, x_add = 0), any R >= 1; RESID writes Ntot / 16 statistics slots per row (<= ssq_stride).  With
+// (x_mul = 1, x_add = 0), any R >= 1; RESID writes Ntot / 16 statistics slots per row (<= ssq_stride); LOGITS writes
+// one softmax partial per row and 16-column tile (n_tiles = Ntot / 16).  With
 // statistics of the input (a.ssq_in) the row scales are first reduced into scale_buf (device, R floats).
 // `forced` = 100 WM + WN selects the block shape (0 = automatic).
 hipError_t launch_gemm_mfma(const GemvArgs &a0, int epi, int forced, float *scale_buf, hipEvent_t ev_start,
@@ -393,6 +400,7 @@ hipError_t launch_gemm_mfma(const GemvArgs &a0, int epi, int forced, float *scal
         case EPI_QKV: return launch_gemm_cfg<EPI_QKV>(a, Ntot, forced, ev_start, ev_stop, s);
         case EPI_RESID: return launch_gemm_cfg<EPI_RESID>(a, Ntot, forced, ev_start, ev_stop, s);
         case EPI_SWIGLU: return launch_gemm_cfg<EPI_SWIGLU>(a, Ntot, forced, ev_start, ev_stop, s);
+        case EPI_LOGITS: return launch_gemm_cfg<EPI_LOGITS>(a, Ntot, forced, ev_start, ev_stop, s);
     }
     return hipErrorInvalidValue;
 }

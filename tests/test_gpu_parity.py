@@ -407,9 +407,24 @@ def test_small_bf16_pair_batch_forced_early_stop_graphs():
     assert max(int(r["gamma"].max()) for r in trace) >= 3
 
 
+@pytest.mark.parametrize("pair,batch,gamma", [("small-bf16", 24, 7), ("small-bf16-hd128", 40, 15), ("small-bf16", 64, 15),
+                                              ("small-bf16", 43, 2)])
+def test_small_bf16_pair_beyond_128_rows(pair, batch, gamma):
+    """Verification passes of 192, 640, 1024 (the limit) and a ragged 129 rows: beyond the 128 rows of the
+    weight-streaming kernels every projection of the pass, the LM head with its softmax partials included, runs on
+    the dense-contraction kernels; the draft passes (one or two rows per sequence) stay on the streaming ones."""
+    from dataclasses import replace
+    cfg = replace(synth.pair(pair), gamma_max=gamma)
+    c, toks, trace = _run_pair(cfg, controller=f"fixed{gamma}", temperature=1.0, seed=9, batch=batch, n_generate=8,
+                               prompt_len=20)
+    _assert_clean(c, full_coverage=False)
+    assert c.max_logit_err <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("batch,gamma", [(8, 15), (64, 1), (42, 2)])
 def test_small_bf16_pair_at_the_row_limit(batch, gamma):
-    """128 rows per verification pass (the library's limit) and a ragged 126: eight 16-row blocks of x."""
+    """128 rows per verification pass (the limit of the weight-streaming kernels) and a ragged 126: eight 16-row
+    blocks of x."""
     from dataclasses import replace
     cfg = replace(synth.pair("small-bf16"), gamma_max=gamma)
     c, toks, trace = _run_pair(cfg, controller=f"fixed{gamma}", temperature=1.0, seed=8, batch=batch, n_generate=12,
@@ -538,3 +553,14 @@ def test_call_order_and_argument_errors():
     bad = synth.ModelShape(2, 128, 4, 3, 32, 344, 512, dtype="fp32")
     with pytest.raises(pk.SpecError):
         pk.SpecEngine(bad, Wt_g, cfg.draft, Wd_g, max_seq=64, gamma_max=4)
+    # rows of one verification pass: 128 for an fp32 target, 1024 for a bf16 target on the matrix cores; 64 sequences
+    with pytest.raises(pk.SpecError) as e:
+        pk.SpecEngine(cfg.target, Wt_g, cfg.draft, Wd_g, batch=26, max_seq=64, gamma_max=4)
+    assert e.value.code == bd.SPEC_EINVAL
+    cb = synth.pair("small-bf16")
+    Wb, Wbd = synth.make_pair_weights(cb, 0)
+    Wb_g, Wbd_g = to_gpu(Wb), to_gpu(Wbd)
+    for batch, gamma in [(65, 1), (41, 24)]:
+        with pytest.raises(pk.SpecError) as e:
+            pk.SpecEngine(cb.target, Wb_g, cb.draft, Wbd_g, batch=batch, max_seq=128, gamma_max=gamma)
+        assert e.value.code == bd.SPEC_EINVAL
