@@ -236,12 +236,16 @@ int spec_k_gemv(const void *w, int32_t dtype, int32_t N, int32_t K, const float 
 int spec_k_gemv_tiled(const void *w_tiled, int32_t N, int32_t K, const void *x_bf16, const void *x_lo_bf16, int32_t R,
                       float *y, int32_t cfg, void *stream);
 
-/* The prompt-ingestion kernel alone (a dense contraction on the matrix cores, for many rows), asynchronous, no
- * allocation: y[r][n] = sum_k x[r][k] * W[n][k] with w_tiled from spec_k_retile (N % 16 == 0, K % 32 == 0), x device
- * fp32 [R][K] (multiplied as its two-term bf16 split, about 16 significant bits), y device fp32 [R][N], any R >= 1.
- * cfg = 0 picks the block shape from (N, R); 408 / 404 force blocks of 128 rows of x by 256 / 128 rows of W. */
+/* The dense-contraction kernel alone (prompt ingestion, verification of large batches: many rows on the matrix
+ * cores), asynchronous, no allocation: y[r][n] = sum_k x[r][k] * W[n][k] with w_tiled from spec_k_retile (N % 16 == 0,
+ * K % 32 == 0), x device fp32 [R][K] (multiplied as its two-term bf16 split, about 16 significant bits), y device
+ * fp32 [R][N], any R >= 1.  cfg = 0 picks the block shape and the split of K from (N, K, R); otherwise cfg = 1000 *
+ * shares + shape with shape 408 / 404 (blocks of 128 rows of x by 256 / 128 rows of W; 0: automatic) and shares = 2..8
+ * workgroups per block, each multiplying its share of K, followed by a summing pass (shape 404 only; 0: automatic).
+ * workspace: device scratch for the shares' partial results, at least shares * R * N * 4 bytes (NULL: never split).
+ * SPEC_EINVAL when the forced split does not fit (workspace too small, fewer k-tiles than shares). */
 int spec_k_gemm_tiled(const void *w_tiled, int32_t N, int32_t K, const float *x, int32_t R, float *y, int32_t cfg,
-                      void *stream);
+                      void *workspace, int64_t workspace_bytes, void *stream);
 
 /* Re-tile a row-major bf16 matrix [N][K] into the streaming layout of the matrix-core kernel:
  * 16-row groups, each group a run of 1 KiB tiles (16 rows x 32 k) stored lane-major.  out: device,

@@ -117,7 +117,8 @@ def load() -> C.CDLL:
                                 C.c_void_p]
     lib.spec_k_gemv_tiled.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
                                       C.c_void_p]
-    lib.spec_k_gemm_tiled.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
+    lib.spec_k_gemm_tiled.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
+                                      C.c_int64, C.c_void_p]
     lib.spec_k_retile.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.spec_k_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     lib.spec_k_philox.argtypes = [C.c_uint64, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
@@ -387,9 +388,12 @@ def k_gemv_tiled(w_tiled, N, K, x_bf16, y, cfg: int = 0, stream: int = 0, x_lo=N
         raise SpecError(rc, "spec_k_gemv_tiled")
 
 
-def k_gemm_tiled(w_tiled, N, K, x, y, cfg: int = 0, stream: int = 0):
-    """x: fp32 [R][K]; y: fp32 [R][N]; the prompt-ingestion kernel with the plain epilogue."""
-    rc = load().spec_k_gemm_tiled(w_tiled.data_ptr(), N, K, x.data_ptr(), y.shape[0], y.data_ptr(), cfg, stream)
+def k_gemm_tiled(w_tiled, N, K, x, y, cfg: int = 0, stream: int = 0, workspace=None):
+    """x: fp32 [R][K]; y: fp32 [R][N]; the dense-contraction kernel with the plain epilogue.  workspace: a device
+    tensor for the partial results when K is shared out over workgroups (cfg = 1000 * shares + shape)."""
+    ws = None if workspace is None else workspace.data_ptr()
+    nb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().spec_k_gemm_tiled(w_tiled.data_ptr(), N, K, x.data_ptr(), y.shape[0], y.data_ptr(), cfg, ws, nb, stream)
     if rc != 0:
         raise SpecError(rc, "spec_k_gemm_tiled")
 

@@ -26,7 +26,6 @@ constexpr int SSQ_STRIDE = 512;
 constexpr int ATT_CHUNK = 64;
 constexpr int RESID_CHUNKS = 64;
 constexpr int PREFILL_ROWS = 32;        // rows per sequence of one ingestion launch on the weight-streaming kernels
-constexpr int64_t DENSE_MIN_ROWS_X_N = 640 * 1024;  // rows x output columns from which the dense kernel is the faster one
 constexpr int PREFILL_GEMM_ROWS = 1024;  // rows (all sequences) of one ingestion launch on the dense-contraction kernels
 
 struct ModelRT {
@@ -40,7 +39,8 @@ struct ModelRT {
     void *t_lm = nullptr;
     bool mfma_ok = false;
     int Rmax = 0;
-    float *x = nullptr, *xg = nullptr, *ssq = nullptr, *row_scale = nullptr, *q = nullptr, *ao = nullptr, *act = nullptr;
+    size_t gemm_ws_bytes = 0;
+    float *x = nullptr, *xg = nullptr, *ssq = nullptr, *row_scale = nullptr, *gemm_ws = nullptr, *q = nullptr, *ao = nullptr, *act = nullptr;
     uint16_t *xgb = nullptr, *qb = nullptr, *aob = nullptr, *actb = nullptr;
     int32_t *row_pos = nullptr, *row_seq = nullptr;
     std::vector<void *> kpool, vpool;
@@ -250,6 +250,12 @@ int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights
     TRY(dalloc(c, &m.xgb, 2 * R * d));  // hi half, then the remainder half
     TRY(dalloc(c, &m.ssq, R * SSQ_STRIDE));
     TRY(dalloc(c, &m.row_scale, R));
+    if (m.mfma_ok) {
+        // partial results of projections whose k-tiles are shared out over workgroups: the matrices with few
+        // output columns (d_model, QKV) at up to 512 rows, eight shares
+        m.gemm_ws_bytes = (size_t)8 * std::min<size_t>(R, 512) * std::max(d, qd + 2 * kvd) * sizeof(float);
+        TRY(dalloc(c, &m.gemm_ws, m.gemm_ws_bytes / sizeof(float)));
+    }
     TRY(dalloc(c, &m.q, R * qd));
     TRY(dalloc(c, &m.qb, 2 * R * qd));
     TRY(dalloc(c, &m.ao, R * qd));
@@ -365,12 +371,16 @@ bool use_mfma(const spec_ctx *c, const ModelRT &m, int R) {
 int launch_proj(spec_ctx *c, ModelRT &m, GemvArgs a, int epi, const void *tiled, int Ntot, int *blocks,
                 int *tile_cols) {
     ProfScope ps_(c, m, epi, use_mfma(c, m, a.R));
-    // Many rows (prompt ingestion, verification of a large batch): the dense-contraction kernel.  Its time hardly
-    // depends on the row count (about 0.6 us per k-tile while its blocks fit the chip once), the weight-streaming
-    // kernel's grows with rows x N (about 3e-8 us per row, output column and k): measured on the 8B shapes the
-    // dense kernel wins from N * R ~ 640 k up; beyond 128 rows it is the only one.
-    const bool dense = m.mfma_ok && gemm_mfma_serves(epi, Ntot, a.K, a.R) && a.x_mul == 1 && a.x_add == 0 &&
-                       (a.R > 128 || (int64_t)Ntot * a.R >= DENSE_MIN_ROWS_X_N);
+    // Many rows (prompt ingestion, verification of a batch): the dense-contraction kernel.  Its time hardly depends
+    // on the row count, the weight-streaming kernel's grows with rows x N x K beyond the 16 rows of its persistent
+    // form (measured on the 8B shapes: 1.6e-8 us per row, column and k up to 32 rows, 1.8e-8 up to 64, 2.8e-8 up to
+    // 128, never under ~5 us); whichever estimate is lower runs.  Beyond 128 rows the dense kernel is the only one.
+    bool dense = m.mfma_ok && gemm_mfma_serves(epi, Ntot, a.K, a.R) && a.x_mul == 1 && a.x_add == 0;
+    if (dense && a.R <= 128) {
+        const double per = a.R <= 32 ? 1.6e-8 : (a.R <= 64 ? 1.8e-8 : 2.8e-8);
+        const double stream_us = std::max(5.0, per * Ntot * (double)a.K * a.R);
+        dense = gemm_mfma_estimate_us(Ntot, a.K, a.R, m.gemm_ws_bytes) < stream_us;
+    }
     if (dense) {
         // statistics slots and softmax partials are per 16-row group of W
         a.w0 = tiled; a.w1 = a.w2 = nullptr;
@@ -379,7 +389,7 @@ int launch_proj(spec_ctx *c, ModelRT &m, GemvArgs a, int epi, const void *tiled,
         if (tile_cols) *tile_cols = 16;
         if (epi == EPI_LOGITS && Ntot / 16 > m.tiles_cap) return fail(c, SPEC_EINVAL, "logits tiling exceeds the partial buffers");
         if (epi == EPI_RESID && Ntot / 16 > SSQ_STRIDE) return fail(c, SPEC_EINVAL, "too many statistics slots");
-        HIPCHK(c, launch_gemm_mfma(a, epi, 0, m.row_scale, ps_.ev0, ps_.ev1, c->stream));
+        HIPCHK(c, launch_gemm_mfma(a, epi, 0, m.row_scale, m.gemm_ws, m.gemm_ws_bytes, ps_.ev0, ps_.ev1, c->stream));
         return SPEC_OK;
     }
     if (use_mfma(c, m, a.R)) {
@@ -1174,13 +1184,16 @@ int spec_k_gemv_tiled(const void *w_tiled, int32_t N, int32_t K, const void *x_b
 }
 
 int spec_k_gemm_tiled(const void *w_tiled, int32_t N, int32_t K, const float *x, int32_t R, float *y, int32_t cfg,
-                      void *stream) {
-    if (!w_tiled || !x || !y || N < 16 || K < 32 || N % 16 || K % 32 || R < 1) return SPEC_EINVAL;
-    if (cfg != 0 && cfg != 408 && cfg != 404) return SPEC_EINVAL;
+                      void *workspace, int64_t workspace_bytes, void *stream) {
+    if (!w_tiled || !x || !y || N < 16 || K < 32 || N % 16 || K % 32 || R < 1 || workspace_bytes < 0) return SPEC_EINVAL;
+    const int shape = cfg % 1000, shares = cfg / 1000;
+    if (cfg < 0 || (shape != 0 && shape != 408 && shape != 404) || shares > 8) return SPEC_EINVAL;
     GemvArgs a{};
     a.w0 = w_tiled; a.n0 = N; a.K = K; a.R = R; a.x = x; a.x_mul = 1; a.y = y;
     const hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    return launch_gemm_mfma(a, EPI_PLAIN, cfg, nullptr, nullptr, nullptr, st) == hipSuccess ? SPEC_OK : SPEC_EHIP;
+    const hipError_t e = launch_gemm_mfma(a, EPI_PLAIN, cfg, nullptr, reinterpret_cast<float *>(workspace),
+                                          workspace ? (size_t)workspace_bytes : 0, nullptr, nullptr, st);
+    return e == hipSuccess ? SPEC_OK : (e == hipErrorInvalidValue ? SPEC_EINVAL : SPEC_EHIP);
 }
 
 int spec_k_retile(const void *w, int32_t N, int32_t K, void *out, void *stream) {

@@ -19,6 +19,8 @@
 // time.
 #include <hip/hip_ext.h>
 
+#include <algorithm>
+
 #include "common.hpp"
 #include "epilogue.hpp"
 #include "kv.hpp"
@@ -75,6 +77,25 @@ __device__ __forceinline__ void stage_barrier() { asm volatile("s_waitcnt lgkmcn
 
 template <int WM, int WN> struct GemmFrags { u32x4_t ah[WM], al[WM], bw[WN]; };
 
+// The arguments of a projection as seen from row `row0`: the epilogues index rows from zero.
+template <int EPI> __device__ __forceinline__ GemvArgs rows_from(const GemvArgs &a, int row0) {
+    GemvArgs b = a;
+    const size_t ro = (size_t)row0;
+    if constexpr (EPI == EPI_PLAIN) {
+        b.y += ro * a.n0;
+    } else if constexpr (EPI == EPI_RESID) {
+        b.xres += ro * a.n0; b.xg += ro * a.n0; b.xgb += ro * a.n0; b.ssq_out += ro * a.ssq_stride;
+    } else if constexpr (EPI == EPI_SWIGLU) {
+        b.y += ro * a.n0; b.yb += ro * a.n0;
+    } else if constexpr (EPI == EPI_QKV) {
+        b.y += ro * a.nq * a.hd; b.yb += ro * a.nq * a.hd; b.row_pos += row0; b.row_seq += row0;
+    } else if constexpr (EPI == EPI_LOGITS) {
+        const size_t orow = ro * a.y_mul;
+        b.y += orow * a.y_stride; b.pm += orow * a.n_tiles; b.ps += orow * a.n_tiles; b.pa += orow * a.n_tiles;
+    }
+    return b;
+}
+
 // scale[r] = rsqrt(mean(x_r^2) + eps) from the statistics slots of the producer: one wave per row.
 __global__ __launch_bounds__(256) void row_scale_k(const float *ssq, int slots, int stride, int R, int K, float eps,
                                                    float *scale) {
@@ -97,8 +118,8 @@ __global__ __launch_bounds__(256) void row_scale_k(const float *ssq, int slots, 
 //   multiply t
 // Stages past the last k-tile repeat it into slots nobody reads again, which keeps the loop uniform.
 template <int EPI, int WM, int WN, bool DEEP>
-__global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_SIMD)) void gemm_mfma_k(const GemvArgs a,
-                                                                                                    const int m_blocks) {
+__global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_SIMD)) void gemm_mfma_k(
+    const GemvArgs a, const int m_blocks, const int ksplit, const int64_t split_stride) {
     using S = GemmShape<WM, WN, DEEP>;
     constexpr int XI = S::XI;
     if (a.active != nullptr && *a.active == 0) return;
@@ -112,11 +133,16 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
     const int n_groups = Ntot >> 4;
     const int n_blocks = (n_groups + S::BNG - 1) / S::BNG;
     // consecutive workgroup ids go round the XCDs: the m_blocks row blocks of one W block stay on one XCD
+    // ksplit > 1 (plain epilogue only): the workgroup multiplies its share of the k-tiles and leaves a partial
+    // result in slab ks of a.y (slabs split_stride floats apart) for gemm_finish_k
     const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-    const int nb = (j / m_blocks) * 8 + xcd, mb = j % m_blocks;
+    const int ks = j % ksplit, jm = j / ksplit;
+    const int nb = (jm / m_blocks) * 8 + xcd, mb = jm % m_blocks;
     if (nb >= n_blocks) return;
     const int g0 = nb * S::BNG, m0 = mb * S::BMB * 16;
-    const int K = a.K, KT = K >> 5, R = a.R;
+    const int K = a.K, R = a.R;
+    const int KTall = K >> 5, KTs = (KTall + ksplit - 1) / ksplit;
+    const int kt0 = ks * KTs, KT = min(KTall, kt0 + KTs) - kt0;  // the host leaves no share empty
     char *const xs = smem;               // [2][XS]
     char *const ws = smem + 2 * S::XS;   // [2][WS]
 
@@ -126,7 +152,7 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
 #pragma unroll
     for (int i = 0; i < S::BNG / 4; ++i) {
         const int g = min(g0 + wave + 4 * i, n_groups - 1);
-        wsrc[i] = reinterpret_cast<const char *>(a.w0) + (size_t)g * KT * 1024 + lane * 16;
+        wsrc[i] = reinterpret_cast<const char *>(a.w0) + ((size_t)g * KTall + kt0) * 1024 + lane * 16;
     }
     // x: the block's fragments are filled in units of 512 contiguous bytes (16 rows x two k-chunks of 8 columns), one
     // unit per wave-wide load, so that the LDS writes of a wave touch every bank once: unit q = XI wave + i is row
@@ -139,7 +165,7 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
     for (int i = 0; i < XI; ++i) {
         const int q = XI * wave + i, rb = q >> 1, c = 2 * (q & 1) + (lane >> 5);
         const int row = m0 + rb * 16 + ((lane >> 1) & 15);
-        xsrc[i] = a.x + (size_t)min(row, R - 1) * K + 8 * c + 4 * (lane & 1);
+        xsrc[i] = a.x + (size_t)min(row, R - 1) * K + (size_t)kt0 * 32 + 8 * c + 4 * (lane & 1);
         xdst[i] = rb * 2048 + (q & 1) * 512 + lane * 8;
     }
 
@@ -239,23 +265,8 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
     const int row0 = m0 + wm * WM * 16;
     const int Rw = max(0, min(WM * 16, R - row0));
     for (int r = lane; r < WM * 16; r += 64) scale[r] = (a.row_scale != nullptr && r < Rw) ? a.row_scale[row0 + r] : 1.f;
-    GemvArgs b = a;  // the same arguments, seen from this wave's first row
-    {
-        const size_t ro = (size_t)row0;
-        if constexpr (EPI == EPI_PLAIN) {
-            b.y += ro * a.n0;
-        } else if constexpr (EPI == EPI_RESID) {
-            b.xres += ro * a.n0; b.xg += ro * a.n0; b.xgb += ro * a.n0; b.ssq_out += ro * a.ssq_stride;
-        } else if constexpr (EPI == EPI_SWIGLU) {
-            b.y += ro * a.n0; b.yb += ro * a.n0;
-        } else if constexpr (EPI == EPI_QKV) {
-            b.y += ro * a.nq * a.hd; b.yb += ro * a.nq * a.hd; b.row_pos += row0; b.row_seq += row0;
-        } else if constexpr (EPI == EPI_LOGITS) {
-            // logical row r writes output row r * y_mul + y_add: one softmax partial per row and 16-column tile
-            const size_t orow = ro * a.y_mul;
-            b.y += orow * a.y_stride; b.pm += orow * a.n_tiles; b.ps += orow * a.n_tiles; b.pa += orow * a.n_tiles;
-        }
-    }
+    GemvArgs b = rows_from<EPI>(a, row0);  // the same arguments, seen from this wave's first row
+    if constexpr (EPI == EPI_PLAIN) b.y += (size_t)ks * split_stride;
     // the tile and the scales are private to the wave: LDS serves a wave's accesses in order, so a wave-level
     // wait orders its writes before its reads
     auto wave_sync = [] { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); };
@@ -332,12 +343,47 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
     }
 }
 
+// Second half of a projection whose k-tiles were shared out: sums the ksplit partial results in slab order (the
+// result does not depend on which workgroup finished first) and applies the epilogue.  One workgroup per 16-row
+// group of W and 64 rows of x, one wave per 16 rows.
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_finish_k(const GemvArgs a, const float *part, const int ksplit,
+                                                     const int64_t split_stride) {
+    if (a.active != nullptr && *a.active == 0) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int Ntot = a.n0;
+    if (EPI == EPI_QKV) Ntot = (a.nq + 2 * a.nkv) * a.hd;
+    if (EPI == EPI_SWIGLU) Ntot = 2 * a.n0;
+    const int g = blockIdx.x, row0 = blockIdx.y * 64 + wave * 16;
+    const int Rw = max(0, min(16, a.R - row0));
+    __shared__ __attribute__((aligned(16))) float tiles[4][16 * 20];
+    __shared__ float scales[4][16];
+    float *tile = tiles[wave], *scale = scales[wave];
+    const int r = lane >> 2, c4 = (lane & 3) * 4;
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    if (r < Rw) {
+        const float *p = part + (size_t)(row0 + r) * Ntot + g * 16 + c4;
+        for (int sl = 0; sl < ksplit; ++sl) {
+            const f32x4_t v = *reinterpret_cast<const f32x4_t *>(p + (size_t)sl * split_stride);
+            acc[0] += v[0]; acc[1] += v[1]; acc[2] += v[2]; acc[3] += v[3];
+        }
+    }
+    *reinterpret_cast<f32x4_t *>(tile + r * 20 + c4) = acc;
+    if (lane < 16) scale[lane] = (a.row_scale != nullptr && lane < Rw) ? a.row_scale[row0 + lane] : 1.f;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the tile is private to the wave
+    if (Rw > 0) {
+        const GemvArgs b = rows_from<EPI>(a, row0);
+        epilogue_tile<EPI, 16, 64>(b, tile, 20, scale, Rw, g, Ntot, lane);
+    }
+}
+
 template <int EPI, int WM, int WN, bool DEEP>
-static hipError_t launch_gemm_one(const GemvArgs &a, int Ntot, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s) {
+static hipError_t launch_gemm_one(const GemvArgs &a, int Ntot, int ksplit, int64_t split_stride, hipEvent_t ev0, hipEvent_t ev1,
+                                  hipStream_t s) {
     using S = GemmShape<WM, WN, DEEP>;
     const int n_blocks = (Ntot / 16 + S::BNG - 1) / S::BNG;
     const int m_blocks = (a.R + S::BMB * 16 - 1) / (S::BMB * 16);
-    const int grid = ((n_blocks + 7) / 8) * 8 * m_blocks;
+    const int grid = ((n_blocks + 7) / 8) * 8 * m_blocks * ksplit;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_mfma_k<EPI, WM, WN, DEEP>),
@@ -346,24 +392,53 @@ static hipError_t launch_gemm_one(const GemvArgs &a, int Ntot, hipEvent_t ev0, h
         attr_set = true;
     }
     if (ev0 != nullptr)
-        hipExtLaunchKernelGGL((gemm_mfma_k<EPI, WM, WN, DEEP>), dim3(grid), dim3(GEMM_THREADS), S::LDS, s, ev0, ev1, 0, a, m_blocks);
+        hipExtLaunchKernelGGL((gemm_mfma_k<EPI, WM, WN, DEEP>), dim3(grid), dim3(GEMM_THREADS), S::LDS, s, ev0, ev1, 0, a, m_blocks,
+                              ksplit, split_stride);
     else
-        hipLaunchKernelGGL((gemm_mfma_k<EPI, WM, WN, DEEP>), dim3(grid), dim3(GEMM_THREADS), S::LDS, s, a, m_blocks);
+        hipLaunchKernelGGL((gemm_mfma_k<EPI, WM, WN, DEEP>), dim3(grid), dim3(GEMM_THREADS), S::LDS, s, a, m_blocks, ksplit,
+                           split_stride);
     return hipGetLastError();
 }
 
+// Shares of K for a projection whose blocks would leave most compute units idle: a workgroup's time is its k-tiles
+// times the load latency it cannot hide (about 0.6 us per k-tile), whatever the rows, so a matrix with few blocks
+// (N = d_model at up to a few hundred rows) is served faster by more, shorter workgroups plus one summing pass.
+static int pick_ksplit(int Ntot, int K, int R, size_t ws_bytes) {
+    const int wgs = ((Ntot + 127) / 128) * ((R + 127) / 128), KT = K / 32;
+    if (wgs > 128 || KT < 8) return 1;
+    int sp = std::min(std::min(8, 256 / wgs), KT / 4);
+    while (sp > 1 && (size_t)sp * R * Ntot * sizeof(float) > ws_bytes) --sp;
+    while (sp > 1 && (sp - 1) * ((KT + sp - 1) / sp) >= KT) --sp;  // no empty share
+    return std::max(sp, 1);
+}
+
 template <int EPI>
-static hipError_t launch_gemm_cfg(const GemvArgs &a, int Ntot, int forced, hipEvent_t ev0, hipEvent_t ev1, hipStream_t s) {
-    int cfg = forced;
+static hipError_t launch_gemm_cfg(const GemvArgs &a, int Ntot, int forced, float *ws, size_t ws_bytes, hipEvent_t ev0,
+                                  hipEvent_t ev1, hipStream_t s) {
+    int cfg = forced % 1000, ksplit = forced / 1000;
     if (cfg == 0) {
         // both shapes are bound by what a compute unit can fetch from L2 per matrix instruction: the wide block
         // needs a third less, the narrow one fills the chip when the wide one would leave compute units idle
         const int m_blocks = (a.R + 127) / 128;
         cfg = ((Ntot + 255) / 256) * m_blocks > 256 ? 408 : 404;
     }
+    if (ksplit == 0) ksplit = (cfg == 404 && ws != nullptr) ? pick_ksplit(Ntot, a.K, a.R, ws_bytes) : 1;
+    if (ksplit > 1) {
+        const int KT = a.K / 32;
+        if (cfg != 404 || ws == nullptr || (size_t)ksplit * a.R * Ntot * sizeof(float) > ws_bytes || ksplit > KT ||
+            (ksplit - 1) * ((KT + ksplit - 1) / ksplit) >= KT)
+            return hipErrorInvalidValue;
+        const int64_t stride = (int64_t)a.R * Ntot;
+        GemvArgs p = a;  // partial results: plain rows of Ntot columns, unscaled
+        p.n0 = Ntot; p.y = ws; p.row_scale = nullptr; p.ssq_in = nullptr;
+        hipError_t e = launch_gemm_one<EPI_PLAIN, 4, 4, true>(p, Ntot, ksplit, stride, ev0, ev1, s);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((gemm_finish_k<EPI>), dim3(Ntot / 16, (a.R + 63) / 64), dim3(256), 0, s, a, ws, ksplit, stride);
+        return hipGetLastError();
+    }
     switch (cfg) {
-        case 408: return launch_gemm_one<EPI, 4, 8, false>(a, Ntot, ev0, ev1, s);
-        case 404: return launch_gemm_one<EPI, 4, 4, true>(a, Ntot, ev0, ev1, s);
+        case 408: return launch_gemm_one<EPI, 4, 8, false>(a, Ntot, 1, 0, ev0, ev1, s);
+        case 404: return launch_gemm_one<EPI, 4, 4, true>(a, Ntot, 1, 0, ev0, ev1, s);
     }
     return hipErrorInvalidValue;
 }
@@ -373,13 +448,30 @@ bool gemm_mfma_serves(int epi, int Ntot, int K, int R) {
     return R >= GEMM_MIN_ROWS && Ntot % 16 == 0 && K % 32 == 0;
 }
 
+// Rough time of one launch in microseconds, from what was measured on the chip: a workgroup spends a fixed time per
+// k-tile whatever its rows (load latency it cannot hide: 0.57 us for the narrow block alone on a compute unit, 1.17
+// us per pair sharing one; 1.19 / 1.87 us for the wide block), the blocks run in rounds of 512, and a split of K
+// adds its summing pass.
+float gemm_mfma_estimate_us(int Ntot, int K, int R, size_t ws_bytes) {
+    const int m_blocks = (R + 127) / 128, KT = K / 32;
+    if (((Ntot + 255) / 256) * m_blocks > 256) {
+        const int wgs = ((Ntot + 255) / 256) * m_blocks;
+        return 3.f + KT * 1.87f * ((wgs + 511) / 512);
+    }
+    const int sp = pick_ksplit(Ntot, K, R, ws_bytes);
+    const int wgs = ((Ntot + 127) / 128) * m_blocks * sp, stages = (KT + sp - 1) / sp;
+    const float per_stage = wgs <= 256 ? 0.57f : 1.17f * ((wgs + 511) / 512);
+    return 3.f + stages * per_stage + (sp > 1 ? 8.f : 0.f);
+}
+
 // Host-side contract: w0 is the re-tiled matrix, Ntot % 16 == 0, K % 32 == 0, a.x holds R fp32 rows of length K
 // (x_mul = 1, x_add = 0), any R >= 1; RESID writes Ntot / 16 statistics slots per row (<= ssq_stride); LOGITS writes
 // one softmax partial per row and 16-column tile (n_tiles = Ntot / 16).  With
 // statistics of the input (a.ssq_in) the row scales are first reduced into scale_buf (device, R floats).
-// `forced` = 100 WM + WN selects the block shape (0 = automatic).
-hipError_t launch_gemm_mfma(const GemvArgs &a0, int epi, int forced, float *scale_buf, hipEvent_t ev_start,
-                            hipEvent_t ev_stop, hipStream_t s) {
+// `forced` = 1000 shares of K + 100 WM + WN selects the block shape and the split (0 = automatic; shares need the
+// narrow block and the workspace `ws`: shares x R x Ntot floats).
+hipError_t launch_gemm_mfma(const GemvArgs &a0, int epi, int forced, float *scale_buf, float *ws, size_t ws_bytes,
+                            hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t s) {
     GemvArgs a = a0;
     int Ntot = a.n0;
     if (epi == EPI_QKV) Ntot = (a.nq + 2 * a.nkv) * a.hd;
@@ -396,11 +488,11 @@ hipError_t launch_gemm_mfma(const GemvArgs &a0, int epi, int forced, float *scal
         a.row_scale = scale_buf;
     }
     switch (epi) {
-        case EPI_PLAIN: return launch_gemm_cfg<EPI_PLAIN>(a, Ntot, forced, ev_start, ev_stop, s);
-        case EPI_QKV: return launch_gemm_cfg<EPI_QKV>(a, Ntot, forced, ev_start, ev_stop, s);
-        case EPI_RESID: return launch_gemm_cfg<EPI_RESID>(a, Ntot, forced, ev_start, ev_stop, s);
-        case EPI_SWIGLU: return launch_gemm_cfg<EPI_SWIGLU>(a, Ntot, forced, ev_start, ev_stop, s);
-        case EPI_LOGITS: return launch_gemm_cfg<EPI_LOGITS>(a, Ntot, forced, ev_start, ev_stop, s);
+        case EPI_PLAIN: return launch_gemm_cfg<EPI_PLAIN>(a, Ntot, forced, ws, ws_bytes, ev_start, ev_stop, s);
+        case EPI_QKV: return launch_gemm_cfg<EPI_QKV>(a, Ntot, forced, ws, ws_bytes, ev_start, ev_stop, s);
+        case EPI_RESID: return launch_gemm_cfg<EPI_RESID>(a, Ntot, forced, ws, ws_bytes, ev_start, ev_stop, s);
+        case EPI_SWIGLU: return launch_gemm_cfg<EPI_SWIGLU>(a, Ntot, forced, ws, ws_bytes, ev_start, ev_stop, s);
+        case EPI_LOGITS: return launch_gemm_cfg<EPI_LOGITS>(a, Ntot, forced, ws, ws_bytes, ev_start, ev_stop, s);
     }
     return hipErrorInvalidValue;
 }

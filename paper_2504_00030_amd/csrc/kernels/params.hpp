@@ -182,10 +182,11 @@ hipError_t launch_gemv_mfma(const GemvArgs &a, int epi, int forced_cfg, hipEvent
                             hipStream_t s);
 int gemv_mfma_groups_per_wg(int epi, int Ntot, int K, int R, int forced_cfg);  // 16-row groups per workgroup
 // Prompt ingestion: the dense-contraction kernel for many rows (x read as fp32 rows, a.x).
-constexpr int GEMM_MIN_ROWS = 64;  // below this the weight-streaming kernels are the faster ones
+constexpr int GEMM_MIN_ROWS = 17;  // up to 16 rows the persistent weight-streaming kernel is the faster one at any shape
 bool gemm_mfma_serves(int epi, int Ntot, int K, int R);
-hipError_t launch_gemm_mfma(const GemvArgs &a, int epi, int forced_cfg, float *scale_buf, hipEvent_t ev_start,
-                            hipEvent_t ev_stop, hipStream_t s);
+float gemm_mfma_estimate_us(int Ntot, int K, int R, size_t workspace_bytes);  // rough time of one launch
+hipError_t launch_gemm_mfma(const GemvArgs &a, int epi, int forced_cfg, float *scale_buf, float *workspace,
+                            size_t workspace_bytes, hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t s);
 bool gemv_wavedot_uses_split(int epi, int Ntot, int K, int R, int w_dtype);
 int gemv_wavedot_tile_cols(int epi, int Ntot, int K, int R, int w_dtype);
 int gemv_wavedot_pick_rpw(int epi, int N, int K, int R, int w_dtype);
