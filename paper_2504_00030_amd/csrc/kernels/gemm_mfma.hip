@@ -1,5 +1,6 @@
-// Prompt ingestion: the same fused projections as the decode kernels, for hundreds of rows of x, where the
-// work is a dense contraction on the matrix cores rather than a weight stream.
+// Prompt ingestion and verification of many sequences at once: the same fused projections as the decode
+// kernels, for tens to a thousand rows of x, where the work is a dense contraction on the matrix cores rather
+// than a weight stream.
 //
 // One workgroup of four waves (2 x 2) computes a block of 32 WM rows of x by 32 WN rows of W.  Per k-tile
 // (32 columns) a stage in LDS holds the operands of the whole block in the register layout of
@@ -15,8 +16,9 @@
 // (narrow block) iterations ahead of the matrix instructions, two workgroups share a compute unit, and the
 // block index is mapped so that the workgroups an XCD runs at the same time share their W block (one L2 per
 // XCD).  The epilogues are the decode kernels' own arithmetic (RoPE + KV write, residual + next-norm
-// statistics, SwiGLU): each wave passes its 32 WM x 32 result tiles through LDS, two 16-row groups of W at a
-// time.
+// statistics, SwiGLU, logits + softmax partials): each wave passes its 32 WM x 32 result tiles through LDS, two
+// 16-row groups of W at a time.  A projection with too few blocks to fill the chip shares K out over several
+// workgroups per block; gemm_finish_k sums their partial results and applies the epilogue.
 #include <hip/hip_ext.h>
 
 #include <algorithm>

@@ -81,12 +81,21 @@ def test_gemv_mfma_matches_fp64_matmul(R, N, K):
     assert np.abs(got - want).max() <= tol
 
 
-@pytest.mark.parametrize("cfg", [0, 404, 408])
+@pytest.mark.parametrize("cfg", [0, 404, 408, 2404, 3404, 8404])
 @pytest.mark.parametrize("R", [1, 63, 64, 129, 200, 1023])
 @pytest.mark.parametrize("N,K", [(4096, 4096), (2064, 768), (48, 4096), (272, 96), (16384, 2048), (16, 32)])
 def test_gemm_mfma_matches_fp64_matmul(N, K, R, cfg):
-    # the prompt-ingestion kernel: row counts around its 128-row blocks, group counts off its 128 / 256-row blocks
+    # the dense-contraction kernel: row counts around its 128-row blocks, group counts off its 128 / 256-row blocks,
+    # K whole or shared out over 2, 3 or 8 workgroups per block (3 leaves a ragged last share)
     pk = _pk()
+    shares = cfg // 1000
+    ws = torch.empty(max(shares, 8) * R * N, device="cuda")
+    if shares > 1 and (K // 32 < shares or (shares - 1) * -(-(K // 32) // shares) >= K // 32):
+        # fewer k-tiles than shares, or a share would be empty: refused, not mis-run
+        with pytest.raises(pk.SpecError):
+            pk.k_gemm_tiled(torch.empty(N, K, dtype=torch.bfloat16, device="cuda"), N, K, torch.zeros(R, K, device="cuda"),
+                            torch.empty(R, N, device="cuda"), cfg, workspace=ws)
+        return
     g = torch.Generator().manual_seed(N * 5 + K + R)
     w = (torch.randn(N, K, generator=g) * 0.02).to(torch.bfloat16)
     x = torch.randn(R, K, generator=g)
@@ -94,7 +103,7 @@ def test_gemm_mfma_matches_fp64_matmul(N, K, R, cfg):
     wt = torch.empty_like(w, device="cuda")
     pk.k_retile(w.cuda().contiguous(), wt)
     y = torch.full((R, N), float("nan"), device="cuda")
-    pk.k_gemm_tiled(wt, N, K, x.cuda().contiguous(), y, cfg)
+    pk.k_gemm_tiled(wt, N, K, x.cuda().contiguous(), y, cfg, workspace=ws)
     torch.cuda.synchronize()
     got = y.cpu().numpy()
     tol = 2e-6 * np.sqrt(K) * np.abs(want).max() + 1e-7
