@@ -56,9 +56,9 @@ __device__ __forceinline__ void split4(const f32x4_t v, u32x2_t &hi, u32x2_t &lo
 constexpr int GEMM_THREADS = 256;
 constexpr int GEMM_TS = 36;                      // row stride (floats) of a wave's result tile in the epilogue
 
-// DEEP: loads two iterations ahead and the fragments of the next iteration read while this one multiplies (both
-// double-buffered in registers); otherwise loads one iteration ahead and fragments read where they are used,
-// which fits the registers of the wide block.
+// Loads run two iterations ahead in both forms (two sets of staging registers).  DEEP: the fragments of the next
+// iteration are read while this one multiplies (double-buffered in registers as well); otherwise they are read where
+// they are used, which fits the registers of the wide block.
 template <int WM, int WN, bool DEEP>
 struct GemmShape {
     static constexpr int BMB = 2 * WM;              // 16-row blocks of x per workgroup
@@ -246,16 +246,26 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
         }
         if (KT & 1) multiply(fa);  // the last k-tile of an odd count was read by the trip before
     } else {
-        // iteration t: issue t + 1, read and multiply t, stash t + 1, meet
+        // iteration t: issue t + 2, read and multiply t, stash t + 1 (loaded an iteration ago), meet
         issue(0, r0);
+        issue(1, r1);
         stash(r0, 0);
         stage_barrier();
-        for (int t = 0; t < KT; ++t) {
-            issue(t + 1, r0);
+        for (int t = 0; t + 1 < KT; t += 2) {  // two iterations per trip: the staging registers alternate
+            issue(t + 2, r0);
             read(t, fa);
             multiply(fa);
-            stash(r0, (t + 1) & 1);
+            stash(r1, 1);
             stage_barrier();
+            issue(t + 3, r1);
+            read(t + 1, fa);
+            multiply(fa);
+            stash(r0, 0);
+            stage_barrier();
+        }
+        if (KT & 1) {
+            read(KT - 1, fa);
+            multiply(fa);
         }
     }
     __syncthreads();  // every load has landed and every wave has left the stages before they are reused
@@ -452,13 +462,13 @@ bool gemm_mfma_serves(int epi, int Ntot, int K, int R) {
 
 // Rough time of one launch in microseconds, from what was measured on the chip: a workgroup spends a fixed time per
 // k-tile whatever its rows (load latency it cannot hide: 0.57 us for the narrow block alone on a compute unit, 1.17
-// us per pair sharing one; 1.19 / 1.87 us for the wide block), the blocks run in rounds of 512, and a split of K
+// us per pair sharing one; 1.0 / 1.7 us for the wide block), the blocks run in rounds of 512, and a split of K
 // adds its summing pass.
 float gemm_mfma_estimate_us(int Ntot, int K, int R, size_t ws_bytes) {
     const int m_blocks = (R + 127) / 128, KT = K / 32;
     if (((Ntot + 255) / 256) * m_blocks > 256) {
         const int wgs = ((Ntot + 255) / 256) * m_blocks;
-        return 3.f + KT * 1.87f * ((wgs + 511) / 512);
+        return 3.f + KT * 1.7f * ((wgs + 511) / 512);
     }
     const int sp = pick_ksplit(Ntot, K, R, ws_bytes);
     const int wgs = ((Ntot + 127) / 128) * m_blocks * sp, stages = (KT + sp - 1) / sp;
