@@ -286,6 +286,34 @@ def main():
                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.pair), "kernel": "target gate/up projection + SwiGLU",
                     "launches": n_launch, "avg_us": avg_ms * 1e3, "bytes_per_launch": bytes_per_launch}
 
+    verify_pass = None
+    if not args.skip_roofline and B == 1:
+        # the whole verification pass against the HBM roofline: gamma = 2 (the run's mean), graphs, one
+        # synchronisation on either side of spec_verify; bytes = every target weight once + the visible KV cache
+        e3 = engine(not args.no_graphs)
+        e3.prefill(prompts)
+        g, n_pass, t_ver = 2, 48, 0.0
+        for i in range(n_pass + 4):
+            e3.draft(g)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            e3.verify(g)
+            torch.cuda.synchronize()
+            if i >= 4:
+                t_ver += time.perf_counter() - t0
+            e3.accept()
+        e3.close()
+        m = cfg.target
+        qd, kvd = m.n_q_heads * m.head_dim, m.n_kv_heads * m.head_dim
+        esz = 2 if m.dtype == "bf16" else 4
+        w_bytes = (m.n_layers * (m.d_model * (qd + 2 * kvd) + qd * m.d_model + 3 * m.d_model * m.d_ffn) + m.vocab * m.d_model) * esz
+        kv_bytes = m.n_layers * 2 * kvd * (n_prompt + n_pass) * esz  # context at the middle of the leg, roughly
+        ms = 1e3 * t_ver / n_pass
+        gbs = (w_bytes + kv_bytes) / (ms * 1e-3) / 1e9
+        verify_pass = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                       "ms": ms, "bytes": w_bytes + kv_bytes, "gamma": g, "passes": n_pass,
+                       "timing": "host clock around spec_verify between two device synchronisations"}
+
     seq_steps = max(stats.get("seq_steps", stats["spec_steps"]), 1)  # (sequence, speculative step) pairs
     tokens_per_step = stats["generated"] / seq_steps
     mean_gamma = stats["gamma_sum"] / seq_steps
@@ -312,6 +340,7 @@ def main():
         },
         "roofline": roofline, "cpu_baseline": cpu,
         "prefill": prefill_report(t_prefill / steps) if args.steps > 0 else None,
+        "verify_pass": verify_pass,
     }
     print(json.dumps(line))
 
