@@ -247,6 +247,17 @@ int spec_k_gemv_tiled(const void *w_tiled, int32_t N, int32_t K, const void *x_b
 int spec_k_gemm_tiled(const void *w_tiled, int32_t N, int32_t K, const float *x, int32_t R, float *y, int32_t cfg,
                       void *workspace, int64_t workspace_bytes, void *stream);
 
+/* 8-bit weights, W[n][k] = w_scale[n] * q[n][k] with q int8 in [-127, 127] (the quantised matrices of the paper's
+ * largest pair stand behind this; here they are synthetic).  spec_k_retile_q8 re-tiles q [N][K] (device, row-major,
+ * K % 64 == 0, N % 16 == 0) into 16-row groups of 1 KiB tiles of 16 rows x 64 k (N*K bytes).  The two kernels
+ * below are spec_k_gemv_tiled / spec_k_gemm_tiled on such a matrix: the int8 values become bf16 in registers
+ * (exactly), and the result is multiplied by w_scale (device, fp32 [N]). */
+int spec_k_retile_q8(const void *w_q8, int32_t N, int32_t K, void *out, void *stream);
+int spec_k_gemv_tiled_q8(const void *w_tiled, const float *w_scale, int32_t N, int32_t K, const void *x_bf16,
+                         const void *x_lo_bf16, int32_t R, float *y, void *stream);
+int spec_k_gemm_tiled_q8(const void *w_tiled, const float *w_scale, int32_t N, int32_t K, const float *x, int32_t R,
+                         float *y, int32_t cfg, void *workspace, int64_t workspace_bytes, void *stream);
+
 /* Re-tile a row-major bf16 matrix [N][K] into the streaming layout of the matrix-core kernel:
  * 16-row groups, each group a run of 1 KiB tiles (16 rows x 32 k) stored lane-major.  out: device,
  * N*K*2 bytes. */

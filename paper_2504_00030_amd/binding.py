@@ -27,7 +27,7 @@ EXPORTS = [
     "spec_init", "spec_prefill", "spec_prefill_ragged", "spec_debug_set_step", "spec_draft", "spec_draft_batch", "spec_verify", "spec_accept",
     "spec_set_forced_alpha", "spec_set_early_stop", "spec_generate", "spec_read_tokens", "spec_debug_logits",
     "spec_debug_drafted", "spec_debug_read", "spec_debug_fill_kv", "spec_debug_write_kv", "spec_debug_set_block_table", "spec_device_bytes", "spec_profile_kernel", "spec_profile_read", "spec_destroy",
-    "spec_strerror", "spec_last_error", "spec_k_gemv", "spec_k_gemv_tiled", "spec_k_gemm_tiled", "spec_k_retile", "spec_k_copy", "spec_k_philox", "spec_k_accept",
+    "spec_strerror", "spec_last_error", "spec_k_gemv", "spec_k_gemv_tiled", "spec_k_gemm_tiled", "spec_k_retile_q8", "spec_k_gemv_tiled_q8", "spec_k_gemm_tiled_q8", "spec_k_retile", "spec_k_copy", "spec_k_philox", "spec_k_accept",
     "gammatune_init", "gammatune_update",
 ]
 
@@ -119,6 +119,11 @@ def load() -> C.CDLL:
                                       C.c_void_p]
     lib.spec_k_gemm_tiled.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
                                       C.c_int64, C.c_void_p]
+    lib.spec_k_retile_q8.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.spec_k_gemv_tiled_q8.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                         C.c_void_p]
+    lib.spec_k_gemm_tiled_q8.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
+                                         C.c_void_p, C.c_int64, C.c_void_p]
     lib.spec_k_retile.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.spec_k_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     lib.spec_k_philox.argtypes = [C.c_uint64, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
@@ -396,6 +401,28 @@ def k_gemm_tiled(w_tiled, N, K, x, y, cfg: int = 0, stream: int = 0, workspace=N
     rc = load().spec_k_gemm_tiled(w_tiled.data_ptr(), N, K, x.data_ptr(), y.shape[0], y.data_ptr(), cfg, ws, nb, stream)
     if rc != 0:
         raise SpecError(rc, "spec_k_gemm_tiled")
+
+
+def k_retile_q8(w_q8, out, stream: int = 0):
+    rc = load().spec_k_retile_q8(w_q8.data_ptr(), w_q8.shape[0], w_q8.shape[1], out.data_ptr(), stream)
+    if rc != 0:
+        raise SpecError(rc, "spec_k_retile_q8")
+
+
+def k_gemv_tiled_q8(w_tiled, w_scale, N, K, x_bf16, y, stream: int = 0, x_lo=None):
+    rc = load().spec_k_gemv_tiled_q8(w_tiled.data_ptr(), w_scale.data_ptr(), N, K, x_bf16.data_ptr(),
+                                     None if x_lo is None else x_lo.data_ptr(), y.shape[0], y.data_ptr(), stream)
+    if rc != 0:
+        raise SpecError(rc, "spec_k_gemv_tiled_q8")
+
+
+def k_gemm_tiled_q8(w_tiled, w_scale, N, K, x, y, cfg: int = 0, stream: int = 0, workspace=None):
+    ws = None if workspace is None else workspace.data_ptr()
+    nb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().spec_k_gemm_tiled_q8(w_tiled.data_ptr(), w_scale.data_ptr(), N, K, x.data_ptr(), y.shape[0], y.data_ptr(), cfg,
+                                     ws, nb, stream)
+    if rc != 0:
+        raise SpecError(rc, "spec_k_gemm_tiled_q8")
 
 
 def k_retile(w, out, stream: int = 0):

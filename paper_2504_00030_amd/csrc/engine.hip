@@ -1196,6 +1196,38 @@ int spec_k_gemm_tiled(const void *w_tiled, int32_t N, int32_t K, const float *x,
     return e == hipSuccess ? SPEC_OK : (e == hipErrorInvalidValue ? SPEC_EINVAL : SPEC_EHIP);
 }
 
+int spec_k_retile_q8(const void *w_q8, int32_t N, int32_t K, void *out, void *stream) {
+    if (!w_q8 || !out || N < 16 || K < 64 || N % 16 || K % 64) return SPEC_EINVAL;
+    RetileArgs ra{};
+    ra.w0 = w_q8; ra.mode = EPI_PLAIN; ra.Ntot = N; ra.K = K; ra.q8 = 1;
+    if (launch_retile(ra, out, reinterpret_cast<hipStream_t>(stream)) != hipSuccess) return SPEC_EHIP;
+    return SPEC_OK;
+}
+
+int spec_k_gemv_tiled_q8(const void *w_tiled, const float *w_scale, int32_t N, int32_t K, const void *x_bf16,
+                         const void *x_lo_bf16, int32_t R, float *y, void *stream) {
+    if (!w_tiled || !w_scale || !x_bf16 || !y || N < 16 || K < 64 || N % 16 || K % 64 || R < 1 || R > 128) return SPEC_EINVAL;
+    GemvArgs a{};
+    a.w0 = w_tiled; a.wscale = w_scale; a.n0 = N; a.K = K; a.R = R; a.xb = reinterpret_cast<const uint16_t *>(x_bf16);
+    a.x_mul = 1; a.y = y;
+    if (x_lo_bf16) a.xb_lo = reinterpret_cast<const uint16_t *>(x_lo_bf16) - a.xb;
+    const hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    return launch_gemv_mfma(a, EPI_PLAIN, 0, nullptr, nullptr, st) == hipSuccess ? SPEC_OK : SPEC_EHIP;
+}
+
+int spec_k_gemm_tiled_q8(const void *w_tiled, const float *w_scale, int32_t N, int32_t K, const float *x, int32_t R,
+                         float *y, int32_t cfg, void *workspace, int64_t workspace_bytes, void *stream) {
+    if (!w_tiled || !w_scale || !x || !y || N < 16 || K < 64 || N % 16 || K % 64 || R < 1 || workspace_bytes < 0) return SPEC_EINVAL;
+    const int shape = cfg % 1000, shares = cfg / 1000;
+    if (cfg < 0 || (shape != 0 && shape != 408 && shape != 404) || shares > 8) return SPEC_EINVAL;
+    GemvArgs a{};
+    a.w0 = w_tiled; a.wscale = w_scale; a.n0 = N; a.K = K; a.R = R; a.x = x; a.x_mul = 1; a.y = y;
+    const hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const hipError_t e = launch_gemm_mfma(a, EPI_PLAIN, cfg, nullptr, reinterpret_cast<float *>(workspace),
+                                          workspace ? (size_t)workspace_bytes : 0, nullptr, nullptr, st);
+    return e == hipSuccess ? SPEC_OK : (e == hipErrorInvalidValue ? SPEC_EINVAL : SPEC_EHIP);
+}
+
 int spec_k_retile(const void *w, int32_t N, int32_t K, void *out, void *stream) {
     if (!w || !out || N < 16 || K < 32 || N % 16 || K % 32) return SPEC_EINVAL;
     RetileArgs ra{};

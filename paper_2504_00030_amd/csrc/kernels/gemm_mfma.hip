@@ -27,6 +27,7 @@
 #include "epilogue.hpp"
 #include "kv.hpp"
 #include "params.hpp"
+#include "q8.hpp"
 
 namespace sd {
 
@@ -79,6 +80,12 @@ __device__ __forceinline__ void stage_barrier() { asm volatile("s_waitcnt lgkmcn
 
 template <int WM, int WN> struct GemmFrags { u32x4_t ah[WM], al[WM], bw[WN]; };
 
+// k-tiles per share when K is shared out over `shares` workgroups (8-bit weights: whole 64-k tiles, i.e. even)
+__host__ __device__ inline int share_ktiles(int KT, int shares, int q8) {
+    const int n = (KT + shares - 1) / shares;
+    return q8 ? n + (n & 1) : n;
+}
+
 // The arguments of a projection as seen from row `row0`: the epilogues index rows from zero.
 template <int EPI> __device__ __forceinline__ GemvArgs rows_from(const GemvArgs &a, int row0) {
     GemvArgs b = a;
@@ -119,7 +126,10 @@ __global__ __launch_bounds__(256) void row_scale_k(const float *ssq, int slots, 
 //   read    t + 1      fragments for the next iteration
 //   multiply t
 // Stages past the last k-tile repeat it into slots nobody reads again, which keeps the loop uniform.
-template <int EPI, int WM, int WN, bool DEEP>
+// WQ: 1 = 8-bit weights (q8.hpp).  A k-tile of the loop is then half of a 64-k weight tile: the lane's first or
+// second eight bytes, turned into bf16 on the way into LDS, and the x fragments gather the matching k sets (chunk c
+// of k-tile t holds k = 64 (t / 2) + 16 c + 8 (t % 2) .. + 8).  The column scales multiply the result tile.
+template <int EPI, int WM, int WN, bool DEEP, int WQ>
 __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_SIMD)) void gemm_mfma_k(
     const GemvArgs a, const int m_blocks, const int ksplit, const int64_t split_stride) {
     using S = GemmShape<WM, WN, DEEP>;
@@ -143,7 +153,7 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
     if (nb >= n_blocks) return;
     const int g0 = nb * S::BNG, m0 = mb * S::BMB * 16;
     const int K = a.K, R = a.R;
-    const int KTall = K >> 5, KTs = (KTall + ksplit - 1) / ksplit;
+    const int KTall = K >> 5, KTs = share_ktiles(KTall, ksplit, WQ);
     const int kt0 = ks * KTs, KT = min(KTall, kt0 + KTs) - kt0;  // the host leaves no share empty
     char *const xs = smem;               // [2][XS]
     char *const ws = smem + 2 * S::XS;   // [2][WS]
@@ -154,7 +164,9 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
 #pragma unroll
     for (int i = 0; i < S::BNG / 4; ++i) {
         const int g = min(g0 + wave + 4 * i, n_groups - 1);
-        wsrc[i] = reinterpret_cast<const char *>(a.w0) + ((size_t)g * KTall + kt0) * 1024 + lane * 16;
+        // 16-bit: tile (g, kt) of 1 KiB; 8-bit: k-tile kt is half kt % 2 of tile (g, kt / 2) (the host keeps kt0 even)
+        wsrc[i] = reinterpret_cast<const char *>(a.w0) + (WQ ? ((size_t)g * (KTall >> 1) + (kt0 >> 1)) * 1024 : ((size_t)g * KTall + kt0) * 1024) +
+                  lane * 16;
     }
     // x: the block's fragments are filled in units of 512 contiguous bytes (16 rows x two k-chunks of 8 columns), one
     // unit per wave-wide load, so that the LDS writes of a wave touch every bank once: unit q = XI wave + i is row
@@ -167,7 +179,7 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
     for (int i = 0; i < XI; ++i) {
         const int q = XI * wave + i, rb = q >> 1, c = 2 * (q & 1) + (lane >> 5);
         const int row = m0 + rb * 16 + ((lane >> 1) & 15);
-        xsrc[i] = a.x + (size_t)min(row, R - 1) * K + (size_t)kt0 * 32 + 8 * c + 4 * (lane & 1);
+        xsrc[i] = a.x + (size_t)min(row, R - 1) * K + (size_t)kt0 * 32 + (8 << WQ) * c + 4 * (lane & 1);
         xdst[i] = rb * 2048 + (q & 1) * 512 + lane * 8;
     }
 
@@ -177,13 +189,22 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
 #pragma unroll
         for (int n = 0; n < WN; ++n) acc[i][n] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    struct Staged { f32x4_t x[XI]; u32x4_t w[S::WI]; };
+    struct Staged { f32x4_t x[XI]; u32x4_t w[S::WI]; };  // 8-bit weights use half of each w
     auto issue = [&](int stage, Staged &r) {
         const int kt = min(stage, KT - 1);
 #pragma unroll
-        for (int i = 0; i < S::WI; ++i) r.w[i] = *reinterpret_cast<const u32x4_t *>(wsrc[i] + (size_t)kt * 1024);
+        for (int i = 0; i < S::WI; ++i) {
+            if constexpr (WQ) {
+                const q8_u32x2_t h = *reinterpret_cast<const q8_u32x2_t *>(wsrc[i] + (size_t)(kt >> 1) * 1024 + (kt & 1) * 8);
+                r.w[i] = u32x4_t{h.x, h.y, 0u, 0u};
+            } else {
+                r.w[i] = *reinterpret_cast<const u32x4_t *>(wsrc[i] + (size_t)kt * 1024);
+            }
+        }
+        // 8-bit weights: k-tile kt starts at 64 (kt / 2) + 8 (kt % 2) and its chunks are 16 columns apart
+        const size_t xo = WQ ? (size_t)(kt >> 1) * 64 + (kt & 1) * 8 : (size_t)kt * 32;
 #pragma unroll
-        for (int i = 0; i < XI; ++i) r.x[i] = *reinterpret_cast<const f32x4_t *>(xsrc[i] + (size_t)kt * 32);
+        for (int i = 0; i < XI; ++i) r.x[i] = *reinterpret_cast<const f32x4_t *>(xsrc[i] + xo);
     };
     auto stash = [&](const Staged &r, int slot) {
         char *xslot = xs + slot * S::XS, *wslot = ws + slot * S::WS;
@@ -195,7 +216,9 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
             *reinterpret_cast<u32x2_t *>(xslot + xdst[i] + 1024) = lo;
         }
 #pragma unroll
-        for (int i = 0; i < S::WI; ++i) *reinterpret_cast<u32x4_t *>(wslot + (wave + 4 * i) * 1024 + lane * 16) = r.w[i];
+        for (int i = 0; i < S::WI; ++i)
+            *reinterpret_cast<u32x4_t *>(wslot + (wave + 4 * i) * 1024 + lane * 16) =
+                WQ ? q8_half_to_bf16(q8_u32x2_t{r.w[i].x, r.w[i].y}) : r.w[i];
     };
     auto read = [&](int stage, GemmFrags<WM, WN> &f) {
         const char *xslot = xs + (stage & 1) * S::XS + lane * 16;
@@ -305,6 +328,13 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
             if (col_ok && a.g_next != nullptr) gn = *reinterpret_cast<const f32x4_t *>(a.g_next + n);
             fetch(0);
         }
+        // 8-bit weights: the scales of this lane's two columns of the pass (a partial result of a shared-out K is
+        // scaled by gemm_finish_k instead)
+        float wcs[2] = {1.f, 1.f};
+        if (WQ && a.wscale != nullptr) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) wcs[h] = a.wscale[(size_t)min(g + h, n_groups - 1) * 16 + (lane & 15)];
+        }
         wave_sync();  // the previous pass has read the tile
         // register v of lane l is x row 4 (l / 16) + v, W row l % 16
 #pragma unroll
@@ -313,7 +343,7 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
             for (int i = 0; i < WM; ++i)
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    tile[(i * 16 + (lane >> 4) * 4 + v) * TS + h * 16 + (lane & 15)] = acc[i][2 * p + h][v];
+                    tile[(i * 16 + (lane >> 4) * 4 + v) * TS + h * 16 + (lane & 15)] = WQ ? acc[i][2 * p + h][v] * wcs[h] : acc[i][2 * p + h][v];
         wave_sync();
         if constexpr (EPI == EPI_RESID) {
 #pragma unroll
@@ -379,6 +409,10 @@ __global__ __launch_bounds__(256) void gemm_finish_k(const GemvArgs a, const flo
             const f32x4_t v = *reinterpret_cast<const f32x4_t *>(p + (size_t)sl * split_stride);
             acc[0] += v[0]; acc[1] += v[1]; acc[2] += v[2]; acc[3] += v[3];
         }
+        if (a.wscale != nullptr) {  // 8-bit weights: the column scales
+            const f32x4_t sc = *reinterpret_cast<const f32x4_t *>(a.wscale + (size_t)g * 16 + c4);
+            acc[0] *= sc[0]; acc[1] *= sc[1]; acc[2] *= sc[2]; acc[3] *= sc[3];
+        }
     }
     *reinterpret_cast<f32x4_t *>(tile + r * 20 + c4) = acc;
     if (lane < 16) scale[lane] = (a.row_scale != nullptr && lane < Rw) ? a.row_scale[row0 + lane] : 1.f;
@@ -389,7 +423,7 @@ __global__ __launch_bounds__(256) void gemm_finish_k(const GemvArgs a, const flo
     }
 }
 
-template <int EPI, int WM, int WN, bool DEEP>
+template <int EPI, int WM, int WN, bool DEEP, int WQ>
 static hipError_t launch_gemm_one(const GemvArgs &a, int Ntot, int ksplit, int64_t split_stride, hipEvent_t ev0, hipEvent_t ev1,
                                   hipStream_t s) {
     using S = GemmShape<WM, WN, DEEP>;
@@ -398,16 +432,16 @@ static hipError_t launch_gemm_one(const GemvArgs &a, int Ntot, int ksplit, int64
     const int grid = ((n_blocks + 7) / 8) * 8 * m_blocks * ksplit;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_mfma_k<EPI, WM, WN, DEEP>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_mfma_k<EPI, WM, WN, DEEP, WQ>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     if (ev0 != nullptr)
-        hipExtLaunchKernelGGL((gemm_mfma_k<EPI, WM, WN, DEEP>), dim3(grid), dim3(GEMM_THREADS), S::LDS, s, ev0, ev1, 0, a, m_blocks,
+        hipExtLaunchKernelGGL((gemm_mfma_k<EPI, WM, WN, DEEP, WQ>), dim3(grid), dim3(GEMM_THREADS), S::LDS, s, ev0, ev1, 0, a, m_blocks,
                               ksplit, split_stride);
     else
-        hipLaunchKernelGGL((gemm_mfma_k<EPI, WM, WN, DEEP>), dim3(grid), dim3(GEMM_THREADS), S::LDS, s, a, m_blocks, ksplit,
+        hipLaunchKernelGGL((gemm_mfma_k<EPI, WM, WN, DEEP, WQ>), dim3(grid), dim3(GEMM_THREADS), S::LDS, s, a, m_blocks, ksplit,
                            split_stride);
     return hipGetLastError();
 }
@@ -415,18 +449,20 @@ static hipError_t launch_gemm_one(const GemvArgs &a, int Ntot, int ksplit, int64
 // Shares of K for a projection whose blocks would leave most compute units idle: a workgroup's time is its k-tiles
 // times the load latency it cannot hide (about 0.6 us per k-tile), whatever the rows, so a matrix with few blocks
 // (N = d_model at up to a few hundred rows) is served faster by more, shorter workgroups plus one summing pass.
-static int pick_ksplit(int Ntot, int K, int R, size_t ws_bytes) {
+static int pick_ksplit(int Ntot, int K, int R, size_t ws_bytes, bool q8) {
     const int wgs = ((Ntot + 127) / 128) * ((R + 127) / 128), KT = K / 32;
     if (wgs > 128 || KT < 8) return 1;
     int sp = std::min(std::min(8, 256 / wgs), KT / 4);
     while (sp > 1 && (size_t)sp * R * Ntot * sizeof(float) > ws_bytes) --sp;
-    while (sp > 1 && (sp - 1) * ((KT + sp - 1) / sp) >= KT) --sp;  // no empty share
+    while (sp > 1 && (sp - 1) * share_ktiles(KT, sp, q8) >= KT) --sp;  // no empty share
     return std::max(sp, 1);
 }
 
 template <int EPI>
 static hipError_t launch_gemm_cfg(const GemvArgs &a, int Ntot, int forced, float *ws, size_t ws_bytes, hipEvent_t ev0,
                                   hipEvent_t ev1, hipStream_t s) {
+    const bool q8 = a.wscale != nullptr;
+    if (q8 && a.K % 64) return hipErrorInvalidValue;
     int cfg = forced % 1000, ksplit = forced / 1000;
     if (cfg == 0) {
         // both shapes are bound by what a compute unit can fetch from L2 per matrix instruction: the wide block
@@ -434,23 +470,26 @@ static hipError_t launch_gemm_cfg(const GemvArgs &a, int Ntot, int forced, float
         const int m_blocks = (a.R + 127) / 128;
         cfg = ((Ntot + 255) / 256) * m_blocks > 256 ? 408 : 404;
     }
-    if (ksplit == 0) ksplit = (cfg == 404 && ws != nullptr) ? pick_ksplit(Ntot, a.K, a.R, ws_bytes) : 1;
+    if (ksplit == 0) ksplit = (cfg == 404 && ws != nullptr) ? pick_ksplit(Ntot, a.K, a.R, ws_bytes, q8) : 1;
     if (ksplit > 1) {
         const int KT = a.K / 32;
         if (cfg != 404 || ws == nullptr || (size_t)ksplit * a.R * Ntot * sizeof(float) > ws_bytes || ksplit > KT ||
-            (ksplit - 1) * ((KT + ksplit - 1) / ksplit) >= KT)
+            (ksplit - 1) * share_ktiles(KT, ksplit, q8) >= KT)
             return hipErrorInvalidValue;
         const int64_t stride = (int64_t)a.R * Ntot;
         GemvArgs p = a;  // partial results: plain rows of Ntot columns, unscaled
-        p.n0 = Ntot; p.y = ws; p.row_scale = nullptr; p.ssq_in = nullptr;
-        hipError_t e = launch_gemm_one<EPI_PLAIN, 4, 4, true>(p, Ntot, ksplit, stride, ev0, ev1, s);
+        p.n0 = Ntot; p.y = ws; p.row_scale = nullptr; p.ssq_in = nullptr; p.wscale = nullptr;
+        hipError_t e = q8 ? launch_gemm_one<EPI_PLAIN, 4, 4, true, 1>(p, Ntot, ksplit, stride, ev0, ev1, s)
+                          : launch_gemm_one<EPI_PLAIN, 4, 4, true, 0>(p, Ntot, ksplit, stride, ev0, ev1, s);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL((gemm_finish_k<EPI>), dim3(Ntot / 16, (a.R + 63) / 64), dim3(256), 0, s, a, ws, ksplit, stride);
         return hipGetLastError();
     }
-    switch (cfg) {
-        case 408: return launch_gemm_one<EPI, 4, 8, false>(a, Ntot, 1, 0, ev0, ev1, s);
-        case 404: return launch_gemm_one<EPI, 4, 4, true>(a, Ntot, 1, 0, ev0, ev1, s);
+    switch (cfg + 1000 * (int)q8) {
+        case 408: return launch_gemm_one<EPI, 4, 8, false, 0>(a, Ntot, 1, 0, ev0, ev1, s);
+        case 404: return launch_gemm_one<EPI, 4, 4, true, 0>(a, Ntot, 1, 0, ev0, ev1, s);
+        case 1408: return launch_gemm_one<EPI, 4, 8, false, 1>(a, Ntot, 1, 0, ev0, ev1, s);
+        case 1404: return launch_gemm_one<EPI, 4, 4, true, 1>(a, Ntot, 1, 0, ev0, ev1, s);
     }
     return hipErrorInvalidValue;
 }
@@ -464,13 +503,13 @@ bool gemm_mfma_serves(int epi, int Ntot, int K, int R) {
 // k-tile whatever its rows (load latency it cannot hide: 0.57 us for the narrow block alone on a compute unit, 1.17
 // us per pair sharing one; 1.0 / 1.7 us for the wide block), the blocks run in rounds of 512, and a split of K
 // adds its summing pass.
-float gemm_mfma_estimate_us(int Ntot, int K, int R, size_t ws_bytes) {
+float gemm_mfma_estimate_us(int Ntot, int K, int R, size_t ws_bytes, bool q8) {
     const int m_blocks = (R + 127) / 128, KT = K / 32;
     if (((Ntot + 255) / 256) * m_blocks > 256) {
         const int wgs = ((Ntot + 255) / 256) * m_blocks;
         return 3.f + KT * 1.7f * ((wgs + 511) / 512);
     }
-    const int sp = pick_ksplit(Ntot, K, R, ws_bytes);
+    const int sp = pick_ksplit(Ntot, K, R, ws_bytes, q8);
     const int wgs = ((Ntot + 127) / 128) * m_blocks * sp, stages = (KT + sp - 1) / sp;
     const float per_stage = wgs <= 256 ? 0.57f : 1.17f * ((wgs + 511) / 512);
     return 3.f + stages * per_stage + (sp > 1 ? 8.f : 0.f);

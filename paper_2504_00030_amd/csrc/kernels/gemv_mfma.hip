@@ -18,6 +18,7 @@
 #include "epilogue.hpp"
 #include "kv.hpp"
 #include "params.hpp"
+#include "q8.hpp"
 
 namespace sd {
 
@@ -208,14 +209,17 @@ constexpr int PW = 16;  // waves
 
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-template <int EPI, int KTW, int TERMS>
+//   WQ: 1 = 8-bit weights (q8.hpp): a tile spans 64 k and feeds two matrix instructions, so a wave holds KTW x
+//   fragments for KTW / 2 tiles.
+template <int EPI, int KTW, int TERMS, int WQ>
 __global__ __launch_bounds__(PW * 64) void gemv_persist_k(const GemvArgs a) {
     if (a.active != nullptr && *a.active == 0) return;
     constexpr int NT = PW * 64;
+    constexpr int TPW = KTW >> WQ;         // weight tiles per wave and group
     // tiles per burst of loads: 8 KiB per wave, 4 where 64 registers already hold x fragments
-    constexpr int UB = KTW * TERMS >= 16 ? 4 : (KTW < 8 ? KTW : 8);
-    constexpr int NB = KTW / UB;           // bursts per group
-    static_assert(KTW % UB == 0, "bursts tile the wave's k-tiles");
+    constexpr int UB = KTW * TERMS >= 16 ? 4 : (TPW < 8 ? TPW : 8);
+    constexpr int NB = TPW / UB;           // bursts per group
+    static_assert(TPW % UB == 0, "bursts tile the wave's k-tiles");
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     int Ntot = a.n0;
     if (EPI == EPI_QKV) Ntot = (a.nq + 2 * a.nkv) * a.hd;
@@ -223,7 +227,7 @@ __global__ __launch_bounds__(PW * 64) void gemv_persist_k(const GemvArgs a) {
     const int n_groups = Ntot >> 4;
     const int G = gridDim.x, b = blockIdx.x;
     const int n_my = (n_groups - b + G - 1) / G;  // host: G <= n_groups
-    const int K = a.K, KT = K >> 5;               // host: KT == PW * KTW
+    const int K = a.K, KT = K >> (5 + WQ);        // tiles per group; host: KT == PW * TPW
     const int R = a.R;
 
     __shared__ float part[PW * 256];
@@ -242,14 +246,17 @@ __global__ __launch_bounds__(PW * 64) void gemv_persist_k(const GemvArgs a) {
         if (fold && r >= 8) { r -= 8; off = (size_t)a.xb_lo; }
         const bool row_ok = r < R;
         const size_t xr = (size_t)(min(r, R - 1) * a.x_mul + a.x_add);
-        const uint16_t *xp = a.xb + off + xr * K + (size_t)wave * 32 + (lane >> 4) * 8;
+        // fragment j: 16-bit weights, k-tile wave + 16 j, k-chunk lane / 16 of 8; 8-bit weights, tile wave + 16 (j / 2),
+        // k-chunk lane / 16 of 16, its first or second 8 columns
+        const uint16_t *xp = a.xb + off + xr * K + (size_t)wave * (32 << WQ) + (lane >> 4) * (8 << WQ);
 #pragma unroll
         for (int j = 0; j < KTW; ++j) {
             xh[j] = u32x4_t{0u, 0u, 0u, 0u};
             if (TERMS == 2) xl[j] = u32x4_t{0u, 0u, 0u, 0u};
+            const size_t ko = WQ ? (size_t)(j >> 1) * PW * 64 + (j & 1) * 8 : (size_t)j * PW * 32;
             if (row_ok) {
-                xh[j] = *reinterpret_cast<const u32x4_t *>(xp + (size_t)j * PW * 32);
-                if (TERMS == 2) xl[j] = *reinterpret_cast<const u32x4_t *>(xp + a.xb_lo + (size_t)j * PW * 32);
+                xh[j] = *reinterpret_cast<const u32x4_t *>(xp + ko);
+                if (TERMS == 2) xl[j] = *reinterpret_cast<const u32x4_t *>(xp + a.xb_lo + ko);
             }
         }
     }
@@ -268,16 +275,32 @@ __global__ __launch_bounds__(PW * 64) void gemv_persist_k(const GemvArgs a) {
 
     for (int i = 0; i < n_my; ++i) {
         if constexpr (PRE) epi_prefetch_group<EPI>(a, R, b + i * G, Ntot, threadIdx.x, pre);
+        // 8-bit weights: the scale of this thread's column of the reduced tile, fetched ahead like the operands above
+        float wsc = 1.f;
+        if (WQ && threadIdx.x < 256) wsc = a.wscale[(size_t)(b + i * G) * 16 + (lane & 15)];
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
 #pragma unroll
             for (int u = 0; u < UB; ++u) {
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xh[nb * UB + u]),
-                                                              __builtin_bit_cast(bf16x8_t, bw[u]), acc, 0, 0, 0);
-                if (TERMS == 2)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xl[nb * UB + u]),
+                const int t = nb * UB + u;
+                if constexpr (WQ == 0) {
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xh[t]),
                                                                   __builtin_bit_cast(bf16x8_t, bw[u]), acc, 0, 0, 0);
+                    if (TERMS == 2)
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xl[t]),
+                                                                      __builtin_bit_cast(bf16x8_t, bw[u]), acc, 0, 0, 0);
+                } else {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const u32x4_t wb = q8_half_to_bf16(h == 0 ? q8_u32x2_t{bw[u].x, bw[u].y} : q8_u32x2_t{bw[u].z, bw[u].w});
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xh[2 * t + h]),
+                                                                      __builtin_bit_cast(bf16x8_t, wb), acc, 0, 0, 0);
+                        if (TERMS == 2)
+                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xl[2 * t + h]),
+                                                                          __builtin_bit_cast(bf16x8_t, wb), acc, 0, 0, 0);
+                    }
+                }
             }
             // next burst: the rest of this group, or the head of the next one
             if (nb + 1 < NB) {
@@ -307,13 +330,123 @@ __global__ __launch_bounds__(PW * 64) void gemv_persist_k(const GemvArgs a) {
                     for (int w = 1; w < PW; ++w) s2 += part[w * 256 + idx + 32];
                     s += s2;
                 }
-                tile[((l >> 4) * 4 + v) * 17 + (l & 15)] = s;
+                tile[((l >> 4) * 4 + v) * 17 + (l & 15)] = WQ ? s * wsc : s;
             }
         }
         lds_barrier();
         if constexpr (PRE) epilogue_tile_pre<EPI>(a, tile, 17, s_scale, R, b + i * G, Ntot, threadIdx.x, pre);
         else epilogue_tile<EPI, 16, NT>(a, tile, 17, s_scale, R, b + i * G, Ntot, threadIdx.x);
     }
+}
+
+// ---- 8-bit weights, any shape ---------------------------------------------------------------------------
+// One workgroup per 16-row group of W, its NW waves split the group's 64-k tiles in contiguous slices (the shapes
+// the persistent kernel does not take: K = 14336, more than 16 rows, K not a multiple of 1024).  Per burst a wave
+// issues U tile loads, then per tile and half gathers the x fragments of every row block, turns the half tile into
+// bf16 and multiplies.  Reduction, row scales and epilogues as in gemv_mfma_k; the column scales of the weights are
+// multiplied into the reduced tile.
+template <int EPI, int MB, int NW>
+__global__ __launch_bounds__(NW * 64) void gemv_q8_k(const GemvArgs a) {
+    if (a.active != nullptr && *a.active == 0) return;
+    constexpr int NT = NW * 64;
+    constexpr int FR = MB * 256;
+    constexpr int TS = 17;
+    constexpr int U = MB == 1 ? 4 : (MB == 2 ? 2 : 1);
+    static_assert(NW * MB <= 32, "partial tiles must fit 32 KiB of LDS");
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // scalar: see above
+    int Ntot = a.n0;
+    if (EPI == EPI_QKV) Ntot = (a.nq + 2 * a.nkv) * a.hd;
+    if (EPI == EPI_SWIGLU) Ntot = 2 * a.n0;
+    const int g = blockIdx.x;
+    const int K = a.K, KT = K >> 6;
+    const int KTw = (KT + NW - 1) / NW;
+    const int kt_begin = min(wave * KTw, KT), kt_end = min(kt_begin + KTw, KT);
+    const int R = a.R;
+
+    __shared__ float part[NW * FR];
+    __shared__ float tile[MB * 16 * TS];
+    __shared__ float s_scale[MB * 16];
+
+    RowScales<NT> rs;
+    rs.begin(a, R);
+
+    const u32x4_t *bp = reinterpret_cast<const u32x4_t *>(a.w0) + ((size_t)g * KT + kt_begin) * 64 + lane;
+    const bool has_lo = a.xb_lo != 0;
+    const bool fold = has_lo && MB == 1 && R <= 8;  // hi rows in 0..7, lo rows in 8..15 of one fragment
+    const bool two_terms = has_lo && !fold;
+    const uint16_t *ap[MB];
+    bool row_ok[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        int r = mb * 16 + (lane & 15);
+        size_t off = 0;
+        if (fold && r >= 8) { r -= 8; off = (size_t)a.xb_lo; }
+        row_ok[mb] = r < R;
+        const size_t xr = (size_t)(min(r, R - 1) * a.x_mul + a.x_add);
+        ap[mb] = a.xb + off + xr * K + (size_t)kt_begin * 64 + (lane >> 4) * 16;
+    }
+    f32x4_t acc[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) acc[mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    for (int kt = kt_begin; kt < kt_end; kt += U) {
+        u32x4_t bw[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (kt + u < kt_end) bw[u] = __builtin_nontemporal_load(bp + 64 * u);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (kt + u < kt_end) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    u32x4_t xh[MB], xl[MB];
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        xh[mb] = u32x4_t{0u, 0u, 0u, 0u};
+                        xl[mb] = u32x4_t{0u, 0u, 0u, 0u};
+                        if (row_ok[mb]) {
+                            xh[mb] = *reinterpret_cast<const u32x4_t *>(ap[mb] + u * 64 + h * 8);
+                            if (two_terms) xl[mb] = *reinterpret_cast<const u32x4_t *>(ap[mb] + a.xb_lo + u * 64 + h * 8);
+                        }
+                    }
+                    const u32x4_t wb = q8_half_to_bf16(h == 0 ? q8_u32x2_t{bw[u].x, bw[u].y} : q8_u32x2_t{bw[u].z, bw[u].w});
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xh[mb]),
+                                                                          __builtin_bit_cast(bf16x8_t, wb), acc[mb], 0, 0, 0);
+                        if (two_terms)
+                            acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xl[mb]),
+                                                                              __builtin_bit_cast(bf16x8_t, wb), acc[mb], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        bp += 64 * U;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) ap[mb] += 64 * U;
+    }
+
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) part[wave * FR + ((mb * 4 + v) << 6) + lane] = acc[mb][v];
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < FR; idx += NT) {
+        float s = part[idx];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) s += part[w * FR + idx];
+        const int l = idx & 63, v = (idx >> 6) & 3, mb = idx >> 8;
+        if (fold) {
+            if (l >= 32) continue;
+            float s2 = part[idx + 32];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) s2 += part[w * FR + idx + 32];
+            s += s2;
+        }
+        tile[(mb * 16 + (l >> 4) * 4 + v) * TS + (l & 15)] = s * a.wscale[(size_t)g * 16 + (l & 15)];
+    }
+    rs.finish(a, s_scale, R);  // ends with a barrier
+    epilogue_tile<EPI, 16, NT>(a, tile, TS, s_scale, R, g, Ntot, threadIdx.x);
 }
 
 // ---- launch configuration ---------------------------------------------------------------------------
@@ -335,8 +468,9 @@ static MfmaCfg pick_cfg(int n_groups, int KT, int MB, int forced) {
     return c;
 }
 
-int gemv_mfma_groups_per_wg(int epi, int Ntot, int K, int R, int forced) {
+int gemv_mfma_groups_per_wg(int epi, int Ntot, int K, int R, int forced, bool q8) {
     (void)epi;
+    if (q8) return 1;
     const int MB = R <= 16 ? 1 : (R <= 32 ? 2 : (R <= 64 ? 4 : 8));
     return pick_cfg(Ntot / 16, K / 32, MB, forced).ng;
 }
@@ -373,38 +507,54 @@ static hipError_t launch_mb(const GemvArgs &a, int MB, int blocks, LaunchEvents 
 static int persist_terms(const GemvArgs &a) { return (a.xb_lo != 0 && a.R > 8) ? 2 : 1; }
 static bool persist_fits(const GemvArgs &a) {
     if (a.R > 16 || a.K % 512) return false;
+    if (a.wscale != nullptr && a.K % 1024) return false;  // 8-bit tiles span 64 k: 16 waves x 64
     const int ktw = a.K / 512;
     if (ktw != 4 && ktw != 8 && ktw != 16) return false;
     return ktw * persist_terms(a) <= 16;
 }
 
-template <int EPI, int KTW, int TERMS>
+template <int EPI, int KTW, int TERMS, int WQ>
 static hipError_t launch_persist_one(const GemvArgs &a, int n_groups, LaunchEvents ev, hipStream_t s) {
     const int G = n_groups < 256 ? n_groups : 256;  // one workgroup per compute unit
     if (ev.start != nullptr)
-        hipExtLaunchKernelGGL((gemv_persist_k<EPI, KTW, TERMS>), dim3(G), dim3(PW * 64), 0, s, ev.start, ev.stop, 0, a);
+        hipExtLaunchKernelGGL((gemv_persist_k<EPI, KTW, TERMS, WQ>), dim3(G), dim3(PW * 64), 0, s, ev.start, ev.stop, 0, a);
     else
-        hipLaunchKernelGGL((gemv_persist_k<EPI, KTW, TERMS>), dim3(G), dim3(PW * 64), 0, s, a);
+        hipLaunchKernelGGL((gemv_persist_k<EPI, KTW, TERMS, WQ>), dim3(G), dim3(PW * 64), 0, s, a);
     return hipGetLastError();
 }
 
-template <int EPI>
+template <int EPI, int WQ>
 static hipError_t launch_persist(const GemvArgs &a, int n_groups, LaunchEvents ev, hipStream_t s) {
     const int ktw = a.K / 512;
     if (persist_terms(a) == 2) {
-        if (ktw == 4) return launch_persist_one<EPI, 4, 2>(a, n_groups, ev, s);
-        return launch_persist_one<EPI, 8, 2>(a, n_groups, ev, s);
+        if (ktw == 4) return launch_persist_one<EPI, 4, 2, WQ>(a, n_groups, ev, s);
+        return launch_persist_one<EPI, 8, 2, WQ>(a, n_groups, ev, s);
     }
-    if (ktw == 4) return launch_persist_one<EPI, 4, 1>(a, n_groups, ev, s);
-    if (ktw == 8) return launch_persist_one<EPI, 8, 1>(a, n_groups, ev, s);
-    return launch_persist_one<EPI, 16, 1>(a, n_groups, ev, s);
+    if (ktw == 4) return launch_persist_one<EPI, 4, 1, WQ>(a, n_groups, ev, s);
+    if (ktw == 8) return launch_persist_one<EPI, 8, 1, WQ>(a, n_groups, ev, s);
+    return launch_persist_one<EPI, 16, 1, WQ>(a, n_groups, ev, s);
 }
 
 template <int EPI>
 static hipError_t launch_cfg(const GemvArgs &a, int Ntot, int forced, LaunchEvents ev, hipStream_t s) {
     const int MB = a.R <= 16 ? 1 : (a.R <= 32 ? 2 : (a.R <= 64 ? 4 : 8));
     const int n_groups = Ntot / 16;
-    if (forced == 0 && persist_fits(a)) return launch_persist<EPI>(a, n_groups, ev, s);
+    if (a.wscale != nullptr) {
+        if (a.K % 64) return hipErrorInvalidValue;
+        if (forced == 0 && persist_fits(a)) return launch_persist<EPI, 1>(a, n_groups, ev, s);
+        auto go = [&](auto kern, int nw) {
+            if (ev.start != nullptr) hipExtLaunchKernelGGL(kern, dim3(n_groups), dim3(nw * 64), 0, s, ev.start, ev.stop, 0, a);
+            else hipLaunchKernelGGL(kern, dim3(n_groups), dim3(nw * 64), 0, s, a);
+            return hipGetLastError();
+        };
+        switch (MB) {
+            case 1: return go(gemv_q8_k<EPI, 1, 8>, 8);
+            case 2: return go(gemv_q8_k<EPI, 2, 8>, 8);
+            case 4: return go(gemv_q8_k<EPI, 4, 8>, 8);
+            default: return go(gemv_q8_k<EPI, 8, 4>, 4);
+        }
+    }
+    if (forced == 0 && persist_fits(a)) return launch_persist<EPI, 0>(a, n_groups, ev, s);
     const MfmaCfg c = pick_cfg(n_groups, a.K / 32, MB, forced);
     const int blocks = (n_groups + c.ng - 1) / c.ng;
     const int key = c.ng * 100 + c.nw;

@@ -79,43 +79,58 @@ hipError_t launch_embed(const EmbedArgs &a, hipStream_t s) {
 // Packed rows of the fused matrices are ordered so that an epilogue finds both partners of a pair in
 // one group: rows 0-7 of a group are first elements (gate rows, or RoPE elements j), rows 8-15 the
 // matching second elements (up rows, or RoPE elements j + hd/2).
-__device__ __forceinline__ const uint16_t *retile_src(const RetileArgs &a, int p) {
-    const uint16_t *w0 = reinterpret_cast<const uint16_t *>(a.w0);
+// Packed row p -> (source matrix 0..2, row in it).
+__device__ __forceinline__ void retile_source(const RetileArgs &a, int p, int &which, int &row) {
+    which = 0;
+    row = p;
     if (a.mode == EPI_SWIGLU) {
         const int gi = p >> 4, pos = p & 15;
-        const int j = gi * 8 + (pos & 7);
-        const uint16_t *base = pos < 8 ? w0 : reinterpret_cast<const uint16_t *>(a.w1);
-        return base + (size_t)j * a.K;
-    }
-    if (a.mode == EPI_QKV) {
+        row = gi * 8 + (pos & 7);
+        which = pos < 8 ? 0 : 1;
+    } else if (a.mode == EPI_QKV) {
         const int half = a.hd >> 1;
         const int gi = p >> 4, pos = p & 15;
         const int P = gi * 8 + (pos & 7);
         int hh = P / half;
         const int j = P % half + (pos < 8 ? 0 : half);
-        const uint16_t *base = w0;
-        if (hh >= a.nq + a.nkv) { base = reinterpret_cast<const uint16_t *>(a.w2); hh -= a.nq + a.nkv; }
-        else if (hh >= a.nq) { base = reinterpret_cast<const uint16_t *>(a.w1); hh -= a.nq; }
-        return base + ((size_t)hh * a.hd + j) * a.K;
+        if (hh >= a.nq + a.nkv) { which = 2; hh -= a.nq + a.nkv; }
+        else if (hh >= a.nq) { which = 1; hh -= a.nq; }
+        row = hh * a.hd + j;
     }
-    return w0 + (size_t)p * a.K;
 }
 
 __global__ __launch_bounds__(256) void retile_k(const RetileArgs a, uint4 *__restrict__ out) {
-    const int KT = a.K / 32;
+    // 16-bit weights: tiles of 16 rows x 32 k; 8-bit weights: 16 rows x 64 k.  Either way lane l of a tile holds 16
+    // bytes of row l % 16: k-chunk l / 16 of four.
+    const int esz = a.q8 ? 1 : 2, tk = a.q8 ? 64 : 32;
+    const int KT = a.K / tk;
     const int64_t total = (int64_t)(a.Ntot / 16) * KT * 64;
+    const char *base[3] = {reinterpret_cast<const char *>(a.w0), reinterpret_cast<const char *>(a.w1),
+                           reinterpret_cast<const char *>(a.w2)};
     for (int64_t idx = blockIdx.x * (int64_t)256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
         const int l = (int)(idx & 63);
         const int64_t tile = idx >> 6;
         const int t = (int)(tile % KT);
         const int g = (int)(tile / KT);
-        const uint16_t *row = retile_src(a, g * 16 + (l & 15));
-        out[idx] = *reinterpret_cast<const uint4 *>(row + t * 32 + (l >> 4) * 8);
+        int which, row;
+        retile_source(a, g * 16 + (l & 15), which, row);
+        const char *src = (which == 0 ? base[0] : (which == 1 ? base[1] : base[2])) +
+                          ((size_t)row * a.K + (size_t)t * tk + (l >> 4) * (tk / 4)) * esz;
+        out[idx] = *reinterpret_cast<const uint4 *>(src);
+    }
+    // the per-row scales of 8-bit weights, in packed row order
+    if (a.q8 && a.scale_out != nullptr) {
+        const float *sc[3] = {a.s0, a.s1, a.s2};
+        for (int p = blockIdx.x * 256 + threadIdx.x; p < a.Ntot; p += gridDim.x * 256) {
+            int which, row;
+            retile_source(a, p, which, row);
+            a.scale_out[p] = (which == 0 ? sc[0] : (which == 1 ? sc[1] : sc[2]))[row];
+        }
     }
 }
 
 hipError_t launch_retile(const RetileArgs &a, void *out, hipStream_t s) {
-    if (a.Ntot % 16 != 0 || a.K % 32 != 0) return hipErrorInvalidValue;
+    if (a.Ntot % 16 != 0 || a.K % (a.q8 ? 64 : 32) != 0) return hipErrorInvalidValue;
     if (a.mode == EPI_QKV && ((a.hd / 2) % 8 != 0)) return hipErrorInvalidValue;
     if (a.mode == EPI_SWIGLU && (a.Ntot / 2) % 8 != 0) return hipErrorInvalidValue;
     hipLaunchKernelGGL(retile_k, dim3(4096), dim3(256), 0, s, a, reinterpret_cast<uint4 *>(out));

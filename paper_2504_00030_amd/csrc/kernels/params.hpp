@@ -55,6 +55,7 @@ struct GemvArgs {
     const float *row_scale;   // dense-contraction kernel only: ready-made row scales [R] (null: ones)
     int32_t rpw;              // W rows per wave (wave-dot) / 16-row groups per workgroup (matrix-core)
     const int32_t *active;    // when non-null and *active == 0 the kernel does nothing (drafting has stopped)
+    const float *wscale;      // 8-bit weights: one scale per packed output column, multiplied into the reduced tile (null: 16-bit weights)
     // ---- epilogue ----
     float *y;                 // PLAIN: [R][N]; LOGITS: logits base; QKV: q [R][nq*hd]
     int32_t y_mul, y_add, y_stride;  // LOGITS: logical row r writes row r * y_mul + y_add
@@ -87,6 +88,9 @@ struct GemvArgs {
 struct RetileArgs {
     const void *w0, *w1, *w2;
     int32_t mode, Ntot, K, nq, nkv, hd;
+    int32_t q8;                  // 1: int8 sources (tiles of 16 rows x 64 k) with one fp32 scale per row
+    const float *s0, *s1, *s2;   // q8: the scales of w0, w1, w2
+    float *scale_out;            // q8: [Ntot] scales in packed row order (may be null)
 };
 
 struct EmbedArgs {
@@ -180,11 +184,11 @@ hipError_t launch_embed(const EmbedArgs &a, hipStream_t s);
 hipError_t launch_gemv_wavedot(const GemvArgs &a, int epi, int w_dtype, hipStream_t s);
 hipError_t launch_gemv_mfma(const GemvArgs &a, int epi, int forced_cfg, hipEvent_t ev_start, hipEvent_t ev_stop,
                             hipStream_t s);
-int gemv_mfma_groups_per_wg(int epi, int Ntot, int K, int R, int forced_cfg);  // 16-row groups per workgroup
+int gemv_mfma_groups_per_wg(int epi, int Ntot, int K, int R, int forced_cfg, bool q8 = false);  // 16-row groups per workgroup
 // Prompt ingestion: the dense-contraction kernel for many rows (x read as fp32 rows, a.x).
 constexpr int GEMM_MIN_ROWS = 17;  // up to 16 rows the persistent weight-streaming kernel is the faster one at any shape
 bool gemm_mfma_serves(int epi, int Ntot, int K, int R);
-float gemm_mfma_estimate_us(int Ntot, int K, int R, size_t workspace_bytes);  // rough time of one launch
+float gemm_mfma_estimate_us(int Ntot, int K, int R, size_t workspace_bytes, bool q8 = false);  // rough time of one launch
 hipError_t launch_gemm_mfma(const GemvArgs &a, int epi, int forced_cfg, float *scale_buf, float *workspace,
                             size_t workspace_bytes, hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t s);
 bool gemv_wavedot_uses_split(int epi, int Ntot, int K, int R, int w_dtype);

@@ -21,7 +21,8 @@ class ModelShape:
     vocab: int
     rope_theta: float = 10000.0
     rms_eps: float = 1e-5
-    dtype: str = "bf16"  # "fp32" or "bf16": storage type of weights and KV cache
+    dtype: str = "bf16"  # "fp32" or "bf16": storage type of weights and KV cache; "q8": projection matrices and LM
+                         # head as int8 with one fp32 scale per output row, everything else as for "bf16"
 
     def n_params(self) -> int:
         per_layer = (
@@ -33,10 +34,10 @@ class ModelShape:
 
     def weight_bytes(self) -> int:
         """Bytes streamed by one forward pass: every matrix once (embedding rows excluded)."""
-        return self.n_params() * (2 if self.dtype == "bf16" else 4)
+        return self.n_params() * {"bf16": 2, "q8": 1}.get(self.dtype, 4)
 
     def kv_bytes_per_token(self) -> int:
-        return 2 * self.n_layers * self.n_kv_heads * self.head_dim * (2 if self.dtype == "bf16" else 4)
+        return 2 * self.n_layers * self.n_kv_heads * self.head_dim * (4 if self.dtype == "fp32" else 2)
 
 
 @dataclass(frozen=True)
@@ -80,6 +81,10 @@ PAIRS: Dict[str, PairConfig] = {
     "7b": PairConfig("7b", _T2, _D2, "independent", 512, 256, 8),
     # 8B-shaped target with a 1B-shaped draft (headline)
     "8b": PairConfig("8b", _T3, _T1, "independent", 1024, 512, 16),
+    # the headline shapes with 8-bit weights (the paper's largest pair runs quantised)
+    "8b-q8": PairConfig("8b-q8", replace(_T3, dtype="q8"), replace(_T1, dtype="q8"), "independent", 1024, 512, 16),
+    "small-q8": PairConfig("small-q8", replace(_TS, dtype="q8"), replace(_DS, dtype="q8"), "independent", 48, 64, 16),
+    "small-q8-hd128": PairConfig("small-q8-hd128", replace(_TH, dtype="q8"), replace(_DH, dtype="q8"), "independent", 80, 64, 16),
     # 13B-shaped target, verify-only sweeps; the draft slot reuses the 160m-shaped model
     "13b": PairConfig("13b", _T4, _D2, "independent", 512, 64, 16),
 }

@@ -18,7 +18,37 @@ STD = 0.02
 
 
 def _dtype(shape: ModelShape):
-    return torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+    # "q8" models keep embedding, norms and KV cache in bf16; their matrices are quantised by quantize_weights
+    return torch.float32 if shape.dtype == "fp32" else torch.bfloat16
+
+
+MATRICES = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+
+
+def quantize_rows(w: torch.Tensor):
+    """Symmetric 8-bit weights with one fp32 scale per output row: w ~ scale[n] * q[n][k], q in [-127, 127].
+    The quantised model is DEFINED by (q, scale); how they were obtained from a random matrix is immaterial."""
+    q = torch.empty(w.shape, dtype=torch.int8, device=w.device)
+    scale = torch.empty(w.shape[0], dtype=torch.float32, device=w.device)
+    step = max(1, (1 << 26) // max(w.shape[1], 1))
+    for r0 in range(0, w.shape[0], step):
+        blk = w[r0:r0 + step].float()
+        sc = blk.abs().amax(dim=1).clamp_min(1e-12) / 127.0
+        scale[r0:r0 + step] = sc
+        q[r0:r0 + step] = torch.round(blk / sc[:, None]).clamp_(-127, 127).to(torch.int8)
+    return q, scale
+
+
+def quantize_weights(W: Dict) -> Dict:
+    """The projection matrices and the LM head of W as (int8, per-row fp32 scale) pairs: key k holds q, key
+    k + "_scale" the scales.  Embedding and norm weights stay as they are."""
+    out = dict(W)
+    for k in MATRICES:
+        qs = [quantize_rows(w) for w in W[k]]
+        out[k] = [q for q, _ in qs]
+        out[k + "_scale"] = [s for _, s in qs]
+    out["lm_head"], out["lm_head_scale"] = quantize_rows(W["lm_head"])
+    return out
 
 
 def _normal(gen, rows, cols, dtype, device, std=STD):
@@ -86,6 +116,10 @@ def make_pair_weights(cfg: PairConfig, seed: int, device="cpu", norm_jitter: flo
         for r0 in range(0, cfg.draft.vocab, step):
             head[r0:r0 + step] = (Wt["lm_head"][r0:r0 + step].float() @ P.t()).to(head.dtype)
         Wd["lm_head"] = head
+    if cfg.target.dtype == "q8":
+        Wt = quantize_weights(Wt)
+    if cfg.draft.dtype == "q8":
+        Wd = quantize_weights(Wd)
     return Wt, Wd
 
 
@@ -97,5 +131,17 @@ def _np(t: torch.Tensor) -> np.ndarray:
 
 
 def to_numpy_weights(W: Dict) -> Dict:
-    """Host numpy copy for the oracle (bf16 -> uint16 bit patterns)."""
-    return {k: ([_np(t) for t in v] if isinstance(v, list) else _np(v)) for k, v in W.items()}
+    """Host numpy copy for the oracle (bf16 -> uint16 bit patterns).  Quantised matrices (int8 with a "_scale"
+    partner) come out as the fp64 matrices they stand for, scale[n] * q[n][k], and the scale keys are dropped."""
+    out = {}
+    for k, v in W.items():
+        if k.endswith("_scale"):
+            continue
+        sc = W.get(k + "_scale")
+        if sc is None:
+            out[k] = [_np(t) for t in v] if isinstance(v, list) else _np(v)
+        elif isinstance(v, list):
+            out[k] = [_np(s).astype(np.float64)[:, None] * _np(q).astype(np.float64) for q, s in zip(v, sc)]
+        else:
+            out[k] = _np(sc).astype(np.float64)[:, None] * _np(v).astype(np.float64)
+    return out
