@@ -47,7 +47,7 @@ enum {
     SPEC_ENOTIMPL = -6
 };
 
-enum { SPEC_F32 = 0, SPEC_BF16 = 1 };
+enum { SPEC_F32 = 0, SPEC_BF16 = 1, SPEC_Q8 = 2 };
 enum { SPEC_ACCEPT_NATURAL = 0, SPEC_ACCEPT_FORCED = 1 };
 enum { SPEC_PATH_AUTO = 0, SPEC_PATH_WAVEDOT = 1, SPEC_PATH_MFMA = 2 };
 
@@ -55,7 +55,10 @@ typedef struct spec_ctx spec_ctx; /* opaque */
 
 typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
-    int32_t dtype;      /* SPEC_F32 or SPEC_BF16: storage type of every weight and of the KV cache */
+    int32_t dtype;      /* SPEC_F32 or SPEC_BF16: storage type of every weight and of the KV cache.  SPEC_Q8: the seven
+                           projection matrices of every layer and the LM head are int8 with one fp32 scale per output
+                           row (W[n][k] = scale[n] * q[n][k], |q| <= 127); embedding, norm weights and the KV cache
+                           are bf16.  Needs d_model, n_q_heads * head_dim and d_ffn multiples of 64, vocab of 16. */
     float   rope_theta; /* rotary base */
     float   rms_eps;
 } spec_shape;
@@ -72,7 +75,11 @@ typedef struct {
     const void *const *w_down;                       /* [d_model][d_ffn] */
     const void *const *attn_norm, *const *ffn_norm;  /* [d_model] */
     const void *final_norm;                          /* [d_model] */
-    const void *lm_head;                             /* [vocab][d_model]; may alias tok_embed */
+    const void *lm_head;                             /* [vocab][d_model]; may alias tok_embed (not with SPEC_Q8) */
+    /* SPEC_Q8 only (ignored otherwise): fp32 scales, one per output row of the matrix of the same name */
+    const void *const *wq_scale, *const *wk_scale, *const *wv_scale, *const *wo_scale;
+    const void *const *w_gate_scale, *const *w_up_scale, *const *w_down_scale;
+    const void *lm_head_scale;
 } spec_weights;
 
 typedef struct {

@@ -17,7 +17,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "lib", "libspecdecode.so")
 
 SPEC_OK, SPEC_EINVAL, SPEC_ESTATE, SPEC_ENOMEM, SPEC_EHIP, SPEC_ECAP, SPEC_ENOTIMPL = 0, -1, -2, -3, -4, -5, -6
-SPEC_F32, SPEC_BF16 = 0, 1
+SPEC_F32, SPEC_BF16, SPEC_Q8 = 0, 1, 2
 ACCEPT_NATURAL, ACCEPT_FORCED = 0, 1
 PATH_AUTO, PATH_WAVEDOT, PATH_MFMA = 0, 1, 2
 GT_EXPAND_A, GT_LITERAL, GT_SHORT_TERM = 0, 1, 2
@@ -43,7 +43,9 @@ _PP = C.POINTER(C.c_void_p)
 class SpecWeights(C.Structure):
     _fields_ = [("tok_embed", C.c_void_p), ("wq", _PP), ("wk", _PP), ("wv", _PP), ("wo", _PP), ("w_gate", _PP),
                 ("w_up", _PP), ("w_down", _PP), ("attn_norm", _PP), ("ffn_norm", _PP), ("final_norm", C.c_void_p),
-                ("lm_head", C.c_void_p)]
+                ("lm_head", C.c_void_p),
+                ("wq_scale", _PP), ("wk_scale", _PP), ("wv_scale", _PP), ("wo_scale", _PP), ("w_gate_scale", _PP),
+                ("w_up_scale", _PP), ("w_down_scale", _PP), ("lm_head_scale", C.c_void_p)]
 
 
 class SpecConfig(C.Structure):
@@ -179,7 +181,7 @@ class FixedGamma:
 # ---- engine -------------------------------------------------------------------------------------------
 def _shape_struct(ms) -> SpecShape:
     return SpecShape(ms.n_layers, ms.d_model, ms.n_q_heads, ms.n_kv_heads, ms.head_dim, ms.d_ffn, ms.vocab,
-                     SPEC_BF16 if ms.dtype == "bf16" else SPEC_F32, ms.rope_theta, ms.rms_eps)
+                     {"bf16": SPEC_BF16, "q8": SPEC_Q8}.get(ms.dtype, SPEC_F32), ms.rope_theta, ms.rms_eps)
 
 
 def _weights_struct(W: Dict, keep: list) -> SpecWeights:
@@ -192,9 +194,12 @@ def _weights_struct(W: Dict, keep: list) -> SpecWeights:
         for t in (v if isinstance(v, list) else [v]):
             if not t.is_cuda or not t.is_contiguous():
                 raise ValueError(f"weight {k} must be a contiguous GPU tensor")
+    def sc(k):  # scales of 8-bit weights (synth.quantize_weights); absent for the other storage types
+        return arr(W[k + "_scale"]) if (k + "_scale") in W else None
     return SpecWeights(W["tok_embed"].data_ptr(), arr(W["wq"]), arr(W["wk"]), arr(W["wv"]), arr(W["wo"]),
                        arr(W["w_gate"]), arr(W["w_up"]), arr(W["w_down"]), arr(W["attn_norm"]), arr(W["ffn_norm"]),
-                       W["final_norm"].data_ptr(), W["lm_head"].data_ptr())
+                       W["final_norm"].data_ptr(), W["lm_head"].data_ptr(), sc("wq"), sc("wk"), sc("wv"), sc("wo"), sc("w_gate"),
+                       sc("w_up"), sc("w_down"), W["lm_head_scale"].data_ptr() if "lm_head_scale" in W else None)
 
 
 class SpecEngine:

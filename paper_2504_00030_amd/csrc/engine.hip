@@ -40,6 +40,9 @@ struct ModelRT {
     bool mfma_ok = false;
     int Rmax = 0;
     size_t gemm_ws_bytes = 0;
+    bool q8 = false;                                   // projection matrices and LM head are 8-bit
+    std::vector<float *> sc_qkv, sc_wo, sc_gu, sc_wd;  // their scales in packed row order (null entries otherwise)
+    float *sc_lm = nullptr;
     float *x = nullptr, *xg = nullptr, *ssq = nullptr, *row_scale = nullptr, *gemm_ws = nullptr, *q = nullptr, *ao = nullptr, *act = nullptr;
     uint16_t *xgb = nullptr, *qb = nullptr, *aob = nullptr, *actb = nullptr;
     int32_t *row_pos = nullptr, *row_seq = nullptr;
@@ -152,13 +155,18 @@ int check_shape(spec_ctx *c, const spec_shape &s, const char *who) {
         return bad("non-positive dimension");
     if (s.n_q_heads % s.n_kv_heads) return bad("n_q_heads not a multiple of n_kv_heads");
     if (s.head_dim % 8) return bad("head_dim must be a multiple of 8");
-    if (s.dtype != SPEC_F32 && s.dtype != SPEC_BF16) return bad("unknown dtype");
-    const int vec = s.dtype == SPEC_BF16 ? 8 : 4;
+    if (s.dtype != SPEC_F32 && s.dtype != SPEC_BF16 && s.dtype != SPEC_Q8) return bad("unknown dtype");
+    if (s.dtype == SPEC_Q8) {
+        if (s.d_model % 64 || s.d_ffn % 64 || (s.n_q_heads * s.head_dim) % 64 || s.vocab % 16 || (s.head_dim / 2) % 8)
+            return bad("8-bit weights need d_model, n_q_heads * head_dim, d_ffn multiples of 64, vocab of 16, head_dim of 16");
+        if (c->cfg.gemv_path == SPEC_PATH_WAVEDOT) return bad("8-bit weights run on the matrix-core kernels only");
+    }
+    const int vec = s.dtype == SPEC_F32 ? 4 : 8;
     if (s.d_model % vec || s.d_ffn % vec || (s.n_q_heads * s.head_dim) % vec) return bad("row length not 16-byte aligned");
     if (s.d_ffn % 2) return bad("d_ffn must be even");
     if (!(s.rms_eps > 0.f) || !(s.rope_theta > 0.f)) return bad("bad rms_eps / rope_theta");
     for (int R = 1; R <= 4; ++R) {
-        const int cols = gemv_wavedot_tile_cols(EPI_RESID, s.d_model, s.d_ffn, R, s.dtype);
+        const int cols = gemv_wavedot_tile_cols(EPI_RESID, s.d_model, s.d_ffn, R, s.dtype == SPEC_F32 ? SPEC_F32 : SPEC_BF16);
         if ((s.d_model + cols - 1) / cols > SSQ_STRIDE) return bad("d_model too large");
     }
     return SPEC_OK;
@@ -177,12 +185,25 @@ int check_weights(spec_ctx *c, const spec_shape &s, const spec_weights *w, const
             if (reinterpret_cast<uintptr_t>(p) % 16) return bad("weight not 16-byte aligned");
         }
     }
+    if (s.dtype == SPEC_Q8) {
+        if (!w->wq_scale || !w->wk_scale || !w->wv_scale || !w->wo_scale || !w->w_gate_scale || !w->w_up_scale ||
+            !w->w_down_scale || !w->lm_head_scale)
+            return bad("8-bit weights without scales");
+        for (int l = 0; l < s.n_layers; ++l) {
+            const void *ps[] = {w->wq_scale[l], w->wk_scale[l], w->wv_scale[l], w->wo_scale[l], w->w_gate_scale[l],
+                                w->w_up_scale[l], w->w_down_scale[l]};
+            for (const void *p : ps)
+                if (!p) return bad("null layer scale");
+        }
+        if (w->lm_head == w->tok_embed) return bad("8-bit LM head cannot alias the bf16 embedding");
+    }
     return SPEC_OK;
 }
 
 // Whether the projections of a model run on the matrix-core kernels (re-tiled bf16 weights).
 bool model_on_matrix_cores(const spec_config &g, const spec_shape &s) {
     const int d = s.d_model, qd = s.n_q_heads * s.head_dim;
+    if (s.dtype == SPEC_Q8) return true;  // check_shape admits no other 8-bit model
     return s.dtype == SPEC_BF16 && g.gemv_path != SPEC_PATH_WAVEDOT && d % 32 == 0 && qd % 32 == 0 && s.d_ffn % 32 == 0 &&
            s.vocab % 16 == 0 && (s.head_dim / 2) % 8 == 0 && d % 16 == 0;
 }
@@ -201,6 +222,8 @@ int ingest_rows(const spec_config &g, const spec_shape &s) {
 
 int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights *w, int Rmax, int logit_rows) {
     m.s = s;
+    m.q8 = s.dtype == SPEC_Q8;
+    if (m.q8) m.s.dtype = SPEC_BF16;  // from here on dtype is the storage type of embedding, norms and KV cache
     m.Rmax = Rmax;
     const int L = s.n_layers, d = s.d_model, qd = s.n_q_heads * s.head_dim;
     const hipStream_t st = c->stream;
@@ -210,13 +233,13 @@ int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights
         float *a = nullptr, *f = nullptr;
         TRY(dalloc(c, &a, d));
         TRY(dalloc(c, &f, d));
-        HIPCHK(c, launch_cast_to_f32(w->attn_norm[l], s.dtype, a, d, st));
-        HIPCHK(c, launch_cast_to_f32(w->ffn_norm[l], s.dtype, f, d, st));
+        HIPCHK(c, launch_cast_to_f32(w->attn_norm[l], m.s.dtype, a, d, st));
+        HIPCHK(c, launch_cast_to_f32(w->ffn_norm[l], m.s.dtype, f, d, st));
         m.attn_norm.push_back(a);
         m.ffn_norm.push_back(f);
     }
     TRY(dalloc(c, &m.final_norm, d));
-    HIPCHK(c, launch_cast_to_f32(w->final_norm, s.dtype, m.final_norm, d, st));
+    HIPCHK(c, launch_cast_to_f32(w->final_norm, m.s.dtype, m.final_norm, d, st));
     m.embed = w->tok_embed;
     m.lm_head = w->lm_head;
 
@@ -224,24 +247,45 @@ int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights
     const int kvd = s.n_kv_heads * s.head_dim;
     m.mfma_ok = model_on_matrix_cores(c->cfg, s);
     if (m.mfma_ok) {
-        auto retile = [&](int mode, const void *w0, const void *w1, const void *w2, int Ntot, int K, void **out) {
-            uint16_t *buf = nullptr;
-            TRY(dalloc_raw(c, &buf, (size_t)Ntot * K));
+        // 8-bit weights: the tiled copy holds N*K bytes and comes with the scales in packed row order
+        auto retile = [&](int mode, const void *w0, const void *w1, const void *w2, const void *s0, const void *s1,
+                          const void *s2, int Ntot, int K, void **out, float **scale_out) {
+            uint8_t *buf = nullptr;
+            TRY(dalloc_raw(c, &buf, (size_t)Ntot * K * (m.q8 ? 1 : 2)));
             RetileArgs ra{};
             ra.w0 = w0; ra.w1 = w1; ra.w2 = w2; ra.mode = mode; ra.Ntot = Ntot; ra.K = K;
             ra.nq = s.n_q_heads; ra.nkv = s.n_kv_heads; ra.hd = s.head_dim;
+            *scale_out = nullptr;
+            if (m.q8) {
+                float *sc = nullptr;
+                TRY(dalloc(c, &sc, (size_t)Ntot));
+                ra.q8 = 1; ra.scale_out = sc;
+                ra.s0 = reinterpret_cast<const float *>(s0); ra.s1 = reinterpret_cast<const float *>(s1);
+                ra.s2 = reinterpret_cast<const float *>(s2);
+                *scale_out = sc;
+            }
             HIPCHK(c, launch_retile(ra, buf, st));
             *out = buf;
             return (int)SPEC_OK;
         };
         for (int l = 0; l < L; ++l) {
             void *t = nullptr;
-            TRY(retile(EPI_QKV, w->wq[l], w->wk[l], w->wv[l], qd + 2 * kvd, d, &t)); m.t_qkv.push_back(t);
-            TRY(retile(EPI_PLAIN, w->wo[l], nullptr, nullptr, d, qd, &t)); m.t_wo.push_back(t);
-            TRY(retile(EPI_SWIGLU, w->w_gate[l], w->w_up[l], nullptr, 2 * s.d_ffn, d, &t)); m.t_gu.push_back(t);
-            TRY(retile(EPI_PLAIN, w->w_down[l], nullptr, nullptr, d, s.d_ffn, &t)); m.t_wd.push_back(t);
+            float *sc = nullptr;
+            const bool q = m.q8;
+            TRY(retile(EPI_QKV, w->wq[l], w->wk[l], w->wv[l], q ? w->wq_scale[l] : nullptr, q ? w->wk_scale[l] : nullptr,
+                       q ? w->wv_scale[l] : nullptr, qd + 2 * kvd, d, &t, &sc));
+            m.t_qkv.push_back(t); m.sc_qkv.push_back(sc);
+            TRY(retile(EPI_PLAIN, w->wo[l], nullptr, nullptr, q ? w->wo_scale[l] : nullptr, nullptr, nullptr, d, qd, &t, &sc));
+            m.t_wo.push_back(t); m.sc_wo.push_back(sc);
+            TRY(retile(EPI_SWIGLU, w->w_gate[l], w->w_up[l], nullptr, q ? w->w_gate_scale[l] : nullptr,
+                       q ? w->w_up_scale[l] : nullptr, nullptr, 2 * s.d_ffn, d, &t, &sc));
+            m.t_gu.push_back(t); m.sc_gu.push_back(sc);
+            TRY(retile(EPI_PLAIN, w->w_down[l], nullptr, nullptr, q ? w->w_down_scale[l] : nullptr, nullptr, nullptr, d, s.d_ffn,
+                       &t, &sc));
+            m.t_wd.push_back(t); m.sc_wd.push_back(sc);
         }
-        TRY(retile(EPI_PLAIN, w->lm_head, nullptr, nullptr, s.vocab, d, &m.t_lm));
+        TRY(retile(EPI_PLAIN, w->lm_head, nullptr, nullptr, m.q8 ? w->lm_head_scale : nullptr, nullptr, nullptr, s.vocab, d,
+                   &m.t_lm, &m.sc_lm));
     }
 
     const size_t R = (size_t)Rmax;
@@ -269,7 +313,7 @@ int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights
     const int PT = c->cfg.page_tokens;
     m.pages_per_seq = (c->cfg.max_seq + PT - 1) / PT;
     m.n_pages = m.pages_per_seq * c->cfg.batch;
-    const size_t esz = s.dtype == SPEC_BF16 ? 2 : 4;
+    const size_t esz = m.s.dtype == SPEC_BF16 ? 2 : 4;
     const size_t pool = (size_t)m.n_pages * s.n_kv_heads * PT * s.head_dim * esz;
     for (int l = 0; l < L; ++l) {
         uint8_t *k = nullptr, *v = nullptr;
@@ -379,7 +423,7 @@ int launch_proj(spec_ctx *c, ModelRT &m, GemvArgs a, int epi, const void *tiled,
     if (dense && a.R <= 128) {
         const double per = a.R <= 32 ? 1.6e-8 : (a.R <= 64 ? 1.8e-8 : 2.8e-8);
         const double stream_us = std::max(5.0, per * Ntot * (double)a.K * a.R);
-        dense = gemm_mfma_estimate_us(Ntot, a.K, a.R, m.gemm_ws_bytes) < stream_us;
+        dense = gemm_mfma_estimate_us(Ntot, a.K, a.R, m.gemm_ws_bytes, m.q8) < stream_us;
     }
     if (dense) {
         // statistics slots and softmax partials are per 16-row group of W
@@ -394,7 +438,7 @@ int launch_proj(spec_ctx *c, ModelRT &m, GemvArgs a, int epi, const void *tiled,
     }
     if (use_mfma(c, m, a.R)) {
         a.w0 = tiled; a.w1 = a.w2 = nullptr;
-        const int ng = gemv_mfma_groups_per_wg(epi, Ntot, a.K, a.R, 0);
+        const int ng = gemv_mfma_groups_per_wg(epi, Ntot, a.K, a.R, 0, m.q8);
         const int nb = (Ntot / 16 + ng - 1) / ng;
         if (epi == EPI_LOGITS) a.n_tiles = nb;
         if (blocks) *blocks = nb;
@@ -461,6 +505,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             a.y = m.q; a.yb = m.qb; a.yb_lo = qb_lo; a.nq = s.n_q_heads; a.nkv = s.n_kv_heads; a.hd = s.head_dim;
             a.rope_cos = m.rope_cos; a.rope_sin = m.rope_sin; a.row_pos = m.row_pos; a.row_seq = m.row_seq;
             a.kv = kv_of(c, m, l); a.kv_dtype = s.dtype;
+            a.wscale = tiled ? m.sc_qkv[l] : nullptr;
             TRY(launch_proj(c, m, a, EPI_QKV, tiled ? m.t_qkv[l] : nullptr, qd + 2 * kvd, nullptr, nullptr));
         }
         {
@@ -482,6 +527,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             GemvArgs a = base(qd, m.ao, m.aob, aob_lo);
             a.w0 = m.wo[l]; a.n0 = d;
             a.xres = m.x; a.g_next = m.ffn_norm[l]; a.xg = m.xg; a.xgb = m.xgb; a.xgb_lo = xgb_lo; a.ssq_out = m.ssq;
+            a.wscale = tiled ? m.sc_wo[l] : nullptr;
             TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wo[l] : nullptr, d, &slots, nullptr));
         }
         {   // gate / up projections + SwiGLU
@@ -489,6 +535,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             a.w0 = m.wg[l]; a.w1 = m.wu[l]; a.n0 = ffn;
             a.ssq_in = m.ssq; a.ssq_in_slots = slots;
             a.y = m.act; a.yb = m.actb; a.yb_lo = actb_lo;
+            a.wscale = tiled ? m.sc_gu[l] : nullptr;
             TRY(launch_proj(c, m, a, EPI_SWIGLU, tiled ? m.t_gu[l] : nullptr, 2 * ffn, nullptr, nullptr));
         }
         {   // down projection + residual
@@ -496,6 +543,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             a.w0 = m.wd[l]; a.n0 = d;
             a.xres = m.x; a.g_next = (l + 1 < s.n_layers) ? m.attn_norm[l + 1] : m.final_norm;
             a.xg = m.xg; a.xgb = m.xgb; a.xgb_lo = xgb_lo; a.ssq_out = m.ssq;
+            a.wscale = tiled ? m.sc_wd[l] : nullptr;
             TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wd[l] : nullptr, d, &slots, nullptr));
         }
     }
@@ -508,6 +556,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
         a.y = m.logits; a.y_mul = lp.y_mul; a.y_add = lp.y_add; a.y_stride = s.vocab;
         a.pm = m.pm; a.ps = m.ps; a.pa = m.pa; a.inv_t = c->scfg.inv_t;
         int nb = 0, tile = 0;
+        a.wscale = tiled ? m.sc_lm : nullptr;
         TRY(launch_proj(c, m, a, EPI_LOGITS, tiled ? m.t_lm : nullptr, s.vocab, &nb, &tile));
         *lp.tile = tile;
         *lp.ntiles = nb;

@@ -249,6 +249,82 @@ def test_long_prompts_through_the_ingestion_kernels(pair, batch, prompt_len):
     assert c.max_logit_err <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("N,K,R", [(16, 64, 1), (48, 128, 5), (272, 192, 9), (4096, 4096, 3), (4096, 4096, 12), (2048, 2048, 8),
+                                   (2048, 8192, 2), (4096, 14336, 7), (6144, 4096, 17), (528, 2048, 40), (1024, 1024, 100),
+                                   (4096, 4096, 128), (1024, 512, 300), (28672, 4096, 16)])
+def test_q8_kernels_match_fp64_matmul(N, K, R):
+    # 8-bit weights: the persistent and the generic streaming kernel (K = 14336, more than 16 rows, K off 1024) and
+    # the dense kernel in both block shapes, automatic and with K shared out, against (scale * q) @ x in fp64
+    pk = _pk()
+    g = torch.Generator().manual_seed(N * 3 + K + R)
+    q, sc = synth.quantize_rows(torch.randn(N, K, generator=g) * 0.02)
+    x = torch.randn(R, K, generator=g)
+    want = (x.double() @ (sc.double()[:, None] * q.double()).t()).numpy()
+    qg, scg, xg = q.cuda(), sc.cuda(), x.cuda()
+    wt = torch.empty_like(qg)
+    pk.k_retile_q8(qg, wt)
+    tol = 2e-6 * np.sqrt(K) * np.abs(want).max() + 1e-7
+    ws = torch.empty(8 * R * N, device="cuda")
+    outs = []
+    if R <= 128:
+        hi = xg.to(torch.bfloat16)
+        xb = torch.stack([hi, (xg - hi.float()).to(torch.bfloat16)]).contiguous()
+        y = torch.full((R, N), float("nan"), device="cuda")
+        pk.k_gemv_tiled_q8(wt, scg, N, K, xb[0], y, x_lo=xb[1])
+        outs.append(("streaming", y))
+    for cfg in (0, 404, 408, 2404):
+        if cfg == 2404 and K // 64 < 2:
+            continue
+        y = torch.full((R, N), float("nan"), device="cuda")
+        pk.k_gemm_tiled_q8(wt, scg, N, K, xg, y, cfg, workspace=ws)
+        outs.append((f"dense {cfg}", y))
+    torch.cuda.synchronize()
+    for name, y in outs:
+        got = y.cpu().numpy()
+        assert np.isfinite(got).all(), name
+        assert np.abs(got - want).max() <= tol, name
+
+
+@pytest.mark.parametrize("pair,batch,temperature,prompt_len", [("small-q8", 1, 1.0, None), ("small-q8", 1, 0.0, None),
+                                                               ("small-q8-hd128", 2, 1.0, None), ("small-q8", 1, 1.0, 300),
+                                                               ("small-q8", 24, 1.0, 20)])
+def test_small_q8_pair_end_to_end(pair, batch, temperature, prompt_len):
+    # both models with 8-bit projection matrices and LM head (bf16 embedding, norms and KV cache): decode on the
+    # streaming kernels, a 300-token prompt and a 24-sequence batch on the dense ones; the oracle runs on the fp64
+    # matrices scale * q
+    cfg = synth.pair(pair)
+    c, toks, trace = _run_pair(cfg, controller="gammatune", temperature=temperature, seed=4, batch=batch, norm_jitter=0.05,
+                               prompt_len=prompt_len, n_generate=24 if batch > 1 else None)
+    _assert_clean(c, full_coverage=False)
+    assert c.max_logit_err <= TOL["q8"]
+
+
+def test_8b_q8_pair_at_reduced_depth():
+    """The 8-bit 8B-shaped pair at full width, two target layers and one draft layer deep, in the benchmark's launch
+    configuration: every 8-bit kernel at its real shape (K = 14336 on the generic kernel, the rest persistent)."""
+    from oracle import model as om
+    pk = _pk()
+    cfg = synth.shrink(synth.pair("8b-q8"), 2, 1)
+    Wt, Wd = synth.make_pair_weights(cfg, 0, device="cuda")
+    torch.cuda.synchronize()
+    widen = lambda W: {k: ([om.as_f64(a) for a in v] if isinstance(v, list) else om.as_f64(v))
+                       for k, v in synth.to_numpy_weights(W).items()}
+    Wt_np, Wd_np = widen(Wt), widen(Wd)
+    prompts = synth.make_prompts(1, 200, cfg.target.vocab, 7)
+    alpha = synth.alpha_piecewise(64, 8)
+    tau = float(np.float32(0.4))
+    eng = pk.SpecEngine(cfg.target, Wt, cfg.draft, Wd, batch=1, max_seq=1024 + 512 + 2 * 16 + 8, gamma_max=cfg.gamma_max,
+                        temperature=0.7, seed=0, accept_mode=pk.ACCEPT_FORCED, use_graphs=True)
+    eng.set_forced_alpha(alpha)
+    eng.set_early_stop(tau)
+    c = run_lockstep(eng, cfg, Wt_np, Wd_np, prompts, 24, controller="gammatune", temperature=0.7, seed=0,
+                     accept_mode=1, alpha=alpha, tau=tau)
+    eng.close()
+    _assert_clean(c, full_coverage=False, min_coverage=0.7)
+    assert c.steps_total >= 8
+    assert c.max_logit_err <= TOL["q8"]
+
+
 def test_small_bf16_pair_head_sizes_batch2_gamma16():
     # 30-row last prefill chunk with K = 128 on the draft: the shape whose matrix instructions once ran
     # under an empty execution mask (non-finite logits, then an out-of-range argmax index)
