@@ -37,7 +37,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--pair", default="8b", choices=["tiny", "1b", "7b", "8b"])
+    ap.add_argument("--pair", default="8b", choices=["tiny", "1b", "7b", "8b", "8b-q8"])
     ap.add_argument("--alpha", default="piecewise", help="piecewise | a constant such as 0.6")
     ap.add_argument("--controller", default="gammatune+", choices=["gammatune", "gammatune+", "fixed"])
     ap.add_argument("--gamma0", type=int, default=4)
@@ -100,7 +100,7 @@ def cpu_baseline(cfg, Wt, Wd, tokens_per_step, mean_gamma):
 
     def oshape(ms, L):
         return om.Shape(L, ms.d_model, ms.n_q_heads, ms.n_kv_heads, ms.head_dim, ms.d_ffn, ms.vocab, ms.rope_theta,
-                        ms.rms_eps, ms.dtype == "bf16")
+                        ms.rms_eps, ms.dtype in ("bf16", "q8"))
 
     def host(W, L):
         return synth.to_numpy_weights({k: (v[:L] if isinstance(v, list) else v) for k, v in W.items()})
@@ -279,7 +279,7 @@ def main():
         pk.k_copy(dst, src)
         torch.cuda.synchronize()
         del src, dst
-        bytes_per_launch = 2 * cfg.target.d_ffn * cfg.target.d_model * (2 if cfg.target.dtype == "bf16" else 4)
+        bytes_per_launch = 2 * cfg.target.d_ffn * cfg.target.d_model * {"bf16": 2, "q8": 1}.get(cfg.target.dtype, 4)
         avg_ms = ms / max(n_launch, 1)
         achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -305,9 +305,9 @@ def main():
         e3.close()
         m = cfg.target
         qd, kvd = m.n_q_heads * m.head_dim, m.n_kv_heads * m.head_dim
-        esz = 2 if m.dtype == "bf16" else 4
+        esz = {"bf16": 2, "q8": 1}.get(m.dtype, 4)
         w_bytes = (m.n_layers * (m.d_model * (qd + 2 * kvd) + qd * m.d_model + 3 * m.d_model * m.d_ffn) + m.vocab * m.d_model) * esz
-        kv_bytes = m.n_layers * 2 * kvd * (n_prompt + n_pass) * esz  # context at the middle of the leg, roughly
+        kv_bytes = m.n_layers * 2 * kvd * (n_prompt + n_pass) * (4 if m.dtype == "fp32" else 2)  # context at the middle of the leg, roughly
         ms = 1e3 * t_ver / n_pass
         gbs = (w_bytes + kv_bytes) / (ms * 1e-3) / 1e9
         verify_pass = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
@@ -326,12 +326,14 @@ def main():
                    else f"generated tokens/s ({args.pair} pair, bs{B})"),
         "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": 1e3 * total / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": cfg.target.dtype, "data": "synthetic",
+        "dtype": "bf16" if cfg.target.dtype == "q8" else cfg.target.dtype, "data": "synthetic",
         "config": {
             "workload": (f"{args.pair}: target {cfg.target.n_layers}L d{cfg.target.d_model} ffn{cfg.target.d_ffn} "
                          f"V{cfg.target.vocab}, draft {cfg.draft.n_layers}L d{cfg.draft.d_model}; batch {B}, prompt {n_prompt}, "
                          f"generate {n_gen}; {args.controller} gamma in [1,{cfg.gamma_max}] gamma0 {args.gamma0}, "
-                         f"T={args.temperature}, forced alpha {args.alpha}, tau {tau}; seeded random-init weights"),
+                         f"T={args.temperature}, forced alpha {args.alpha}, tau {tau}; seeded random-init weights"
+                         + ("; projection matrices and LM head int8 with per-row scales, turned into bf16 in registers"
+                            if cfg.target.dtype == "q8" else "")),
             "step": f"one generation of {n_gen} tokens (prefill excluded)",
             "graphs": not args.no_graphs, "spec_steps": stats["spec_steps"], "tokens_per_spec_step": tokens_per_step,
             "mean_gamma": mean_gamma, "mean_accepted": stats["accepted"] / seq_steps,
