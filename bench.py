@@ -134,7 +134,7 @@ def cpu_baseline(cfg, Wt, Wd, tokens_per_step, mean_gamma):
 
 
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "gemv_gate_up_8b_pmc.json")
-KERNEL_SOURCES = ["gemv_mfma.hip", "epilogue.hpp", "common.hpp", "kv.hpp"]  # the files that hold the kernel's code
+KERNEL_SOURCES = ["gemv_mfma.hip", "epilogue.hpp", "common.hpp", "kv.hpp", "q8.hpp"]  # the files that hold the kernel's code
 COPY_BYTES = 1 << 30
 
 
