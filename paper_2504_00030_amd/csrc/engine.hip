@@ -1,7 +1,9 @@
-// Host engine behind the C ABI of include/spec.h: owns the paged KV caches, the activation and
-// logits buffers and the HIP graphs (one per draft pass index, one per verification length), and strings the kernels into the three phases of a
-// speculative step (Background section): gamma draft decode steps, one target verification pass
-// over gamma+1 rows, and the accept / resample step.
+// Host engine behind the C ABI of include/spec.h: owns the paged KV caches, the re-tiled weights (16-bit, or
+// 8-bit with per-row scales), the activation and logits buffers and the HIP graphs (one per draft pass index,
+// one per verification length), and strings the kernels into the three phases of a speculative step (Background
+// section): gamma draft decode steps, one target verification pass over gamma+1 rows, and the accept / resample
+// step.  Per projection it picks the weight-streaming or the dense-contraction kernel from measured time
+// estimates (launch_proj).
 #include "spec.h"
 #include "gammatune.h"
 

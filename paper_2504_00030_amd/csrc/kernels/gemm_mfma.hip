@@ -12,13 +12,14 @@
 // Both pass through registers on their way to LDS: the compiler then counts every load exactly and waits for
 // the oldest ones only.  (A direct global-to-LDS copy of the W tiles saves the registers, but the compiler
 // drains every outstanding load before any LDS access that might alias such a copy, and with it the
-// prefetch; measured, that cost more than half of the kernel's time.)  Loads run one (wide block) or two
-// (narrow block) iterations ahead of the matrix instructions, two workgroups share a compute unit, and the
+// prefetch; measured, that cost more than half of the kernel's time.)  Loads run two iterations ahead of the
+// matrix instructions (two sets of staging registers), two workgroups share a compute unit, and the
 // block index is mapped so that the workgroups an XCD runs at the same time share their W block (one L2 per
 // XCD).  The epilogues are the decode kernels' own arithmetic (RoPE + KV write, residual + next-norm
 // statistics, SwiGLU, logits + softmax partials): each wave passes its 32 WM x 32 result tiles through LDS, two
 // 16-row groups of W at a time.  A projection with too few blocks to fill the chip shares K out over several
-// workgroups per block; gemm_finish_k sums their partial results and applies the epilogue.
+// workgroups per block; gemm_finish_k sums their partial results and applies the epilogue.  8-bit weights
+// (q8.hpp) enter as half tiles that are turned into bf16 on the way into LDS.
 #include <hip/hip_ext.h>
 
 #include <algorithm>

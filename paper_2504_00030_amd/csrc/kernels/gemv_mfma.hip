@@ -1,5 +1,5 @@
-// Weight-streaming projections on the matrix cores, 1..128 rows of x (draft decode, the verification
-// pass of a speculative step over gamma+1 rows per sequence, and prompt ingestion).
+// Weight-streaming projections on the matrix cores, 1..128 rows of x (draft decode and the verification
+// pass of a speculative step over gamma+1 rows per sequence).
 //
 // Weights are read from a re-tiled copy: 16-row groups, each a contiguous run of 1 KiB tiles
 // (16 rows x 32 k) stored lane-major, so that a wave's 16-byte-per-lane load of one tile is one
@@ -12,6 +12,9 @@
 //
 //   gemv_mfma_k     one workgroup per NG groups, any row count: x fragments re-read per workgroup
 //   gemv_persist_k  up to 16 rows: 16-wave workgroups walk the groups with the x fragments resident
+//   gemv_q8_k       8-bit weights (q8.hpp: int8 + per-row scale, bf16 in registers) at the shapes the persistent
+//                   kernel's 8-bit form does not take
+// From a few dozen rows on the dense-contraction kernel (gemm_mfma.hip) is the faster one; the host picks.
 #include <hip/hip_ext.h>
 
 #include "common.hpp"
@@ -351,7 +354,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_q8_k(const GemvArgs a) {
     constexpr int NT = NW * 64;
     constexpr int FR = MB * 256;
     constexpr int TS = 17;
-    constexpr int U = MB == 1 ? 4 : (MB == 2 ? 2 : 1);
+    constexpr int U = MB == 1 ? 8 : (MB == 2 ? 4 : (MB == 4 ? 2 : 1));  // tile loads in flight per wave
     static_assert(NW * MB <= 32, "partial tiles must fit 32 KiB of LDS");
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // scalar: see above
     int Ntot = a.n0;
