@@ -97,6 +97,47 @@ __global__ __launch_bounds__(NW * 64) void gemv_mfma_k(const GemvArgs a) {
     // first half before the weight loads and the second after the first half's matrix instructions, so that
     // they take half the registers; the weight loads (HBM) of the whole batch are in flight together.
     constexpr int UH = U >= 2 ? U / 2 : 1;
+    if constexpr (NG == 1 && MB == 1 && NW <= 8) {  // 16 waves leave 128 registers per lane: too few for two batches
+        // One group per workgroup and one row block (the K = 14336 down projection of a decode or verification
+        // pass): the registers allow two batches of weight tiles, so the next batch is requested before this one's
+        // matrix instructions and the stream does not pause for a load latency per batch.  The x fragments of the
+        // whole batch go out before those requests (waiting for a younger load would wait for them too).
+        u32x4_t bwA[U], bwB[U];
+        auto load_w = [&](u32x4_t(&bw)[U], int kt) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (kt + u < kt_end) bw[u] = __builtin_nontemporal_load(bp[0] + 64 * (kt - kt_begin + u));
+        };
+        auto batch = [&](const u32x4_t(&bw)[U], u32x4_t(&next)[U], int kt) {
+            u32x4_t aw[U], al[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                aw[u] = u32x4_t{0u, 0u, 0u, 0u};
+                al[u] = u32x4_t{0u, 0u, 0u, 0u};
+                if (kt + u < kt_end && row_ok[0]) {
+                    const u32x4_t *xp = ap[0] + 4 * (kt - kt_begin + u);
+                    aw[u] = *xp;
+                    if (two_terms) al[u] = *reinterpret_cast<const u32x4_t *>(reinterpret_cast<const uint16_t *>(xp) + a.xb_lo);
+                }
+            }
+            load_w(next, kt + U);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (kt + u < kt_end) {
+                    acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, aw[u]),
+                                                                        __builtin_bit_cast(bf16x8_t, bw[u]), acc[0][0], 0, 0, 0);
+                    if (two_terms)
+                        acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, al[u]),
+                                                                            __builtin_bit_cast(bf16x8_t, bw[u]), acc[0][0], 0, 0, 0);
+                }
+            }
+        };
+        load_w(bwA, kt_begin);
+        for (int kt = kt_begin; kt < kt_end; kt += 2 * U) {
+            batch(bwA, bwB, kt);
+            if (kt + U < kt_end) batch(bwB, bwA, kt + U);
+        }
+    } else
     for (int kt = kt_begin; kt < kt_end; kt += U) {
         u32x4_t bw[U][NG], aw[UH][MB], al[UH][MB];
         auto load_x = [&](int h) {
