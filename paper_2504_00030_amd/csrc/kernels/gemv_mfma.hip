@@ -433,6 +433,53 @@ __global__ __launch_bounds__(NW * 64) void gemv_q8_k(const GemvArgs a) {
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) acc[mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
+    if constexpr (MB == 1) {
+        // one row block: two half-size batches of tiles in registers, the next requested before this one's matrix
+        // instructions, after the x fragments of the whole batch (a younger load would make waiting for them wait
+        // for the weight tiles too)
+        constexpr int UP = U / 2;
+        u32x4_t bwA[UP], bwB[UP];
+        auto load_w = [&](u32x4_t(&bw)[UP], int kt) {
+#pragma unroll
+            for (int u = 0; u < UP; ++u)
+                if (kt + u < kt_end) bw[u] = __builtin_nontemporal_load(bp + 64 * (kt - kt_begin + u));
+        };
+        auto batch = [&](const u32x4_t(&bw)[UP], u32x4_t(&next)[UP], int kt) {
+            u32x4_t xh[UP][2], xl[UP][2];
+#pragma unroll
+            for (int u = 0; u < UP; ++u)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    xh[u][h] = u32x4_t{0u, 0u, 0u, 0u};
+                    xl[u][h] = u32x4_t{0u, 0u, 0u, 0u};
+                    if (kt + u < kt_end && row_ok[0]) {
+                        const uint16_t *xp = ap[0] + (size_t)(kt - kt_begin + u) * 64 + h * 8;
+                        xh[u][h] = *reinterpret_cast<const u32x4_t *>(xp);
+                        if (two_terms) xl[u][h] = *reinterpret_cast<const u32x4_t *>(xp + a.xb_lo);
+                    }
+                }
+            load_w(next, kt + UP);
+#pragma unroll
+            for (int u = 0; u < UP; ++u) {
+                if (kt + u < kt_end) {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const u32x4_t wb = q8_half_to_bf16(h == 0 ? q8_u32x2_t{bw[u].x, bw[u].y} : q8_u32x2_t{bw[u].z, bw[u].w});
+                        acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xh[u][h]),
+                                                                         __builtin_bit_cast(bf16x8_t, wb), acc[0], 0, 0, 0);
+                        if (two_terms)
+                            acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xl[u][h]),
+                                                                             __builtin_bit_cast(bf16x8_t, wb), acc[0], 0, 0, 0);
+                    }
+                }
+            }
+        };
+        load_w(bwA, kt_begin);
+        for (int kt = kt_begin; kt < kt_end; kt += 2 * UP) {
+            batch(bwA, bwB, kt);
+            if (kt + UP < kt_end) batch(bwB, bwA, kt + UP);
+        }
+    } else
     for (int kt = kt_begin; kt < kt_end; kt += U) {
         u32x4_t bw[U];
 #pragma unroll
