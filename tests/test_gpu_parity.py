@@ -587,6 +587,44 @@ def test_random_small_shapes(case):
     assert c.max_logit_err <= TOL[dtype]
 
 
+@pytest.mark.parametrize("case", range(8))
+def test_random_small_shapes_q8(case):
+    """The same sweep for 8-bit weight models (dimensions that its 64-k tiles need), with prompts and batches that
+    reach the dense kernels as well."""
+    rng = np.random.default_rng(2000 + case)
+    hd = int(rng.choice([32, 64, 128]))
+    n_kv = int(rng.choice([1, 2, 4]))
+    n_q = n_kv * int(rng.choice([1, 2, 4]))
+    while (n_q * hd) % 64:
+        n_q *= 2
+    d = int(rng.choice([128, 256, 384]))
+    ffn = int(rng.choice([256, 320, 512]))
+    vocab = int(rng.choice([512, 1008, 2048]))
+    target = synth.ModelShape(int(rng.integers(1, 4)), d, n_q, n_kv, hd, ffn, vocab, 10000.0, 1e-5, "q8")
+    dhd = int(rng.choice([32, 64]))
+    dq = int(rng.choice([2, 4]))
+    while (dq * dhd) % 64:
+        dq *= 2
+    draft = synth.ModelShape(int(rng.integers(1, 3)), int(rng.choice([128, 256])), dq, int(rng.choice([1, 2])), dhd,
+                             int(rng.choice([256, 384])), vocab, 10000.0, 1e-5, "q8")
+    gamma_max = int(rng.choice([4, 8, 16]))
+    batch = int(rng.choice([1, 1, 2, 3, 9, 20]))
+    if batch > 3:
+        gamma_max = 4
+    cfg = synth.PairConfig(f"random-q8-{case}", target, draft, "independent", int(rng.choice([1, 16, 63, 65, 130, 200])),
+                           int(rng.integers(10, 30)), gamma_max, batch)
+    temperature = float(rng.choice([0.0, 0.7, 1.0]))
+    forced = bool(rng.integers(0, 2))
+    alpha = synth.alpha_piecewise(256, 8) if forced else None
+    tau = float(np.float32(0.4)) if (forced and rng.integers(0, 2)) else 0.0
+    controller = str(rng.choice(["gammatune", f"fixed{int(rng.integers(1, gamma_max + 1))}"]))
+    c, toks, trace = _run_pair(cfg, controller=controller, temperature=temperature, seed=case, batch=batch,
+                               accept_mode=1 if forced else 0, alpha=alpha, tau=tau, norm_jitter=0.05,
+                               use_graphs=bool(rng.integers(0, 2)), page_tokens=int(rng.choice([8, 16, 64])))
+    _assert_clean(c, full_coverage=False, min_coverage=0.5)
+    assert c.max_logit_err <= TOL["q8"]
+
+
 def test_prompt_of_one_token_and_gamma_one():
     cfg = synth.pair("tiny")
     c, toks, _ = _run_pair(cfg, controller="fixed1", temperature=1.0, seed=8, prompt_len=1, n_generate=12)
