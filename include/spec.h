@@ -98,7 +98,7 @@ typedef struct {
 } spec_config;
 
 /* Create a context: validates shapes (both models must share `vocab`), allocates the
- * paged KV caches, activations and logits buffers, re-tiles bf16 weights for the
+ * paged KV caches, activations and logits buffers, re-tiles bf16 and 8-bit weights for the
  * matrix-core kernels, builds the rotary tables.  On failure *out is NULL. */
 int spec_init(const spec_shape *target, const spec_weights *target_w,
               const spec_shape *draft, const spec_weights *draft_w,
@@ -106,7 +106,8 @@ int spec_init(const spec_shape *target, const spec_weights *target_w,
 
 /* Load the prompts: host_tokens is host int32 [batch][n], n >= 1, every id in
  * [0, vocab).  Both models ingest tokens 0..n-2 into their KV caches (the last
- * prompt token is fed by the first step).  Resets step counter, lengths and
+ * prompt token is fed by the first step), up to 1024 rows per launch for a model on the
+ * matrix-core kernels (32 rows per sequence otherwise).  Resets step counter, lengths and
  * generated count; may be called again to start a new generation.  Synchronises. */
 int spec_prefill(spec_ctx *ctx, const int32_t *host_tokens, int32_t n);
 
