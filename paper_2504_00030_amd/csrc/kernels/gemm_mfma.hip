@@ -55,24 +55,24 @@ __device__ __forceinline__ void split4(const f32x4_t v, u32x2_t &hi, u32x2_t &lo
 
 }  // namespace
 
-constexpr int GEMM_THREADS = 256;
 constexpr int GEMM_TS = 36;                      // row stride (floats) of a wave's result tile in the epilogue
 
 // Loads run two iterations ahead in both forms (two sets of staging registers).  DEEP: the fragments of the next
 // iteration are read while this one multiplies (double-buffered in registers as well); otherwise they are read where
 // they are used, which fits the registers of the wide block.
-template <int WM, int WN, bool DEEP>
+template <int WM, int WN, bool DEEP, int MW>
 struct GemmShape {
-    static constexpr int BMB = 2 * WM;              // 16-row blocks of x per workgroup
+    static constexpr int NWAVES = 2 * MW;           // MW x 2 waves, each 16 WM rows of x by 16 WN rows of W
+    static constexpr int THREADS = 64 * NWAVES;
+    static constexpr int BMB = MW * WM;             // 16-row blocks of x per workgroup
     static constexpr int BNG = 2 * WN;              // 16-row groups of W per workgroup
     static constexpr int XS = BMB * 2 * 1024;       // bytes of the x fragments of a stage (hi and lo)
     static constexpr int WS = BNG * 1024;           // bytes of the W tiles of a stage
-    static constexpr int XI = BMB / 2;              // x loads per thread and stage
-    static constexpr int WI = BNG / 4;              // W loads per thread and stage
+    static constexpr int XI = 2 * BMB / NWAVES;     // x loads per thread and stage
+    static constexpr int WI = BNG / NWAVES;         // W loads per thread and stage
     static constexpr int RING = 2 * (XS + WS);      // two stages alternate
-    static constexpr int EPI_BYTES = 4 * (WM * 16 * GEMM_TS + WM * 16) * 4;  // four waves: result tile + row scales
+    static constexpr int EPI_BYTES = NWAVES * (WM * 16 * GEMM_TS + WM * 16) * 4;  // per wave: result tile + row scales
     static constexpr int LDS = RING > EPI_BYTES ? RING : EPI_BYTES;
-    static constexpr int WAVES_PER_SIMD = 2 * LDS <= 160 * 1024 ? 2 : 1;
 };
 
 // The workgroup meets once this wave's LDS traffic is done.  (__syncthreads would also drain every global
@@ -130,10 +130,12 @@ __global__ __launch_bounds__(256) void row_scale_k(const float *ssq, int slots, 
 // WQ: 1 = 8-bit weights (q8.hpp).  A k-tile of the loop is then half of a 64-k weight tile: the lane's first or
 // second eight bytes, turned into bf16 on the way into LDS, and the x fragments gather the matching k sets (chunk c
 // of k-tile t holds k = 64 (t / 2) + 16 c + 8 (t % 2) .. + 8).  The column scales multiply the result tile.
-template <int EPI, int WM, int WN, bool DEEP, int WQ>
-__global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_SIMD)) void gemm_mfma_k(
+// MW: wave rows of the workgroup (2: four waves, blocks of 32 WM rows of x; 4: eight waves, 64 WM rows, one
+// workgroup per compute unit - a third fewer bytes fetched per matrix instruction than the wide four-wave block).
+template <int EPI, int WM, int WN, bool DEEP, int WQ, int MW>
+__global__ __launch_bounds__((GemmShape<WM, WN, DEEP, MW>::THREADS), 2) void gemm_mfma_k(
     const GemvArgs a, const int m_blocks, const int ksplit, const int64_t split_stride) {
-    using S = GemmShape<WM, WN, DEEP>;
+    using S = GemmShape<WM, WN, DEEP, MW>;
     constexpr int XI = S::XI;
     if (a.active != nullptr && *a.active == 0) return;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -160,11 +162,11 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
     char *const ws = smem + 2 * S::XS;   // [2][WS]
 
     // ---- load plan -------------------------------------------------------------------------------------
-    // W: wave w moves the tiles w, w + 4, ... of the stage
-    const char *wsrc[S::BNG / 4];
+    // W: wave w moves the tiles w, w + NWAVES, ... of the stage
+    const char *wsrc[S::WI];
 #pragma unroll
-    for (int i = 0; i < S::BNG / 4; ++i) {
-        const int g = min(g0 + wave + 4 * i, n_groups - 1);
+    for (int i = 0; i < S::WI; ++i) {
+        const int g = min(g0 + wave + S::NWAVES * i, n_groups - 1);
         // 16-bit: tile (g, kt) of 1 KiB; 8-bit: k-tile kt is half kt % 2 of tile (g, kt / 2) (the host keeps kt0 even)
         wsrc[i] = reinterpret_cast<const char *>(a.w0) + (WQ ? ((size_t)g * (KTall >> 1) + (kt0 >> 1)) * 1024 : ((size_t)g * KTall + kt0) * 1024) +
                   lane * 16;
@@ -218,7 +220,7 @@ __global__ __launch_bounds__(GEMM_THREADS, (GemmShape<WM, WN, DEEP>::WAVES_PER_S
         }
 #pragma unroll
         for (int i = 0; i < S::WI; ++i)
-            *reinterpret_cast<u32x4_t *>(wslot + (wave + 4 * i) * 1024 + lane * 16) =
+            *reinterpret_cast<u32x4_t *>(wslot + (wave + S::NWAVES * i) * 1024 + lane * 16) =
                 WQ ? q8_half_to_bf16(q8_u32x2_t{r.w[i].x, r.w[i].y}) : r.w[i];
     };
     auto read = [&](int stage, GemmFrags<WM, WN> &f) {
@@ -424,25 +426,25 @@ __global__ __launch_bounds__(256) void gemm_finish_k(const GemvArgs a, const flo
     }
 }
 
-template <int EPI, int WM, int WN, bool DEEP, int WQ>
+template <int EPI, int WM, int WN, bool DEEP, int WQ, int MW = 2>
 static hipError_t launch_gemm_one(const GemvArgs &a, int Ntot, int ksplit, int64_t split_stride, hipEvent_t ev0, hipEvent_t ev1,
                                   hipStream_t s) {
-    using S = GemmShape<WM, WN, DEEP>;
+    using S = GemmShape<WM, WN, DEEP, MW>;
     const int n_blocks = (Ntot / 16 + S::BNG - 1) / S::BNG;
     const int m_blocks = (a.R + S::BMB * 16 - 1) / (S::BMB * 16);
     const int grid = ((n_blocks + 7) / 8) * 8 * m_blocks * ksplit;
     static bool attr_set = false;  // per instantiation
     if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_mfma_k<EPI, WM, WN, DEEP, WQ>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_mfma_k<EPI, WM, WN, DEEP, WQ, MW>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     if (ev0 != nullptr)
-        hipExtLaunchKernelGGL((gemm_mfma_k<EPI, WM, WN, DEEP, WQ>), dim3(grid), dim3(GEMM_THREADS), S::LDS, s, ev0, ev1, 0, a, m_blocks,
+        hipExtLaunchKernelGGL((gemm_mfma_k<EPI, WM, WN, DEEP, WQ, MW>), dim3(grid), dim3(S::THREADS), S::LDS, s, ev0, ev1, 0, a, m_blocks,
                               ksplit, split_stride);
     else
-        hipLaunchKernelGGL((gemm_mfma_k<EPI, WM, WN, DEEP, WQ>), dim3(grid), dim3(GEMM_THREADS), S::LDS, s, a, m_blocks, ksplit,
+        hipLaunchKernelGGL((gemm_mfma_k<EPI, WM, WN, DEEP, WQ, MW>), dim3(grid), dim3(S::THREADS), S::LDS, s, a, m_blocks, ksplit,
                            split_stride);
     return hipGetLastError();
 }
@@ -468,8 +470,10 @@ static hipError_t launch_gemm_cfg(const GemvArgs &a, int Ntot, int forced, float
     if (cfg == 0) {
         // both shapes are bound by what a compute unit can fetch from L2 per matrix instruction: the wide block
         // needs a third less, the narrow one fills the chip when the wide one would leave compute units idle
+        // (measured: eight waves on 256 x 256 blocks win by 5-8 % once they fill the chip)
         const int m_blocks = (a.R + 127) / 128;
-        cfg = ((Ntot + 255) / 256) * m_blocks > 256 ? 408 : 404;
+        if (((Ntot + 255) / 256) * ((a.R + 255) / 256) >= 256) cfg = 808;
+        else cfg = ((Ntot + 255) / 256) * m_blocks > 256 ? 408 : 404;
     }
     if (ksplit == 0) ksplit = (cfg == 404 && ws != nullptr) ? pick_ksplit(Ntot, a.K, a.R, ws_bytes, q8) : 1;
     if (ksplit > 1) {
@@ -490,6 +494,8 @@ static hipError_t launch_gemm_cfg(const GemvArgs &a, int Ntot, int forced, float
         case 408: return launch_gemm_one<EPI, 4, 8, false, 0>(a, Ntot, 1, 0, ev0, ev1, s);
         case 404: return launch_gemm_one<EPI, 4, 4, true, 0>(a, Ntot, 1, 0, ev0, ev1, s);
         case 1408: return launch_gemm_one<EPI, 4, 8, false, 1>(a, Ntot, 1, 0, ev0, ev1, s);
+        case 808: return launch_gemm_one<EPI, 4, 8, false, 0, 4>(a, Ntot, 1, 0, ev0, ev1, s);
+        case 1808: return launch_gemm_one<EPI, 4, 8, false, 1, 4>(a, Ntot, 1, 0, ev0, ev1, s);
         case 1404: return launch_gemm_one<EPI, 4, 4, true, 1>(a, Ntot, 1, 0, ev0, ev1, s);
     }
     return hipErrorInvalidValue;
