@@ -518,7 +518,9 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             t.part_m = m.part_m; t.part_l = m.part_l; t.part_o = m.part_o; t.o = m.ao; t.ob = m.aob; t.active = active;
             t.qb_lo = qb_lo; t.ob_lo = aob_lo;
             if (attention_uses_mfma(t, s.head_dim)) {
-                const int chunk = attention_mfma_chunk(c->cfg.max_seq, c->cfg.attn_chunk);
+                // long row runs (prompt ingestion) take the largest chunk: their cost is the traffic of the chunk
+                // partials, one per (row, head, chunk), not the latency of a chunk
+                const int chunk = attention_mfma_chunk(c->cfg.max_seq, plan.rps >= 64 && c->cfg.attn_chunk == 0 ? 256 : c->cfg.attn_chunk);
                 const int nch = (c->cfg.max_seq + chunk - 1) / chunk;
                 if (nch <= ATT_NC_MAX) { t.chunk = chunk; t.n_chunks = nch; }
                 else t.qb = nullptr;  // capacity beyond the merge of the matrix-core kernel: plain kernel
