@@ -140,6 +140,30 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
     // the sequence length: the loads then depend on nothing but the block table and start at once; whatever finite
     // values lie beyond the last visible position meet a zero probability.
     const int cap = a.kv.pages_per_seq * a.kv.page_tokens;
+    // What depends on the rows alone goes out first: the sequence's last position and the first tile's queries are
+    // older loads than the K / V fragments below, so waiting for them does not wait for the cache, and they are in
+    // flight while the block table is looked up.
+    const bool has_qlo = a.qb_lo != 0;
+    const int QT = (QN + 15) / 16, TPW = (QT + QS - 1) / QS;
+    const int last_pos_l = a.row_pos[r_first + a.rps - 1];
+    struct QTile { int qpos; u32x4_t qf[ES], ql[ES]; };
+    auto load_q = [&](int qt, QTile &q) {
+        // query handled by this lane in the score product (column l16 of S^T); q enters as hi + lo bf16 terms
+        const int qi = min(qt * 16 + l16, QN - 1);
+        const int gq = qi / a.rps, i = qi % a.rps;
+        const int r = r_first + i, h = kvh * G + gq;
+        q.qpos = a.row_pos[r];
+        const bf16_t *qp = a.qb + ((size_t)r * a.nq + h) * HD + 8 * g;
+#pragma unroll
+        for (int s = 0; s < ES; ++s) {
+            q.qf[s] = *reinterpret_cast<const u32x4_t *>(qp + 32 * s);
+            q.ql[s] = has_qlo ? *reinterpret_cast<const u32x4_t *>(qp + a.qb_lo + 32 * s) : u32x4_t{0u, 0u, 0u, 0u};
+        }
+    };
+    // (with chunks beyond 128 positions the K / V fragments leave no registers for queries held ahead)
+    constexpr bool AHEAD = SPW <= 2;
+    QTile qn;
+    if constexpr (AHEAD) load_q(qs * TPW, qn);
     u32x4_t kf[SPW][ES];
     u32x2_t vf[SPW][ET];
 #pragma unroll
@@ -155,29 +179,21 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
         for (int et = 0; et < ET; ++et)
             vf[sl][et] = *reinterpret_cast<const u32x2_t *>(vp + vb + (size_t)(16 * et) * a.kv.page_tokens);
     }
-    const int last_pos = __builtin_amdgcn_readfirstlane(a.row_pos[r_first + a.rps - 1]);
+    const int last_pos = __builtin_amdgcn_readfirstlane(last_pos_l);
     if (t0 > last_pos) return;
     const int n_live = last_pos / CT + 1;
 
-    const bool has_qlo = a.qb_lo != 0;
-    const int QT = (QN + 15) / 16, TPW = (QT + QS - 1) / QS;
-    for (int qt = qs * TPW; qt < min(QT, (qs + 1) * TPW); ++qt) {
-        // query handled by this lane in the score product (column l16 of S^T); q enters as hi + lo bf16 terms
-        const int qi = min(qt * 16 + l16, QN - 1);
-        const int gq = qi / a.rps, i = qi % a.rps;
-        const int r = r_first + i, h = kvh * G + gq;
-        const int qpos = a.row_pos[r];
+    const int qt_end = min(QT, (qs + 1) * TPW);
+    for (int qt = qs * TPW; qt < qt_end; ++qt) {
+        // this tile's queries were requested a tile ago and the next tile's go out now, or every tile loads its own
+        if constexpr (!AHEAD) load_q(qt, qn);
+        const QTile qc = qn;
+        if (AHEAD && qt + 1 < qt_end) load_q(qt + 1, qn);
+        const int qpos = qc.qpos;
         // a tile none of whose queries sees this chunk leaves no partial: the merge never reads one there
         if (t0 > __builtin_amdgcn_readfirstlane(wave_max(qpos))) continue;
-        u32x4_t qf[ES], ql[ES];
-        {
-            const bf16_t *qp = a.qb + ((size_t)r * a.nq + h) * HD + 8 * g;
-#pragma unroll
-            for (int s = 0; s < ES; ++s) {
-                qf[s] = *reinterpret_cast<const u32x4_t *>(qp + 32 * s);
-                ql[s] = has_qlo ? *reinterpret_cast<const u32x4_t *>(qp + a.qb_lo + 32 * s) : u32x4_t{0u, 0u, 0u, 0u};
-            }
-        }
+        const u32x4_t(&qf)[ES] = qc.qf;
+        const u32x4_t(&ql)[ES] = qc.ql;
         // scores of every slab of this wave; S[sl][v] = (position tw + 4 g + v, query l16)
         f32x4_t S[SPW];
         float m = -INFINITY;
