@@ -131,7 +131,9 @@ int spec_draft_batch(spec_ctx *ctx, const int32_t *gammas);
 /* Verify phase, asynchronous: one target forward over the gamma+1 rows
  * [last token, x_1 .. x_gamma] of every sequence, causal inside the rows, against the
  * target KV cache; produces the logits rows p_1 .. p_{gamma+1}.  `gamma` must equal the
- * (largest) gamma of the preceding spec_draft call. */
+ * (largest) gamma of the preceding spec_draft call.  After spec_draft_batch with differing
+ * gammas a bf16 / 8-bit target on the matrix-core kernels runs only the gamma_b + 1 rows each
+ * sequence planned (spec_debug_logits still returns the padded [batch][gamma + 1] layout). */
 int spec_verify(spec_ctx *ctx, int32_t gamma);
 
 /* Accept phase: runs the fused accept / resample kernels, waits for the stream, and

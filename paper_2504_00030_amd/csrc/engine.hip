@@ -42,6 +42,7 @@ struct ModelRT {
     bool mfma_ok = false;
     int Rmax = 0;
     size_t gemm_ws_bytes = 0;
+    int32_t *row_off = nullptr;                        // [batch + 1] first row of every sequence of a ragged pass
     bool q8 = false;                                   // projection matrices and LM head are 8-bit
     std::vector<float *> sc_qkv, sc_wo, sc_gu, sc_wd;  // their scales in packed row order (null entries otherwise)
     float *sc_lm = nullptr;
@@ -95,6 +96,8 @@ struct spec_ctx {
     // state machine: 0 = created, 1 = ready to draft, 2 = drafted, 3 = verified
     int phase = 0;
     int cur_gamma = 0;
+    int cur_rows = 0;      // rows of the current step's verification pass when it is ragged, else 0
+    bool ragged_ok = false;  // several sequences and a target whose attention takes ragged rows
     bool prefilled = false;
     std::map<int, hipGraphExec_t> g_draft, g_verify, g_pass;  // whole draft phase per gamma, verify per gamma, draft pass j
     std::vector<hipGraph_t> graphs;
@@ -213,11 +216,15 @@ bool model_on_matrix_cores(const spec_config &g, const spec_shape &s) {
 // Rows of one prompt-ingestion launch (all sequences together).  A model on the matrix cores whose attention
 // also runs on them ingests through the dense-contraction kernels, PREFILL_GEMM_ROWS rows at a time; otherwise
 // PREFILL_ROWS per sequence (the plain attention kernel holds at most 128 rows of a sequence).
-int ingest_rows(const spec_config &g, const spec_shape &s) {
+// Whether the attention of a model on the matrix cores runs on the matrix-core attention kernels as well.
+bool attention_on_matrix_cores(const spec_config &g, const spec_shape &s) {
     const int hd = s.head_dim;
     const int chunk = attention_mfma_chunk(g.max_seq, g.attn_chunk);
-    const bool attn_mc = g.page_tokens % 4 == 0 && (hd == 32 || hd == 64 || hd == 128) &&
-                         (g.max_seq + chunk - 1) / chunk <= ATT_NC_MAX;
+    return g.page_tokens % 4 == 0 && (hd == 32 || hd == 64 || hd == 128) && (g.max_seq + chunk - 1) / chunk <= ATT_NC_MAX;
+}
+
+int ingest_rows(const spec_config &g, const spec_shape &s) {
+    const bool attn_mc = attention_on_matrix_cores(g, s);
     if (model_on_matrix_cores(g, s) && attn_mc && s.d_model / 16 <= SSQ_STRIDE) return std::max(PREFILL_GEMM_ROWS, g.batch);
     return std::min(128, g.batch * PREFILL_ROWS);
 }
@@ -310,6 +317,7 @@ int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights
     TRY(dalloc(c, &m.actb, 2 * R * s.d_ffn));
     TRY(dalloc(c, &m.row_pos, R));
     TRY(dalloc(c, &m.row_seq, R));
+    TRY(dalloc(c, &m.row_off, (size_t)c->cfg.batch + 1));
 
     // paged KV cache: sequence-interleaved physical pages by default
     const int PT = c->cfg.page_tokens;
@@ -472,9 +480,10 @@ struct LogitsPlan {
 };
 
 // Enqueue one forward pass of model m over R = batch * plan.rps rows.
-int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, bool draft_phase) {
+// `rows_total`: rows of a ragged plan (sequence b has its planned gamma + 1 of them), else 0.
+int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, bool draft_phase, int rows_total = 0) {
     const spec_shape &s = m.s;
-    const int B = c->cfg.batch, R = B * plan.rps;
+    const int B = c->cfg.batch, R = plan.ragged ? rows_total : B * plan.rps;
     const int d = s.d_model, qd = s.n_q_heads * s.head_dim, ffn = s.d_ffn;
     const hipStream_t st = c->stream;
     const int32_t *active = (draft_phase && plan.mode == ROWS_DRAFT_NEXT) ? &c->st.ctl[1] : nullptr;
@@ -486,7 +495,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
     const int64_t RM = m.mfma_ok ? (int64_t)m.Rmax : 0;
     const int64_t xgb_lo = RM * s.d_model, qb_lo = RM * s.n_q_heads * s.head_dim, aob_lo = qb_lo, actb_lo = RM * s.d_ffn;
     e.g_next = m.attn_norm[0]; e.x = m.x; e.xg = m.xg; e.xgb = m.xgb; e.xgb_lo = xgb_lo; e.ssq_out = m.ssq; e.ssq_stride = SSQ_STRIDE;
-    e.row_pos = m.row_pos; e.row_seq = m.row_seq;
+    e.row_pos = m.row_pos; e.row_seq = m.row_seq; e.row_off = m.row_off;
     HIPCHK(c, launch_embed(e, st));
     int slots = 1;
 
@@ -512,7 +521,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
         }
         {
             AttnArgs t{};
-            t.q = m.q; t.qb = c->cfg.gemv_path == SPEC_PATH_WAVEDOT ? nullptr : m.qb; t.kv = kv_of(c, m, l); t.kv_dtype = s.dtype; t.R = R; t.rps = plan.rps; t.nq = s.n_q_heads;
+            t.q = m.q; t.qb = c->cfg.gemv_path == SPEC_PATH_WAVEDOT ? nullptr : m.qb; t.kv = kv_of(c, m, l); t.kv_dtype = s.dtype; t.R = R; t.rps = plan.rps; t.nq = s.n_q_heads; t.batch = B; t.row_off = plan.ragged ? m.row_off : nullptr;
             t.row_pos = m.row_pos; t.row_seq = m.row_seq; t.chunk = ATT_CHUNK; t.n_chunks = m.n_chunks;
             t.scale = 1.0f / std::sqrt((float)s.head_dim);
             t.part_m = m.part_m; t.part_l = m.part_l; t.part_o = m.part_o; t.o = m.ao; t.ob = m.aob; t.active = active;
@@ -621,21 +630,23 @@ int wait_draft_pass(spec_ctx *c, int n, int *active) {
     return SPEC_OK;
 }
 
-int enqueue_verify(spec_ctx *c, int gamma) {
+// `rows_total` > 0: the sequences differ in their planned gamma and the pass holds only the gamma_b + 1 rows each
+// of them planned, one sequence after the other.
+int enqueue_verify(spec_ctx *c, int gamma, int rows_total) {
     RowPlan plan{};
-    plan.mode = ROWS_VERIFY; plan.rps = gamma + 1; plan.arg = 0;
+    plan.mode = ROWS_VERIFY; plan.rps = gamma + 1; plan.arg = 0; plan.ragged = rows_total > 0;
     LogitsPlan lp{};
     lp.want = true;
-    lp.rows = c->cfg.batch * (gamma + 1);
+    lp.rows = rows_total > 0 ? rows_total : c->cfg.batch * (gamma + 1);
     lp.tile = &c->t_tile;
     lp.ntiles = &c->t_ntiles;
-    return forward(c, c->tgt, plan, lp, false);
+    return forward(c, c->tgt, plan, lp, false, rows_total);
 }
 
 int enqueue_accept(spec_ctx *c, int gamma) {
     AcceptArgs a{};
     a.st = c->st; a.cfg = c->scfg; a.gamma = gamma; a.gamma_max = c->cfg.gamma_max; a.vocab = c->tgt.s.vocab;
-    a.p_logits = c->tgt.logits; a.pm = c->tgt.pm; a.ps = c->tgt.ps; a.pa = c->tgt.pa;
+    a.p_logits = c->tgt.logits; a.row_off = c->cur_rows > 0 ? c->tgt.row_off : nullptr; a.pm = c->tgt.pm; a.ps = c->tgt.ps; a.pa = c->tgt.pa;
     a.n_tiles = c->t_ntiles; a.tile = c->t_tile;
     a.pm2 = c->tgt.pm2; a.ps2 = c->tgt.ps2; a.pa2 = c->tgt.pa2; a.n2 = (c->t_ntiles + 63) / 64;
     a.q_logits = c->drf.logits; a.q_logit = c->q_logit; a.q_max = c->q_max; a.q_sum = c->q_sum;
@@ -776,6 +787,7 @@ int spec_init(const spec_shape *t, const spec_weights *tw, const spec_shape *d, 
         return bail(rc);
     c->st.max_seq = g.max_seq;
     c->st.batch = B;
+    c->ragged_ok = B > 1 && model_on_matrix_cores(c->cfg, *t) && attention_on_matrix_cores(c->cfg, *t);
     c->h_len.assign(B, 0);
 
     void *hp = nullptr;
@@ -976,16 +988,25 @@ int spec_verify(spec_ctx *c, int32_t gamma) {
     if (!c) return SPEC_EINVAL;
     if (c->phase != 2) return fail(c, SPEC_ESTATE, "verify: expected after draft");
     if (gamma != c->cur_gamma) return fail(c, SPEC_EINVAL, "verify: gamma differs from the draft phase");
+    // sequences that planned different gammas: pack only the rows each of them planned
+    int rows_total = 0;
+    if (c->ragged_ok) {
+        int sum = 0;
+        for (int b = 0; b < c->cfg.batch; ++b) sum += c->h_gamma_plan[b] + 1;
+        if (sum < c->cfg.batch * (gamma + 1)) rows_total = sum;
+    }
+    c->cur_rows = rows_total;
     if (c->cfg.use_graphs) {
-        auto it = c->g_verify.find(gamma);
+        const int key = rows_total * 128 + gamma;  // gamma <= 64
+        auto it = c->g_verify.find(key);
         if (it == c->g_verify.end()) {
             hipGraphExec_t ex = nullptr;
-            TRY(capture(c, [&] { return enqueue_verify(c, gamma); }, &ex));
-            it = c->g_verify.emplace(gamma, ex).first;
+            TRY(capture(c, [&] { return enqueue_verify(c, gamma, rows_total); }, &ex));
+            it = c->g_verify.emplace(key, ex).first;
         }
         HIPCHK(c, hipGraphLaunch(it->second, c->stream));
     } else {
-        TRY(enqueue_verify(c, gamma));
+        TRY(enqueue_verify(c, gamma, rows_total));
     }
     c->phase = 3;
     return SPEC_OK;
@@ -1058,7 +1079,16 @@ int spec_debug_logits(spec_ctx *c, int32_t which, float *host_out, int64_t cap, 
     const int B = c->cfg.batch, V = c->tgt.s.vocab;
     const int rps = which == 0 ? c->cur_gamma : c->cur_gamma + 1;
     if (cap < (int64_t)B * rps * V) return fail(c, SPEC_EINVAL, "debug_logits: buffer too small");
-    if (which == 1) {
+    if (which == 1 && c->cur_rows > 0) {
+        // ragged pass: sequence b's gamma_b + 1 rows into its slot of the padded layout, zeros behind them
+        std::memset(host_out, 0, sizeof(float) * (size_t)B * rps * V);
+        size_t off = 0;
+        for (int b = 0; b < B; ++b) {
+            const size_t n = (size_t)c->h_gamma_plan[b] + 1;
+            HIPCHK(c, hipMemcpy(host_out + (size_t)b * rps * V, c->tgt.logits + off * V, sizeof(float) * n * V, hipMemcpyDeviceToHost));
+            off += n;
+        }
+    } else if (which == 1) {
         HIPCHK(c, hipMemcpy(host_out, c->tgt.logits, sizeof(float) * (size_t)B * rps * V, hipMemcpyDeviceToHost));
     } else {
         for (int b = 0; b < B; ++b)

@@ -120,14 +120,16 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
     constexpr int CT = 64 * SPW;
     // grid.z = sequences x query splits: with many rows per sequence (prompt ingestion) the 16-query tiles of a
     // sequence are shared out over several workgroups, each of which loads the chunk for itself
-    const int QS = gridDim.z / (a.R / a.rps);
+    const int QS = gridDim.z / a.batch;
     const int c = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z / QS, qs = blockIdx.z % QS;
     // wave index and last position are scalars, so that branches on them are scalar branches
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l16 = lane & 15, g = lane >> 4;
     const int G = a.nq / a.kv.n_kv;
-    const int QN = G * a.rps;
-    const int r_first = b * a.rps;
+    // rows of this sequence: a.rps each, or its own count when the sequences of a verification pass differ
+    const int r_first = a.row_off != nullptr ? a.row_off[b] : b * a.rps;
+    const int rps = a.row_off != nullptr ? a.row_off[b + 1] - r_first : a.rps;
+    const int QN = G * rps;
     const int t0 = c * CT;
     const bf16_t *kp = reinterpret_cast<const bf16_t *>(a.kv.k);
     const bf16_t *vp = reinterpret_cast<const bf16_t *>(a.kv.v);
@@ -145,12 +147,12 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
     // flight while the block table is looked up.
     const bool has_qlo = a.qb_lo != 0;
     const int QT = (QN + 15) / 16, TPW = (QT + QS - 1) / QS;
-    const int last_pos_l = a.row_pos[r_first + a.rps - 1];
+    const int last_pos_l = a.row_pos[r_first + rps - 1];
     struct QTile { int qpos; u32x4_t qf[ES], ql[ES]; };
     auto load_q = [&](int qt, QTile &q) {
         // query handled by this lane in the score product (column l16 of S^T); q enters as hi + lo bf16 terms
         const int qi = min(qt * 16 + l16, QN - 1);
-        const int gq = qi / a.rps, i = qi % a.rps;
+        const int gq = qi / rps, i = qi % rps;
         const int r = r_first + i, h = kvh * G + gq;
         q.qpos = a.row_pos[r];
         const bf16_t *qp = a.qb + ((size_t)r * a.nq + h) * HD + 8 * g;
@@ -266,7 +268,7 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
                 acc += f * sO[w][q][e];
                 L += f * sL[w][q];
             }
-            const int rr = r_first + qj % a.rps, hh = kvh * G + qj / a.rps;
+            const int rr = r_first + qj % rps, hh = kvh * G + qj / rps;
             if (n_live == 1) {
                 const float v = acc / L;
                 const size_t o = ((size_t)rr * a.nq + hh) * HD + e;
@@ -295,7 +297,7 @@ __global__ __launch_bounds__(256) void attn_mfma_merge_k(const AttnArgs a) {
     const int idx = blockIdx.x * 256 + threadIdx.x;
     if (idx >= a.R * a.nq * E4) return;
     const int e = (idx % E4) * 4, hh = (idx / E4) % a.nq, rr = idx / (E4 * a.nq);
-    const int b = rr / a.rps;
+    const int b = a.row_off != nullptr ? a.row_seq[rr] : rr / a.rps;
     const size_t pb = ((size_t)rr * a.nq + hh) * a.n_chunks;
     float pm[NCB], pl[NCB];
     f32x4_t po[NCB];
@@ -308,7 +310,7 @@ __global__ __launch_bounds__(256) void attn_mfma_merge_k(const AttnArgs a) {
             po[cc] = *reinterpret_cast<const f32x4_t *>(a.part_o + (pb + cc) * HD + e);
         }
     }
-    const int last_pos = a.row_pos[b * a.rps + a.rps - 1];
+    const int last_pos = a.row_pos[a.row_off != nullptr ? a.row_off[b + 1] - 1 : b * a.rps + a.rps - 1];
     if (last_pos / a.chunk == 0) return;
     const int nc = a.row_pos[rr] / a.chunk + 1;  // chunks that hold a position this row may see
     float M = -INFINITY;
@@ -375,7 +377,8 @@ static hipError_t launch_attn_mfma(const AttnArgs &a, dim3 grid, hipStream_t s) 
 // a.chunk / a.n_chunks: 64 and ceil(max_seq / 64) for the plain kernel, attention_mfma_chunk() and the
 // matching count for the matrix-core kernel.
 hipError_t launch_attention(const AttnArgs &a, int hd, hipStream_t s) {
-    const int B = a.R / a.rps;
+    const int B = a.batch;
+    if (a.row_off != nullptr && !attention_uses_mfma(a, hd)) return hipErrorInvalidValue;  // ragged rows: matrix-core kernels only
     if (attention_uses_mfma(a, hd)) {
         const int spw = a.chunk / 64;
         if (a.chunk % 64 || (spw != 1 && spw != 2 && spw != 4 && spw != 8) || a.n_chunks > ATT_NC_MAX)

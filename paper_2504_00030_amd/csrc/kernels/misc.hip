@@ -41,7 +41,19 @@ __device__ __forceinline__ int row_position(const State &st, const RowPlan &p, i
 __global__ __launch_bounds__(256) void embed_k(const EmbedArgs a) {
     if (a.plan.mode == ROWS_DRAFT_NEXT && a.st.ctl[1] == 0) return;
     const int r = blockIdx.x;
-    const int b = r / a.plan.rps, i = r % a.plan.rps;
+    int b = r / a.plan.rps, i = r % a.plan.rps;
+    if (a.plan.ragged) {
+        // sequence b owns rows off_b .. off_b + gamma_b[b]: a scan over at most 64 sequences
+        int off = 0;
+        b = 0;
+        while (b + 1 < a.st.batch && r >= off + a.st.gamma_b[b] + 1) off += a.st.gamma_b[b++] + 1;
+        i = r - off;
+        if (r == 0 && threadIdx.x == 0) {
+            int o = 0;
+            for (int s = 0; s < a.st.batch; ++s) { a.row_off[s] = o; o += a.st.gamma_b[s] + 1; }
+            a.row_off[a.st.batch] = o;
+        }
+    }
     int pos = row_position(a.st, a.plan, b, i);
     pos = min(max(pos, 0), a.st.max_seq - 1);
     int tok = a.st.tokens[(size_t)b * a.st.max_seq + pos];

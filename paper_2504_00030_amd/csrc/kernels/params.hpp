@@ -26,8 +26,9 @@ enum { ROWS_PREFILL = 0, ROWS_VERIFY = 1, ROWS_DRAFT_FIRST = 2, ROWS_DRAFT_NEXT 
 
 struct RowPlan {
     int32_t mode;   // ROWS_*
-    int32_t rps;    // rows per sequence
+    int32_t rps;    // rows per sequence (ragged: the most any sequence has)
     int32_t arg;    // PREFILL: first position; DRAFT_NEXT: draft step j (>= 2)
+    int32_t ragged; // VERIFY only: sequence b has gamma_b[b] + 1 rows, packed one sequence after the other
 };
 
 struct KVCache {
@@ -106,6 +107,7 @@ struct EmbedArgs {
     float *ssq_out;
     int32_t ssq_stride;
     int32_t *row_pos, *row_seq;
+    int32_t *row_off;   // ragged plans: [batch + 1] first row of every sequence, written by the kernel
 };
 
 struct AttnArgs {
@@ -114,7 +116,9 @@ struct AttnArgs {
     int64_t qb_lo, ob_lo; // offsets to the remainder halves of qb / ob (0: none)
     KVCache kv;
     int32_t kv_dtype;
-    int32_t R, rps, nq;
+    int32_t R, rps, nq;     // rps: rows per sequence (with row_off: the most any sequence has)
+    int32_t batch;
+    const int32_t *row_off; // [batch + 1] first row of every sequence when they differ in rows (null: b * rps)
     const int32_t *row_pos, *row_seq;
     int32_t chunk;        // KV positions per workgroup
     int32_t n_chunks;     // grid.x
@@ -160,7 +164,8 @@ struct AcceptArgs {
     int32_t gamma;        // rows per sequence in the target logits buffer = gamma + 1
     int32_t gamma_max;
     int32_t vocab;
-    const float *p_logits;  // [B][gamma+1][V]
+    const float *p_logits;  // [B][gamma+1][V], or packed rows when row_off is set
+    const int32_t *row_off; // [B + 1] first target row of every sequence (null: b * (gamma + 1))
     const float *pm; const double *ps; const int32_t *pa;  // target partials [B*(gamma+1)][n_tiles]
     int32_t n_tiles, tile;
     const float *pm2; const double *ps2; const int32_t *pa2;  // level 2: one per 64 tiles, [..][n2]

@@ -255,6 +255,11 @@ __device__ __forceinline__ void commit_step(const AcceptArgs &a, int b, int A, i
     a.out_k[b] = a.st.k[b];
 }
 
+// First row of sequence b in the target's logits and row statistics.
+__device__ __forceinline__ size_t target_row0(const AcceptArgs &a, int b, int rows) {
+    return a.row_off != nullptr ? (size_t)a.row_off[b] : (size_t)b * rows;
+}
+
 __global__ __launch_bounds__(ACC_THREADS) void accept_scan_k(const AcceptArgs a) {
     const int b = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -266,7 +271,7 @@ __global__ __launch_bounds__(ACC_THREADS) void accept_scan_k(const AcceptArgs a)
     __shared__ int sBonus;
 
     for (int i = wave; i <= k; i += ACC_THREADS / 64) {  // target rows 1..k+1 (0-based i)
-        const size_t row = (size_t)b * rows + i;
+        const size_t row = target_row0(a, b, rows) + i;
         const RowStats rs = wave_row_stats(part_row(a.pm, a.ps, a.pa, a.n_tiles, a.tile, a.pm2, a.ps2, a.pa2, a.n2, row),
                                            inv_t, lane);
         if (lane == 0) {
@@ -292,7 +297,7 @@ __global__ __launch_bounds__(ACC_THREADS) void accept_scan_k(const AcceptArgs a)
             } else if (greedy) {
                 ok = x == sArg[i - 1];
             } else {
-                const size_t prow = (size_t)b * rows + (i - 1);
+                const size_t prow = target_row0(a, b, rows) + (i - 1);
                 const size_t qrow = (size_t)b * a.gamma_max + (i - 1);
                 const double p = exp(((double)a.p_logits[prow * a.vocab + x] - sM[i - 1]) * inv_t) / sS[i - 1];
                 const double q = exp(((double)a.q_logit[qrow] - (double)a.q_max[qrow]) * inv_t) / a.q_sum[qrow];
@@ -319,7 +324,7 @@ __global__ __launch_bounds__(ACC_THREADS) void accept_scan_k(const AcceptArgs a)
     __syncthreads();
     if (sBonus && wave == 0) {
         const int i = k;  // 0-based bonus row
-        const size_t row = (size_t)b * rows + i;
+        const size_t row = target_row0(a, b, rows) + i;
         const double u = philox_uniform(a.cfg.seed, step, (uint32_t)(k + 1), PURPOSE_BONUS, (uint32_t)b);
         const int y = wave_sample_row(a.p_logits + row * a.vocab, a.vocab,
                                       part_row(a.pm, a.ps, a.pa, a.n_tiles, a.tile, a.pm2, a.ps2, a.pa2, a.n2, row), sM[i],
@@ -349,7 +354,7 @@ __global__ __launch_bounds__(RES_THREADS) void residual_k(const AcceptArgs a) {
         return;
     }
     const int rows = a.gamma + 1;
-    const size_t prow = (size_t)b * rows + (row1 - 1);
+    const size_t prow = target_row0(a, b, rows) + (row1 - 1);
     const size_t qrow = (size_t)b * a.gamma_max + (row1 - 1);
     const float *lp = a.p_logits + prow * a.vocab;
     const float *lq = a.q_logits + qrow * a.vocab;

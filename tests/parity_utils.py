@@ -52,11 +52,15 @@ class Compare:
 
 
 def make_controllers(kind: str, n: int, gamma_max: int, which: str):
-    """kind: 'fixed<g>' or 'gammatune'; which: 'gpu' (C controller) or 'oracle'."""
+    """kind: 'fixed<g>', 'spread' (sequence b keeps the fixed gamma 1 + 3 b mod gamma_max: every step's sequences
+    differ in their rows) or 'gammatune'; which: 'gpu' (C controller) or 'oracle'."""
     import paper_2504_00030_amd as pk
     out = []
-    for _ in range(n):
-        if kind.startswith("fixed"):
+    for b in range(n):
+        if kind == "spread":
+            g = 1 + (3 * b) % gamma_max
+            out.append(pk.FixedGamma(g) if which == "gpu" else ogt.FixedGamma(g))
+        elif kind.startswith("fixed"):
             g = int(kind[5:])
             out.append(pk.FixedGamma(g) if which == "gpu" else ogt.FixedGamma(g))
         elif which == "gpu":

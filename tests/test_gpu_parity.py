@@ -506,6 +506,20 @@ def test_small_bf16_pair_beyond_128_rows(pair, batch, gamma):
     assert c.max_logit_err <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("pair,batch,graphs", [("small-bf16", 5, False), ("small-bf16-hd128", 7, True), ("small-q8", 12, True),
+                                               ("small-bf16", 40, False)])
+def test_sequences_with_different_gammas_share_a_packed_pass(pair, batch, graphs):
+    """Every sequence keeps its own fixed gamma (1, 4, 7, ... mod gamma_max), so each verification pass holds
+    gamma_b + 1 rows per sequence, packed one sequence after the other: row offsets in the embedding, attention
+    (queries per sequence, merge) and accept kernels, and the unpacking of the logits read-back."""
+    cfg = synth.pair(pair)
+    c, toks, trace = _run_pair(cfg, controller="spread", temperature=1.0, seed=13, batch=batch, n_generate=10, prompt_len=24,
+                               use_graphs=graphs)
+    _assert_clean(c, full_coverage=False)
+    assert c.max_logit_err <= TOL[cfg.target.dtype]
+    assert len({int(g) for r in trace for g in np.atleast_1d(r["gamma"])}) > 1
+
+
 @pytest.mark.parametrize("batch,gamma", [(8, 15), (64, 1), (42, 2)])
 def test_small_bf16_pair_at_the_row_limit(batch, gamma):
     """128 rows per verification pass (the limit of the weight-streaming kernels) and a ragged 126: eight 16-row
