@@ -112,7 +112,10 @@ typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 constexpr int ATT_SPW_MAX = 8;   // slabs per wave -> chunks of up to 512 positions
 constexpr int ATT_TILES_PER_WG = 8;  // 16-query tiles a workgroup works through (decode and verification: all of them)
 
-template <int HD, int SPW>
+// AHEAD: the row-dependent loads (a sequence's last position, the queries of the tile after this one) are held a
+// step ahead in registers - shorter dependent chains for the few workgroups of a single sequence, but 30-40 more
+// registers, which cost a workgroup per compute unit when a batch launches thousands.
+template <int HD, int SPW, bool AHEAD>
 __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
     if (a.active != nullptr && *a.active == 0) return;
     constexpr int ES = HD / 32;  // k-steps of the score product
@@ -162,8 +165,6 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
             q.ql[s] = has_qlo ? *reinterpret_cast<const u32x4_t *>(qp + a.qb_lo + 32 * s) : u32x4_t{0u, 0u, 0u, 0u};
         }
     };
-    // (with chunks beyond 128 positions the K / V fragments leave no registers for queries held ahead)
-    constexpr bool AHEAD = SPW <= 2;
     QTile qn;
     if constexpr (AHEAD) load_q(qs * TPW, qn);
     u32x4_t kf[SPW][ES];
@@ -360,11 +361,20 @@ bool attention_uses_mfma(const AttnArgs &a, int hd) {
 
 template <int HD>
 static hipError_t launch_attn_mfma(const AttnArgs &a, dim3 grid, hipStream_t s) {
+    // queries held ahead: chunks of up to 128 positions (beyond, the K / V fragments leave no registers) and few
+    // enough workgroups that a compute unit does not wait for a slot
+    const bool ahead = a.chunk <= 128 && (size_t)grid.x * grid.y * grid.z <= 1024;
     switch (a.chunk / 64) {
-        case 1: hipLaunchKernelGGL((attn_mfma_k<HD, 1>), grid, dim3(256), 0, s, a); break;
-        case 2: hipLaunchKernelGGL((attn_mfma_k<HD, 2>), grid, dim3(256), 0, s, a); break;
-        case 4: hipLaunchKernelGGL((attn_mfma_k<HD, 4>), grid, dim3(256), 0, s, a); break;
-        default: hipLaunchKernelGGL((attn_mfma_k<HD, 8>), grid, dim3(256), 0, s, a); break;
+        case 1:
+            if (ahead) hipLaunchKernelGGL((attn_mfma_k<HD, 1, true>), grid, dim3(256), 0, s, a);
+            else hipLaunchKernelGGL((attn_mfma_k<HD, 1, false>), grid, dim3(256), 0, s, a);
+            break;
+        case 2:
+            if (ahead) hipLaunchKernelGGL((attn_mfma_k<HD, 2, true>), grid, dim3(256), 0, s, a);
+            else hipLaunchKernelGGL((attn_mfma_k<HD, 2, false>), grid, dim3(256), 0, s, a);
+            break;
+        case 4: hipLaunchKernelGGL((attn_mfma_k<HD, 4, false>), grid, dim3(256), 0, s, a); break;
+        default: hipLaunchKernelGGL((attn_mfma_k<HD, 8, false>), grid, dim3(256), 0, s, a); break;
     }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.n_chunks == 1) return e;
