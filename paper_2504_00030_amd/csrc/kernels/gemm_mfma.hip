@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void row_scale_k(const float *ssq, int slots, 
 }
 
 // Arguments as for the decode kernels, except: x is a.x (fp32, row-major, row length K, x_mul = 1, x_add = 0) and the
-// row scales come ready-made in a.row_scale (null: ones).  grid.x = 8 * ceil(n_blocks / 8) * m_blocks.
+// row scales come ready-made in a.row_scale (null: ones).  grid.x = 8 * ceil(n_blocks / 8) * m_blocks * ksplit.
 //
 // Timeline of the deep main loop (iteration t multiplies k-tile t from fragments already in registers):
 //   barrier            stage t + 1 is complete in LDS; nobody reads stage t any more
