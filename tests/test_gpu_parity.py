@@ -325,6 +325,27 @@ def test_8b_q8_pair_at_reduced_depth():
     assert c.max_logit_err <= TOL["q8"]
 
 
+def test_8b_q8_pair_at_full_depth_and_width():
+    """The 8-bit 8B-shaped pair at its full size: a 300-token prompt through the dense kernels' 8-bit forms and a few
+    speculative steps, against the fp64 oracle on scale * q (about 75 GB of host memory, about a minute)."""
+    pk = _pk()
+    cfg = synth.pair("8b-q8")
+    Wt, Wd = synth.make_pair_weights(cfg, 0, device="cuda")
+    torch.cuda.synchronize()
+    Wt_np, Wd_np = synth.to_numpy_weights(Wt), synth.to_numpy_weights(Wd)
+    prompts = synth.make_prompts(1, 300, cfg.target.vocab, 7)
+    alpha = synth.alpha_constant(0.9, 4)
+    eng = pk.SpecEngine(cfg.target, Wt, cfg.draft, Wd, batch=1, max_seq=1024 + 512 + 40, gamma_max=cfg.gamma_max, temperature=0.7,
+                        seed=0, accept_mode=pk.ACCEPT_FORCED, use_graphs=True)
+    eng.set_forced_alpha(alpha)
+    c = run_lockstep(eng, cfg, Wt_np, Wd_np, prompts, 6, controller="fixed2", temperature=0.7, seed=0, accept_mode=1,
+                     alpha=alpha)
+    eng.close()
+    _assert_clean(c, full_coverage=False, min_coverage=0.0)
+    assert c.steps_total >= 3
+    assert c.max_logit_err <= TOL["q8"]
+
+
 def test_small_bf16_pair_head_sizes_batch2_gamma16():
     # 30-row last prefill chunk with K = 128 on the draft: the shape whose matrix instructions once ran
     # under an empty execution mask (non-finite logits, then an out-of-range argmax index)
