@@ -70,6 +70,7 @@ struct spec_ctx {
     spec_config cfg{};
     hipStream_t stream = nullptr;
     bool own_stream = false;
+    hipStream_t side_stream = nullptr;  // second stream of the same (default) priority: the draft model's prompt ingestion
     ModelRT tgt, drf;
     State st{};
     std::vector<void *> dev_allocs, host_allocs;
@@ -721,6 +722,7 @@ void spec_destroy(spec_ctx *c) {
     for (void *p : c->dev_allocs) (void)hipFree(p);
     for (void *p : c->host_allocs) (void)hipHostFree(p);
     for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
+    if (c->side_stream) (void)hipStreamDestroy(c->side_stream);
     if (c->own_stream) (void)hipStreamDestroy(c->stream);
     delete c;
 }
@@ -900,8 +902,19 @@ int spec_prefill_ragged(spec_ctx *c, const int32_t *host_tokens, int32_t n_max, 
     c->h_len.assign(lens, lens + B);
     // every sequence ingests positions 0 .. n_max-2; rows past a shorter sequence's end hold padding
     // tokens whose cache entries are rewritten by the decode steps before anything reads them
+    // the two models share nothing they write: the draft ingests on a stream of its own beside the target (both are
+    // bound by load latency rather than by throughput, so their kernels interleave to a shorter whole)
+    if (c->side_stream == nullptr) HIPCHK(c, hipStreamCreateWithFlags(&c->side_stream, hipStreamNonBlocking));
     TRY(prefill_model(c, c->tgt, n_max - 1));
-    TRY(prefill_model(c, c->drf, n_max - 1));
+    {
+        const hipStream_t main_stream = c->stream;
+        c->stream = c->side_stream;
+        const int rc_d = prefill_model(c, c->drf, n_max - 1);
+        c->stream = main_stream;
+        const hipError_t e_d = hipStreamSynchronize(c->side_stream);
+        if (rc_d != SPEC_OK) return rc_d;
+        HIPCHK(c, e_d);
+    }
     HIPCHK(c, hipStreamSynchronize(c->stream));
     c->prefilled = true;
     c->phase = 1;
