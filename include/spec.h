@@ -107,7 +107,9 @@ int spec_init(const spec_shape *target, const spec_weights *target_w,
 /* Load the prompts: host_tokens is host int32 [batch][n], n >= 1, every id in
  * [0, vocab).  Both models ingest tokens 0..n-2 into their KV caches (the last
  * prompt token is fed by the first step), up to 1024 rows per launch for a model on the
- * matrix-core kernels (32 rows per sequence otherwise).  Resets step counter, lengths and
+ * matrix-core kernels (32 rows per sequence otherwise); the draft model ingests on a second
+ * stream of the library's own beside the target (environment variable SPEC_PREFILL_ONE_STREAM:
+ * both on the context's stream, for kernel traces).  Resets step counter, lengths and
  * generated count; may be called again to start a new generation.  Synchronises. */
 int spec_prefill(spec_ctx *ctx, const int32_t *host_tokens, int32_t n);
 

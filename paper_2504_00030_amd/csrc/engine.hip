@@ -12,6 +12,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <chrono>
 #include <map>
@@ -904,9 +905,14 @@ int spec_prefill_ragged(spec_ctx *c, const int32_t *host_tokens, int32_t n_max, 
     // tokens whose cache entries are rewritten by the decode steps before anything reads them
     // the two models share nothing they write: the draft ingests on a stream of its own beside the target (both are
     // bound by load latency rather than by throughput, so their kernels interleave to a shorter whole)
-    if (c->side_stream == nullptr) HIPCHK(c, hipStreamCreateWithFlags(&c->side_stream, hipStreamNonBlocking));
+    // (SPEC_PREFILL_ONE_STREAM in the environment keeps both on the context's stream: kernel traces whose durations
+    // do not overlap)
+    static const bool one_stream = std::getenv("SPEC_PREFILL_ONE_STREAM") != nullptr;
+    if (!one_stream && c->side_stream == nullptr) HIPCHK(c, hipStreamCreateWithFlags(&c->side_stream, hipStreamNonBlocking));
     TRY(prefill_model(c, c->tgt, n_max - 1));
-    {
+    if (one_stream) {
+        TRY(prefill_model(c, c->drf, n_max - 1));
+    } else {
         const hipStream_t main_stream = c->stream;
         c->stream = c->side_stream;
         const int rc_d = prefill_model(c, c->drf, n_max - 1);
