@@ -106,6 +106,80 @@ template <int EPI> __device__ __forceinline__ GemvArgs rows_from(const GemvArgs 
     return b;
 }
 
+// QKV epilogue of one wave over ROWS rows x two groups (16 RoPE pairs) of its result tile, with every load that
+// does not depend on the tile issued first: the caller fetched each row's position and KV page once per wave
+// (rows_pos / rows_page, row step `it` = rows 4 it + lane / 16), the rotary factors of this lane's pair are fetched
+// here for all its rows before the first of them is used.  Same arithmetic as epilogue_tile<EPI_QKV>.
+template <int ROWS>
+__device__ __forceinline__ void qkv_wave_epilogue(const GemvArgs &b, const float *tile, int TS, const float *scale, int Rw,
+                                                  int g, int n_groups, int Ntot, int lane, const int (&rows_pos)[ROWS / 4],
+                                                  const int (&rows_page)[ROWS / 4]) {
+    constexpr int NI = ROWS / 4;
+    const int rsub = lane >> 4, p = lane & 15, h = p >> 3, pj = p & 7;
+    if (g + h >= n_groups) return;  // the second group of the pass lies beyond the matrix: no shuffles below
+    const int half = b.hd >> 1;
+    const int P = (g + h) * 8 + pj;
+    if (P >= (Ntot >> 1)) return;
+    const int hh = P / half, j = P % half;
+    const bool rot = hh < b.nq + b.nkv;
+    float cs[NI], sn[NI];
+#pragma unroll
+    for (int it = 0; it < NI; ++it) {
+        cs[it] = 1.f; sn[it] = 0.f;
+        if (rot && it * 4 + rsub < Rw) {
+            cs[it] = b.rope_cos[(size_t)rows_pos[it] * half + j];
+            sn[it] = b.rope_sin[(size_t)rows_pos[it] * half + j];
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < NI; ++it) {
+        const int r = it * 4 + rsub;
+        if (r >= Rw) continue;
+        const float a1 = tile[r * TS + h * 16 + pj] * scale[r];
+        const float a2 = tile[r * TS + h * 16 + 8 + pj] * scale[r];
+        const float y1 = rot ? a1 * cs[it] - a2 * sn[it] : a1;
+        const float y2 = rot ? a2 * cs[it] + a1 * sn[it] : a2;
+        if (hh < b.nq) {
+            const size_t o = (size_t)r * b.nq * b.hd + (size_t)hh * b.hd + j;
+            b.y[o] = y1;
+            b.y[o + half] = y2;
+            store_split_bf16(b.yb, o, b.yb_lo, y1);
+            store_split_bf16(b.yb, o + half, b.yb_lo, y2);
+        } else {
+            const bool is_k = hh < b.nq + b.nkv;
+            const int kvh = hh - b.nq - (is_k ? 0 : b.nkv);
+            const int in_page = rows_pos[it] & (b.kv.page_tokens - 1);
+            const size_t base = kv_head_base(b.kv, rows_page[it], kvh);
+            const size_t e1 = is_k ? base + (size_t)in_page * b.kv.hd + j : base + (size_t)j * b.kv.page_tokens + in_page;
+            const size_t e2 = is_k ? e1 + half : e1 + (size_t)half * b.kv.page_tokens;
+            void *pool = is_k ? b.kv.k : b.kv.v;
+            if (b.kv_dtype == DT_BF16) {
+                reinterpret_cast<bf16_t *>(pool)[e1] = f32_to_bf16(y1);
+                reinterpret_cast<bf16_t *>(pool)[e2] = f32_to_bf16(y2);
+            } else {
+                reinterpret_cast<float *>(pool)[e1] = y1;
+                reinterpret_cast<float *>(pool)[e2] = y2;
+            }
+        }
+    }
+}
+
+// positions and KV pages of a wave's rows for qkv_wave_epilogue (b: arguments seen from the wave's first row)
+template <int ROWS>
+__device__ __forceinline__ void qkv_wave_rows(const GemvArgs &b, int Rw, int lane, int (&rows_pos)[ROWS / 4],
+                                              int (&rows_page)[ROWS / 4]) {
+#pragma unroll
+    for (int it = 0; it < ROWS / 4; ++it) {
+        const int r = it * 4 + (lane >> 4);
+        rows_pos[it] = 0;
+        rows_page[it] = 0;
+        if (r < Rw) {
+            rows_pos[it] = b.row_pos[r];
+            rows_page[it] = kv_page(b.kv, b.row_seq[r], rows_pos[it]);
+        }
+    }
+}
+
 // scale[r] = rsqrt(mean(x_r^2) + eps) from the statistics slots of the producer: one wave per row.
 __global__ __launch_bounds__(256) void row_scale_k(const float *ssq, int slots, int stride, int R, int K, float eps,
                                                    float *scale) {
@@ -308,6 +382,8 @@ __global__ __launch_bounds__((GemmShape<WM, WN, DEEP, MW>::THREADS), 2) void gem
     // the tile and the scales are private to the wave: LDS serves a wave's accesses in order, so a wave-level
     // wait orders its writes before its reads
     auto wave_sync = [] { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); };
+    int rows_pos[WM * 4], rows_page[WM * 4];  // QKV: positions and KV pages of this lane's rows
+    if constexpr (EPI == EPI_QKV) qkv_wave_rows<WM * 16>(b, Rw, lane, rows_pos, rows_page);
     constexpr int RI = WM;  // residual epilogue: row steps (8 rows each) of half a pass
 #pragma unroll
     for (int p = 0; p < WN / 2; ++p) {
@@ -380,6 +456,8 @@ __global__ __launch_bounds__((GemmShape<WM, WN, DEEP, MW>::THREADS), 2) void gem
                     if (ok && (lane & 3) == 0) b.ssq_out[(size_t)r * a.ssq_stride + gl] = sq;
                 }
             }
+        } else if constexpr (EPI == EPI_QKV) {
+            if (g < n_groups && Rw > 0) qkv_wave_epilogue<WM * 16>(b, tile, TS, scale, Rw, g, n_groups, Ntot, lane, rows_pos, rows_page);
         } else {
 #pragma unroll
             for (int h = 0; h < 2; ++h)
@@ -404,6 +482,9 @@ __global__ __launch_bounds__(256) void gemm_finish_k(const GemvArgs a, const flo
     __shared__ __attribute__((aligned(16))) float tiles[4][16 * 20];
     __shared__ float scales[4][16];
     float *tile = tiles[wave], *scale = scales[wave];
+    const GemvArgs b = rows_from<EPI>(a, row0);
+    int rows_pos[4], rows_page[4];  // QKV: positions and KV pages of this lane's rows, in flight beside the partial sums
+    if constexpr (EPI == EPI_QKV) qkv_wave_rows<16>(b, Rw, lane, rows_pos, rows_page);
     const int r = lane >> 2, c4 = (lane & 3) * 4;
     f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
     if (r < Rw) {
@@ -421,8 +502,9 @@ __global__ __launch_bounds__(256) void gemm_finish_k(const GemvArgs a, const flo
     if (lane < 16) scale[lane] = (a.row_scale != nullptr && lane < Rw) ? a.row_scale[row0 + lane] : 1.f;
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the tile is private to the wave
     if (Rw > 0) {
-        const GemvArgs b = rows_from<EPI>(a, row0);
-        epilogue_tile<EPI, 16, 64>(b, tile, 20, scale, Rw, g, Ntot, lane);
+        // (the QKV form works on pairs of groups: told that the matrix ends after this one, it leaves the second alone)
+        if constexpr (EPI == EPI_QKV) qkv_wave_epilogue<16>(b, tile, 20, scale, Rw, g, g + 1, Ntot, lane, rows_pos, rows_page);
+        else epilogue_tile<EPI, 16, 64>(b, tile, 20, scale, Rw, g, Ntot, lane);
     }
 }
 
