@@ -549,25 +549,44 @@ static hipError_t launch_gemm_cfg(const GemvArgs &a, int Ntot, int forced, float
     const bool q8 = a.wscale != nullptr;
     if (q8 && a.K % 64) return hipErrorInvalidValue;
     int cfg = forced % 1000, ksplit = forced / 1000;
+    const int KT = a.K / 32;
+    auto shares_ok = [&](int sp) {
+        return sp <= KT && (sp - 1) * share_ktiles(KT, sp, q8) < KT && ws != nullptr &&
+               (size_t)sp * a.R * Ntot * sizeof(float) <= ws_bytes;
+    };
     if (cfg == 0) {
-        // both shapes are bound by what a compute unit can fetch from L2 per matrix instruction: the wide block
-        // needs a third less, the narrow one fills the chip when the wide one would leave compute units idle
-        // (measured: eight waves on 256 x 256 blocks win by 5-8 % once they fill the chip)
+        // all shapes are bound by what a compute unit can fetch per matrix instruction: the 256 x 256 block of eight
+        // waves needs the least (measured 5-8 % ahead of the wide four-wave block once it fills the chip), the
+        // narrow block fills the chip when the wider ones would leave compute units idle
         const int m_blocks = (a.R + 127) / 128;
-        if (((Ntot + 255) / 256) * ((a.R + 255) / 256) >= 256) cfg = 808;
-        else cfg = ((Ntot + 255) / 256) * m_blocks > 256 ? 408 : 404;
+        const int wg8 = ((Ntot + 255) / 256) * ((a.R + 255) / 256);
+        if (wg8 >= 256) {
+            cfg = 808;
+        } else if (ksplit == 0 && wg8 <= 128 && a.R >= 256 && KT >= 320) {
+            // few 256 x 256 blocks, many rows and a long K (the down projection at prefill sizes): the big block with
+            // K shared out fetches half of what the narrow block would for the same work (measured 285 -> 233 us at
+            // K = 14336; at K <= 8192 the summing pass eats the gain)
+            int sp = std::min(std::min(8, 256 / wg8), KT / 4);
+            while (sp > 1 && !shares_ok(sp)) --sp;
+            if (sp > 1) { cfg = 808; ksplit = sp; }
+        }
+        if (cfg == 0) cfg = ((Ntot + 255) / 256) * m_blocks > 256 ? 408 : 404;
     }
     if (ksplit == 0) ksplit = (cfg == 404 && ws != nullptr) ? pick_ksplit(Ntot, a.K, a.R, ws_bytes, q8) : 1;
     if (ksplit > 1) {
-        const int KT = a.K / 32;
-        if (cfg != 404 || ws == nullptr || (size_t)ksplit * a.R * Ntot * sizeof(float) > ws_bytes || ksplit > KT ||
-            (ksplit - 1) * share_ktiles(KT, ksplit, q8) >= KT)
-            return hipErrorInvalidValue;
+        if (!shares_ok(ksplit)) return hipErrorInvalidValue;
         const int64_t stride = (int64_t)a.R * Ntot;
         GemvArgs p = a;  // partial results: plain rows of Ntot columns, unscaled
         p.n0 = Ntot; p.y = ws; p.row_scale = nullptr; p.ssq_in = nullptr; p.wscale = nullptr;
-        hipError_t e = q8 ? launch_gemm_one<EPI_PLAIN, 4, 4, true, 1>(p, Ntot, ksplit, stride, ev0, ev1, s)
-                          : launch_gemm_one<EPI_PLAIN, 4, 4, true, 0>(p, Ntot, ksplit, stride, ev0, ev1, s);
+        hipError_t e = hipErrorInvalidValue;
+        switch (cfg + 1000 * (int)q8) {
+            case 404: e = launch_gemm_one<EPI_PLAIN, 4, 4, true, 0>(p, Ntot, ksplit, stride, ev0, ev1, s); break;
+            case 1404: e = launch_gemm_one<EPI_PLAIN, 4, 4, true, 1>(p, Ntot, ksplit, stride, ev0, ev1, s); break;
+            case 408: e = launch_gemm_one<EPI_PLAIN, 4, 8, false, 0>(p, Ntot, ksplit, stride, ev0, ev1, s); break;
+            case 1408: e = launch_gemm_one<EPI_PLAIN, 4, 8, false, 1>(p, Ntot, ksplit, stride, ev0, ev1, s); break;
+            case 808: e = launch_gemm_one<EPI_PLAIN, 4, 8, false, 0, 4>(p, Ntot, ksplit, stride, ev0, ev1, s); break;
+            case 1808: e = launch_gemm_one<EPI_PLAIN, 4, 8, false, 1, 4>(p, Ntot, ksplit, stride, ev0, ev1, s); break;
+        }
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL((gemm_finish_k<EPI>), dim3(Ntot / 16, (a.R + 63) / 64), dim3(256), 0, s, a, ws, ksplit, stride);
         return hipGetLastError();

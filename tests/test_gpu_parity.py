@@ -81,7 +81,7 @@ def test_gemv_mfma_matches_fp64_matmul(R, N, K):
     assert np.abs(got - want).max() <= tol
 
 
-@pytest.mark.parametrize("cfg", [0, 404, 408, 808, 2404, 3404, 8404])
+@pytest.mark.parametrize("cfg", [0, 404, 408, 808, 2404, 3404, 8404, 2408, 4808])
 @pytest.mark.parametrize("R", [1, 63, 64, 129, 200, 1023])
 @pytest.mark.parametrize("N,K", [(4096, 4096), (2064, 768), (48, 4096), (272, 96), (16384, 2048), (16, 32)])
 def test_gemm_mfma_matches_fp64_matmul(N, K, R, cfg):
