@@ -428,13 +428,16 @@ int launch_proj(spec_ctx *c, ModelRT &m, GemvArgs a, int epi, const void *tiled,
                 int *tile_cols) {
     ProfScope ps_(c, m, epi, use_mfma(c, m, a.R));
     // Many rows (prompt ingestion, verification of a batch): the dense-contraction kernel.  Its time hardly depends
-    // on the row count, the weight-streaming kernel's grows with rows x N x K beyond the 16 rows of its persistent
-    // form (measured on the 8B shapes: 1.6e-8 us per row, column and k up to 32 rows, 1.8e-8 up to 64, 2.8e-8 up to
-    // 128, never under ~5 us); whichever estimate is lower runs.  Beyond 128 rows the dense kernel is the only one.
+    // on the row count.  The weight-streaming kernel beyond the 16 rows of its persistent form is bound by what a
+    // compute unit fetches: per 16-row group of W its 32 K bytes (16 K with 8-bit weights) plus the 4 K bytes of
+    // each row of x, shared by the groups of a workgroup, at about 38 GB/s per compute unit (measured on the 8B and
+    // 1B shapes at 17-128 rows: this model and the dense estimate pick the faster kernel to within 0.5 % of the
+    // summed times).  Whichever estimate is lower runs; beyond 128 rows the dense kernel is the only one.
     bool dense = m.mfma_ok && gemm_mfma_serves(epi, Ntot, a.K, a.R) && a.x_mul == 1 && a.x_add == 0;
     if (dense && a.R <= 128) {
-        const double per = a.R <= 32 ? 1.6e-8 : (a.R <= 64 ? 1.8e-8 : 2.8e-8);
-        const double stream_us = std::max(5.0, per * Ntot * (double)a.K * a.R);
+        const int ng = gemv_mfma_groups_per_wg(epi, Ntot, a.K, a.R, 0, m.q8);
+        const double groups_per_cu = std::max(1.0, Ntot / 16 / 256.0);
+        const double stream_us = 2.5 + groups_per_cu * a.K * ((m.q8 ? 16.0 : 32.0) + 4.0 * a.R / ng) / 38e3;
         dense = gemm_mfma_estimate_us(Ntot, a.K, a.R, m.gemm_ws_bytes, m.q8) < stream_us;
     }
     if (dense) {

@@ -609,18 +609,19 @@ bool gemm_mfma_serves(int epi, int Ntot, int K, int R) {
 
 // Rough time of one launch in microseconds, from what was measured on the chip: a workgroup spends a fixed time per
 // k-tile whatever its rows (load latency it cannot hide: 0.57 us for the narrow block alone on a compute unit, 1.17
-// us per pair sharing one; 1.0 / 1.7 us for the wide block), the blocks run in rounds of 512, and a split of K
-// adds its summing pass.
+// us per pair sharing one; 1.0 / 1.7 us for the wide block), the blocks run in rounds of 512, a split of K
+// adds its summing pass, and the live rows of a block cost about 0.075 us each (x rows fetched, epilogue rows).
 float gemm_mfma_estimate_us(int Ntot, int K, int R, size_t ws_bytes, bool q8) {
     const int m_blocks = (R + 127) / 128, KT = K / 32;
+    const float rows_us = 0.075f * std::min(R, 128);
     if (((Ntot + 255) / 256) * m_blocks > 256) {
         const int wgs = ((Ntot + 255) / 256) * m_blocks;
-        return 3.f + KT * 1.7f * ((wgs + 511) / 512);
+        return 3.f + KT * 1.7f * ((wgs + 511) / 512) + rows_us;
     }
     const int sp = pick_ksplit(Ntot, K, R, ws_bytes, q8);
     const int wgs = ((Ntot + 127) / 128) * m_blocks * sp, stages = (KT + sp - 1) / sp;
     const float per_stage = wgs <= 256 ? 0.57f : 1.17f * ((wgs + 511) / 512);
-    return 3.f + stages * per_stage + (sp > 1 ? 8.f : 0.f);
+    return 3.f + stages * per_stage + (sp > 1 ? 8.f : 0.f) + rows_us;
 }
 
 // Host-side contract: w0 is the re-tiled matrix, Ntot % 16 == 0, K % 32 == 0, a.x holds R fp32 rows of length K
