@@ -487,16 +487,59 @@ __global__ __launch_bounds__(256) void gemm_finish_k(const GemvArgs a, const flo
     if constexpr (EPI == EPI_QKV) qkv_wave_rows<16>(b, Rw, lane, rows_pos, rows_page);
     const int r = lane >> 2, c4 = (lane & 3) * 4;
     f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    // residual form: a lane's four sums meet its four residual values directly, so everything it needs - residual,
+    // next norm's gains, row scale, the slabs - is requested at once and the kernel is one round of loads deep
+    f32x4_t xo = {0.f, 0.f, 0.f, 0.f}, gn = {1.f, 1.f, 1.f, 1.f};
+    float sc = 1.f;
+    if constexpr (EPI == EPI_RESID) {
+        if (r < Rw) {
+            xo = *reinterpret_cast<const f32x4_t *>(b.xres + (size_t)r * a.n0 + g * 16 + c4);
+            if (a.g_next != nullptr) gn = *reinterpret_cast<const f32x4_t *>(a.g_next + g * 16 + c4);
+            if (a.row_scale != nullptr) sc = a.row_scale[row0 + r];
+        }
+    }
     if (r < Rw) {
         const float *p = part + (size_t)(row0 + r) * Ntot + g * 16 + c4;
-        for (int sl = 0; sl < ksplit; ++sl) {
-            const f32x4_t v = *reinterpret_cast<const f32x4_t *>(p + (size_t)sl * split_stride);
-            acc[0] += v[0]; acc[1] += v[1]; acc[2] += v[2]; acc[3] += v[3];
+        // eight slabs in flight at a time (a loop of dependent load-and-add rounds costs a memory latency per slab);
+        // slab indices past the last one re-read it and are left out of the sum, which stays in slab order
+        for (int s0 = 0; s0 < ksplit; s0 += 8) {
+            f32x4_t v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                v[i] = *reinterpret_cast<const f32x4_t *>(p + (size_t)min(s0 + i, ksplit - 1) * split_stride);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (s0 + i < ksplit) { acc[0] += v[i][0]; acc[1] += v[i][1]; acc[2] += v[i][2]; acc[3] += v[i][3]; }
+            }
         }
         if (a.wscale != nullptr) {  // 8-bit weights: the column scales
             const f32x4_t sc = *reinterpret_cast<const f32x4_t *>(a.wscale + (size_t)g * 16 + c4);
             acc[0] *= sc[0]; acc[1] *= sc[1]; acc[2] *= sc[2]; acc[3] *= sc[3];
         }
+    }
+    if constexpr (EPI == EPI_RESID) {
+        const bool ok = r < Rw;
+        f32x4_t xn, xg;
+        float sq = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            xn[e] = xo[e] + acc[e] * sc;
+            xg[e] = xn[e] * gn[e];
+            sq += xn[e] * xn[e];
+        }
+        if (ok) {
+            const size_t o = (size_t)r * a.n0 + g * 16 + c4;
+            *reinterpret_cast<f32x4_t *>(b.xres + o) = xn;
+            *reinterpret_cast<f32x4_t *>(b.xg + o) = xg;
+            u32x2_t hi, lo;
+            split4(xg, hi, lo);
+            *reinterpret_cast<u32x2_t *>(b.xgb + o) = hi;
+            if (a.xgb_lo) *reinterpret_cast<u32x2_t *>(b.xgb + o + a.xgb_lo) = lo;
+        }
+        sq += __shfl_xor(sq, 1, WAVE);
+        sq += __shfl_xor(sq, 2, WAVE);
+        if (ok && (lane & 3) == 0) b.ssq_out[(size_t)r * a.ssq_stride + g] = sq;
+        return;
     }
     *reinterpret_cast<f32x4_t *>(tile + r * 20 + c4) = acc;
     if (lane < 16) scale[lane] = (a.row_scale != nullptr && lane < Rw) ? a.row_scale[row0 + lane] : 1.f;
