@@ -385,6 +385,35 @@ def test_full_width_pairs_at_reduced_depth(pair_name, batch):
     assert c.max_logit_err <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("batch", [8, 16, 40])
+def test_8b_widths_at_verification_rows_of_a_batch(batch):
+    """The 8B pair's widths, two target layers and one draft layer deep, with enough sequences that a verification
+    pass holds 17 to over 128 rows (each sequence its own GammaTune+ controller, packed rows): the projections
+    of such a pass are shared between the weight-streaming kernels in their several-row-block forms and the
+    dense-contraction kernel with K shared out over workgroups, as the engine's time estimates decide per shape."""
+    from oracle import model as om
+    pk = _pk()
+    cfg = synth.shrink(synth.pair("8b"), 2, 1)
+    Wt, Wd = synth.make_pair_weights(cfg, 0, device="cuda")
+    torch.cuda.synchronize()
+    widen = lambda W: {k: ([om.as_f64(a) for a in v] if isinstance(v, list) else om.as_f64(v))
+                       for k, v in synth.to_numpy_weights(W).items()}
+    Wt_np, Wd_np = widen(Wt), widen(Wd)
+    prompts = synth.make_prompts(batch, 40, cfg.target.vocab, 11)
+    alpha = synth.alpha_piecewise(64, 8)
+    tau = float(np.float32(0.4))
+    eng = pk.SpecEngine(cfg.target, Wt, cfg.draft, Wd, batch=batch, max_seq=256, gamma_max=cfg.gamma_max,
+                        temperature=0.7, seed=0, accept_mode=pk.ACCEPT_FORCED, use_graphs=True)
+    eng.set_forced_alpha(alpha)
+    eng.set_early_stop(tau)
+    c = run_lockstep(eng, cfg, Wt_np, Wd_np, prompts, 6, controller="gammatune", temperature=0.7, seed=0,
+                     accept_mode=1, alpha=alpha, tau=tau)
+    eng.close()
+    _assert_clean(c, full_coverage=False, min_coverage=0.5)
+    assert c.steps_total >= 2 * batch
+    assert c.max_logit_err <= TOL["bf16"]
+
+
 def test_8b_pair_at_full_depth_and_width():
     """The headline pair at its full size (32 / 16 layers): a 600-token prompt (ingested by the dense-contraction
     kernels in every block shape the benchmark's prefill uses) and a few speculative steps against the fp64 oracle
