@@ -137,7 +137,7 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
     const bf16_t *kp = reinterpret_cast<const bf16_t *>(a.kv.k);
     const bf16_t *vp = reinterpret_cast<const bf16_t *>(a.kv.v);
 
-    __shared__ float sO[4][16][HD + 1];
+    __shared__ __attribute__((aligned(16))) float sO[4][16][HD + 4];  // rows 16-byte aligned, 4 g apart on different banks
     __shared__ float sM[4][16], sL[4][16];
 
     // K fragment: position tw + l16, channels 32 s + 8 g .. + 8; V fragment: channel 16 et + l16, positions
@@ -256,29 +256,48 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) sO[wave][4 * g + v][16 * et + l16] = O[et][v];
         __syncthreads();
-        // merge the four wave partials: thread -> (query, channel)
-        for (int idx = threadIdx.x; idx < 16 * HD; idx += 256) {
-            const int q = idx / HD, e = idx % HD;
+        // merge the four wave partials: thread -> (query, HD / 16 consecutive channels), so that the weights of a
+        // query's four partials are formed once per thread and the channels move as vectors
+        {
+            constexpr int EPT = HD / 16;
+            const int q = threadIdx.x >> 4, e0 = (threadIdx.x & 15) * EPT;
             const int qj = qt * 16 + q;
-            if (qj >= QN) continue;
-            const float M = fmaxf(fmaxf(sM[0][q], sM[1][q]), fmaxf(sM[2][q], sM[3][q]));
-            float acc = 0.f, L = 0.f;
+            if (qj < QN) {
+                const float M = fmaxf(fmaxf(sM[0][q], sM[1][q]), fmaxf(sM[2][q], sM[3][q]));
+                float f[4], L = 0.f, acc[EPT];
 #pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const float f = sM[w][q] == -INFINITY ? 0.f : __expf(sM[w][q] - M);
-                acc += f * sO[w][q][e];
-                L += f * sL[w][q];
-            }
-            const int rr = r_first + qj % rps, hh = kvh * G + qj / rps;
-            if (n_live == 1) {
-                const float v = acc / L;
-                const size_t o = ((size_t)rr * a.nq + hh) * HD + e;
-                a.o[o] = v;
-                store_split_bf16(a.ob, o, a.ob_lo, v);
-            } else {
-                const size_t pi = ((size_t)rr * a.nq + hh) * a.n_chunks + c;
-                a.part_o[pi * HD + e] = acc;
-                if (e == 0) { a.part_m[pi] = M; a.part_l[pi] = L; }
+                for (int w = 0; w < 4; ++w) {
+                    f[w] = sM[w][q] == -INFINITY ? 0.f : __expf(sM[w][q] - M);
+                    L += f[w] * sL[w][q];
+                }
+#pragma unroll
+                for (int k = 0; k < EPT; ++k) acc[k] = 0.f;
+#pragma unroll
+                for (int w = 0; w < 4; ++w)
+#pragma unroll
+                    for (int k = 0; k < EPT; ++k) acc[k] += f[w] * sO[w][q][e0 + k];
+                const int rr = r_first + qj % rps, hh = kvh * G + qj / rps;
+                if (n_live == 1) {
+                    const size_t o = ((size_t)rr * a.nq + hh) * HD + e0;
+#pragma unroll
+                    for (int k = 0; k < EPT; ++k) {
+                        const float v = acc[k] / L;
+                        a.o[o + k] = v;
+                        store_split_bf16(a.ob, o + k, a.ob_lo, v);
+                    }
+                } else {
+                    const size_t pi = ((size_t)rr * a.nq + hh) * a.n_chunks + c;
+                    float *po = a.part_o + pi * HD + e0;
+                    if constexpr (EPT % 4 == 0) {
+#pragma unroll
+                        for (int k = 0; k < EPT; k += 4)
+                            *reinterpret_cast<f32x4_t *>(po + k) = f32x4_t{acc[k], acc[k + 1], acc[k + 2], acc[k + 3]};
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < EPT; ++k) po[k] = acc[k];
+                    }
+                    if (e0 == 0) { a.part_m[pi] = M; a.part_l[pi] = L; }
+                }
             }
         }
         __syncthreads();
