@@ -603,7 +603,9 @@ static hipError_t launch_gemm_cfg(const GemvArgs &a, int Ntot, int forced, float
         // narrow block fills the chip when the wider ones would leave compute units idle
         const int m_blocks = (a.R + 127) / 128;
         const int wg8 = ((Ntot + 255) / 256) * ((a.R + 255) / 256);
-        if (wg8 >= 256) {
+        // (not when its 256-row blocks would leave the last band of rows half empty: up to 128 rows, 257-384, ... the
+        // 128-row blocks do a quarter or more less work; measured on the LM head at 100 rows 267 against 411 us)
+        if (wg8 >= 256 && (m_blocks % 2 == 0 || m_blocks >= 7)) {
             cfg = 808;
         } else if (ksplit == 0 && wg8 <= 128 && a.R >= 256 && KT >= 320) {
             // few 256 x 256 blocks, many rows and a long K (the down projection at prefill sizes): the big block with
