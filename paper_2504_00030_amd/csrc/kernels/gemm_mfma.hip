@@ -619,7 +619,7 @@ static hipError_t launch_gemm_cfg(const GemvArgs &a, int Ntot, int forced, float
         // up to 64 rows the narrow block is 64 rows high, up to 32 rows 32: a half or a quarter of the matrix
         // instructions and fragment reads per k-tile (measured 20-30 % and a further 12-18 % faster on every
         // projection shape of the 8B and 1B models)
-        if (cfg == 404 && a.R <= 64) cfg = a.R <= 32 ? 104 : 204;
+        if ((cfg == 404 || cfg == 408) && a.R <= 64) cfg = a.R <= 32 ? 104 : 204;
     }
     if (ksplit == 0) ksplit = ((cfg == 404 || cfg == 204 || cfg == 104) && ws != nullptr) ? pick_ksplit(Ntot, a.K, a.R, ws_bytes, q8) : 1;
     if (ksplit > 1) {
@@ -673,7 +673,8 @@ float gemm_mfma_estimate_us(int Ntot, int K, int R, size_t ws_bytes, bool q8) {
     const float rows_us = 0.075f * std::min(R, 128);
     if (((Ntot + 255) / 256) * m_blocks > 256) {
         const int wgs = ((Ntot + 255) / 256) * m_blocks;
-        return 3.f + KT * 1.7f * ((wgs + 511) / 512) + rows_us;
+        // (up to 64 rows the lower blocks serve these matrices too: measured 1.55 us per k-tile on the LM heads)
+        return 3.f + KT * (R <= 64 ? 1.55f : 1.7f) * ((wgs + 511) / 512) + rows_us;
     }
     const int sp = pick_ksplit(Ntot, K, R, ws_bytes, q8);
     const int wgs = ((Ntot + 127) / 128) * m_blocks * sp, stages = (KT + sp - 1) / sp;
