@@ -252,7 +252,7 @@ int spec_k_gemv_tiled(const void *w_tiled, int32_t N, int32_t K, const void *x_b
  * cores), asynchronous, no allocation: y[r][n] = sum_k x[r][k] * W[n][k] with w_tiled from spec_k_retile (N % 16 == 0,
  * K % 32 == 0), x device fp32 [R][K] (multiplied as its two-term bf16 split, about 16 significant bits), y device
  * fp32 [R][N], any R >= 1.  cfg = 0 picks the block shape and the split of K from (N, K, R); otherwise cfg = 1000 *
- * shares + shape with shape 808 / 408 / 404 / 204 / 104 (blocks of 256 x 256, 128 x 256, 128 x 128, 64 x 128, 32 x 128 rows of x by rows of W; 0: automatic) and shares = 2..8
+ * shares + shape with shape 808 / 408 / 404 / 304 / 204 / 104 (blocks of 256 x 256, 128 x 256, 128 x 128, 96 x 128, 64 x 128, 32 x 128 rows of x by rows of W; 0: automatic) and shares = 2..8
  * workgroups per block, each multiplying its share of K, followed by a summing pass (0: automatic).
  * workspace: device scratch for the shares' partial results, at least shares * R * N * 4 bytes (NULL: never split).
  * SPEC_EINVAL when the forced split does not fit (workspace too small, fewer k-tiles than shares). */

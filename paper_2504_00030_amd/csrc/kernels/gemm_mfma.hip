@@ -616,12 +616,13 @@ static hipError_t launch_gemm_cfg(const GemvArgs &a, int Ntot, int forced, float
             if (sp > 1) { cfg = 808; ksplit = sp; }
         }
         if (cfg == 0) cfg = ((Ntot + 255) / 256) * m_blocks > 256 ? 408 : 404;
-        // up to 64 rows the narrow block is 64 rows high, up to 32 rows 32: a half or a quarter of the matrix
-        // instructions and fragment reads per k-tile (measured 20-30 % and a further 12-18 % faster on every
-        // projection shape of the 8B and 1B models)
+        // up to 96 rows the narrow block is 96 rows high, up to 64 rows 64, up to 32 rows 32: fewer matrix
+        // instructions and fragment reads per k-tile (measured on every projection shape of the 8B and 1B models:
+        // 8-15 % faster at 96 rows, 20-30 % at 64, a further 12-18 % at 32)
         if ((cfg == 404 || cfg == 408) && a.R <= 64) cfg = a.R <= 32 ? 104 : 204;
+        if (cfg == 404 && a.R <= 96) cfg = 304;
     }
-    if (ksplit == 0) ksplit = ((cfg == 404 || cfg == 204 || cfg == 104) && ws != nullptr) ? pick_ksplit(Ntot, a.K, a.R, ws_bytes, q8) : 1;
+    if (ksplit == 0) ksplit = ((cfg == 404 || cfg == 304 || cfg == 204 || cfg == 104) && ws != nullptr) ? pick_ksplit(Ntot, a.K, a.R, ws_bytes, q8) : 1;
     if (ksplit > 1) {
         if (!shares_ok(ksplit)) return hipErrorInvalidValue;
         const int64_t stride = (int64_t)a.R * Ntot;
@@ -631,6 +632,8 @@ static hipError_t launch_gemm_cfg(const GemvArgs &a, int Ntot, int forced, float
         switch (cfg + 1000 * (int)q8) {
             case 404: e = launch_gemm_one<EPI_PLAIN, 4, 4, true, 0>(p, Ntot, ksplit, stride, ev0, ev1, s); break;
             case 204: e = launch_gemm_one<EPI_PLAIN, 2, 4, true, 0>(p, Ntot, ksplit, stride, ev0, ev1, s); break;
+            case 304: e = launch_gemm_one<EPI_PLAIN, 3, 4, true, 0>(p, Ntot, ksplit, stride, ev0, ev1, s); break;
+            case 1304: e = launch_gemm_one<EPI_PLAIN, 3, 4, true, 1>(p, Ntot, ksplit, stride, ev0, ev1, s); break;
             case 104: e = launch_gemm_one<EPI_PLAIN, 1, 4, true, 0>(p, Ntot, ksplit, stride, ev0, ev1, s); break;
             case 1104: e = launch_gemm_one<EPI_PLAIN, 1, 4, true, 1>(p, Ntot, ksplit, stride, ev0, ev1, s); break;
             case 1204: e = launch_gemm_one<EPI_PLAIN, 2, 4, true, 1>(p, Ntot, ksplit, stride, ev0, ev1, s); break;
@@ -648,6 +651,8 @@ static hipError_t launch_gemm_cfg(const GemvArgs &a, int Ntot, int forced, float
         case 408: return launch_gemm_one<EPI, 4, 8, false, 0>(a, Ntot, 1, 0, ev0, ev1, s);
         case 404: return launch_gemm_one<EPI, 4, 4, true, 0>(a, Ntot, 1, 0, ev0, ev1, s);
         case 204: return launch_gemm_one<EPI, 2, 4, true, 0>(a, Ntot, 1, 0, ev0, ev1, s);
+        case 304: return launch_gemm_one<EPI, 3, 4, true, 0>(a, Ntot, 1, 0, ev0, ev1, s);
+        case 1304: return launch_gemm_one<EPI, 3, 4, true, 1>(a, Ntot, 1, 0, ev0, ev1, s);
         case 104: return launch_gemm_one<EPI, 1, 4, true, 0>(a, Ntot, 1, 0, ev0, ev1, s);
         case 1104: return launch_gemm_one<EPI, 1, 4, true, 1>(a, Ntot, 1, 0, ev0, ev1, s);
         case 1204: return launch_gemm_one<EPI, 2, 4, true, 1>(a, Ntot, 1, 0, ev0, ev1, s);
@@ -679,6 +684,7 @@ float gemm_mfma_estimate_us(int Ntot, int K, int R, size_t ws_bytes, bool q8) {
     const int sp = pick_ksplit(Ntot, K, R, ws_bytes, q8);
     const int wgs = ((Ntot + 127) / 128) * m_blocks * sp, stages = (KT + sp - 1) / sp;
     float per_stage = wgs <= 256 ? 0.57f : 1.17f * ((wgs + 511) / 512);
+    if (R <= 96) per_stage = wgs <= 256 ? 0.50f : 1.0f * ((wgs + 511) / 512);   // the 96-row block
     if (R <= 64) per_stage = wgs <= 256 ? 0.40f : 0.62f * ((wgs + 511) / 512);  // the 64-row block
     if (R <= 32) per_stage = wgs <= 256 ? 0.33f : 0.55f * ((wgs + 511) / 512);  // the 32-row block
     return 3.f + stages * per_stage + (sp > 1 ? 8.f : 0.f) + rows_us;
@@ -688,7 +694,7 @@ float gemm_mfma_estimate_us(int Ntot, int K, int R, size_t ws_bytes, bool q8) {
 // (x_mul = 1, x_add = 0), any R >= 1; RESID writes Ntot / 16 statistics slots per row (<= ssq_stride); LOGITS writes
 // one softmax partial per row and 16-column tile (n_tiles = Ntot / 16).  With
 // statistics of the input (a.ssq_in) the row scales are first reduced into scale_buf (device, R floats).
-// `forced` = 1000 shares of K + 100 WM + WN selects the block shape and the split (0 = automatic; 104: 32 x 128, 204: 64 x 128, 404:
+// `forced` = 1000 shares of K + 100 WM + WN selects the block shape and the split (0 = automatic; 104: 32 x 128, 204: 64 x 128, 304: 96 x 128, 404:
 // 128 x 128, 408: 128 x 256, 808: 256 x 256; shares need the workspace `ws`: shares x R x Ntot floats).
 hipError_t launch_gemm_mfma(const GemvArgs &a0, int epi, int forced, float *scale_buf, float *ws, size_t ws_bytes,
                             hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t s) {

@@ -81,7 +81,7 @@ def test_gemv_mfma_matches_fp64_matmul(R, N, K):
     assert np.abs(got - want).max() <= tol
 
 
-@pytest.mark.parametrize("cfg", [0, 104, 204, 404, 408, 808, 3104, 2204, 8204, 2404, 3404, 8404, 2408, 4808])
+@pytest.mark.parametrize("cfg", [0, 104, 204, 304, 404, 408, 808, 3104, 2204, 8204, 2304, 2404, 3404, 8404, 2408, 4808])
 @pytest.mark.parametrize("R", [1, 33, 63, 64, 129, 200, 1023])
 @pytest.mark.parametrize("N,K", [(4096, 4096), (2064, 768), (48, 4096), (272, 96), (16384, 2048), (16, 32)])
 def test_gemm_mfma_matches_fp64_matmul(N, K, R, cfg):
@@ -272,8 +272,8 @@ def test_q8_kernels_match_fp64_matmul(N, K, R):
         y = torch.full((R, N), float("nan"), device="cuda")
         pk.k_gemv_tiled_q8(wt, scg, N, K, xb[0], y, x_lo=xb[1])
         outs.append(("streaming", y))
-    for cfg in (0, 104, 204, 404, 408, 808, 2104, 2204, 2404):
-        if cfg in (2104, 2204, 2404) and K // 64 < 2:
+    for cfg in (0, 104, 204, 304, 404, 408, 808, 2104, 2204, 2304, 2404):
+        if cfg in (2104, 2204, 2304, 2404) and K // 64 < 2:
             continue
         y = torch.full((R, N), float("nan"), device="cuda")
         pk.k_gemm_tiled_q8(wt, scg, N, K, xg, y, cfg, workspace=ws)
