@@ -620,7 +620,8 @@ static hipError_t launch_gemm_cfg(const GemvArgs &a, int Ntot, int forced, float
         // instructions and fragment reads per k-tile (measured on every projection shape of the 8B and 1B models:
         // 8-15 % faster at 96 rows, 20-30 % at 64, a further 12-18 % at 32)
         if ((cfg == 404 || cfg == 408) && a.R <= 64) cfg = a.R <= 32 ? 104 : 204;
-        if (cfg == 404 && a.R <= 96) cfg = 304;
+        // (the 96-row block also wherever it needs no more blocks than the 128-row one: 129-192 rows, 257-288)
+        if (cfg == 404 && (a.R + 95) / 96 == (a.R + 127) / 128) cfg = 304;
     }
     if (ksplit == 0) ksplit = ((cfg == 404 || cfg == 304 || cfg == 204 || cfg == 104) && ws != nullptr) ? pick_ksplit(Ntot, a.K, a.R, ws_bytes, q8) : 1;
     if (ksplit > 1) {
