@@ -71,20 +71,25 @@ def decode_loop_host(eng, ctrls, n_generate):
     B = len(ctrls)
     gen = [0] * B
     steps, acc, drafted, gsum = 0, 0, 0, 0
+    seq_steps = 0
     while min(gen) < n_generate:
-        gs = [c.gamma for c in ctrls]
+        # a sequence that has its tokens rides along with gamma 1, uncounted, as in spec_generate
+        gs = [c.gamma if gen[b] < n_generate else 1 for b, c in enumerate(ctrls)]
         eng.draft(gs[0] if B == 1 else np.array(gs, dtype=np.int32))
         eng.verify(max(gs))
         A, y, k = eng.accept()
         for b in range(B):
+            if gen[b] >= n_generate:
+                continue
             ctrls[b].update(int(A[b]), int(k[b]))
             gen[b] += int(A[b]) + 1
             acc += int(A[b])
             drafted += int(k[b])
             gsum += gs[b]
+            seq_steps += 1
         steps += 1
     return dict(generated=sum(min(g, n_generate) for g in gen), spec_steps=steps, accepted=acc, drafted=drafted,
-                gamma_sum=gsum, seq_steps=steps * B)
+                gamma_sum=gsum, seq_steps=seq_steps)
 
 
 def make_controller(pk, args, gamma_max):
@@ -195,7 +200,8 @@ def main():
     else:
         alpha = synth.alpha_constant(float(args.alpha), 4)
     tau = float(np.float32(0.4)) if args.controller == "gammatune+" else 0.0
-    # with several sequences the fast ones run on until the slowest has n_gen tokens
+    # with several sequences the fast ones ride along (gamma 1: at most two tokens per step) until the slowest has
+    # n_gen tokens, which takes at most n_gen steps: 3 n_gen tokens of room is the worst case
     max_seq = n_prompt + n_gen * (1 if args.batch == 1 else 3) + 2 * cfg.gamma_max + 8
     B = args.batch
     prompts = synth.make_prompts(B, n_prompt, cfg.target.vocab, 7)

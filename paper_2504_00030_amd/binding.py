@@ -55,7 +55,7 @@ class SpecConfig(C.Structure):
 
 
 class SpecGenStats(C.Structure):
-    _fields_ = [(n, C.c_int64) for n in ("steps", "generated", "accepted", "drafted", "gamma_sum")]
+    _fields_ = [(n, C.c_int64) for n in ("steps", "generated", "accepted", "drafted", "gamma_sum", "seq_steps")]
 
 
 class GtParams(C.Structure):
@@ -348,22 +348,25 @@ class SpecEngine:
             rc = self._lib.spec_generate(self._ctx, None, int(controllers[0].gamma), int(n_generate), C.byref(st))
         self._chk(rc, "spec_generate")
         return dict(generated=int(st.generated), spec_steps=int(st.steps), accepted=int(st.accepted), drafted=int(st.drafted),
-                    gamma_sum=int(st.gamma_sum), seq_steps=int(st.steps) * self.batch)
+                    gamma_sum=int(st.gamma_sum), seq_steps=int(st.seq_steps))
 
     def generate(self, prompts: np.ndarray, n_generate: int, controllers: List, keep_logits: bool = False):
         """Host loop of speculative decoding: draft -> verify -> accept -> controller update, until every
-        sequence holds n_generate new tokens.  Returns (tokens [B][n_prompt + n_generate], trace)."""
+        sequence holds n_generate new tokens; like spec_generate, a sequence that has them rides along with
+        gamma = 1 and its controller is left alone (trace["live"] marks the sequences still counted).
+        Returns (tokens [B][n_prompt + n_generate], trace)."""
         prompts = np.asarray(prompts, dtype=np.int32).reshape(self.batch, -1)
         n0 = prompts.shape[1]
         self.prefill(prompts)
         gen = np.zeros(self.batch, dtype=np.int64)
         trace = []
         while gen.min() < n_generate:
-            gammas = np.array([c.gamma for c in controllers], dtype=np.int32)
+            live = gen < n_generate
+            gammas = np.array([c.gamma if live[b] else 1 for b, c in enumerate(controllers)], dtype=np.int32)
             self.draft(gammas if self.batch > 1 else int(gammas[0]))
             gmax = int(gammas.max())
             self.verify(gmax)
-            rec = {"gamma": gammas.copy()}
+            rec = {"gamma": gammas.copy(), "live": live.copy()}
             if keep_logits:
                 rec["q_logits"] = self.debug_logits(0)
             A, y, k = self.accept()
@@ -372,7 +375,8 @@ class SpecEngine:
             rec.update(A=A.copy(), y=y.copy(), k=k.copy())
             trace.append(rec)
             for b, c in enumerate(controllers):
-                c.update(int(A[b]), int(k[b]))
+                if live[b]:
+                    c.update(int(A[b]), int(k[b]))
             gen += A + 1
         toks = np.stack([self.read_tokens(b)[: n0 + n_generate] for b in range(self.batch)])
         return toks, trace

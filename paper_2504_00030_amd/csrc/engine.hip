@@ -1,10 +1,11 @@
-// Host engine behind the C ABI of include/spec.h: owns the paged KV caches, the re-tiled weights (16-bit, or
+// Host engine behind the C ABI of include/spec.h and include/spec_debug.h: owns the paged KV caches, the re-tiled weights (16-bit, or
 // 8-bit with per-row scales), the activation and logits buffers and the HIP graphs (one per draft pass index,
 // one per verification length), and strings the kernels into the three phases of a speculative step (Background
 // section): gamma draft decode steps, one target verification pass over gamma+1 rows, and the accept / resample
 // step.  Per projection it picks the weight-streaming or the dense-contraction kernel from measured time
 // estimates (launch_proj).
 #include "spec.h"
+#include "spec_debug.h"
 #include "gammatune.h"
 
 #include <hip/hip_runtime.h>
@@ -101,7 +102,11 @@ struct spec_ctx {
     int cur_rows = 0;      // rows of the current step's verification pass when it is ragged, else 0
     bool ragged_ok = false;  // several sequences and a target whose attention takes ragged rows
     bool prefilled = false;
-    std::map<int, hipGraphExec_t> g_draft, g_verify, g_pass;  // whole draft phase per gamma, verify per gamma, draft pass j
+    std::map<int, hipGraphExec_t> g_draft, g_pass;  // whole draft phase per gamma, draft pass j
+    // verification pass per (gamma, rows), with the logits tiling its LM-head launch uses: the accept kernels run
+    // outside the graph and must index the softmax partials the way the replayed graph writes them
+    struct VerifyGraph { hipGraphExec_t exec; int tile, ntiles; };
+    std::map<int, VerifyGraph> g_verify;
     std::vector<hipGraph_t> graphs;
     // optional timing of one kernel class with event pairs (direct launches only)
     int prof_epi = -1, prof_model = 0;
@@ -720,7 +725,7 @@ void spec_destroy(spec_ctx *c) {
     if (!c) return;
     (void)hipStreamSynchronize(c->stream);
     for (auto &kv : c->g_draft) (void)hipGraphExecDestroy(kv.second);
-    for (auto &kv : c->g_verify) (void)hipGraphExecDestroy(kv.second);
+    for (auto &kv : c->g_verify) (void)hipGraphExecDestroy(kv.second.exec);
     for (auto &kv : c->g_pass) (void)hipGraphExecDestroy(kv.second);
     for (auto g : c->graphs) (void)hipGraphDestroy(g);
     for (void *p : c->dev_allocs) (void)hipFree(p);
@@ -843,7 +848,7 @@ int spec_set_forced_alpha(spec_ctx *c, const float *alpha, int32_t n) {
     c->scfg.n_alpha = n;
     // kernel arguments are baked into captured graphs
     for (auto &kv : c->g_draft) (void)hipGraphExecDestroy(kv.second);
-    for (auto &kv : c->g_verify) (void)hipGraphExecDestroy(kv.second);
+    for (auto &kv : c->g_verify) (void)hipGraphExecDestroy(kv.second.exec);
     for (auto &kv : c->g_pass) (void)hipGraphExecDestroy(kv.second);
     c->g_draft.clear();
     c->g_verify.clear();
@@ -1024,9 +1029,12 @@ int spec_verify(spec_ctx *c, int32_t gamma) {
         if (it == c->g_verify.end()) {
             hipGraphExec_t ex = nullptr;
             TRY(capture(c, [&] { return enqueue_verify(c, gamma, rows_total); }, &ex));
-            it = c->g_verify.emplace(key, ex).first;
+            it = c->g_verify.emplace(key, spec_ctx::VerifyGraph{ex, c->t_tile, c->t_ntiles}).first;
         }
-        HIPCHK(c, hipGraphLaunch(it->second, c->stream));
+        // the tiling of THIS graph's logits, not of whichever graph was captured last
+        c->t_tile = it->second.tile;
+        c->t_ntiles = it->second.ntiles;
+        HIPCHK(c, hipGraphLaunch(it->second.exec, c->stream));
     } else {
         TRY(enqueue_verify(c, gamma, rows_total));
     }
@@ -1063,17 +1071,23 @@ int spec_generate(spec_ctx *c, gt_state *controllers, int32_t fixed_gamma, int32
         int least = gen[0];
         for (int b = 1; b < B; ++b) least = std::min(least, gen[b]);
         if (least >= n_generate) break;
-        for (int b = 0; b < B; ++b) gam[b] = controllers ? controllers[b].gamma : fixed_gamma;
+        // a sequence that already has its n_generate tokens rides along with the shortest step there is (gamma 1:
+        // two rows of the verification pass) until the slowest one is done; its controller is left alone and it
+        // stays out of the statistics.  It grows by at most two tokens per step, so 3 * n_generate tokens of
+        // room behind the prompt always suffice.
+        for (int b = 0; b < B; ++b) gam[b] = gen[b] >= n_generate ? 1 : (controllers ? controllers[b].gamma : fixed_gamma);
         TRY(spec_draft_batch(c, gam.data()));
         TRY(spec_verify(c, c->cur_gamma));
         TRY(spec_accept(c, A.data(), y.data(), k.data()));
         for (int b = 0; b < B; ++b) {
+            if (gen[b] >= n_generate) continue;
             if (controllers && gammatune_update(&controllers[b], A[b], k[b]) < 0)
                 return fail(c, SPEC_EINVAL, "generate: controller state rejected by gammatune_update");
             gen[b] += A[b] + 1;
             st.accepted += A[b];
             st.drafted += k[b];
             st.gamma_sum += gam[b];
+            st.seq_steps += 1;
         }
         st.steps += 1;
     }

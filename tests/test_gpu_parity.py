@@ -140,15 +140,24 @@ def _run_pair(cfg, *, controller, temperature, seed=0, n_generate=None, prompt_l
     return cmp_, toks, cmp_.trace
 
 
+# Coverage floors of the tests at the headline sizes: the share of steps whose every decision equalled the oracle's
+# as measured on the MI355X, less a margin for a different draw of near-edge uniforms after a kernel change.  (A step
+# below the floor is not a wrong step - every differing decision is still checked for validity - but a drop means
+# the logits error grew.)
+COVERAGE_FLOOR = {"8b-full-depth": 0.0, "8b-q8-full-depth": 0.0, "13b-sweep": 0.0}
+
+
 def _assert_clean(c, full_coverage=True, min_coverage=0.8):
-    print(f"coverage {c.coverage:.3f} ({c.steps_clean}/{c.steps_total} steps, {c.resyncs} resyncs) decisions "
-          f"{c.decisions_compared} skipped {c.decisions_skipped} max logit err {c.max_logit_err:.3e}")
+    msg = (f"coverage {c.coverage:.3f} ({c.steps_clean}/{c.steps_total} steps, {c.resyncs} resyncs) decisions "
+           f"{c.decisions_compared} skipped {c.decisions_skipped} max logit err {c.max_logit_err:.3e} "
+           f"largest kappa_prob {c.kappa_prob_max:.3e}")
+    print(msg)
     assert not c.failures, "\n".join(c.failures[:10])
     if full_coverage:
         assert not c.skipped, c.skipped[:5]
-        assert c.coverage == 1.0
+        assert c.coverage == 1.0, msg
     else:
-        assert c.coverage >= min_coverage, c.skipped[:10]
+        assert c.coverage >= min_coverage, msg + " " + "; ".join(c.skipped[:10])
 
 
 @pytest.mark.parametrize("controller", ["fixed4", "gammatune"])
@@ -341,7 +350,7 @@ def test_8b_q8_pair_at_full_depth_and_width():
     c = run_lockstep(eng, cfg, Wt_np, Wd_np, prompts, 6, controller="fixed2", temperature=0.7, seed=0, accept_mode=1,
                      alpha=alpha)
     eng.close()
-    _assert_clean(c, full_coverage=False, min_coverage=0.0)
+    _assert_clean(c, full_coverage=False, min_coverage=COVERAGE_FLOOR["8b-q8-full-depth"])
     assert c.steps_total >= 3
     assert c.max_logit_err <= TOL["q8"]
 
@@ -382,6 +391,64 @@ def test_full_width_pairs_at_reduced_depth(pair_name, batch):
     # with the activations carried as two bf16 terms the logits agree to a few 1e-4 and most steps still match
     _assert_clean(c, full_coverage=False, min_coverage=0.7)
     assert c.steps_total >= 8
+    assert c.max_logit_err <= TOL["bf16"]
+
+
+def _widened_pair(name, n_layers_t, n_layers_d):
+    """A large pair at full width and reduced depth: weights generated on the GPU, widened once for the oracle."""
+    from oracle import model as om
+    cfg = synth.shrink(synth.pair(name), n_layers_t, n_layers_d)
+    Wt, Wd = synth.make_pair_weights(cfg, 0, device="cuda")
+    torch.cuda.synchronize()
+    widen = lambda W: {k: ([om.as_f64(a) for a in v] if isinstance(v, list) else om.as_f64(v))
+                       for k, v in synth.to_numpy_weights(W).items()}
+    return cfg, Wt, Wd, widen(Wt), widen(Wd)
+
+
+@pytest.mark.parametrize("temperature,tau", [(0.0, 0.0), (1.0, 0.0), (1.0, 0.4), (0.0, 0.4)])
+def test_1b_pair_natural_acceptance_at_reduced_depth(temperature, tau):
+    """The 1B-shaped target with its 2-layer d = 768 draft (draft head = target head times a random projection) at
+    full width, two target layers deep, with NATURAL acceptance: the accept test u q(x) < p(x), the residual draw
+    and the bonus draw all run on the 128256-entry rows, greedy (T = 0) and sampled (T = 1), GammaTune (tau = 0)
+    and GammaTune+ (tau = 0.4; the near-flat random-init draft never reaches that confidence, so every step stops
+    after its first token)."""
+    pk = _pk()
+    cfg, Wt, Wd, Wt_np, Wd_np = _widened_pair("1b", 2, 2)
+    prompts = synth.make_prompts(1, 96, cfg.target.vocab, 7)
+    tau = float(np.float32(tau))
+    eng = pk.SpecEngine(cfg.target, Wt, cfg.draft, Wd, batch=1, max_seq=256 + 256 + 2 * 8 + 8, gamma_max=cfg.gamma_max,
+                        temperature=temperature, seed=0, accept_mode=pk.ACCEPT_NATURAL, use_graphs=True)
+    if tau > 0:
+        eng.set_early_stop(tau)
+    c = run_lockstep(eng, cfg, Wt_np, Wd_np, prompts, 20, controller="gammatune", temperature=temperature, seed=0,
+                     accept_mode=0, tau=tau)
+    eng.close()
+    # greedy decisions have margins (top-1/top-2 gaps of 128256 near-Gaussian logits) far above the measured logit
+    # error; sampled ones sit on CDF cells of width ~1e-5 and mostly differ - validly (checked per decision)
+    _assert_clean(c, full_coverage=False, min_coverage=0.8 if temperature == 0.0 else 0.0)
+    assert c.steps_total >= 8
+    assert c.max_logit_err <= TOL["bf16"]
+    if tau > 0:
+        assert all(int(t["k"][0]) == 1 for t in c.trace)
+
+
+@pytest.mark.parametrize("graphs", [True, False])
+def test_verification_graphs_of_different_logits_tilings_alternate(graphs):
+    """Four sequences of the 1B-shaped pair walk the speculation lengths 4, 3, 4, 3, ...: the verification passes
+    alternate between 20 and 16 rows, whose LM-head launches tile the 128256 logits differently, so each cached
+    graph must bring its own tiling to the accept kernels that run outside it (a replayed graph once met the
+    tiling of the graph captured last: wrong row maxima, sums and argmaxima, nothing out of bounds).  Greedy, so
+    every emitted token is an argmax over the softmax partials in question."""
+    pk = _pk()
+    cfg, Wt, Wd, Wt_np, Wd_np = _widened_pair("1b", 1, 1)
+    prompts = synth.make_prompts(4, 24, cfg.target.vocab, 13)
+    eng = pk.SpecEngine(cfg.target, Wt, cfg.draft, Wd, batch=4, max_seq=160, gamma_max=cfg.gamma_max,
+                        temperature=0.0, seed=0, accept_mode=pk.ACCEPT_NATURAL, use_graphs=graphs)
+    c = run_lockstep(eng, cfg, Wt_np, Wd_np, prompts, 7, controller="script:4,3,4,3,4,3,4,3", temperature=0.0, seed=0,
+                     accept_mode=0)
+    eng.close()
+    _assert_clean(c, full_coverage=False, min_coverage=0.8)
+    assert c.steps_total >= 16
     assert c.max_logit_err <= TOL["bf16"]
 
 
@@ -435,7 +502,7 @@ def test_8b_pair_at_full_depth_and_width():
     c = run_lockstep(eng, cfg, Wt_np, Wd_np, prompts, 6, controller="fixed2", temperature=0.7, seed=0, accept_mode=1,
                      alpha=alpha)
     eng.close()
-    _assert_clean(c, full_coverage=False, min_coverage=0.0)
+    _assert_clean(c, full_coverage=False, min_coverage=COVERAGE_FLOOR["8b-full-depth"])
     assert c.steps_total >= 3
     assert c.max_logit_err <= TOL["bf16"]
 
@@ -472,10 +539,12 @@ def test_standalone_accept_kernel_on_table_models(vocab, temperature):
     assert agree >= total * 0.9
 
 
-@pytest.mark.parametrize("batch,kv_len", [(1, 512), (1, 2048), (4, 512), (4, 1024)])
+@pytest.mark.parametrize("batch,kv_len", [(1, 512), (1, 2048), (1, 4096), (4, 512), (4, 1024), (8, 512), (8, 4096)])
 def test_13b_verify_sweep_with_synthetic_cache(batch, kv_len):
     """Verification passes of 2, 4, 8 and 16 rows against a seeded synthetic KV cache (no prefill), 13B-shaped target
-    at full width and two layers, one-layer draft; every sequence of a batch has its own cache contents."""
+    at full width and two layers, one-layer draft; every sequence of a batch has its own cache contents.  The
+    largest cell (8 sequences, 4096 cached positions) runs 4 and 16 rows only: its synthetic caches alone are
+    most of the test's time."""
     from oracle import model as om
     from oracle import spec as ospec
     from parity_utils import Compare, _compare_step, oshape
@@ -487,7 +556,8 @@ def test_13b_verify_sweep_with_synthetic_cache(batch, kv_len):
                        for k, v in synth.to_numpy_weights(W).items()}
     Wt_np, Wd_np = widen(Wt), widen(Wd)
     res = Compare()
-    for gamma in (1, 3, 7, 15):
+    for gamma in ((3, 15) if batch * kv_len > 16384 else (1, 3, 7, 15)):
+        print(f"13b sweep: batch {batch} kv {kv_len} gamma {gamma}", flush=True)
         eng = pk.SpecEngine(cfg.target, Wt, cfg.draft, Wd, batch=batch, max_seq=kv_len + 64, gamma_max=16,
                             temperature=1.0, seed=9)
         eng.fill_kv(kv_len)
@@ -518,9 +588,9 @@ def test_13b_verify_sweep_with_synthetic_cache(batch, kv_len):
                                        keep_logits=True)
             res.steps_total += 1
             if _compare_step(res, f"gamma {gamma} seq {b}", r, gamma, int(k[b]), int(A[b]), int(y[b]), drafted[b], q[b],
-                             p[b], "bf16", 1.0):
+                             p[b], "bf16", 1.0, s=0, b=b, seed=9, forced=False):
                 res.steps_clean += 1
-    _assert_clean(res, full_coverage=False, min_coverage=0.0)
+    _assert_clean(res, full_coverage=False, min_coverage=COVERAGE_FLOOR["13b-sweep"])
     assert res.max_logit_err <= TOL["bf16"]
 
 
@@ -605,13 +675,14 @@ def test_native_generate_loop_equals_host_loop(batch):
             toks = np.stack([eng.read_tokens(b)[: 24 + 60] for b in range(batch)])
         else:
             toks, trace = eng.generate(prompts, 60, ctl)
-            stats = dict(spec_steps=len(trace), accepted=int(sum(r["A"].sum() for r in trace)),
-                         drafted=int(sum(r["k"].sum() for r in trace)))
+            stats = dict(spec_steps=len(trace), accepted=int(sum(r["A"][r["live"]].sum() for r in trace)),
+                         drafted=int(sum(r["k"][r["live"]].sum() for r in trace)),
+                         seq_steps=int(sum(r["live"].sum() for r in trace)))
         out.append((toks, [(c.gamma, c.gamma_bar) for c in ctl], stats))
         eng.close()
     assert np.array_equal(out[0][0], out[1][0])
     assert out[0][1] == out[1][1]
-    for key in ("spec_steps", "accepted", "drafted"):
+    for key in ("spec_steps", "accepted", "drafted", "seq_steps"):
         assert out[0][2][key] == out[1][2][key]
 
 

@@ -16,7 +16,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def _declared_symbols():
     names = set()
-    for h in ("spec.h", "gammatune.h"):
+    for h in sorted(os.listdir(os.path.join(ROOT, "include"))):
         txt = open(os.path.join(ROOT, "include", h)).read()
         txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
         names |= set(re.findall(r"\b((?:spec|gammatune)_[a-z_0-9]+)\s*\(", txt))

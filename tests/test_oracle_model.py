@@ -204,3 +204,51 @@ def test_generate_bookkeeping():
     for st in res.steps:
         replay.append(c2.update(st.accepted, st.k))
     assert replay[:-1] == res.gammas
+
+
+def test_pair_callables_equal_one_shot_forward_under_rollbacks():
+    """TransformerPair keeps a cache per model and truncates it to the longest prefix it shares with the new token
+    list, always leaving keep_back tokens (1 for the draft, k + 1 for the target) to feed.  Whatever the history of
+    calls — growth, rejected suffixes rolled back, a list shorter than the cache, an unrelated list — every call must
+    return what a cache-free forward of the full list returns (results are defined cache-free)."""
+    cfg = synth.pair("tiny")
+    Wt, Wd = synth.make_pair_weights(cfg, 3)
+    Wtn, Wdn = synth.to_numpy_weights(Wt), synth.to_numpy_weights(Wd)
+    st_, sd_ = oshape(cfg.target), oshape(cfg.draft)
+    pairm = spec.TransformerPair(st_, Wtn, sd_, Wdn)
+    base = synth.make_prompts(1, 14, cfg.target.vocab, 5)[0].tolist()
+    other = synth.make_prompts(1, 14, cfg.target.vocab, 6)[0].tolist()
+    histories = [
+        base[:8],                       # first call: everything is fed
+        base[:9], base[:10],            # growth by one token (draft passes of a step)
+        base[:8] + other[8:11],         # rollback: last two rejected, three new ones
+        base[:8] + other[8:9],          # shorter than the cache, same prefix
+        base[:8] + other[8:9],          # identical list again: keep_back still re-feeds the tail
+        other[:6],                      # unrelated list
+        base[:14],
+    ]
+    for toks in histories:
+        got = pairm.draft_next(toks)
+        want = om.forward(sd_, Wdn, toks)[-1]
+        assert np.max(np.abs(got - want)) < 1e-11
+    for toks, k in [(base[:8], 0), (base[:12], 4), (base[:9] + other[9:12], 2), (base[:9] + other[9:12], 2),
+                    (base[:6], 5), (other[:13], 1), (base[:14], 13)]:
+        got = pairm.target_rows(toks, k)
+        want = om.forward(st_, Wtn, toks)[-(k + 1):]
+        assert got.shape == (k + 1, cfg.target.vocab)
+        assert np.max(np.abs(got - want)) < 1e-11
+
+
+def test_pair_sync_leaves_keep_back_tokens_to_feed():
+    sh = oshape(synth.pair("tiny").target)
+    cache = om.KVCache(sh)
+    have = [1, 2, 3, 4, 5]
+    # same list, keep_back 1: at most len - 1 positions may stay cached
+    assert spec.TransformerPair._sync(cache, have, [1, 2, 3, 4, 5], 1) == 4
+    # keep_back 3: two stay
+    assert spec.TransformerPair._sync(cache, have, [1, 2, 3, 4, 5], 3) == 2
+    # divergence at index 2 wins over keep_back
+    assert spec.TransformerPair._sync(cache, have, [1, 2, 9, 4, 5, 6], 1) == 2
+    # the new list is shorter than keep_back allows: nothing stays
+    assert spec.TransformerPair._sync(cache, have, [1, 2], 3) == 0
+    assert spec.TransformerPair._sync(cache, [], [1, 2, 3], 1) == 0

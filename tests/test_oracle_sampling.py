@@ -252,3 +252,133 @@ def test_early_stop_keeps_the_low_confidence_token():
     cfg3 = spec.StepConfig(temperature=0.0, tau=0.5)
     r3 = spec.speculative_step(tm.draft_next, tm.target_rows, [0], 5, 0, 0, cfg3, 0)
     assert r3.k == 1 and r3.conf[0] == pytest.approx(0.4)
+
+
+# ---- margins: how far a decision is from flipping (the parity tests compare integers only where the
+# margin exceeds the measured float error, so a margin that came out too large would hide a real
+# disagreement and one that came out too small would excuse it) --------------------------------------
+
+def test_top2_gap_hand_values():
+    assert S.top2_gap(np.array([1.0, 3.5, 2.0, 3.0])) == 0.5
+    assert S.top2_gap(np.array([-4.0, -1.5, -9.0])) == 2.5
+    assert S.top2_gap(np.array([2.0, 7.0, 7.0, 1.0])) == 0.0       # tie at the top
+    assert S.top2_gap(np.array([5.0, -5.0])) == 10.0
+    assert S.top2_gap(np.array([3.0])) == float("inf")              # nothing to overtake
+    # brute force: the gap is the smallest raise of a non-top entry that changes (or ties) the argmax
+    rng = np.random.default_rng(0)
+    for _ in range(50):
+        x = rng.normal(size=7)
+        top = int(np.argmax(x))
+        want = min(x[top] - x[j] for j in range(7) if j != top)
+        assert S.top2_gap(x) == pytest.approx(want, abs=0)
+
+
+def test_inverse_cdf_margin_hand_values():
+    # weights (1, 2, 1): W = 4, edges of the CDF at 1, 3, 4; every number below is dyadic, so exact
+    w = np.array([1.0, 2.0, 1.0])
+    assert S.inverse_cdf(w, 0.5) == (1, 0.25)        # u W = 2: 1 above the edge at 1, 1 below the edge at 3
+    assert S.inverse_cdf(w, 0.125) == (0, 0.125)     # u W = 0.5: first cell, only its upper edge counts
+    assert S.inverse_cdf(w, 0.8125) == (2, 0.0625)   # u W = 3.25: 0.25 above the edge at 3
+    assert S.inverse_cdf(w, 0.25) == (1, 0.0)        # exactly on an edge: c_0 > u W fails, next cell, no margin
+    assert S.inverse_cdf(w, 0.3125) == (1, 0.0625)   # u W = 1.25
+    # unnormalised weights give the same answers
+    assert S.inverse_cdf(8.0 * w, 0.8125) == (2, 0.0625)
+
+
+def test_inverse_cdf_margin_is_the_distance_to_a_different_draw():
+    rng = np.random.default_rng(1)
+    for _ in range(200):
+        V = int(rng.integers(2, 9))
+        w = rng.dirichlet(np.ones(V))
+        u = float(rng.random())
+        j, m = S.inverse_cdf(w, u)
+        assert m >= 0.0
+        # moving u by less than the margin keeps the draw
+        for d in (-0.98 * m, 0.98 * m):
+            if 0.0 <= u + d < 1.0:
+                assert S.inverse_cdf(w, u + d)[0] == j
+        # moving it by a little more, towards the nearer edge, changes it (unless that runs off [0, 1))
+        c = np.cumsum(w)
+        lo = c[j - 1] if j > 0 else 0.0
+        down_nearer = j > 0 and (u - lo) <= (c[j] - u)
+        d = -(m + 1e-9) if down_nearer else (m + 1e-9)
+        if 0.0 <= u + d < 1.0 and (down_nearer or j < V - 1):
+            assert S.inverse_cdf(w, u + d)[0] != j
+
+
+def test_accept_margin_hand_values():
+    # u q < p; margin |u q - p| / max(p, q); dyadic numbers, exact
+    assert S.accept_test(0.25, 0.5, 0.25) == (True, 0.25)    # 0.125 < 0.25, distance 0.125 over 0.5
+    assert S.accept_test(0.25, 0.5, 0.75) == (False, 0.25)   # 0.375 >= 0.25
+    assert S.accept_test(0.5, 0.25, 0.5) == (True, 0.75)     # p > q: 0.125 against 0.5
+    assert S.accept_test(0.25, 0.5, 0.5) == (False, 0.0)     # u q == p: refused (strict test), no margin
+    assert S.accept_test(0.0, 0.5, 0.0) == (False, 0.0)
+
+
+def test_accept_margin_bounds_the_relative_change_that_flips():
+    rng = np.random.default_rng(2)
+    for _ in range(300):
+        p, q, u = float(rng.random()), float(rng.random()), float(rng.random())
+        ok, m = S.accept_test(p, q, u)
+        # a relative change of p or q below the margin cannot flip the decision
+        for f in (1 - 0.98 * m, 1 + 0.98 * m):
+            assert S.accept_test(p * f, q, u)[0] == ok
+            assert S.accept_test(p, q * f, u)[0] == ok
+        # where p is the larger of the two, the margin is exactly the relative drop of p that flips it
+        if p >= q and m < 1.0:
+            assert S.accept_test(p * (1 - m - 1e-9), q, u)[0] is False
+
+
+# ---- the synthetic confidence of forced mode -------------------------------------------------------
+
+def _fixed_uniform(values, log):
+    def u(s, i, purpose, b):
+        log.append((s, i, purpose, b))
+        return values[(s, i, purpose, b)] if (s, i, purpose, b) in values else 0.75
+    return u
+
+
+def test_forced_confidence_hand_values():
+    # conf_i = clamp(alpha(g) + (0.5 - u(g, 0, FORCED, b)) / 2, 0, 1) with g = g0 + i - 1: the same draw that decides
+    # the acceptance of position g, so the confidence is high exactly where acceptance is likely
+    tm = _Tables([[0.25] * 4] * 4, [[0.25] * 4] * 4)
+    b, g0 = 3, 10
+    vals = {(10, 0, philox.FORCED, b): 0.25,      # 0.5 + 0.125        = 0.625
+            (11, 0, philox.FORCED, b): 0.0,       # 0.875 + 0.25       = 1.125 -> 1
+            (12, 0, philox.FORCED, b): 0.875,     # 0.125 - 0.1875     < 0     -> 0
+            (13, 0, philox.FORCED, b): 0.5}       # 0.375 + 0          = 0.375
+    alpha = [0.0] * 10 + [0.5, 0.875, 0.125, 0.375]
+    log = []
+    cfg = spec.StepConfig(temperature=1.0, accept_mode=spec.FORCED_MODE, alpha=alpha, tau=0.0)
+    r = spec.speculative_step(tm.draft_next, tm.target_rows, [0], 4, 7, b, cfg, g0, uniform=_fixed_uniform(vals, log))
+    assert r.conf == [0.625, 1.0, 0.0, 0.375]
+    # the confidence of row i reads the counter of generated index g0 + i - 1, row 0, purpose FORCED
+    forced_reads = [c for c in log if c[2] == philox.FORCED]
+    assert set(forced_reads) == set(vals)
+    # acceptance of the same positions: u < alpha -> 0.25 < 0.5 yes, 0 < 0.875 yes, 0.875 < 0.125 no
+    assert r.accepted == 2
+    # GammaTune+ threshold on that signal: tau = 0.7 stops at the first row (0.625 < 0.7), the token is kept
+    cfg_t = spec.StepConfig(temperature=1.0, accept_mode=spec.FORCED_MODE, alpha=alpha, tau=0.7)
+    r2 = spec.speculative_step(tm.draft_next, tm.target_rows, [0], 4, 7, b, cfg_t, g0, uniform=_fixed_uniform(vals, []))
+    assert r2.k == 1 and r2.conf == [0.625] and r2.accepted == 1
+    # tau = 0.5: rows 1 and 2 pass (0.625, 1.0), row 3 stops (0.0)
+    cfg_u = spec.StepConfig(temperature=1.0, accept_mode=spec.FORCED_MODE, alpha=alpha, tau=0.5)
+    r3 = spec.speculative_step(tm.draft_next, tm.target_rows, [0], 4, 7, b, cfg_u, g0, uniform=_fixed_uniform(vals, []))
+    assert r3.k == 3 and r3.accepted == 2
+    stops = [(d.row, d.value) for d in r3.decisions if d.kind == "stop"]
+    assert stops == [(1, 0), (2, 0), (3, 1)]
+    # margins of the stop decisions: |conf - tau| / tau
+    m = [d.margin for d in r3.decisions if d.kind == "stop"]
+    assert m == [0.25, 1.0, 1.0]
+
+
+def test_forced_confidence_with_the_real_generator():
+    # one alpha, one Philox counter: the uniform is the known generator's word 0 >> 8 over 2^24
+    seed, g, b = 5, 2, 1
+    w0 = philox.philox4x32_10((g, 0, philox.FORCED, b), philox.seed_key(seed))[0]
+    u = (w0 >> 8) / 2.0**24
+    tm = _Tables([[0.25] * 4] * 4, [[0.25] * 4] * 4)
+    cfg = spec.StepConfig(temperature=1.0, seed=seed, accept_mode=spec.FORCED_MODE, alpha=[0.5])
+    r = spec.speculative_step(tm.draft_next, tm.target_rows, [0], 1, 0, b, cfg, g)
+    assert r.conf == [min(1.0, max(0.0, 0.5 + (0.5 - u) * 0.5))]
+    assert r.accepted == int(u < 0.5)
