@@ -144,7 +144,8 @@ def _run_pair(cfg, *, controller, temperature, seed=0, n_generate=None, prompt_l
 # as measured on the MI355X, less a margin for a different draw of near-edge uniforms after a kernel change.  (A step
 # below the floor is not a wrong step - every differing decision is still checked for validity - but a drop means
 # the logits error grew.)
-COVERAGE_FLOOR = {"8b-full-depth": 0.0, "8b-q8-full-depth": 0.0, "13b-sweep": 0.0}
+# Measured: 8B pair at full depth 3 of 4 steps clean (bf16 and 8-bit alike), every cell of the 13B-shaped sweep 1.0.
+COVERAGE_FLOOR = {"8b-full-depth": 0.5, "8b-q8-full-depth": 0.5, "13b-sweep": 0.8}
 
 
 def _assert_clean(c, full_coverage=True, min_coverage=0.8):
@@ -424,8 +425,9 @@ def test_1b_pair_natural_acceptance_at_reduced_depth(temperature, tau):
                      accept_mode=0, tau=tau)
     eng.close()
     # greedy decisions have margins (top-1/top-2 gaps of 128256 near-Gaussian logits) far above the measured logit
-    # error; sampled ones sit on CDF cells of width ~1e-5 and mostly differ - validly (checked per decision)
-    _assert_clean(c, full_coverage=False, min_coverage=0.8 if temperature == 0.0 else 0.0)
+    # error; sampled ones sit on CDF cells of width ~1e-5, which two layers' worth of error (6e-5 of max |logit|)
+    # still rarely crosses
+    _assert_clean(c, full_coverage=False, min_coverage=0.8 if temperature == 0.0 else 0.7)  # measured: 1.0 in all four cases
     assert c.steps_total >= 8
     assert c.max_logit_err <= TOL["bf16"]
     if tau > 0:
