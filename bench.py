@@ -37,7 +37,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--pair", default="8b", choices=["tiny", "1b", "7b", "8b", "8b-q8"])
+    ap.add_argument("--pair", default="8b", choices=["tiny", "1b", "7b", "8b", "8b-q8", "13b"])
     ap.add_argument("--alpha", default="piecewise", help="piecewise | a constant such as 0.6")
     ap.add_argument("--controller", default="gammatune+", choices=["gammatune", "gammatune+", "fixed"])
     ap.add_argument("--gamma0", type=int, default=4)
@@ -54,6 +54,18 @@ def parse():
                                                          "(the headline metric is batch 1)")
     ap.add_argument("--prefill-only", action="store_true",
                     help="time --steps prompt ingestions (after --warmup untimed ones) and print the prefill object alone")
+    ap.add_argument("--accept", default="forced", choices=["forced", "natural"],
+                    help="forced: seeded Bernoulli acceptance landscape (--alpha); natural: the accept test u q(x) < p(x)")
+    ap.add_argument("--cpu-full", action="store_true",
+                    help="CPU baseline: time two whole oracle steps at full depth instead of the 0-/1-layer extrapolation "
+                         "(8B pair: about 75 GB of host memory and several minutes)")
+    ap.add_argument("--verify-sweep", action="store_true",
+                    help="verification-only sweep on the --pair's target (default there: 13b): rows x cache length x batch "
+                         "on a seeded synthetic KV cache; prints one JSON object with a cell per combination")
+    ap.add_argument("--sweep-rows", default="1,2,4,8,16")
+    ap.add_argument("--sweep-kv", default="512,1024,2048,4096")
+    ap.add_argument("--sweep-batch", default="1,4,8")
+    ap.add_argument("--sweep-reps", type=int, default=20)
     ap.add_argument("--roofline-only", action="store_true",
                     help="skip the timed generations: prefill, the event-timed decode leg and the reference copy only "
                          "(a short run for profiler counter passes)")
@@ -98,6 +110,143 @@ def make_controller(pk, args, gamma_max):
     return pk.GammaTune(eta=0.25, delta=1, gamma_min=1, gamma_max=gamma_max, gamma0=args.gamma0)
 
 
+def cpu_model_name():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def esz_of(m):
+    return {"bf16": 2, "q8": 1}.get(m.dtype, 4)
+
+
+def proj_shapes(m):
+    """(class id, name, output rows, K) of the weight-streaming launches of one layer and of the LM head; class ids
+    are those of spec_profile_kernel."""
+    qd, kvd = m.n_q_heads * m.head_dim, m.n_kv_heads * m.head_dim
+    return [(1, "QKV", qd + 2 * kvd, m.d_model), (5, "Wo", m.d_model, qd), (3, "gate/up", 2 * m.d_ffn, m.d_model),
+            (6, "down", m.d_model, m.d_ffn), (4, "LM head", m.vocab, m.d_model)]
+
+
+def weight_bytes(m):
+    per_layer = sum(n * k for cls, _, n, k in proj_shapes(m) if cls != 4)
+    return (m.n_layers * per_layer + m.vocab * m.d_model) * esz_of(m)
+
+
+def kv_bytes(m, context):
+    """K and V of `context` positions over all layers (what one pass of one sequence attends to)."""
+    return m.n_layers * 2 * m.n_kv_heads * m.head_dim * context * (4 if m.dtype == "fp32" else 2)
+
+
+def kernel_table(eng, cfg, context, n_tokens, ctrls, decode):
+    """Every kernel class of both models timed over one decode leg with direct launches: projections by the dispatch's
+    own start / stop events, attention (+ merge) by events on the stream around its two launches.  Bytes are the
+    algorithmic ones: the matrix once per launch; for attention the K and V of one layer at the leg's context."""
+    eng.profile_kernel(0, 0)
+    decode(eng, ctrls, n_tokens)
+    rows = []
+    for model, name, m in ((1, "target", cfg.target), (0, "draft", cfg.draft)):
+        for cls, kname, n, k in proj_shapes(m):
+            cnt, ms = eng.profile_read_class(model, cls)
+            if cnt == 0:
+                continue
+            b = n * k * esz_of(m)
+            us = 1e3 * ms / cnt
+            rows.append({"model": name, "kernel": kname, "launches": cnt, "avg_us": us, "bytes": b,
+                         "frac": b / (us * 1e-6) / 1e9 / HBM_PEAK_GBS})
+        cnt, ms = eng.profile_read_class(model, 7)
+        if cnt:
+            b = kv_bytes(m, context) // m.n_layers
+            us = 1e3 * ms / cnt
+            rows.append({"model": name, "kernel": "attention + merge", "launches": cnt, "avg_us": us, "bytes": b,
+                         "frac": b / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, "timing": "stream events around both launches"})
+    eng.profile_read()
+    eng.profile_kernel(0, -1)
+    return rows
+
+
+def verify_sweep(args, pk, torch, synth):
+    """Verification passes alone (Experimental Details' largest Vicuna pair by shape unless --pair says otherwise):
+    rows per sequence x cached positions x sequences, on a seeded synthetic cache; per cell the time of one pass
+    (graph replay, host clock between two synchronisations over --sweep-reps passes) and its algorithmic bytes -
+    every target weight once, the K / V the rows attend to, the logits written - against the HBM peak."""
+    cfg = synth.pair(args.pair)
+    m = cfg.target
+    Wt, Wd = synth.make_pair_weights(synth.shrink(cfg, m.n_layers, 1), 0, device="cuda")
+    torch.cuda.synchronize()
+    rows_list = [int(x) for x in args.sweep_rows.split(",")]
+    kv_list = [int(x) for x in args.sweep_kv.split(",")]
+    b_list = [int(x) for x in args.sweep_batch.split(",")]
+    gamma_max = max(max(rows_list) - 1, 1)
+    cells = []
+    for B in b_list:
+        for kv in kv_list:
+            eng = pk.SpecEngine(m, Wt, synth.shrink(cfg, m.n_layers, 1).draft, Wd, batch=B, max_seq=kv + 2 * gamma_max + 8,
+                                gamma_max=gamma_max, temperature=1.0, seed=0, use_graphs=not args.no_graphs,
+                                attn_chunk=args.attn_chunk)
+            eng.fill_kv(kv)
+            for rows in rows_list:
+                for _ in range(3):
+                    eng.verify_rows(rows)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(args.sweep_reps):
+                    eng.verify_rows(rows)
+                torch.cuda.synchronize()
+                ms = 1e3 * (time.perf_counter() - t0) / args.sweep_reps
+                nbytes = weight_bytes(m) + B * kv_bytes(m, kv + rows) + B * rows * m.vocab * 4
+                gbs = nbytes / (ms * 1e-3) / 1e9
+                # matrix-instruction work of the projections: 2 flop per weight and row, twice over (two bf16 terms of x)
+                mfma_tflops = 2 * 2.0 * B * rows * (weight_bytes(m) / esz_of(m)) / (ms * 1e-3) / 1e12
+                cells.append({"batch": B, "kv_len": kv, "rows_per_seq": rows, "rows": B * rows, "ms": ms, "bytes": nbytes,
+                              "GB/s": gbs, "frac": gbs / HBM_PEAK_GBS, "mfma_tflops_issued": mfma_tflops,
+                              "mfma_frac_of_peak": mfma_tflops / MFMA_BF16_PEAK_TFLOPS})
+                print(f"# sweep batch {B} kv {kv} rows {rows}: {ms:.3f} ms {gbs:.0f} GB/s", file=sys.stderr, flush=True)
+            eng.close()
+    print(json.dumps({"verify_sweep": cells, "peak_GB/s": HBM_PEAK_GBS, "pair": args.pair,
+                      "timing": "host clock around --sweep-reps spec_debug_verify_rows calls between two device synchronisations",
+                      "config": {"workload": f"{args.pair} target {m.n_layers}L d{m.d_model} ffn{m.d_ffn} V{m.vocab}: verification "
+                                             f"passes alone on a seeded synthetic KV cache"}}))
+
+
+def cpu_baseline_full(cfg, Wt, Wd, gamma):
+    """Two whole speculative steps of the fp64 oracle at full depth and width after a 32-token prompt."""
+    import synth
+    from oracle import gammatune as ogt
+    from oracle import model as om
+    from oracle import spec as ospec
+
+    def oshape(ms):
+        return om.Shape(ms.n_layers, ms.d_model, ms.n_q_heads, ms.n_kv_heads, ms.head_dim, ms.d_ffn, ms.vocab, ms.rope_theta,
+                        ms.rms_eps, ms.dtype in ("bf16", "q8"))
+
+    widen = lambda W: {k: ([om.as_f64(a) for a in v] if isinstance(v, list) else om.as_f64(v))
+                       for k, v in synth.to_numpy_weights(W).items()}
+    Wt_np, Wd_np = widen(Wt), widen(Wd)
+    prompt = synth.make_prompts(1, 32, cfg.target.vocab, 11)[0].tolist()
+    pair = ospec.TransformerPair(oshape(cfg.target), Wt_np, oshape(cfg.draft), Wd_np)
+    scfg = ospec.StepConfig(temperature=0.7, seed=0, accept_mode=1, alpha=[0.6])
+    toks = list(prompt)
+    pair.target_rows(toks, 0)  # context, untimed
+    pair.draft_next(toks)
+    t0 = time.time()
+    emitted = 0
+    for s_ in range(2):
+        r = ospec.speculative_step(pair.draft_next, pair.target_rows, toks, gamma, s_, 0, scfg, emitted)
+        toks.extend(r.emitted)
+        emitted += len(r.emitted)
+    dt = time.time() - t0
+    return {"value": emitted / dt, "unit": "tokens/s", "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
+            "kind": "oracle", "cpu": cpu_model_name(),
+            "sample": f"fp64 oracle, full depth and width: two whole speculative steps (gamma {gamma}, forced alpha 0.6) after a "
+                      f"32-token context, {emitted} tokens in {dt:.1f} s"}
+
+
 def cpu_baseline(cfg, Wt, Wd, tokens_per_step, mean_gamma):
     """Time the fp64 oracle at full width on a bounded sample and extrapolate over the layers."""
     import synth
@@ -131,6 +280,7 @@ def cpu_baseline(cfg, Wt, Wd, tokens_per_step, mean_gamma):
         "unit": "tokens/s",
         "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
         "kind": "oracle",
+        "cpu": cpu_model_name(),
         "sample": (f"fp64 oracle, full width: one {gamma + 1}-row target pass and one 1-row draft pass after a 32-token "
                    f"context, timed with 0 and 1 layers (+ embedding, final norm, LM head) and extrapolated linearly to "
                    f"{cfg.target.n_layers}/{cfg.draft.n_layers} layers; step = {gamma} draft passes + 1 target pass, "
@@ -187,6 +337,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.verify_sweep:
+        verify_sweep(args, pk, torch, synth)
+        return
     cfg = synth.pair(args.pair)
     n_gen = args.n_generate or cfg.n_generate
     n_prompt = args.prompt_len or cfg.prompt_len
@@ -206,12 +359,15 @@ def main():
     B = args.batch
     prompts = synth.make_prompts(B, n_prompt, cfg.target.vocab, 7)
 
-    def engine(use_graphs):
+    forced = args.accept == "forced"
+
+    def engine(use_graphs, early_stop=True):
         e = pk.SpecEngine(cfg.target, Wt, cfg.draft, Wd, batch=B, max_seq=max_seq, gamma_max=cfg.gamma_max,
-                          temperature=args.temperature, seed=0, accept_mode=pk.ACCEPT_FORCED, use_graphs=use_graphs,
-                          gemv_path=args.gemv_path, attn_chunk=args.attn_chunk)
-        e.set_forced_alpha(alpha)
-        if tau > 0:
+                          temperature=args.temperature, seed=0, accept_mode=pk.ACCEPT_FORCED if forced else pk.ACCEPT_NATURAL,
+                          use_graphs=use_graphs, gemv_path=args.gemv_path, attn_chunk=args.attn_chunk)
+        if forced:
+            e.set_forced_alpha(alpha)
+        if tau > 0 and early_stop:
             e.set_early_stop(tau)
         return e
 
@@ -288,9 +444,15 @@ def main():
         bytes_per_launch = 2 * cfg.target.d_ffn * cfg.target.d_model * {"bf16": 2, "q8": 1}.get(cfg.target.dtype, 4)
         avg_ms = ms / max(n_launch, 1)
         achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
+        traffic = measured_traffic(args.pair)
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.pair), "kernel": "target gate/up projection + SwiGLU",
-                    "launches": n_launch, "avg_us": avg_ms * 1e3, "bytes_per_launch": bytes_per_launch}
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": "target gate/up projection + SwiGLU",
+                    "launches": n_launch, "avg_us": avg_ms * 1e3, "bytes_per_launch": bytes_per_launch,
+                    "timing": "hip events of the dispatch (kernel start to kernel end), averaged over every launch of the "
+                              "kernel in a decode leg of this run with direct launches",
+                    "traffic_source": (None if traffic is None else
+                                       "stored rocprofv3 FETCH_SIZE / WRITE_SIZE passes (profiles/gemv_gate_up_8b_pmc.json), "
+                                       "not measured in this run; nulled when the kernel's sources change")}
 
     verify_pass = None
     if not args.skip_roofline and B == 1:
@@ -312,20 +474,54 @@ def main():
         m = cfg.target
         qd, kvd = m.n_q_heads * m.head_dim, m.n_kv_heads * m.head_dim
         esz = {"bf16": 2, "q8": 1}.get(m.dtype, 4)
-        w_bytes = (m.n_layers * (m.d_model * (qd + 2 * kvd) + qd * m.d_model + 3 * m.d_model * m.d_ffn) + m.vocab * m.d_model) * esz
-        kv_bytes = m.n_layers * 2 * kvd * (n_prompt + n_pass) * (4 if m.dtype == "fp32" else 2)  # context at the middle of the leg, roughly
+        w_bytes = weight_bytes(m)
+        kv_b = kv_bytes(m, n_prompt + n_pass)  # context at the middle of the leg, roughly
         ms = 1e3 * t_ver / n_pass
-        gbs = (w_bytes + kv_bytes) / (ms * 1e-3) / 1e9
+        gbs = (w_bytes + kv_b) / (ms * 1e-3) / 1e9
         verify_pass = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
-                       "ms": ms, "bytes": w_bytes + kv_bytes, "gamma": g, "passes": n_pass,
+                       "ms": ms, "bytes": w_bytes + kv_b, "gamma": g, "passes": n_pass,
                        "timing": "host clock around spec_verify between two device synchronisations"}
+
+    draft_pass = None
+    kernels = None
+    if not args.skip_roofline and B == 1:
+        # one draft-model decode pass against the HBM roofline: a fixed gamma = 3 without early stopping is one graph
+        # of three passes (the first ingests the one or two pending rows); bytes = every draft weight once + its KV
+        e4 = engine(not args.no_graphs, early_stop=False)
+        e4.prefill(prompts)
+        g, n_rep, t_dr = 3, 48, 0.0
+        for i in range(n_rep + 4):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            e4.draft(g)
+            torch.cuda.synchronize()
+            if i >= 4:
+                t_dr += time.perf_counter() - t0
+            e4.verify(g)
+            e4.accept()
+        e4.close()
+        md = cfg.draft
+        d_bytes = weight_bytes(md) + kv_bytes(md, n_prompt + n_rep)
+        ms = 1e3 * t_dr / (n_rep * g)
+        gbs = d_bytes / (ms * 1e-3) / 1e9
+        draft_pass = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                      "ms": ms, "bytes": d_bytes, "gamma": g, "passes": n_rep * g,
+                      "timing": "host clock around spec_draft (one graph of gamma passes with their samplers) between two "
+                                "device synchronisations, divided by gamma"}
+        # every kernel class of both models over one decode leg (direct launches)
+        e5 = engine(False)
+        e5.prefill(prompts)
+        kernels = kernel_table(e5, cfg, n_prompt + 32, 64, [make_controller(pk, args, cfg.gamma_max) for _ in range(B)],
+                               decode_loop)
+        e5.close()
 
     seq_steps = max(stats.get("seq_steps", stats["spec_steps"]), 1)  # (sequence, speculative step) pairs
     tokens_per_step = stats["generated"] / seq_steps
     mean_gamma = stats["gamma_sum"] / seq_steps
     cpu = None
     if not args.skip_cpu:
-        cpu = cpu_baseline(cfg, Wt, Wd, tokens_per_step, mean_gamma)
+        cpu = (cpu_baseline_full(cfg, Wt, Wd, max(1, int(round(mean_gamma)))) if args.cpu_full
+               else cpu_baseline(cfg, Wt, Wd, tokens_per_step, mean_gamma))
 
     line = {
         "metric": ("generated tokens/s (8B-shaped pair, bs1); verify-pass HBM GB/s % of peak" if (args.pair == "8b" and B == 1)
@@ -337,7 +533,8 @@ def main():
             "workload": (f"{args.pair}: target {cfg.target.n_layers}L d{cfg.target.d_model} ffn{cfg.target.d_ffn} "
                          f"V{cfg.target.vocab}, draft {cfg.draft.n_layers}L d{cfg.draft.d_model}; batch {B}, prompt {n_prompt}, "
                          f"generate {n_gen}; {args.controller} gamma in [1,{cfg.gamma_max}] gamma0 {args.gamma0}, "
-                         f"T={args.temperature}, forced alpha {args.alpha}, tau {tau}; seeded random-init weights"
+                         f"T={args.temperature}, " + (f"forced alpha {args.alpha}" if forced else "natural acceptance")
+                         + f", tau {tau}; seeded random-init weights"
                          + ("; projection matrices and LM head int8 with per-row scales, turned into bf16 in registers"
                             if cfg.target.dtype == "q8" else "")),
             "step": f"one generation of {n_gen} tokens (prefill excluded)",
@@ -348,7 +545,7 @@ def main():
         },
         "roofline": roofline, "cpu_baseline": cpu,
         "prefill": prefill_report(t_prefill / steps) if args.steps > 0 else None,
-        "verify_pass": verify_pass,
+        "verify_pass": verify_pass, "draft_pass": draft_pass, "kernels": kernels,
     }
     print(json.dumps(line))
 

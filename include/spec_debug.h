@@ -54,13 +54,23 @@ int spec_debug_write_kv(spec_ctx *ctx, int32_t model, int32_t layer, int32_t seq
  * a permutation of 0..batch*pages-1.  Must be called before spec_prefill. */
 int spec_debug_set_block_table(spec_ctx *ctx, const int32_t *table);
 
-/* Time one kernel class with HIP event pairs on the context's stream.  model: 0 draft, 1 target.
- * kind: 1 QKV projection, 2 output/down projection with residual, 3 gate/up projection with SwiGLU,
- * 4 LM head; -1 switches timing off.  Only launches made outside captured graphs (use_graphs = 0)
- * are timed.  spec_profile_read() waits for the stream, returns the number of timed launches and the
- * sum of their durations in milliseconds since the last read, and clears the record. */
+/* Time kernel classes with HIP event pairs on the context's stream.  model: 0 draft, 1 target.
+ * kind: 1 QKV projection, 2 output and down projection together, 3 gate/up projection with SwiGLU, 4 LM head,
+ * 5 output projection, 6 down projection, 7 attention with the merge of its chunk partials; 0 times every class of
+ * both models (model is then ignored); -1 switches timing off.  Projections are timed by the dispatch itself (kernel
+ * start to kernel end), class 7 by events recorded on the stream around its two launches.  Only launches made outside
+ * captured graphs (use_graphs = 0) are timed.  spec_profile_read_class() waits for the stream and returns the number
+ * of timed launches of one (model, kind) and the sum of their durations in milliseconds since the last
+ * spec_profile_read(), which returns the same over everything timed and clears the record. */
 int spec_profile_kernel(spec_ctx *ctx, int32_t model, int32_t kind);
+int spec_profile_read_class(spec_ctx *ctx, int32_t model, int32_t kind, int32_t *launches, double *total_ms);
 int spec_profile_read(spec_ctx *ctx, int32_t *launches, double *total_ms);
+
+/* One target verification pass of `rows` rows per sequence (1 <= rows <= gamma_max + 1: the last committed token and
+ * the rows - 1 token slots behind it) on the current state, asynchronous, with no draft phase before it and no accept
+ * after it: the verification-only sweeps over rows, cache length and batch (spec_debug_fill_kv sets up the cache).
+ * The state machine stays where it was; the KV entries of those positions are overwritten. */
+int spec_debug_verify_rows(spec_ctx *ctx, int32_t rows);
 
 /* ---- single kernels on caller buffers (parity tests and roofline measurement) ---------------- */
 

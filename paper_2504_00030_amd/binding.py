@@ -26,7 +26,7 @@ GT_EXPAND_A, GT_LITERAL, GT_SHORT_TERM = 0, 1, 2
 EXPORTS = [
     "spec_init", "spec_prefill", "spec_prefill_ragged", "spec_debug_set_step", "spec_draft", "spec_draft_batch", "spec_verify", "spec_accept",
     "spec_set_forced_alpha", "spec_set_early_stop", "spec_generate", "spec_read_tokens", "spec_debug_logits",
-    "spec_debug_drafted", "spec_debug_read", "spec_debug_fill_kv", "spec_debug_write_kv", "spec_debug_set_block_table", "spec_device_bytes", "spec_profile_kernel", "spec_profile_read", "spec_destroy",
+    "spec_debug_drafted", "spec_debug_read", "spec_debug_fill_kv", "spec_debug_write_kv", "spec_debug_set_block_table", "spec_device_bytes", "spec_profile_kernel", "spec_profile_read", "spec_profile_read_class", "spec_debug_verify_rows", "spec_destroy",
     "spec_strerror", "spec_last_error", "spec_k_gemv", "spec_k_gemv_tiled", "spec_k_gemm_tiled", "spec_k_retile_q8", "spec_k_gemv_tiled_q8", "spec_k_gemm_tiled_q8", "spec_k_retile", "spec_k_copy", "spec_k_philox", "spec_k_accept",
     "gammatune_init", "gammatune_update",
 ]
@@ -106,6 +106,8 @@ def load() -> C.CDLL:
     lib.spec_debug_set_block_table.argtypes = [C.c_void_p, i32p]
     lib.spec_profile_kernel.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     lib.spec_profile_read.argtypes = [C.c_void_p, i32p, C.POINTER(C.c_double)]
+    lib.spec_profile_read_class.argtypes = [C.c_void_p, C.c_int32, C.c_int32, i32p, C.POINTER(C.c_double)]
+    lib.spec_debug_verify_rows.argtypes = [C.c_void_p, C.c_int32]
     lib.spec_generate.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.POINTER(SpecGenStats)]
     lib.spec_device_bytes.argtypes = [C.c_void_p]
     lib.spec_device_bytes.restype = C.c_int64
@@ -332,6 +334,15 @@ class SpecEngine:
         self._chk(self._lib.spec_profile_read(self._ctx, C.byref(n), C.byref(ms)), "spec_profile_read")
         return n.value, ms.value
 
+    def profile_read_class(self, model: int, kind: int):
+        n = C.c_int32()
+        ms = C.c_double()
+        self._chk(self._lib.spec_profile_read_class(self._ctx, model, kind, C.byref(n), C.byref(ms)), "spec_profile_read_class")
+        return n.value, ms.value
+
+    def verify_rows(self, rows: int):
+        self._chk(self._lib.spec_debug_verify_rows(self._ctx, int(rows)), "spec_debug_verify_rows")
+
     def device_bytes(self) -> int:
         return int(self._lib.spec_device_bytes(self._ctx))
 
@@ -458,3 +469,4 @@ def k_accept(p_logits, q_logits, drafted, temperature: float, seed: int, step: i
                               temperature, seed, step, result.data_ptr(), stream)
     if rc != 0:
         raise SpecError(rc, "spec_k_accept")
+

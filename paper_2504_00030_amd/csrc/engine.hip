@@ -109,7 +109,10 @@ struct spec_ctx {
     std::map<int, VerifyGraph> g_verify;
     std::vector<hipGraph_t> graphs;
     // optional timing of one kernel class with event pairs (direct launches only)
+    // timed kernel class (-1: none, 0: every class of both models) and model; classes: 1 QKV, 2 output and down
+    // projection together, 3 gate/up, 4 LM head, 5 output projection, 6 down projection, 7 attention with its merge
     int prof_epi = -1, prof_model = 0;
+    std::vector<int> prof_tag;            // per event pair: 16 * model + class
     bool capturing = false;
     std::vector<hipEvent_t> prof_events;  // start, stop, start, stop, ...
     size_t prof_used = 0;
@@ -401,15 +404,21 @@ struct ProfScope {
     spec_ctx *c;
     bool on, in_dispatch;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
-    ProfScope(spec_ctx *c_, const ModelRT &m, int epi, bool in_dispatch_) : c(c_), on(false), in_dispatch(in_dispatch_) {
-        if (c->prof_epi != epi || c->capturing) return;
-        if ((c->prof_model == 1) != (&m == &c->tgt)) return;
+    ProfScope(spec_ctx *c_, const ModelRT &m, int cls, bool in_dispatch_) : c(c_), on(false), in_dispatch(in_dispatch_) {
+        if (c->prof_epi < 0 || c->capturing) return;
+        const int model = &m == &c->tgt ? 1 : 0;
+        if (c->prof_epi != 0) {
+            const bool hit = c->prof_epi == cls || (c->prof_epi == 2 && (cls == 5 || cls == 6));
+            if (!hit || c->prof_model != model) return;
+        }
         if (c->prof_used + 2 > c->prof_events.size()) {
             hipEvent_t a, b;
             if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
             c->prof_events.push_back(a);
             c->prof_events.push_back(b);
+            c->prof_tag.push_back(0);
         }
+        c->prof_tag[c->prof_used / 2] = 16 * model + cls;
         on = in_dispatch || hipEventRecord(c->prof_events[c->prof_used], c->stream) == hipSuccess;
         if (on && in_dispatch) { ev0 = c->prof_events[c->prof_used]; ev1 = c->prof_events[c->prof_used + 1]; }
     }
@@ -430,8 +439,8 @@ bool use_mfma(const spec_ctx *c, const ModelRT &m, int R) {
 // Launch one fused projection on whichever kernel family serves R rows; `tiled` is the re-tiled
 // copy of the same matrices.  Returns the number of workgroups through *blocks.
 int launch_proj(spec_ctx *c, ModelRT &m, GemvArgs a, int epi, const void *tiled, int Ntot, int *blocks,
-                int *tile_cols) {
-    ProfScope ps_(c, m, epi, use_mfma(c, m, a.R));
+                int *tile_cols, int prof_class = 0) {
+    ProfScope ps_(c, m, prof_class ? prof_class : epi, use_mfma(c, m, a.R));
     // Many rows (prompt ingestion, verification of a batch): the dense-contraction kernel.  Its time hardly depends
     // on the row count.  The weight-streaming kernel beyond the 16 rows of its persistent form is bound by what a
     // compute unit fetches: per 16-row group of W its 32 K bytes (16 K with 8-bit weights) plus the 4 K bytes of
@@ -544,6 +553,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
                 if (nch <= ATT_NC_MAX) { t.chunk = chunk; t.n_chunks = nch; }
                 else t.qb = nullptr;  // capacity beyond the merge of the matrix-core kernel: plain kernel
             }
+            ProfScope ps_(c, m, 7, false);  // events on the stream around both launches (attention and its merge)
             HIPCHK(c, launch_attention(t, s.head_dim, st));
         }
         {   // output projection + residual
@@ -551,7 +561,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             a.w0 = m.wo[l]; a.n0 = d;
             a.xres = m.x; a.g_next = m.ffn_norm[l]; a.xg = m.xg; a.xgb = m.xgb; a.xgb_lo = xgb_lo; a.ssq_out = m.ssq;
             a.wscale = tiled ? m.sc_wo[l] : nullptr;
-            TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wo[l] : nullptr, d, &slots, nullptr));
+            TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wo[l] : nullptr, d, &slots, nullptr, 5));
         }
         {   // gate / up projections + SwiGLU
             GemvArgs a = base(d, m.xg, m.xgb, xgb_lo);
@@ -567,7 +577,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             a.xres = m.x; a.g_next = (l + 1 < s.n_layers) ? m.attn_norm[l + 1] : m.final_norm;
             a.xg = m.xg; a.xgb = m.xgb; a.xgb_lo = xgb_lo; a.ssq_out = m.ssq;
             a.wscale = tiled ? m.sc_wd[l] : nullptr;
-            TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wd[l] : nullptr, d, &slots, nullptr));
+            TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wd[l] : nullptr, d, &slots, nullptr, 6));
         }
     }
     if (lp.want) {
@@ -698,6 +708,79 @@ int prefill_model(spec_ctx *c, ModelRT &m, int n_ingest) {
         TRY(forward(c, m, plan, lp, false));
     }
     return SPEC_OK;
+}
+
+
+// ---- stand-alone accept / resample: scratch layout, kernels and launch sequence shared by its two entry points ----
+struct AcceptScratch {
+    size_t o_ps, o_qs, o_rmax, o_rsum, o_part, o_qsum, o_pm, o_qm, o_pa, o_qa, o_ql, o_qmax, o_rarg, o_tok, o_state,
+        o_ps2, o_pm2, o_pa2, total;
+    int n_tiles, n2;
+};
+constexpr int ACCEPT_TILE = 256;
+
+constexpr size_t accept_scratch_bytes(int k, int vocab) {
+    // mirrors accept_scratch_layout(): every block rounded up to 256 bytes
+    const size_t rp = (size_t)k + 1, rq = (size_t)k, nt = (size_t)((vocab + ACCEPT_TILE - 1) / ACCEPT_TILE), n2 = (nt + 63) / 64;
+    size_t off = 0;
+    const size_t blocks[] = {rp * nt * 8, rq * nt * 8, rp * 8, rp * 8, (size_t)RESID_CHUNKS * 8, rq * 8, rp * nt * 4, rq * nt * 4,
+                             rp * nt * 4, rq * nt * 4, rq * 4, rq * 4, rp * 4, (rp + 1) * 4, 64 * 4, rp * n2 * 8, rp * n2 * 4,
+                             rp * n2 * 4};
+    for (size_t b : blocks) off += (b + 255) & ~(size_t)255;
+    return off;
+}
+
+AcceptScratch accept_scratch_layout(int k, int vocab) {
+    AcceptScratch L{};
+    L.n_tiles = (vocab + ACCEPT_TILE - 1) / ACCEPT_TILE;
+    L.n2 = (L.n_tiles + 63) / 64;
+    const size_t rows_p = (size_t)k + 1, rows_q = (size_t)k, nt = (size_t)L.n_tiles, n2 = (size_t)L.n2;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) & ~(size_t)255; return o; };
+    L.o_ps = take(rows_p * nt * 8); L.o_qs = take(rows_q * nt * 8); L.o_rmax = take(rows_p * 8); L.o_rsum = take(rows_p * 8);
+    L.o_part = take((size_t)RESID_CHUNKS * 8); L.o_qsum = take(rows_q * 8); L.o_pm = take(rows_p * nt * 4);
+    L.o_qm = take(rows_q * nt * 4); L.o_pa = take(rows_p * nt * 4); L.o_qa = take(rows_q * nt * 4); L.o_ql = take(rows_q * 4);
+    L.o_qmax = take(rows_q * 4); L.o_rarg = take(rows_p * 4); L.o_tok = take((rows_p + 1) * 4); L.o_state = take(64 * 4);
+    L.o_ps2 = take(rows_p * n2 * 8); L.o_pm2 = take(rows_p * n2 * 4); L.o_pa2 = take(rows_p * n2 * 4);
+    L.total = off;
+    return L;
+}
+
+// Row partials, their merge, the draft-side statistics and the accept kernels on a zeroed scratch block whose
+// state words and drafted tokens are already in place.  state ints: [0] len = 0, [1] prompt_len = 0, [2] gamma_b,
+// [3] k, [4..7] ctl, [8] resid_row, [9] ticket, [10] A, [11] y, [12] out_A, [13] out_y, [14] out_k.
+hipError_t accept_on_scratch(uint8_t *buf, const AcceptScratch &L, const float *p_logits, const float *q_logits,
+                             const int32_t *drafted, int k, int vocab, float temperature, uint64_t seed, hipStream_t st) {
+    const float inv_t = temperature > 0.f ? 1.f / temperature : 1.f;
+    const int n_tiles = L.n_tiles, n2 = L.n2, tile = ACCEPT_TILE;
+    hipError_t e;
+    int32_t *state = reinterpret_cast<int32_t *>(buf + L.o_state);
+    int32_t *tok = reinterpret_cast<int32_t *>(buf + L.o_tok);
+    float *pm = reinterpret_cast<float *>(buf + L.o_pm), *qm = reinterpret_cast<float *>(buf + L.o_qm);
+    double *ps = reinterpret_cast<double *>(buf + L.o_ps), *qs = reinterpret_cast<double *>(buf + L.o_qs);
+    int32_t *pa = reinterpret_cast<int32_t *>(buf + L.o_pa), *qa = reinterpret_cast<int32_t *>(buf + L.o_qa);
+    if ((e = launch_row_partials(p_logits, k + 1, vocab, tile, inv_t, pm, ps, pa, st)) != hipSuccess) return e;
+    if ((e = launch_row_partials(q_logits, k, vocab, tile, inv_t, qm, qs, qa, st)) != hipSuccess) return e;
+    float *pm2 = reinterpret_cast<float *>(buf + L.o_pm2);
+    double *ps2 = reinterpret_cast<double *>(buf + L.o_ps2);
+    int32_t *pa2 = reinterpret_cast<int32_t *>(buf + L.o_pa2);
+    if ((e = launch_merge_partials(pm, ps, pa, n_tiles, inv_t, pm2, ps2, pa2, k + 1, 1, 0, nullptr, st)) != hipSuccess) return e;
+    float *ql = reinterpret_cast<float *>(buf + L.o_ql), *qmax = reinterpret_cast<float *>(buf + L.o_qmax);
+    double *qsum = reinterpret_cast<double *>(buf + L.o_qsum);
+    if ((e = launch_gather_qstats(q_logits, drafted, k, vocab, qm, qs, qa, n_tiles, inv_t, ql, qmax, qsum, st)) != hipSuccess) return e;
+    AcceptArgs a{};
+    a.st.len = state; a.st.prompt_len = state + 1; a.st.gamma_b = state + 2; a.st.k = state + 3; a.st.ctl = state + 4;
+    a.st.tokens = tok; a.st.max_seq = k + 2; a.st.batch = 1;
+    a.cfg.temperature = temperature; a.cfg.inv_t = inv_t; a.cfg.seed = seed; a.cfg.forced = 0; a.cfg.tau = 0.f;
+    a.cfg.alpha = nullptr; a.cfg.n_alpha = 0;
+    a.gamma = k; a.gamma_max = k; a.vocab = vocab; a.p_logits = p_logits; a.pm = pm; a.ps = ps; a.pa = pa;
+    a.n_tiles = n_tiles; a.tile = tile; a.pm2 = pm2; a.ps2 = ps2; a.pa2 = pa2; a.n2 = n2; a.q_logits = q_logits; a.q_logit = ql; a.q_max = qmax; a.q_sum = qsum;
+    a.row_max = reinterpret_cast<double *>(buf + L.o_rmax); a.row_sum = reinterpret_cast<double *>(buf + L.o_rsum);
+    a.row_arg = reinterpret_cast<int32_t *>(buf + L.o_rarg); a.resid_row = state + 8;
+    a.resid_part = reinterpret_cast<double *>(buf + L.o_part); a.n_resid_chunks = RESID_CHUNKS;
+    a.ticket = reinterpret_cast<uint32_t *>(state + 9);
+    a.A_dev = state + 10; a.y_dev = state + 11; a.out_A = state + 12; a.out_y = state + 13; a.out_k = state + 14;
+    return launch_accept(a, st);
 }
 
 }  // namespace
@@ -1011,18 +1094,8 @@ int spec_draft(spec_ctx *c, int32_t gamma) {
     return spec_draft_batch(c, g.data());
 }
 
-int spec_verify(spec_ctx *c, int32_t gamma) {
-    if (!c) return SPEC_EINVAL;
-    if (c->phase != 2) return fail(c, SPEC_ESTATE, "verify: expected after draft");
-    if (gamma != c->cur_gamma) return fail(c, SPEC_EINVAL, "verify: gamma differs from the draft phase");
-    // sequences that planned different gammas: pack only the rows each of them planned
-    int rows_total = 0;
-    if (c->ragged_ok) {
-        int sum = 0;
-        for (int b = 0; b < c->cfg.batch; ++b) sum += c->h_gamma_plan[b] + 1;
-        if (sum < c->cfg.batch * (gamma + 1)) rows_total = sum;
-    }
-    c->cur_rows = rows_total;
+// Enqueue (or replay the graph of) one verification pass of gamma + 1 rows per sequence, or of rows_total packed rows.
+static int launch_verify(spec_ctx *c, int gamma, int rows_total) {
     if (c->cfg.use_graphs) {
         const int key = rows_total * 128 + gamma;  // gamma <= 64
         auto it = c->g_verify.find(key);
@@ -1035,11 +1108,35 @@ int spec_verify(spec_ctx *c, int32_t gamma) {
         c->t_tile = it->second.tile;
         c->t_ntiles = it->second.ntiles;
         HIPCHK(c, hipGraphLaunch(it->second.exec, c->stream));
-    } else {
-        TRY(enqueue_verify(c, gamma, rows_total));
+        return SPEC_OK;
     }
+    return enqueue_verify(c, gamma, rows_total);
+}
+
+int spec_verify(spec_ctx *c, int32_t gamma) {
+    if (!c) return SPEC_EINVAL;
+    if (c->phase != 2) return fail(c, SPEC_ESTATE, "verify: expected after draft");
+    if (gamma != c->cur_gamma) return fail(c, SPEC_EINVAL, "verify: gamma differs from the draft phase");
+    // sequences that planned different gammas: pack only the rows each of them planned
+    int rows_total = 0;
+    if (c->ragged_ok) {
+        int sum = 0;
+        for (int b = 0; b < c->cfg.batch; ++b) sum += c->h_gamma_plan[b] + 1;
+        if (sum < c->cfg.batch * (gamma + 1)) rows_total = sum;
+    }
+    c->cur_rows = rows_total;
+    TRY(launch_verify(c, gamma, rows_total));
     c->phase = 3;
     return SPEC_OK;
+}
+
+int spec_debug_verify_rows(spec_ctx *c, int32_t rows) {
+    if (!c) return SPEC_EINVAL;
+    if (c->phase != 1) return fail(c, SPEC_ESTATE, "verify_rows: expected after prefill, fill_kv or accept");
+    if (rows < 1 || rows > c->cfg.gamma_max + 1) return fail(c, SPEC_EINVAL, "verify_rows: rows outside 1..gamma_max + 1");
+    for (int b = 0; b < c->cfg.batch; ++b)
+        if (c->h_len[b] - 1 + rows > c->cfg.max_seq) return fail(c, SPEC_ECAP, "verify_rows: rows do not fit max_seq");
+    return launch_verify(c, rows - 1, 0);
 }
 
 int spec_accept(spec_ctx *c, int32_t *n_accepted, int32_t *next_token, int32_t *n_drafted) {
@@ -1234,7 +1331,7 @@ int spec_debug_write_kv(spec_ctx *c, int32_t model, int32_t layer, int32_t seq, 
 int spec_profile_kernel(spec_ctx *c, int32_t model, int32_t kind) {
     if (!c) return SPEC_EINVAL;
     if (model != 0 && model != 1) return fail(c, SPEC_EINVAL, "profile: model must be 0 (draft) or 1 (target)");
-    if (kind < -1 || kind > EPI_LOGITS || kind == EPI_PLAIN) return fail(c, SPEC_EINVAL, "profile: unknown kernel class");
+    if (kind < -1 || kind > 7) return fail(c, SPEC_EINVAL, "profile: unknown kernel class");
     HIPCHK(c, hipStreamSynchronize(c->stream));
     c->prof_epi = kind;
     c->prof_model = model;
@@ -1242,19 +1339,28 @@ int spec_profile_kernel(spec_ctx *c, int32_t model, int32_t kind) {
     return SPEC_OK;
 }
 
-int spec_profile_read(spec_ctx *c, int32_t *launches, double *total_ms) {
+int spec_profile_read_class(spec_ctx *c, int32_t model, int32_t kind, int32_t *launches, double *total_ms) {
     if (!c || !launches || !total_ms) return fail(c, SPEC_EINVAL, "profile_read: null pointer");
     HIPCHK(c, hipStreamSynchronize(c->stream));
     double tot = 0.0;
+    int n = 0;
     for (size_t i = 0; i + 1 < c->prof_used; i += 2) {
+        const int tag = c->prof_tag[i / 2];
+        if (kind >= 0 && tag != 16 * model + kind) continue;
         float ms = 0.f;
         HIPCHK(c, hipEventElapsedTime(&ms, c->prof_events[i], c->prof_events[i + 1]));
         tot += ms;
+        n += 1;
     }
-    *launches = (int32_t)(c->prof_used / 2);
+    *launches = n;
     *total_ms = tot;
-    c->prof_used = 0;
     return SPEC_OK;
+}
+
+int spec_profile_read(spec_ctx *c, int32_t *launches, double *total_ms) {
+    const int rc = spec_profile_read_class(c, 0, -1, launches, total_ms);
+    if (rc == SPEC_OK) c->prof_used = 0;
+    return rc;
 }
 
 // ---- single kernels -------------------------------------------------------------------------------
@@ -1372,58 +1478,18 @@ int spec_k_accept(const float *p_logits, const float *q_logits, const int32_t *d
     if (!p_logits || !q_logits || !drafted || !result || k < 1 || k > 64 || vocab < 2 || !(temperature >= 0.f))
         return SPEC_EINVAL;
     const hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    const int tile = 256;
-    const int n_tiles = (vocab + tile - 1) / tile;
-    const float inv_t = temperature > 0.f ? 1.f / temperature : 1.f;
-    // one scratch block: everything below is carved from it
-    const size_t rows_p = (size_t)k + 1, rows_q = (size_t)k;
-    size_t off = 0;
-    auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) & ~(size_t)255; return o; };
-    const size_t o_ps = take(rows_p * n_tiles * 8), o_qs = take(rows_q * n_tiles * 8), o_rmax = take(rows_p * 8),
-                 o_rsum = take(rows_p * 8), o_part = take(RESID_CHUNKS * 8), o_qsum = take(rows_q * 8),
-                 o_pm = take(rows_p * n_tiles * 4), o_qm = take(rows_q * n_tiles * 4), o_pa = take(rows_p * n_tiles * 4),
-                 o_qa = take(rows_q * n_tiles * 4), o_ql = take(rows_q * 4), o_qmax = take(rows_q * 4),
-                 o_rarg = take(rows_p * 4), o_tok = take((rows_p + 1) * 4), o_state = take(64 * 4);
-    const int n2 = (n_tiles + 63) / 64;
-    const size_t o_ps2 = take(rows_p * n2 * 8), o_pm2 = take(rows_p * n2 * 4), o_pa2 = take(rows_p * n2 * 4);
+    const AcceptScratch L = accept_scratch_layout(k, vocab);
     uint8_t *buf = nullptr;
-    if (hipMalloc(reinterpret_cast<void **>(&buf), off) != hipSuccess) return SPEC_ENOMEM;
+    if (hipMalloc(reinterpret_cast<void **>(&buf), L.total) != hipSuccess) return SPEC_ENOMEM;
     int rc = SPEC_OK;
     auto ok = [&](hipError_t e) { if (e != hipSuccess && rc == SPEC_OK) rc = SPEC_EHIP; return e == hipSuccess; };
-    ok(hipMemsetAsync(buf, 0, off, st));
-    int32_t *state = reinterpret_cast<int32_t *>(buf + o_state);
-    // state ints: [0] len = 0, [1] prompt_len = 0, [2] gamma_b, [3] k, [4..7] ctl, [8] resid_row, [9] ticket,
-    //             [10] A, [11] y, [12] out_A, [13] out_y, [14] out_k
+    ok(hipMemsetAsync(buf, 0, L.total, st));
+    int32_t *state = reinterpret_cast<int32_t *>(buf + L.o_state);
     const int32_t init[16] = {0, 0, k, k, step, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     ok(hipMemcpyAsync(state, init, sizeof(init), hipMemcpyHostToDevice, st));
     ok(hipStreamSynchronize(st));  // `init` lives on this stack frame
-    int32_t *tok = reinterpret_cast<int32_t *>(buf + o_tok);
-    ok(hipMemcpyAsync(tok, drafted, sizeof(int32_t) * k, hipMemcpyDeviceToDevice, st));
-    float *pm = reinterpret_cast<float *>(buf + o_pm), *qm = reinterpret_cast<float *>(buf + o_qm);
-    double *ps = reinterpret_cast<double *>(buf + o_ps), *qs = reinterpret_cast<double *>(buf + o_qs);
-    int32_t *pa = reinterpret_cast<int32_t *>(buf + o_pa), *qa = reinterpret_cast<int32_t *>(buf + o_qa);
-    ok(launch_row_partials(p_logits, k + 1, vocab, tile, inv_t, pm, ps, pa, st));
-    ok(launch_row_partials(q_logits, k, vocab, tile, inv_t, qm, qs, qa, st));
-    float *pm2 = reinterpret_cast<float *>(buf + o_pm2);
-    double *ps2 = reinterpret_cast<double *>(buf + o_ps2);
-    int32_t *pa2 = reinterpret_cast<int32_t *>(buf + o_pa2);
-    ok(launch_merge_partials(pm, ps, pa, n_tiles, inv_t, pm2, ps2, pa2, k + 1, 1, 0, nullptr, st));
-    float *ql = reinterpret_cast<float *>(buf + o_ql), *qmax = reinterpret_cast<float *>(buf + o_qmax);
-    double *qsum = reinterpret_cast<double *>(buf + o_qsum);
-    ok(launch_gather_qstats(q_logits, drafted, k, vocab, qm, qs, qa, n_tiles, inv_t, ql, qmax, qsum, st));
-    AcceptArgs a{};
-    a.st.len = state; a.st.prompt_len = state + 1; a.st.gamma_b = state + 2; a.st.k = state + 3; a.st.ctl = state + 4;
-    a.st.tokens = tok; a.st.max_seq = k + 2; a.st.batch = 1;
-    a.cfg.temperature = temperature; a.cfg.inv_t = inv_t; a.cfg.seed = seed; a.cfg.forced = 0; a.cfg.tau = 0.f;
-    a.cfg.alpha = nullptr; a.cfg.n_alpha = 0;
-    a.gamma = k; a.gamma_max = k; a.vocab = vocab; a.p_logits = p_logits; a.pm = pm; a.ps = ps; a.pa = pa;
-    a.n_tiles = n_tiles; a.tile = tile; a.pm2 = pm2; a.ps2 = ps2; a.pa2 = pa2; a.n2 = n2; a.q_logits = q_logits; a.q_logit = ql; a.q_max = qmax; a.q_sum = qsum;
-    a.row_max = reinterpret_cast<double *>(buf + o_rmax); a.row_sum = reinterpret_cast<double *>(buf + o_rsum);
-    a.row_arg = reinterpret_cast<int32_t *>(buf + o_rarg); a.resid_row = state + 8;
-    a.resid_part = reinterpret_cast<double *>(buf + o_part); a.n_resid_chunks = RESID_CHUNKS;
-    a.ticket = reinterpret_cast<uint32_t *>(state + 9);
-    a.A_dev = state + 10; a.y_dev = state + 11; a.out_A = state + 12; a.out_y = state + 13; a.out_k = state + 14;
-    ok(launch_accept(a, st));
+    ok(hipMemcpyAsync(buf + L.o_tok, drafted, sizeof(int32_t) * k, hipMemcpyDeviceToDevice, st));
+    ok(accept_on_scratch(buf, L, p_logits, q_logits, drafted, k, vocab, temperature, seed, st));
     ok(hipMemcpyAsync(result, state + 12, sizeof(int32_t) * 2, hipMemcpyDeviceToDevice, st));
     ok(hipStreamSynchronize(st));
     (void)hipFree(buf);

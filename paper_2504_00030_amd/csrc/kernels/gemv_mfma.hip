@@ -255,15 +255,27 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 
 //   WQ: 1 = 8-bit weights (q8.hpp): a tile spans 64 k and feeds two matrix instructions, so a wave holds KTW x
 //   fragments for KTW / 2 tiles.
-template <int EPI, int KTW, int TERMS, int WQ>
+//   RAG: 1 = K is not a multiple of 512 (the 768-wide draft models): the last round of k-tiles exists only for the
+//   first waves; the test is on the scalar wave index, so every branch around a matrix instruction stays scalar.
+constexpr int persist_burst(int tpw, int frags) {
+    // tiles per burst of loads: a divisor of the wave's tiles per group, at most 8 KiB per wave, less where the x
+    // fragments already take 64 registers or more
+    const int cap = frags >= 20 ? 5 : (frags >= 16 ? 4 : 8);
+    int ub = 1;
+    for (int d = 1; d <= cap; ++d)
+        if (tpw % d == 0) ub = d;
+    return ub;
+}
+
+template <int EPI, int KTW, int TERMS, int WQ, int RAG>
 __global__ __launch_bounds__(PW * 64) void gemv_persist_k(const GemvArgs a) {
     if (a.active != nullptr && *a.active == 0) return;
     constexpr int NT = PW * 64;
     constexpr int TPW = KTW >> WQ;         // weight tiles per wave and group
-    // tiles per burst of loads: 8 KiB per wave, 4 where 64 registers already hold x fragments
-    constexpr int UB = KTW * TERMS >= 16 ? 4 : (TPW < 8 ? TPW : 8);
+    constexpr int UB = persist_burst(TPW, KTW * TERMS);
     constexpr int NB = TPW / UB;           // bursts per group
     static_assert(TPW % UB == 0, "bursts tile the wave's k-tiles");
+    static_assert(!(RAG && WQ), "8-bit weights come in whole rounds");
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     int Ntot = a.n0;
     if (EPI == EPI_QKV) Ntot = (a.nq + 2 * a.nkv) * a.hd;
@@ -271,8 +283,10 @@ __global__ __launch_bounds__(PW * 64) void gemv_persist_k(const GemvArgs a) {
     const int n_groups = Ntot >> 4;
     const int G = gridDim.x, b = blockIdx.x;
     const int n_my = (n_groups - b + G - 1) / G;  // host: G <= n_groups
-    const int K = a.K, KT = K >> (5 + WQ);        // tiles per group; host: KT == PW * TPW
+    const int K = a.K, KT = K >> (5 + WQ);        // tiles per group; host: PW * (TPW - 1) < KT <= PW * TPW, == unless RAG
     const int R = a.R;
+    // tile j of this wave exists (always, unless K leaves the last round short)
+    auto live = [&](int j) { return !RAG || wave + PW * j < KT; };
 
     __shared__ float part[PW * 256];
     __shared__ float tile[16 * 17];
@@ -298,7 +312,7 @@ __global__ __launch_bounds__(PW * 64) void gemv_persist_k(const GemvArgs a) {
             xh[j] = u32x4_t{0u, 0u, 0u, 0u};
             if (TERMS == 2) xl[j] = u32x4_t{0u, 0u, 0u, 0u};
             const size_t ko = WQ ? (size_t)(j >> 1) * PW * 64 + (j & 1) * 8 : (size_t)j * PW * 32;
-            if (row_ok) {
+            if (row_ok && live(j)) {
                 xh[j] = *reinterpret_cast<const u32x4_t *>(xp + ko);
                 if (TERMS == 2) xl[j] = *reinterpret_cast<const u32x4_t *>(xp + a.xb_lo + ko);
             }
@@ -309,7 +323,8 @@ __global__ __launch_bounds__(PW * 64) void gemv_persist_k(const GemvArgs a) {
     const size_t gstride = (size_t)G * KT * 64;  // in 16-byte units, between two groups of this workgroup
     u32x4_t bw[UB];
 #pragma unroll
-    for (int u = 0; u < UB; ++u) bw[u] = __builtin_nontemporal_load(wp + (size_t)u * PW * 64);
+    for (int u = 0; u < UB; ++u)
+        if (live(u)) bw[u] = __builtin_nontemporal_load(wp + (size_t)u * PW * 64);
 
     // what the residual / QKV epilogues read besides the tile is fetched ahead of the matrix instructions (these
     // loads are older than the next group's weight loads, so waiting for them does not drain the stream)
@@ -329,11 +344,13 @@ __global__ __launch_bounds__(PW * 64) void gemv_persist_k(const GemvArgs a) {
             for (int u = 0; u < UB; ++u) {
                 const int t = nb * UB + u;
                 if constexpr (WQ == 0) {
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xh[t]),
-                                                                  __builtin_bit_cast(bf16x8_t, bw[u]), acc, 0, 0, 0);
-                    if (TERMS == 2)
-                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xl[t]),
+                    if (live(t)) {
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xh[t]),
                                                                       __builtin_bit_cast(bf16x8_t, bw[u]), acc, 0, 0, 0);
+                        if (TERMS == 2)
+                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xl[t]),
+                                                                          __builtin_bit_cast(bf16x8_t, bw[u]), acc, 0, 0, 0);
+                    }
                 } else {
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
@@ -349,10 +366,12 @@ __global__ __launch_bounds__(PW * 64) void gemv_persist_k(const GemvArgs a) {
             // next burst: the rest of this group, or the head of the next one
             if (nb + 1 < NB) {
 #pragma unroll
-                for (int u = 0; u < UB; ++u) bw[u] = __builtin_nontemporal_load(wp + (size_t)((nb + 1) * UB + u) * PW * 64);
+                for (int u = 0; u < UB; ++u)
+                    if (live((nb + 1) * UB + u)) bw[u] = __builtin_nontemporal_load(wp + (size_t)((nb + 1) * UB + u) * PW * 64);
             } else if (i + 1 < n_my) {
 #pragma unroll
-                for (int u = 0; u < UB; ++u) bw[u] = __builtin_nontemporal_load(wp + gstride + (size_t)u * PW * 64);
+                for (int u = 0; u < UB; ++u)
+                    if (live(u)) bw[u] = __builtin_nontemporal_load(wp + gstride + (size_t)u * PW * 64);
             }
         }
         wp += gstride;
@@ -570,6 +589,19 @@ int gemv_mfma_groups_per_wg(int epi, int Ntot, int K, int R, int forced, bool q8
 // nothing of the launch path in between).
 struct LaunchEvents { hipEvent_t start, stop; };
 
+// Compute units of the current device, read once per device (the persistent kernel launches one workgroup per unit).
+static int compute_units() {
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
 template <int EPI, int NG, int MB, int NW>
 static hipError_t launch_one(const GemvArgs &a, int blocks, LaunchEvents ev, hipStream_t s) {
     if constexpr (NW * MB * NG <= 32) {
@@ -594,30 +626,49 @@ static hipError_t launch_mb(const GemvArgs &a, int MB, int blocks, LaunchEvents 
 }
 
 // The persistent kernel serves one 16-row block of x whose fragments fit the registers of a 16-wave workgroup:
-// K = 512 KTW with KTW x (1 or 2 fragments) <= 16.
+// K <= 512 KTW with KTW x (1 or 2 fragments) <= 20, KTW in {2, 3, 4, 6, 8, 10, 16} (the 768-, 1536-, 2048-, 3072-,
+// 4096-, 5120- and 8192-wide projections of the model shapes at hand; K = 768 fills its second round half).
 static int persist_terms(const GemvArgs &a) { return (a.xb_lo != 0 && a.R > 8) ? 2 : 1; }
+static int persist_ktw(const GemvArgs &a) { return (a.K / 32 + PW - 1) / PW; }
 static bool persist_fits(const GemvArgs &a) {
-    if (a.R > 16 || a.K % 512) return false;
-    if (a.wscale != nullptr && a.K % 1024) return false;  // 8-bit tiles span 64 k: 16 waves x 64
-    const int ktw = a.K / 512;
-    if (ktw != 4 && ktw != 8 && ktw != 16) return false;
-    return ktw * persist_terms(a) <= 16;
+    if (a.R > 16 || a.K % 32) return false;
+    const int ktw = persist_ktw(a);
+    const bool ragged = a.K % 512 != 0;
+    if (a.wscale != nullptr) {  // 8-bit tiles span 64 k: 16 waves x 64, whole rounds only
+        if (a.K % 1024 || (ktw != 4 && ktw != 8 && ktw != 16)) return false;
+    } else {
+        if (ktw != 2 && ktw != 3 && ktw != 4 && ktw != 6 && ktw != 8 && ktw != 10 && ktw != 16) return false;
+        if (ragged && ktw != 2) return false;
+    }
+    return ktw * persist_terms(a) <= 20;
 }
 
-template <int EPI, int KTW, int TERMS, int WQ>
+template <int EPI, int KTW, int TERMS, int WQ, int RAG = 0>
 static hipError_t launch_persist_one(const GemvArgs &a, int n_groups, LaunchEvents ev, hipStream_t s) {
-    const int G = n_groups < 256 ? n_groups : 256;  // one workgroup per compute unit
+    const int cus = compute_units();
+    const int G = n_groups < cus ? n_groups : cus;  // one workgroup per compute unit
     if (ev.start != nullptr)
-        hipExtLaunchKernelGGL((gemv_persist_k<EPI, KTW, TERMS, WQ>), dim3(G), dim3(PW * 64), 0, s, ev.start, ev.stop, 0, a);
+        hipExtLaunchKernelGGL((gemv_persist_k<EPI, KTW, TERMS, WQ, RAG>), dim3(G), dim3(PW * 64), 0, s, ev.start, ev.stop, 0, a);
     else
-        hipLaunchKernelGGL((gemv_persist_k<EPI, KTW, TERMS, WQ>), dim3(G), dim3(PW * 64), 0, s, a);
+        hipLaunchKernelGGL((gemv_persist_k<EPI, KTW, TERMS, WQ, RAG>), dim3(G), dim3(PW * 64), 0, s, a);
     return hipGetLastError();
 }
 
 template <int EPI, int WQ>
 static hipError_t launch_persist(const GemvArgs &a, int n_groups, LaunchEvents ev, hipStream_t s) {
-    const int ktw = a.K / 512;
-    if (persist_terms(a) == 2) {
+    const int ktw = persist_ktw(a);
+    const bool two = persist_terms(a) == 2;
+    if constexpr (WQ == 0) {
+        if (a.K % 512) return two ? launch_persist_one<EPI, 2, 2, 0, 1>(a, n_groups, ev, s) : launch_persist_one<EPI, 2, 1, 0, 1>(a, n_groups, ev, s);
+        switch (ktw) {
+            case 2: return two ? launch_persist_one<EPI, 2, 2, 0>(a, n_groups, ev, s) : launch_persist_one<EPI, 2, 1, 0>(a, n_groups, ev, s);
+            case 3: return two ? launch_persist_one<EPI, 3, 2, 0>(a, n_groups, ev, s) : launch_persist_one<EPI, 3, 1, 0>(a, n_groups, ev, s);
+            case 6: return two ? launch_persist_one<EPI, 6, 2, 0>(a, n_groups, ev, s) : launch_persist_one<EPI, 6, 1, 0>(a, n_groups, ev, s);
+            case 10: return two ? launch_persist_one<EPI, 10, 2, 0>(a, n_groups, ev, s) : launch_persist_one<EPI, 10, 1, 0>(a, n_groups, ev, s);
+            default: break;
+        }
+    }
+    if (two) {
         if (ktw == 4) return launch_persist_one<EPI, 4, 2, WQ>(a, n_groups, ev, s);
         return launch_persist_one<EPI, 8, 2, WQ>(a, n_groups, ev, s);
     }
