@@ -129,6 +129,20 @@ int spec_k_accept(const float *p_logits, const float *q_logits, const int32_t *d
                   int32_t vocab, float temperature, uint64_t seed, int32_t step, int32_t *result,
                   void *stream);
 
+/* For callers that cannot allocate device memory - code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc: spec_k_accept with its scratch (tile partials of the k + 1 target rows and k draft rows, row
+ * statistics, step state: 256-byte blocks, about 2.1 MiB at the limits) in a fixed device array of the library
+ * instead of a hipMalloc'ed block.  Same arguments and the same result as spec_k_accept; limits k <= 64 and
+ * vocab <= 262144 (SPEC_EINVAL with a message in spec_last_error(NULL) beyond them).  Calls no hipMalloc / hipFree
+ * and no routine that allocates; every step is a kernel launch on `stream` (no memset or copy nodes), and the call
+ * does NOT synchronise: `result` is valid once the stream has passed the call's last kernel.  The array (one copy
+ * per GPU, held until the process ends) is shared by every call on that GPU and keeps the last call's contents; the
+ * call clears what it uses first.  Calls that overlap on one GPU (different streams, or several threads) race on
+ * it: serialise them. */
+int spec_k_accept_static(const float *p_logits, const float *q_logits, const int32_t *drafted, int32_t k,
+                         int32_t vocab, float temperature, uint64_t seed, int32_t step, int32_t *result,
+                         void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,7 +27,7 @@ EXPORTS = [
     "spec_init", "spec_prefill", "spec_prefill_ragged", "spec_debug_set_step", "spec_draft", "spec_draft_batch", "spec_verify", "spec_accept",
     "spec_set_forced_alpha", "spec_set_early_stop", "spec_generate", "spec_read_tokens", "spec_debug_logits",
     "spec_debug_drafted", "spec_debug_read", "spec_debug_fill_kv", "spec_debug_write_kv", "spec_debug_set_block_table", "spec_device_bytes", "spec_profile_kernel", "spec_profile_read", "spec_profile_read_class", "spec_debug_verify_rows", "spec_destroy",
-    "spec_strerror", "spec_last_error", "spec_k_gemv", "spec_k_gemv_tiled", "spec_k_gemm_tiled", "spec_k_retile_q8", "spec_k_gemv_tiled_q8", "spec_k_gemm_tiled_q8", "spec_k_retile", "spec_k_copy", "spec_k_philox", "spec_k_accept",
+    "spec_strerror", "spec_last_error", "spec_k_gemv", "spec_k_gemv_tiled", "spec_k_gemm_tiled", "spec_k_retile_q8", "spec_k_gemv_tiled_q8", "spec_k_gemm_tiled_q8", "spec_k_retile", "spec_k_copy", "spec_k_philox", "spec_k_accept", "spec_k_accept_static",
     "gammatune_init", "gammatune_update",
 ]
 
@@ -133,6 +133,7 @@ def load() -> C.CDLL:
     lib.spec_k_philox.argtypes = [C.c_uint64, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
     lib.spec_k_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_uint64,
                                   C.c_int32, C.c_void_p, C.c_void_p]
+    lib.spec_k_accept_static.argtypes = lib.spec_k_accept.argtypes
     lib.gammatune_init.argtypes = [C.POINTER(GtState), C.POINTER(GtParams), C.c_int32]
     lib.gammatune_update.argtypes = [C.POINTER(GtState), C.c_int32, C.c_int32]
     lib.gammatune_update.restype = C.c_int32
@@ -470,3 +471,11 @@ def k_accept(p_logits, q_logits, drafted, temperature: float, seed: int, step: i
     if rc != 0:
         raise SpecError(rc, "spec_k_accept")
 
+
+def k_accept_static(p_logits, q_logits, drafted, temperature: float, seed: int, step: int, result, stream: int = 0):
+    """spec_k_accept_static: as k_accept, scratch in the library's fixed device array, asynchronous on `stream`."""
+    k = q_logits.shape[0]
+    rc = load().spec_k_accept_static(p_logits.data_ptr(), q_logits.data_ptr(), drafted.data_ptr(), k, p_logits.shape[1],
+                                     temperature, seed, step, result.data_ptr(), stream)
+    if rc != 0:
+        raise SpecError(rc, "spec_k_accept_static", load().spec_last_error(None).decode())

@@ -17,6 +17,7 @@
 #include <cstring>
 #include <chrono>
 #include <map>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -783,6 +784,67 @@ hipError_t accept_on_scratch(uint8_t *buf, const AcceptScratch &L, const float *
     return launch_accept(a, st);
 }
 
+// Scratch of spec_k_accept_static: one array per GPU the library runs on, held until the process ends; sized for
+// the largest call the entry point admits.  Host code never uses the array's name as an address: the device
+// address is looked up once per device (accept_static_scratch) and passed to the kernels like any other buffer.
+constexpr int SPEC_ACCEPT_STATIC_MAX_K = 64;
+constexpr int SPEC_ACCEPT_STATIC_MAX_VOCAB = 262144;
+constexpr size_t ACCEPT_STATIC_BYTES = accept_scratch_bytes(SPEC_ACCEPT_STATIC_MAX_K, SPEC_ACCEPT_STATIC_MAX_VOCAB);
+static __device__ __align__(256) unsigned char g_accept_scratch[ACCEPT_STATIC_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+uint8_t *g_scratch_ptr[MAX_DEVICES] = {};
+
+// Device address of the current device's copy of the array (looked up on the first call per device).
+int accept_static_scratch(uint8_t **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return fail(nullptr, SPEC_EHIP, "accept_static: no current device");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_accept_scratch));
+        if (e != hipSuccess || p == nullptr)
+            return fail(nullptr, SPEC_EHIP, std::string("accept_static: hipGetSymbolAddress: ") + hipGetErrorString(e));
+        g_scratch_ptr[dev] = reinterpret_cast<uint8_t *>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return SPEC_OK;
+}
+
+// Start state of one stand-alone accept call in its scratch block: the first n16 16-byte words are zeroed, except
+// the state words (gamma_b = k, drafted count = k, step ordinal) and the token slots (the drafted tokens), which the
+// threads that would otherwise zero them write instead, so that no word has two writers.  A kernel rather than a
+// memset and copies: the caller may be capturing the stream.
+__global__ __launch_bounds__(256) void accept_scratch_init_k(uint4 *buf, int n16, int32_t *state, int32_t *tok,
+                                                             const int32_t *drafted, int k, int step) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    const uint4 *s16 = reinterpret_cast<const uint4 *>(state), *t16 = reinterpret_cast<const uint4 *>(tok);
+    const int s_first = (int)(s16 - buf), t_first = (int)(t16 - buf);
+    if (i >= n16) return;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (i >= s_first && i < s_first + 4) {
+        int32_t w[4] = {0, 0, 0, 0};
+        for (int j = 0; j < 4; ++j) {
+            const int idx = (i - s_first) * 4 + j;
+            w[j] = idx == 2 || idx == 3 ? k : (idx == 4 ? step : 0);
+        }
+        v = make_uint4((uint32_t)w[0], (uint32_t)w[1], (uint32_t)w[2], (uint32_t)w[3]);
+    } else if (i >= t_first && i < t_first + (k + 3) / 4) {
+        int32_t w[4];
+        for (int j = 0; j < 4; ++j) {
+            const int idx = (i - t_first) * 4 + j;
+            w[j] = idx < k ? drafted[idx] : 0;
+        }
+        v = make_uint4((uint32_t)w[0], (uint32_t)w[1], (uint32_t)w[2], (uint32_t)w[3]);
+    }
+    buf[i] = v;
+}
+
+__global__ void accept_result_k(const int32_t *out, int32_t *result) {
+    if (threadIdx.x < 2) result[threadIdx.x] = out[threadIdx.x];
+}
+
 }  // namespace
 
 extern "C" {
@@ -841,6 +903,11 @@ int spec_init(const spec_shape *t, const spec_weights *tw, const spec_shape *d, 
         c->own_stream = true;
     }
     int rc;
+    {   // the fixed scratch array of spec_k_accept_static: its address on this device is looked up at set-up, so that
+        // a first call made under stream capture finds it ready
+        uint8_t *scratch = nullptr;
+        if ((rc = accept_static_scratch(&scratch))) return bail(rc);
+    }
     if ((rc = check_shape(c, *t, "target")) || (rc = check_shape(c, *d, "draft")) ||
         (rc = check_weights(c, *t, tw, "target")) || (rc = check_weights(c, *d, dw, "draft")))
         return bail(rc);
@@ -1494,6 +1561,31 @@ int spec_k_accept(const float *p_logits, const float *q_logits, const int32_t *d
     ok(hipStreamSynchronize(st));
     (void)hipFree(buf);
     return rc;
+}
+
+int spec_k_accept_static(const float *p_logits, const float *q_logits, const int32_t *drafted, int32_t k, int32_t vocab,
+                         float temperature, uint64_t seed, int32_t step, int32_t *result, void *stream) {
+    if (!p_logits || !q_logits || !drafted || !result || k < 1 || !(temperature >= 0.f)) return fail(nullptr, SPEC_EINVAL, "accept_static: bad arguments");
+    if (k > SPEC_ACCEPT_STATIC_MAX_K || vocab < 2 || vocab > SPEC_ACCEPT_STATIC_MAX_VOCAB)
+        return fail(nullptr, SPEC_EINVAL, "accept_static: k beyond 64 or vocab beyond 262144: the fixed scratch array does not hold it");
+    const AcceptScratch L = accept_scratch_layout(k, vocab);
+    if (L.total > sizeof(g_accept_scratch)) return fail(nullptr, SPEC_EINVAL, "accept_static: scratch layout exceeds the fixed array");
+    uint8_t *buf = nullptr;
+    const int rc0 = accept_static_scratch(&buf);
+    if (rc0 != SPEC_OK) return rc0;
+    const hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    // every call on this GPU shares the array, which still holds the last call's contents: clear what this call
+    // uses, by a kernel (a caller may be capturing the stream into a graph), and set the step state
+    const int n16 = (int)(L.total / 16);
+    hipLaunchKernelGGL(accept_scratch_init_k, dim3((n16 + 255) / 256), dim3(256), 0, st, reinterpret_cast<uint4 *>(buf), n16,
+                       reinterpret_cast<int32_t *>(buf + L.o_state), reinterpret_cast<int32_t *>(buf + L.o_tok), drafted,
+                       (int)k, (int)step);
+    if (hipGetLastError() != hipSuccess) return fail(nullptr, SPEC_EHIP, "accept_static: launch failed");
+    if (accept_on_scratch(buf, L, p_logits, q_logits, drafted, k, vocab, temperature, seed, st) != hipSuccess)
+        return fail(nullptr, SPEC_EHIP, "accept_static: launch failed");
+    hipLaunchKernelGGL(accept_result_k, dim3(1), dim3(64), 0, st, reinterpret_cast<const int32_t *>(buf + L.o_state) + 12, result);
+    if (hipGetLastError() != hipSuccess) return fail(nullptr, SPEC_EHIP, "accept_static: launch failed");
+    return SPEC_OK;
 }
 
 }  // extern "C"
