@@ -50,6 +50,8 @@ struct ModelRT {
     std::vector<float *> sc_qkv, sc_wo, sc_gu, sc_wd;  // their scales in packed row order (null entries otherwise)
     float *sc_lm = nullptr;
     float *x = nullptr, *xg = nullptr, *ssq = nullptr, *row_scale = nullptr, *gemm_ws = nullptr, *q = nullptr, *ao = nullptr, *act = nullptr;
+    float *ks_part = nullptr;       // partial tiles of the projections whose K is shared out over workgroups
+    uint32_t *ks_ticket = nullptr;  // their arrival counters
     uint16_t *xgb = nullptr, *qb = nullptr, *aob = nullptr, *actb = nullptr;
     int32_t *row_pos = nullptr, *row_seq = nullptr;
     std::vector<void *> kpool, vpool;
@@ -320,6 +322,10 @@ int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights
         m.gemm_ws_bytes = (size_t)8 * std::min<size_t>(R, 512) * std::max(d, qd + 2 * kvd) * sizeof(float);
         TRY(dalloc(c, &m.gemm_ws, m.gemm_ws_bytes / sizeof(float)));
     }
+    if (m.mfma_ok) {
+        TRY(dalloc(c, &m.ks_part, (size_t)KSPLIT_MAX * (d / 16) * 256));
+        TRY(dalloc(c, &m.ks_ticket, (size_t)KSPLIT_TICKETS));
+    }
     TRY(dalloc(c, &m.q, R * qd));
     TRY(dalloc(c, &m.qb, 2 * R * qd));
     TRY(dalloc(c, &m.ao, R * qd));
@@ -561,6 +567,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             GemvArgs a = base(qd, m.ao, m.aob, aob_lo);
             a.w0 = m.wo[l]; a.n0 = d;
             a.xres = m.x; a.g_next = m.ffn_norm[l]; a.xg = m.xg; a.xgb = m.xgb; a.xgb_lo = xgb_lo; a.ssq_out = m.ssq;
+            a.ks_part = m.ks_part; a.ks_ticket = m.ks_ticket;
             a.wscale = tiled ? m.sc_wo[l] : nullptr;
             TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wo[l] : nullptr, d, &slots, nullptr, 5));
         }
@@ -577,6 +584,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             a.w0 = m.wd[l]; a.n0 = d;
             a.xres = m.x; a.g_next = (l + 1 < s.n_layers) ? m.attn_norm[l + 1] : m.final_norm;
             a.xg = m.xg; a.xgb = m.xgb; a.xgb_lo = xgb_lo; a.ssq_out = m.ssq;
+            a.ks_part = m.ks_part; a.ks_ticket = m.ks_ticket;
             a.wscale = tiled ? m.sc_wd[l] : nullptr;
             TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wd[l] : nullptr, d, &slots, nullptr, 6));
         }
@@ -1443,9 +1451,17 @@ int spec_k_gemv(const void *w, int32_t dtype, int32_t N, int32_t K, const float 
         // x is split into two bf16 terms in a scratch copy: the matrix-core kernel reads 16-bit rows
         if (dtype != SPEC_BF16 || N % 16 || K % 32) return SPEC_EINVAL;
         const hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+        // one block: the two bf16 terms of x, then the partial tiles and zeroed arrival counters of the kernel that
+        // shares K out over workgroups
         uint16_t *xb = nullptr;
-        if (hipMalloc(reinterpret_cast<void **>(&xb), (size_t)R * K * 4) != hipSuccess) return SPEC_ENOMEM;
+        const size_t x_bytes = ((size_t)R * K * 4 + 255) & ~(size_t)255;
+        const size_t part_bytes = (size_t)KSPLIT_MAX * (N / 16) * 256 * sizeof(float), tick_bytes = KSPLIT_TICKETS * sizeof(uint32_t);
+        if (hipMalloc(reinterpret_cast<void **>(&xb), x_bytes + part_bytes + tick_bytes) != hipSuccess) return SPEC_ENOMEM;
         int rc = SPEC_OK;
+        uint8_t *blk = reinterpret_cast<uint8_t *>(xb);
+        a.ks_part = reinterpret_cast<float *>(blk + x_bytes);
+        a.ks_ticket = reinterpret_cast<uint32_t *>(blk + x_bytes + part_bytes);
+        if (hipMemsetAsync(a.ks_ticket, 0, tick_bytes, st) != hipSuccess) rc = SPEC_EHIP;
         if (launch_cast_to_bf16(x, xb, (int64_t)R * K, (int64_t)R * K, st) != hipSuccess) rc = SPEC_EHIP;
         a.xb = xb; a.xb_lo = (int64_t)R * K;
         if (rc == SPEC_OK && launch_gemv_mfma(a, EPI_PLAIN, 0, nullptr, nullptr, st) != hipSuccess) rc = SPEC_EHIP;

@@ -17,6 +17,8 @@
 // From a few dozen rows on the dense-contraction kernel (gemm_mfma.hip) is the faster one; the host picks.
 #include <hip/hip_ext.h>
 
+#include <cstdlib>
+
 #include "common.hpp"
 #include "epilogue.hpp"
 #include "kv.hpp"
@@ -258,9 +260,9 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 //   RAG: 1 = K is not a multiple of 512 (the 768-wide draft models): the last round of k-tiles exists only for the
 //   first waves; the test is on the scalar wave index, so every branch around a matrix instruction stays scalar.
 constexpr int persist_burst(int tpw, int frags) {
-    // tiles per burst of loads: a divisor of the wave's tiles per group, at most 8 KiB per wave, less where the x
-    // fragments already take 64 registers or more
-    const int cap = frags >= 20 ? 5 : (frags >= 16 ? 4 : 8);
+    // tiles per burst of loads: a divisor of the wave's tiles per group, at most 8 KiB per wave, 4 KiB where the x
+    // fragments already take 64 registers and 2 KiB where they take 80 (a deeper burst there spills)
+    const int cap = frags >= 20 ? 2 : (frags >= 16 ? 4 : 8);
     int ub = 1;
     for (int d = 1; d <= cap; ++d)
         if (tpw % d == 0) ub = d;
@@ -399,6 +401,151 @@ __global__ __launch_bounds__(PW * 64) void gemv_persist_k(const GemvArgs a) {
         lds_barrier();
         if constexpr (PRE) epilogue_tile_pre<EPI>(a, tile, 17, s_scale, R, b + i * G, Ntot, threadIdx.x, pre);
         else epilogue_tile<EPI, 16, NT>(a, tile, 17, s_scale, R, b + i * G, Ntot, threadIdx.x);
+    }
+}
+
+// ---- K shared out over workgroups, x resident ---------------------------------------------------------------
+// The projections whose K is too long for the persistent kernel's registers (the down projections: K = 11008,
+// 13824, 14336) and those with fewer groups than half the compute units (K = 8192 of the 1B-shaped draft).  The K
+// of every group is cut into S slices; workgroup (s, j) keeps the x fragments of slice s in registers and walks the
+// groups j, j + J, ... like the persistent kernel, leaving one partial tile per group in global memory.  The
+// workgroup that arrives last at the counter of its set j sums the S partial tiles of each of the set's groups in
+// slice order (a fixed order: results repeat bit for bit whoever is last) and runs the epilogue.  Partial tiles and
+// counters cross workgroups - and the chip's eight L2s - as agent-scope stores, loads and atomics; nothing is
+// fenced (measured on the chip: an arrival through such a counter costs about 2 us, a cache write-back and
+// invalidate at agent scope about 5).
+//   KTW: k-tiles per wave and slice; RAG: the slice's last round of k-tiles exists only for the first waves.
+template <int EPI, int KTW, int TERMS, int RAG>
+__global__ __launch_bounds__(PW * 64) void gemv_ksplit_k(const GemvArgs a, const int S) {
+    if (a.active != nullptr && *a.active == 0) return;
+    static_assert(EPI == EPI_PLAIN || EPI == EPI_RESID, "epilogues without row scales");
+    constexpr int UB = persist_burst(KTW, KTW * TERMS);
+    constexpr int NB = KTW / UB;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int Ntot = a.n0, n_groups = Ntot >> 4;
+    const int J = gridDim.x / S, s = blockIdx.x % S, j = blockIdx.x / S;   // host: gridDim.x == S * J, J <= n_groups
+    const int n_my = (n_groups - j + J - 1) / J;
+    const int K = a.K, KT = K >> 5, KTs = KT / S;                          // host: KT % S == 0, PW (KTW - 1) < KTs <= PW KTW
+    const int R = a.R;
+    auto live = [&](int t) { return !RAG || wave + PW * t < KTs; };
+
+    __shared__ float part[PW * 256];
+    __shared__ float s_scale[16];
+    __shared__ int s_last;
+
+    const bool fold = TERMS == 1 && a.xb_lo != 0;  // host: then R <= 8
+    u32x4_t xh[KTW], xl[TERMS == 2 ? KTW : 1];
+    {
+        int r = lane & 15;
+        size_t off = 0;
+        if (fold && r >= 8) { r -= 8; off = (size_t)a.xb_lo; }
+        const bool row_ok = r < R;
+        const size_t xr = (size_t)(min(r, R - 1) * a.x_mul + a.x_add);
+        const uint16_t *xp = a.xb + off + xr * K + ((size_t)s * KTs + wave) * 32 + (lane >> 4) * 8;
+#pragma unroll
+        for (int t = 0; t < KTW; ++t) {
+            xh[t] = u32x4_t{0u, 0u, 0u, 0u};
+            if (TERMS == 2) xl[t] = u32x4_t{0u, 0u, 0u, 0u};
+            if (row_ok && live(t)) {
+                xh[t] = *reinterpret_cast<const u32x4_t *>(xp + (size_t)t * PW * 32);
+                if (TERMS == 2) xl[t] = *reinterpret_cast<const u32x4_t *>(xp + a.xb_lo + (size_t)t * PW * 32);
+            }
+        }
+    }
+    const u32x4_t *wp = reinterpret_cast<const u32x4_t *>(a.w0) + ((size_t)j * KT + (size_t)s * KTs + wave) * 64 + lane;
+    const size_t gstride = (size_t)J * KT * 64;
+    u32x4_t bw[UB];
+#pragma unroll
+    for (int u = 0; u < UB; ++u)
+        if (live(u)) bw[u] = __builtin_nontemporal_load(wp + (size_t)u * PW * 64);
+    if (threadIdx.x < 16) s_scale[threadIdx.x] = 1.f;
+
+    for (int i = 0; i < n_my; ++i) {
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                const int t = nb * UB + u;
+                if (live(t)) {
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xh[t]),
+                                                                  __builtin_bit_cast(bf16x8_t, bw[u]), acc, 0, 0, 0);
+                    if (TERMS == 2)
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xl[t]),
+                                                                      __builtin_bit_cast(bf16x8_t, bw[u]), acc, 0, 0, 0);
+                }
+            }
+            if (nb + 1 < NB) {
+#pragma unroll
+                for (int u = 0; u < UB; ++u)
+                    if (live((nb + 1) * UB + u)) bw[u] = __builtin_nontemporal_load(wp + (size_t)((nb + 1) * UB + u) * PW * 64);
+            } else if (i + 1 < n_my) {
+#pragma unroll
+                for (int u = 0; u < UB; ++u)
+                    if (live(u)) bw[u] = __builtin_nontemporal_load(wp + gstride + (size_t)u * PW * 64);
+            }
+        }
+        wp += gstride;
+        lds_barrier();  // the previous group's partials have been read
+#pragma unroll
+        for (int v = 0; v < 4; ++v) part[wave * 256 + v * 64 + lane] = acc[v];
+        lds_barrier();
+        // this slice's tile: the waves' partials in wave order, to global memory as [row][column]
+        if (threadIdx.x < 256) {
+            const int idx = threadIdx.x, l = idx & 63, v = idx >> 6;
+            if (!fold || l < 32) {
+                float sum = part[idx];
+#pragma unroll
+                for (int w = 1; w < PW; ++w) sum += part[w * 256 + idx];
+                if (fold) {
+                    float s2 = part[idx + 32];
+#pragma unroll
+                    for (int w = 1; w < PW; ++w) s2 += part[w * 256 + idx + 32];
+                    sum += s2;
+                }
+                const int row = (l >> 4) * 4 + v, col = l & 15;
+                if (row < R)
+                    __hip_atomic_store(a.ks_part + ((size_t)s * n_groups + (j + i * J)) * 256 + row * 16 + col, sum,
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+    __syncthreads();  // every store of this workgroup has been acknowledged
+    if (threadIdx.x == 0) {
+        const uint32_t old = __hip_atomic_fetch_add(a.ks_ticket + j, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = old == (uint32_t)(S - 1);
+        if (s_last) __hip_atomic_store(a.ks_ticket + j, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next launch
+    }
+    __syncthreads();
+    if (!s_last) return;
+    // Four groups at a time, 256 threads each (thread -> row, column of the group's tile): what the epilogue reads
+    // besides the tile goes out first, then the S partial tiles, all groups' loads in flight together.
+    const int q = threadIdx.x >> 8, tl = threadIdx.x & 255;
+    float *my_tile = part + q * (16 * 17);  // the partials' LDS is free now; each thread reads back only what it wrote
+    for (int base = 0; base < n_my; base += 4) {
+        const int i = base + q;
+        if (i >= n_my) continue;  // whole waves (a quarter is four waves)
+        const int g = j + i * J;
+        const int row = tl >> 4, col = tl & 15;
+        EpiPre pre{};
+        if constexpr (EPI == EPI_RESID) epi_prefetch_group<EPI>(a, R, g, Ntot, tl, pre);
+        float sum = 0.f;
+        if (row < R) {
+            float v[KSPLIT_MAX];
+#pragma unroll
+            for (int ss = 0; ss < KSPLIT_MAX; ++ss)
+                v[ss] = ss < S ? __hip_atomic_load(a.ks_part + ((size_t)ss * n_groups + g) * 256 + row * 16 + col, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT)
+                               : 0.f;
+#pragma unroll
+            for (int ss = 0; ss < KSPLIT_MAX; ++ss) sum += v[ss];  // slice order; absent slices add an exact zero
+        }
+        if constexpr (EPI == EPI_RESID) {
+            my_tile[row * 17 + col] = sum;
+            epilogue_tile_pre<EPI>(a, my_tile, 17, s_scale, R, g, Ntot, tl, pre);
+        } else {
+            if (row < R && g * 16 + col < Ntot) a.y[(size_t)row * a.n0 + g * 16 + col] = sum;
+        }
     }
 }
 
@@ -677,6 +824,55 @@ static hipError_t launch_persist(const GemvArgs &a, int n_groups, LaunchEvents e
     return launch_persist_one<EPI, 16, 1, WQ>(a, n_groups, ev, s);
 }
 
+// Slices of K for the kernel that shares K out over workgroups (0: that kernel does not serve the shape).
+static int ksplit_slices(const GemvArgs &a, int epi, int n_groups) {
+    static const bool off = std::getenv("SPEC_NO_KSPLIT") != nullptr;  // measurement aid: route as if the kernel were absent
+    if (off || a.ks_part == nullptr || a.ks_ticket == nullptr || a.wscale != nullptr || a.ssq_in != nullptr) return 0;
+    if ((epi != EPI_PLAIN && epi != EPI_RESID) || a.R > 16 || a.K % 32) return 0;
+    const int KT = a.K / 32, terms = persist_terms(a), cus = compute_units();
+    // Where the persistent kernel serves the shape it stays, unless it leaves half the compute units idle on a long
+    // K (the 1B-shaped down projection: 128 groups of K = 8192).  Measured and not taken: sharing K out where the
+    // persistent kernel's last round of groups is mostly empty (13B-shaped output projection, 320 groups on 256
+    // units) - the counter and the finish cost what the even rounds save.
+    if (persist_fits(a) && !(2 * n_groups <= cus && KT >= 256)) return 0;
+    for (int S = 2; S <= KSPLIT_MAX; S *= 2) {
+        if (KT % S || n_groups * S < cus / 2) continue;
+        const int ktw = (KT / S + PW - 1) / PW;
+        if (ktw >= 6 && ktw <= 8 && ktw * terms <= 16) return S;
+    }
+    return 0;
+}
+
+template <int EPI, int KTW, int TERMS>
+static hipError_t launch_ksplit_one(const GemvArgs &a, int S, int J, bool ragged, LaunchEvents ev, hipStream_t s) {
+    if constexpr (EPI == EPI_PLAIN || EPI == EPI_RESID) {
+        auto go = [&](auto kern) {
+            if (ev.start != nullptr) hipExtLaunchKernelGGL(kern, dim3(S * J), dim3(PW * 64), 0, s, ev.start, ev.stop, 0, a, S);
+            else hipLaunchKernelGGL(kern, dim3(S * J), dim3(PW * 64), 0, s, a, S);
+            return hipGetLastError();
+        };
+        return ragged ? go(gemv_ksplit_k<EPI, KTW, TERMS, 1>) : go(gemv_ksplit_k<EPI, KTW, TERMS, 0>);
+    } else {
+        return hipErrorInvalidValue;
+    }
+}
+
+template <int EPI>
+static hipError_t launch_ksplit(const GemvArgs &a, int S, int n_groups, LaunchEvents ev, hipStream_t s) {
+    const int cus = compute_units();
+    int J = cus / S;
+    if (J > n_groups) J = n_groups;
+    if (J > KSPLIT_TICKETS) J = KSPLIT_TICKETS;
+    const int KTs = a.K / 32 / S, ktw = (KTs + PW - 1) / PW;
+    const bool ragged = KTs % PW != 0, two = persist_terms(a) == 2;
+    switch (ktw) {
+        case 6: return two ? launch_ksplit_one<EPI, 6, 2>(a, S, J, ragged, ev, s) : launch_ksplit_one<EPI, 6, 1>(a, S, J, ragged, ev, s);
+        case 7: return two ? launch_ksplit_one<EPI, 7, 2>(a, S, J, ragged, ev, s) : launch_ksplit_one<EPI, 7, 1>(a, S, J, ragged, ev, s);
+        case 8: return two ? launch_ksplit_one<EPI, 8, 2>(a, S, J, ragged, ev, s) : launch_ksplit_one<EPI, 8, 1>(a, S, J, ragged, ev, s);
+    }
+    return hipErrorInvalidValue;
+}
+
 template <int EPI>
 static hipError_t launch_cfg(const GemvArgs &a, int Ntot, int forced, LaunchEvents ev, hipStream_t s) {
     const int MB = a.R <= 16 ? 1 : (a.R <= 32 ? 2 : (a.R <= 64 ? 4 : 8));
@@ -695,6 +891,10 @@ static hipError_t launch_cfg(const GemvArgs &a, int Ntot, int forced, LaunchEven
             case 4: return go(gemv_q8_k<EPI, 4, 8>, 8);
             default: return go(gemv_q8_k<EPI, 8, 4>, 4);
         }
+    }
+    if (forced == 0) {
+        const int S = ksplit_slices(a, EPI, n_groups);
+        if (S > 0) return launch_ksplit<EPI>(a, S, n_groups, ev, s);
     }
     if (forced == 0 && persist_fits(a)) return launch_persist<EPI, 0>(a, n_groups, ev, s);
     const MfmaCfg c = pick_cfg(n_groups, a.K / 32, MB, forced);

@@ -57,6 +57,10 @@ struct GemvArgs {
     int32_t rpw;              // W rows per wave (wave-dot) / 16-row groups per workgroup (matrix-core)
     const int32_t *active;    // when non-null and *active == 0 the kernel does nothing (drafting has stopped)
     const float *wscale;      // 8-bit weights: one scale per packed output column, multiplied into the reduced tile (null: 16-bit weights)
+    // scratch of the kernel that shares K out over workgroups (null: that kernel is not used): partial tiles
+    // [KSPLIT_MAX][Ntot / 16][16][16] fp32 and one arrival counter per set of groups, zero between launches
+    float *ks_part;
+    uint32_t *ks_ticket;
     // ---- epilogue ----
     float *y;                 // PLAIN: [R][N]; LOGITS: logits base; QKV: q [R][nq*hd]
     int32_t y_mul, y_add, y_stride;  // LOGITS: logical row r writes row r * y_mul + y_add
@@ -189,6 +193,8 @@ hipError_t launch_embed(const EmbedArgs &a, hipStream_t s);
 hipError_t launch_gemv_wavedot(const GemvArgs &a, int epi, int w_dtype, hipStream_t s);
 hipError_t launch_gemv_mfma(const GemvArgs &a, int epi, int forced_cfg, hipEvent_t ev_start, hipEvent_t ev_stop,
                             hipStream_t s);
+constexpr int KSPLIT_MAX = 4;      // most workgroups that share the K of one group
+constexpr int KSPLIT_TICKETS = 256; // arrival counters (one per set of groups: at most one per compute unit)
 int gemv_mfma_groups_per_wg(int epi, int Ntot, int K, int R, int forced_cfg, bool q8 = false);  // 16-row groups per workgroup
 // Prompt ingestion: the dense-contraction kernel for many rows (x read as fp32 rows, a.x).
 constexpr int GEMM_MIN_ROWS = 17;  // up to 16 rows the persistent weight-streaming kernel is the faster one at any shape

@@ -62,7 +62,7 @@ def test_gemv_wavedot_matches_fp64_matmul(dtype, R, N, K):
 @pytest.mark.parametrize("N,K", [(4096, 4096), (1024, 11008), (2064, 768), (32000, 1024), (128, 128), (512, 128),
                                  (128, 256), (256, 32), (64, 64), (16384, 2048), (4800, 2048), (6144, 4096), (48, 4096),
                                  (128256, 4096), (5120, 5120), (15360, 5120), (768, 3072), (1040, 1536), (5120, 13824),
-                                 (304, 768), (4096, 8192)])
+                                 (304, 768), (4096, 8192), (2048, 8192), (4096, 14336)])
 def test_gemv_mfma_matches_fp64_matmul(R, N, K):
     # the short-K shapes leave waves with one k-tile or none: their matrix instructions must be skipped by
     # scalar branches (a masked-off v_mfma still executes)
