@@ -458,7 +458,11 @@ int launch_proj(spec_ctx *c, ModelRT &m, GemvArgs a, int epi, const void *tiled,
     if (dense && a.R <= 128) {
         const int ng = gemv_mfma_groups_per_wg(epi, Ntot, a.K, a.R, 0, m.q8);
         const double groups_per_cu = std::max(1.0, Ntot / 16 / 256.0);
-        const double stream_us = 2.5 + groups_per_cu * a.K * ((m.q8 ? 16.0 : 32.0) + 4.0 * a.R / ng) / 38e3;
+        // with the x fragments resident (short K, up to 64 rows) only the weights stream, at what a compute unit
+        // fetches in the persistent kernels (about 23 GB/s)
+        const double stream_us = gemv_mfma_resident_x(a.K, a.R, m.q8)
+                                     ? 2.5 + groups_per_cu * a.K * 32.0 / 23e3
+                                     : 2.5 + groups_per_cu * a.K * ((m.q8 ? 16.0 : 32.0) + 4.0 * a.R / ng) / 38e3;
         dense = gemm_mfma_estimate_us(Ntot, a.K, a.R, m.gemm_ws_bytes, m.q8) < stream_us;
     }
     if (dense) {

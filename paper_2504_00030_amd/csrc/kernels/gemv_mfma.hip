@@ -404,6 +404,111 @@ __global__ __launch_bounds__(PW * 64) void gemv_persist_k(const GemvArgs a) {
     }
 }
 
+// ---- persistent variant for 17 to 64 rows --------------------------------------------------------------------
+// The same walk over the groups with the x fragments of MB 16-row blocks resident: MB x KTW x TERMS fragments of
+// four registers each, at most 16 of them, so K <= 2048 for up to 32 rows and K <= 1024 for up to 64 (the draft
+// models' projections when a batch of 17 to 64 sequences decodes in lock-step).  Every weight tile meets MB x TERMS
+// matrix instructions; the epilogues are the general ones (any row count), run on the reduced MB x 16-row tile.
+template <int EPI, int KTW, int MB, int TERMS, int RAG>
+__global__ __launch_bounds__(PW * 64) void gemv_persist_mb_k(const GemvArgs a) {
+    if (a.active != nullptr && *a.active == 0) return;
+    constexpr int NT = PW * 64;
+    constexpr int UB = persist_burst(KTW, 16);
+    constexpr int NB = KTW / UB;
+    constexpr int FR = MB * 256;  // floats of one wave's partial tile
+    static_assert(MB * KTW * TERMS <= 16 && MB >= 2 && MB <= 4, "x fragments must fit 64 registers");
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    int Ntot = a.n0;
+    if (EPI == EPI_QKV) Ntot = (a.nq + 2 * a.nkv) * a.hd;
+    if (EPI == EPI_SWIGLU) Ntot = 2 * a.n0;
+    const int n_groups = Ntot >> 4;
+    const int G = gridDim.x, b = blockIdx.x;
+    const int n_my = (n_groups - b + G - 1) / G;  // host: G <= n_groups
+    const int K = a.K, KT = K >> 5;               // host: PW (KTW - 1) < KT <= PW KTW, == unless RAG
+    const int R = a.R;
+    auto live = [&](int t) { return !RAG || wave + PW * t < KT; };
+
+    __shared__ float part[PW * FR];
+    __shared__ float tile[MB * 16 * 17];
+    __shared__ float s_scale[MB * 16];
+
+    RowScales<NT, MB> rs;  // 16 waves, rows wave, wave + 16, ...
+    rs.begin(a, R);
+
+    u32x4_t xh[MB][KTW], xl[TERMS == 2 ? MB : 1][TERMS == 2 ? KTW : 1];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        const int r = mb * 16 + (lane & 15);
+        const bool row_ok = r < R;
+        const size_t xr = (size_t)(min(r, R - 1) * a.x_mul + a.x_add);
+        const uint16_t *xp = a.xb + xr * K + (size_t)wave * 32 + (lane >> 4) * 8;
+#pragma unroll
+        for (int t = 0; t < KTW; ++t) {
+            xh[mb][t] = u32x4_t{0u, 0u, 0u, 0u};
+            if (TERMS == 2) xl[mb][t] = u32x4_t{0u, 0u, 0u, 0u};
+            if (row_ok && live(t)) {
+                xh[mb][t] = *reinterpret_cast<const u32x4_t *>(xp + (size_t)t * PW * 32);
+                if (TERMS == 2) xl[mb][t] = *reinterpret_cast<const u32x4_t *>(xp + a.xb_lo + (size_t)t * PW * 32);
+            }
+        }
+    }
+    const u32x4_t *wp = reinterpret_cast<const u32x4_t *>(a.w0) + ((size_t)b * KT + wave) * 64 + lane;
+    const size_t gstride = (size_t)G * KT * 64;
+    u32x4_t bw[UB];
+#pragma unroll
+    for (int u = 0; u < UB; ++u)
+        if (live(u)) bw[u] = __builtin_nontemporal_load(wp + (size_t)u * PW * 64);
+
+    for (int i = 0; i < n_my; ++i) {
+        f32x4_t acc[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) acc[mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                const int t = nb * UB + u;
+                if (live(t)) {
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xh[mb][t]),
+                                                                          __builtin_bit_cast(bf16x8_t, bw[u]), acc[mb], 0, 0, 0);
+                        if (TERMS == 2)
+                            acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xl[mb][t]),
+                                                                              __builtin_bit_cast(bf16x8_t, bw[u]), acc[mb], 0, 0, 0);
+                    }
+                }
+            }
+            if (nb + 1 < NB) {
+#pragma unroll
+                for (int u = 0; u < UB; ++u)
+                    if (live((nb + 1) * UB + u)) bw[u] = __builtin_nontemporal_load(wp + (size_t)((nb + 1) * UB + u) * PW * 64);
+            } else if (i + 1 < n_my) {
+#pragma unroll
+                for (int u = 0; u < UB; ++u)
+                    if (live(u)) bw[u] = __builtin_nontemporal_load(wp + gstride + (size_t)u * PW * 64);
+            }
+        }
+        wp += gstride;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) part[wave * FR + ((mb * 4 + v) << 6) + lane] = acc[mb][v];
+        if (i == 0) rs.finish(a, s_scale, R);  // row scales, once (ends with a full barrier)
+        lds_barrier();
+        // sum the K slices in wave order; register (mb, v, lane) is x row 16 mb + 4 (lane / 16) + v, column lane % 16
+        if (threadIdx.x < FR) {
+            const int idx = threadIdx.x, l = idx & 63, v = (idx >> 6) & 3, mb = idx >> 8;
+            float sum = part[idx];
+#pragma unroll
+            for (int w = 1; w < PW; ++w) sum += part[w * FR + idx];
+            tile[(mb * 16 + (l >> 4) * 4 + v) * 17 + (l & 15)] = sum;
+        }
+        lds_barrier();
+        epilogue_tile<EPI, 16, NT>(a, tile, 17, s_scale, R, b + i * G, Ntot, threadIdx.x);
+    }
+}
+
 // ---- K shared out over workgroups, x resident ---------------------------------------------------------------
 // The projections whose K is too long for the persistent kernel's registers (the down projections: K = 11008,
 // 13824, 14336) and those with fewer groups than half the compute units (K = 8192 of the 1B-shaped draft).  The K
@@ -728,6 +833,7 @@ static MfmaCfg pick_cfg(int n_groups, int KT, int MB, int forced) {
 int gemv_mfma_groups_per_wg(int epi, int Ntot, int K, int R, int forced, bool q8) {
     (void)epi;
     if (q8) return 1;
+    if (forced == 0 && gemv_mfma_resident_x(K, R, q8)) return 1;  // the engine's activations carry two terms
     const int MB = R <= 16 ? 1 : (R <= 32 ? 2 : (R <= 64 ? 4 : 8));
     return pick_cfg(Ntot / 16, K / 32, MB, forced).ng;
 }
@@ -824,6 +930,52 @@ static hipError_t launch_persist(const GemvArgs &a, int n_groups, LaunchEvents e
     return launch_persist_one<EPI, 16, 1, WQ>(a, n_groups, ev, s);
 }
 
+// The persistent kernel for 17 to 64 rows: the x fragments of MB row blocks, KTW k-tiles per wave and `terms` bf16
+// terms fit 16 registers-of-four.
+static bool persist_mb_shape(int K, int R, int terms, bool q8) {
+    if (q8 || R <= 16 || R > 64 || K % 32) return false;
+    const int MB = R <= 32 ? 2 : (R <= 48 ? 3 : 4);
+    const int ktw = (K / 32 + PW - 1) / PW;
+    if (K % 512 && ktw > 2) return false;   // a short last round is compiled for K < 1024 only
+    return (ktw == 1 || ktw == 2 || ktw == 4) && MB * ktw * terms <= 16;
+}
+
+bool gemv_mfma_resident_x(int K, int R, bool q8) {
+    static const bool off = std::getenv("SPEC_NO_PERSIST_MB") != nullptr;  // measurement aid
+    return !off && persist_mb_shape(K, R, 2, q8);
+}
+
+template <int EPI, int KTW, int MB, int TERMS>
+static hipError_t launch_persist_mb_one(const GemvArgs &a, int n_groups, LaunchEvents ev, hipStream_t s) {
+    if constexpr (MB * KTW * TERMS <= 16) {
+        const int cus = compute_units();
+        const int G = n_groups < cus ? n_groups : cus;
+        auto go = [&](auto kern) {
+            if (ev.start != nullptr) hipExtLaunchKernelGGL(kern, dim3(G), dim3(PW * 64), 0, s, ev.start, ev.stop, 0, a);
+            else hipLaunchKernelGGL(kern, dim3(G), dim3(PW * 64), 0, s, a);
+            return hipGetLastError();
+        };
+        if constexpr (KTW <= 2) {
+            if (a.K % 512) return go(gemv_persist_mb_k<EPI, KTW, MB, TERMS, 1>);
+        }
+        return go(gemv_persist_mb_k<EPI, KTW, MB, TERMS, 0>);
+    } else {
+        return hipErrorInvalidValue;
+    }
+}
+
+template <int EPI, int MB>
+static hipError_t launch_persist_mb(const GemvArgs &a, int n_groups, LaunchEvents ev, hipStream_t s) {
+    const int ktw = (a.K / 32 + PW - 1) / PW;
+    const bool two = a.xb_lo != 0;
+    switch (ktw) {
+        case 1: return two ? launch_persist_mb_one<EPI, 1, MB, 2>(a, n_groups, ev, s) : launch_persist_mb_one<EPI, 1, MB, 1>(a, n_groups, ev, s);
+        case 2: return two ? launch_persist_mb_one<EPI, 2, MB, 2>(a, n_groups, ev, s) : launch_persist_mb_one<EPI, 2, MB, 1>(a, n_groups, ev, s);
+        case 4: return two ? launch_persist_mb_one<EPI, 4, MB, 2>(a, n_groups, ev, s) : launch_persist_mb_one<EPI, 4, MB, 1>(a, n_groups, ev, s);
+    }
+    return hipErrorInvalidValue;
+}
+
 // Slices of K for the kernel that shares K out over workgroups (0: that kernel does not serve the shape).
 static int ksplit_slices(const GemvArgs &a, int epi, int n_groups) {
     static const bool off = std::getenv("SPEC_NO_KSPLIT") != nullptr;  // measurement aid: route as if the kernel were absent
@@ -895,6 +1047,12 @@ static hipError_t launch_cfg(const GemvArgs &a, int Ntot, int forced, LaunchEven
     if (forced == 0) {
         const int S = ksplit_slices(a, EPI, n_groups);
         if (S > 0) return launch_ksplit<EPI>(a, S, n_groups, ev, s);
+        static const bool mb_off = std::getenv("SPEC_NO_PERSIST_MB") != nullptr;
+        if (!mb_off && persist_mb_shape(a.K, a.R, a.xb_lo != 0 ? 2 : 1, false)) {
+            if (a.R <= 32) return launch_persist_mb<EPI, 2>(a, n_groups, ev, s);
+            if (a.R <= 48) return launch_persist_mb<EPI, 3>(a, n_groups, ev, s);
+            return launch_persist_mb<EPI, 4>(a, n_groups, ev, s);
+        }
     }
     if (forced == 0 && persist_fits(a)) return launch_persist<EPI, 0>(a, n_groups, ev, s);
     const MfmaCfg c = pick_cfg(n_groups, a.K / 32, MB, forced);

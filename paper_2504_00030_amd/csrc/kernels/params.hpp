@@ -193,6 +193,7 @@ hipError_t launch_embed(const EmbedArgs &a, hipStream_t s);
 hipError_t launch_gemv_wavedot(const GemvArgs &a, int epi, int w_dtype, hipStream_t s);
 hipError_t launch_gemv_mfma(const GemvArgs &a, int epi, int forced_cfg, hipEvent_t ev_start, hipEvent_t ev_stop,
                             hipStream_t s);
+bool gemv_mfma_resident_x(int K, int R, bool q8);  // 17-64 rows: the streaming kernel keeps its x fragments in registers
 constexpr int KSPLIT_MAX = 4;      // most workgroups that share the K of one group
 constexpr int KSPLIT_TICKETS = 256; // arrival counters (one per set of groups: at most one per compute unit)
 int gemv_mfma_groups_per_wg(int epi, int Ntot, int K, int R, int forced_cfg, bool q8 = false);  // 16-row groups per workgroup

@@ -58,7 +58,7 @@ def test_gemv_wavedot_matches_fp64_matmul(dtype, R, N, K):
     assert np.abs(got - want).max() <= tol
 
 
-@pytest.mark.parametrize("R", [1, 3, 8, 9, 16, 17, 31, 32, 40, 128])
+@pytest.mark.parametrize("R", [1, 3, 8, 9, 16, 17, 31, 32, 40, 48, 64, 128])
 @pytest.mark.parametrize("N,K", [(4096, 4096), (1024, 11008), (2064, 768), (32000, 1024), (128, 128), (512, 128),
                                  (128, 256), (256, 32), (64, 64), (16384, 2048), (4800, 2048), (6144, 4096), (48, 4096),
                                  (128256, 4096), (5120, 5120), (15360, 5120), (768, 3072), (1040, 1536), (5120, 13824),
@@ -455,7 +455,7 @@ def test_verification_graphs_of_different_logits_tilings_alternate(graphs):
     assert c.max_logit_err <= TOL["bf16"]
 
 
-@pytest.mark.parametrize("batch", [8, 16, 40])
+@pytest.mark.parametrize("batch", [8, 16, 24, 40])
 def test_8b_widths_at_verification_rows_of_a_batch(batch):
     """The 8B pair's widths, two target layers and one draft layer deep, with enough sequences that a verification
     pass holds 17 to over 128 rows (each sequence its own GammaTune+ controller, packed rows): the projections
