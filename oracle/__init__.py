@@ -19,13 +19,16 @@ gammatune   the speculation-length controller (GammaTune section, eqs. for
 
 Parity pins (see tests/test_oracle_*.py): known-answer vectors for Philox,
 closed forms and hand-worked trajectories for the controller, brute-force
-enumeration of the accept/resample law on tiny vocabularies, greedy
-speculative == greedy target-only, a second forward built from torch CPU
-ops, and structural invariants (RoPE shift, GQA == MHA, cached == one-shot).
+enumeration of the accept/resample law on tiny vocabularies, hand-worked
+values and flip tests for the decision margins, greedy speculative == greedy
+target-only, a second forward built from torch CPU ops, structural
+invariants (RoPE shift, GQA == MHA, cached == one-shot) and the cached pair
+against one-shot forwards under roll-backs.
 
 Parity unpinned by the paper (fixed by convention only, identical text on
 both sides): hyper-parameter defaults (eta, delta, tau), which token an early
 stop keeps, what the controller is fed after an early stop, the batch
 extension, the Philox counter layout, and the synthetic confidence signal of
-forced mode.
+forced mode (its formula is this build's choice; its implementation here is
+pinned by hand-worked values).
 """
