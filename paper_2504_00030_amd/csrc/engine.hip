@@ -323,7 +323,8 @@ int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights
         TRY(dalloc(c, &m.gemm_ws, m.gemm_ws_bytes / sizeof(float)));
     }
     if (m.mfma_ok) {
-        TRY(dalloc(c, &m.ks_part, (size_t)KSPLIT_MAX * (d / 16) * 256));
+        const int n_max = std::max(std::max(d, qd + 2 * kvd), std::max(2 * s.d_ffn, s.vocab));
+        TRY(dalloc(c, &m.ks_part, (size_t)KSPLIT_MAX * ((n_max + 15) / 16) * 256));
         TRY(dalloc(c, &m.ks_ticket, (size_t)KSPLIT_TICKETS));
     }
     TRY(dalloc(c, &m.q, R * qd));
@@ -532,6 +533,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
     auto base = [&](int K, const float *x, const uint16_t *xb, int64_t xb_lo) {
         GemvArgs a{};
         a.K = K; a.R = R; a.x = x; a.xb = xb; a.xb_lo = xb_lo; a.x_mul = 1; a.x_add = 0; a.eps = s.rms_eps; a.active = active;
+        a.ks_part = m.ks_part; a.ks_ticket = m.ks_ticket;
         a.ssq_stride = SSQ_STRIDE;
         return a;
     };
@@ -571,7 +573,6 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             GemvArgs a = base(qd, m.ao, m.aob, aob_lo);
             a.w0 = m.wo[l]; a.n0 = d;
             a.xres = m.x; a.g_next = m.ffn_norm[l]; a.xg = m.xg; a.xgb = m.xgb; a.xgb_lo = xgb_lo; a.ssq_out = m.ssq;
-            a.ks_part = m.ks_part; a.ks_ticket = m.ks_ticket;
             a.wscale = tiled ? m.sc_wo[l] : nullptr;
             TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wo[l] : nullptr, d, &slots, nullptr, 5));
         }
@@ -588,7 +589,6 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             a.w0 = m.wd[l]; a.n0 = d;
             a.xres = m.x; a.g_next = (l + 1 < s.n_layers) ? m.attn_norm[l + 1] : m.final_norm;
             a.xg = m.xg; a.xgb = m.xgb; a.xgb_lo = xgb_lo; a.ssq_out = m.ssq;
-            a.ks_part = m.ks_part; a.ks_ticket = m.ks_ticket;
             a.wscale = tiled ? m.sc_wd[l] : nullptr;
             TRY(launch_proj(c, m, a, EPI_RESID, tiled ? m.t_wd[l] : nullptr, d, &slots, nullptr, 6));
         }

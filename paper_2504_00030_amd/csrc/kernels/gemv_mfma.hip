@@ -523,11 +523,13 @@ __global__ __launch_bounds__(PW * 64) void gemv_persist_mb_k(const GemvArgs a) {
 template <int EPI, int KTW, int TERMS, int RAG>
 __global__ __launch_bounds__(PW * 64) void gemv_ksplit_k(const GemvArgs a, const int S) {
     if (a.active != nullptr && *a.active == 0) return;
-    static_assert(EPI == EPI_PLAIN || EPI == EPI_RESID, "epilogues without row scales");
     constexpr int UB = persist_burst(KTW, KTW * TERMS);
     constexpr int NB = KTW / UB;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int Ntot = a.n0, n_groups = Ntot >> 4;
+    int Ntot = a.n0;
+    if (EPI == EPI_QKV) Ntot = (a.nq + 2 * a.nkv) * a.hd;
+    if (EPI == EPI_SWIGLU) Ntot = 2 * a.n0;
+    const int n_groups = Ntot >> 4;
     const int J = gridDim.x / S, s = blockIdx.x % S, j = blockIdx.x / S;   // host: gridDim.x == S * J, J <= n_groups
     const int n_my = (n_groups - j + J - 1) / J;
     const int K = a.K, KT = K >> 5, KTs = KT / S;                          // host: KT % S == 0, PW (KTW - 1) < KTs <= PW KTW
@@ -537,6 +539,9 @@ __global__ __launch_bounds__(PW * 64) void gemv_ksplit_k(const GemvArgs a, const
     __shared__ float part[PW * 256];
     __shared__ float s_scale[16];
     __shared__ int s_last;
+
+    RowScales<PW * 64, 1> rs;  // only the workgroup that finishes a set uses them; the loads are cheap and early
+    rs.begin(a, R);
 
     const bool fold = TERMS == 1 && a.xb_lo != 0;  // host: then R <= 8
     u32x4_t xh[KTW], xl[TERMS == 2 ? KTW : 1];
@@ -563,7 +568,6 @@ __global__ __launch_bounds__(PW * 64) void gemv_ksplit_k(const GemvArgs a, const
 #pragma unroll
     for (int u = 0; u < UB; ++u)
         if (live(u)) bw[u] = __builtin_nontemporal_load(wp + (size_t)u * PW * 64);
-    if (threadIdx.x < 16) s_scale[threadIdx.x] = 1.f;
 
     for (int i = 0; i < n_my; ++i) {
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
@@ -594,6 +598,7 @@ __global__ __launch_bounds__(PW * 64) void gemv_ksplit_k(const GemvArgs a, const
         lds_barrier();  // the previous group's partials have been read
 #pragma unroll
         for (int v = 0; v < 4; ++v) part[wave * 256 + v * 64 + lane] = acc[v];
+        if (i == 0) rs.finish(a, s_scale, R);  // row scales, once (ends with a full barrier)
         lds_barrier();
         // this slice's tile: the waves' partials in wave order, to global memory as [row][column]
         if (threadIdx.x < 256) {
@@ -626,31 +631,36 @@ __global__ __launch_bounds__(PW * 64) void gemv_ksplit_k(const GemvArgs a, const
     // Four groups at a time, 256 threads each (thread -> row, column of the group's tile): what the epilogue reads
     // besides the tile goes out first, then the S partial tiles, all groups' loads in flight together.
     const int q = threadIdx.x >> 8, tl = threadIdx.x & 255;
-    float *my_tile = part + q * (16 * 17);  // the partials' LDS is free now; each thread reads back only what it wrote
+    float *my_tile = part + q * (16 * 17);  // the partials' LDS is free now
+    constexpr bool PRE = EPI == EPI_RESID || EPI == EPI_QKV;
+    EpiPre pre{};
+    if constexpr (EPI == EPI_QKV) epi_prefetch_rows<EPI>(a, R, tl, pre);
     for (int base = 0; base < n_my; base += 4) {
         const int i = base + q;
-        if (i >= n_my) continue;  // whole waves (a quarter is four waves)
+        const bool mine = i < n_my;  // the same for the four waves of a quarter
         const int g = j + i * J;
         const int row = tl >> 4, col = tl & 15;
-        EpiPre pre{};
-        if constexpr (EPI == EPI_RESID) epi_prefetch_group<EPI>(a, R, g, Ntot, tl, pre);
-        float sum = 0.f;
-        if (row < R) {
-            float v[KSPLIT_MAX];
+        if (mine) {
+            if constexpr (PRE) epi_prefetch_group<EPI>(a, R, g, Ntot, tl, pre);
+            float sum = 0.f;
+            if (row < R) {
+                float v[KSPLIT_MAX];
 #pragma unroll
-            for (int ss = 0; ss < KSPLIT_MAX; ++ss)
-                v[ss] = ss < S ? __hip_atomic_load(a.ks_part + ((size_t)ss * n_groups + g) * 256 + row * 16 + col, __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_AGENT)
-                               : 0.f;
+                for (int ss = 0; ss < KSPLIT_MAX; ++ss)
+                    v[ss] = ss < S ? __hip_atomic_load(a.ks_part + ((size_t)ss * n_groups + g) * 256 + row * 16 + col,
+                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                   : 0.f;
 #pragma unroll
-            for (int ss = 0; ss < KSPLIT_MAX; ++ss) sum += v[ss];  // slice order; absent slices add an exact zero
-        }
-        if constexpr (EPI == EPI_RESID) {
+                for (int ss = 0; ss < KSPLIT_MAX; ++ss) sum += v[ss];  // slice order; absent slices add an exact zero
+            }
             my_tile[row * 17 + col] = sum;
-            epilogue_tile_pre<EPI>(a, my_tile, 17, s_scale, R, g, Ntot, tl, pre);
-        } else {
-            if (row < R && g * 16 + col < Ntot) a.y[(size_t)row * a.n0 + g * 16 + col] = sum;
         }
+        __syncthreads();
+        if (mine) {
+            if constexpr (PRE) epilogue_tile_pre<EPI>(a, my_tile, 17, s_scale, R, g, Ntot, tl, pre);
+            else epilogue_tile<EPI, 16, 256>(a, my_tile, 17, s_scale, R, g, Ntot, tl);
+        }
+        __syncthreads();
     }
 }
 
@@ -979,14 +989,24 @@ static hipError_t launch_persist_mb(const GemvArgs &a, int n_groups, LaunchEvent
 // Slices of K for the kernel that shares K out over workgroups (0: that kernel does not serve the shape).
 static int ksplit_slices(const GemvArgs &a, int epi, int n_groups) {
     static const bool off = std::getenv("SPEC_NO_KSPLIT") != nullptr;  // measurement aid: route as if the kernel were absent
-    if (off || a.ks_part == nullptr || a.ks_ticket == nullptr || a.wscale != nullptr || a.ssq_in != nullptr) return 0;
-    if ((epi != EPI_PLAIN && epi != EPI_RESID) || a.R > 16 || a.K % 32) return 0;
+    if (off || a.ks_part == nullptr || a.ks_ticket == nullptr || a.wscale != nullptr) return 0;
+    if (a.R > 16 || a.K % 32) return 0;
     const int KT = a.K / 32, terms = persist_terms(a), cus = compute_units();
+    const bool plain = epi == EPI_PLAIN || epi == EPI_RESID;
     // Where the persistent kernel serves the shape it stays, unless it leaves half the compute units idle on a long
-    // K (the 1B-shaped down projection: 128 groups of K = 8192).  Measured and not taken: sharing K out where the
-    // persistent kernel's last round of groups is mostly empty (13B-shaped output projection, 320 groups on 256
-    // units) - the counter and the finish cost what the even rounds save.
-    if (persist_fits(a) && !(2 * n_groups <= cus && KT >= 256)) return 0;
+    // K (the 1B-shaped down projection: 128 groups of K = 8192), or both bf16 terms of x take 80 registers there
+    // (K = 5120 at 9 to 16 rows: two slices of five k-tiles per wave leave room for full load bursts; 13B-shaped pass
+    // of 16 rows 7.36 -> 6.54 ms).  Measured and not taken: two slices for the K = 4096 projections of the 8B-shaped
+    // target (QKV 12.3 -> 13.6 us, gate/up 39.0 -> 43.6, LM head 167 -> 193: the persistent kernel is the faster one
+    // wherever its fragments fit).  Measured
+    // and not taken: sharing K out where the persistent kernel's last round of groups is mostly empty (13B-shaped
+    // output projection, 320 groups on 256 units) - the counter and the finish cost what the even rounds save.
+    if (persist_fits(a)) {
+        const int ktw = persist_ktw(a);
+        if (ktw * terms >= 20 && KT % 2 == 0 && ((KT / 2 + PW - 1) / PW) == 5 && KT / 2 == 5 * PW) return 2;
+        if (!(plain && 2 * n_groups <= cus && KT >= 256)) return 0;
+    }
+    if (!plain) return 0;  // the long-K shapes are down projections
     for (int S = 2; S <= KSPLIT_MAX; S *= 2) {
         if (KT % S || n_groups * S < cus / 2) continue;
         const int ktw = (KT / S + PW - 1) / PW;
@@ -997,13 +1017,15 @@ static int ksplit_slices(const GemvArgs &a, int epi, int n_groups) {
 
 template <int EPI, int KTW, int TERMS>
 static hipError_t launch_ksplit_one(const GemvArgs &a, int S, int J, bool ragged, LaunchEvents ev, hipStream_t s) {
-    if constexpr (EPI == EPI_PLAIN || EPI == EPI_RESID) {
+    // instances: five k-tiles per wave with both terms for every epilogue; six to eight for the down projections
+    if constexpr ((KTW == 5 && TERMS == 2) || (KTW >= 6 && (EPI == EPI_PLAIN || EPI == EPI_RESID))) {
         auto go = [&](auto kern) {
             if (ev.start != nullptr) hipExtLaunchKernelGGL(kern, dim3(S * J), dim3(PW * 64), 0, s, ev.start, ev.stop, 0, a, S);
             else hipLaunchKernelGGL(kern, dim3(S * J), dim3(PW * 64), 0, s, a, S);
             return hipGetLastError();
         };
-        return ragged ? go(gemv_ksplit_k<EPI, KTW, TERMS, 1>) : go(gemv_ksplit_k<EPI, KTW, TERMS, 0>);
+        if constexpr (KTW <= 5) return ragged ? hipErrorInvalidValue : go(gemv_ksplit_k<EPI, KTW, TERMS, 0>);
+        else return ragged ? go(gemv_ksplit_k<EPI, KTW, TERMS, 1>) : go(gemv_ksplit_k<EPI, KTW, TERMS, 0>);
     } else {
         return hipErrorInvalidValue;
     }
@@ -1018,6 +1040,7 @@ static hipError_t launch_ksplit(const GemvArgs &a, int S, int n_groups, LaunchEv
     const int KTs = a.K / 32 / S, ktw = (KTs + PW - 1) / PW;
     const bool ragged = KTs % PW != 0, two = persist_terms(a) == 2;
     switch (ktw) {
+        case 5: return two ? launch_ksplit_one<EPI, 5, 2>(a, S, J, ragged, ev, s) : hipErrorInvalidValue;
         case 6: return two ? launch_ksplit_one<EPI, 6, 2>(a, S, J, ragged, ev, s) : launch_ksplit_one<EPI, 6, 1>(a, S, J, ragged, ev, s);
         case 7: return two ? launch_ksplit_one<EPI, 7, 2>(a, S, J, ragged, ev, s) : launch_ksplit_one<EPI, 7, 1>(a, S, J, ragged, ev, s);
         case 8: return two ? launch_ksplit_one<EPI, 8, 2>(a, S, J, ragged, ev, s) : launch_ksplit_one<EPI, 8, 1>(a, S, J, ragged, ev, s);
