@@ -69,7 +69,8 @@ int spec_profile_read(spec_ctx *ctx, int32_t *launches, double *total_ms);
 /* One target verification pass of `rows` rows per sequence (1 <= rows <= gamma_max + 1: the last committed token and
  * the rows - 1 token slots behind it) on the current state, asynchronous, with no draft phase before it and no accept
  * after it: the verification-only sweeps over rows, cache length and batch (spec_debug_fill_kv sets up the cache).
- * The state machine stays where it was; the KV entries of those positions are overwritten. */
+ * The state machine stays where it was; the KV entries of those positions are overwritten.  Until the next
+ * spec_draft, spec_debug_logits(which = 1) returns this pass's rows, [batch][rows]. */
 int spec_debug_verify_rows(spec_ctx *ctx, int32_t rows);
 
 /* ---- single kernels on caller buffers (parity tests and roofline measurement) ---------------- */

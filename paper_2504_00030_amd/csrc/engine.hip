@@ -102,6 +102,7 @@ struct spec_ctx {
     // state machine: 0 = created, 1 = ready to draft, 2 = drafted, 3 = verified
     int phase = 0;
     int cur_gamma = 0;
+    int verify_only_rows = 0;  // rows of the last spec_debug_verify_rows pass (0: the last target pass was a step's)
     int cur_rows = 0;      // rows of the current step's verification pass when it is ragged, else 0
     bool ragged_ok = false;  // several sequences and a target whose attention takes ragged rows
     bool prefilled = false;
@@ -1163,6 +1164,7 @@ int spec_draft_batch(spec_ctx *c, const int32_t *gammas) {
         c->passes_launched += gmax;
     }
     c->cur_gamma = gmax;
+    c->verify_only_rows = 0;
     c->phase = 2;
     return SPEC_OK;
 }
@@ -1215,7 +1217,10 @@ int spec_debug_verify_rows(spec_ctx *c, int32_t rows) {
     if (rows < 1 || rows > c->cfg.gamma_max + 1) return fail(c, SPEC_EINVAL, "verify_rows: rows outside 1..gamma_max + 1");
     for (int b = 0; b < c->cfg.batch; ++b)
         if (c->h_len[b] - 1 + rows > c->cfg.max_seq) return fail(c, SPEC_ECAP, "verify_rows: rows do not fit max_seq");
-    return launch_verify(c, rows - 1, 0);
+    TRY(launch_verify(c, rows - 1, 0));
+    c->verify_only_rows = rows;
+    c->cur_rows = 0;
+    return SPEC_OK;
 }
 
 int spec_accept(spec_ctx *c, int32_t *n_accepted, int32_t *next_token, int32_t *n_drafted) {
@@ -1286,6 +1291,14 @@ int spec_read_tokens(spec_ctx *c, int32_t b, int32_t *host_out, int32_t cap, int
 int spec_debug_logits(spec_ctx *c, int32_t which, float *host_out, int64_t cap, int32_t *rows) {
     if (!c || !host_out || !rows) return fail(c, SPEC_EINVAL, "debug_logits: null pointer");
     if (which != 0 && which != 1) return fail(c, SPEC_EINVAL, "debug_logits: which must be 0 or 1");
+    if (which == 1 && c->verify_only_rows > 0) {  // the rows of the last verification-only pass
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        const int64_t n = (int64_t)c->cfg.batch * c->verify_only_rows * c->tgt.s.vocab;
+        if (cap < n) return fail(c, SPEC_EINVAL, "debug_logits: buffer too small");
+        HIPCHK(c, hipMemcpy(host_out, c->tgt.logits, sizeof(float) * (size_t)n, hipMemcpyDeviceToHost));
+        *rows = c->verify_only_rows;
+        return SPEC_OK;
+    }
     if (c->cur_gamma < 1) return fail(c, SPEC_ESTATE, "debug_logits: no step has run");
     HIPCHK(c, hipStreamSynchronize(c->stream));
     const int B = c->cfg.batch, V = c->tgt.s.vocab;

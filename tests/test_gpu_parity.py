@@ -597,6 +597,45 @@ def test_13b_verify_sweep_with_synthetic_cache(batch, kv_len):
     assert res.max_logit_err <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("pair_name,batch,kv_len", [("13b", 1, 700), ("13b", 3, 300), ("8b", 2, 1500)])
+def test_verification_only_passes_match_the_oracle(pair_name, batch, kv_len):
+    """spec_debug_verify_rows, the call the verification-only sweep of bench.py times: passes of 1, 2, 5 and 16 rows per
+    sequence on a seeded synthetic cache (written to both sides), graphs on as in the sweep, target logits of every
+    row against the oracle's forward of the same tokens (token 0 everywhere, as spec_debug_fill_kv leaves them)."""
+    from oracle import model as om
+    from parity_utils import oshape
+    pk = _pk()
+    cfg, Wt, Wd, Wt_np, Wd_np = _widened_pair(pair_name, 2, 1)
+    ms = cfg.target
+    eng = pk.SpecEngine(cfg.target, Wt, cfg.draft, Wd, batch=batch, max_seq=kv_len + 2 * 16 + 8, gamma_max=15,
+                        temperature=1.0, seed=0, use_graphs=True)
+    eng.fill_kv(kv_len)
+    caches = []
+    for b in range(batch):
+        cache = om.KVCache(oshape(ms))
+        for l in range(ms.n_layers):
+            k, v = synth.make_kv(kv_len, ms.n_kv_heads, ms.head_dim, 500 * b + 7 * l + 1)
+            eng.write_kv(1, l, b, 0, k, v)
+            cache.k[l], cache.v[l] = k.astype(np.float64), v.astype(np.float64)
+        cache.length = kv_len
+        caches.append(cache)
+    worst = 0.0
+    for rows in (1, 2, 5, 16, 2):  # the last one replays a cached graph after others were captured
+        eng.verify_rows(rows)
+        got = eng.debug_logits(1)
+        assert got.shape == (batch, rows, ms.vocab)
+        for b in range(batch):
+            caches[b].truncate(kv_len)
+            want = om.forward(oshape(ms), Wt_np, [0] * rows, caches[b])
+            scale = float(np.abs(want).max())
+            err = float(np.abs(got[b] - want).max()) / scale
+            worst = max(worst, err)
+            assert np.isfinite(got[b]).all()
+            assert err <= TOL["bf16"], f"rows {rows} seq {b}: logits err {err:.3e}"
+    print(f"verification-only passes: worst logits err {worst:.3e}")
+    eng.close()
+
+
 def test_plain_copy_kernel():
     pk = _pk()
     src = torch.randint(0, 255, (1 << 20,), dtype=torch.uint8, device="cuda")
