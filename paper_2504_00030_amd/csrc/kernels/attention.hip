@@ -304,6 +304,186 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
     }
 }
 
+// ---- the same chunk streamed through two register buffers ---------------------------------------------------
+// For passes whose attention launches thousands of workgroups (many sequences decoding in lock-step) a workgroup
+// takes a long chunk (256 or 512 positions) and its waves walk their 16-position slabs w, w + 4, ... with the next
+// slab's K rows and V columns in flight while this one is multiplied: the loads never pause for the arithmetic, and a
+// sequence leaves two or three partials instead of a dozen.  The softmax runs on line: a wave keeps a running
+// maximum per query, and rescales its sum and its output tile when a slab raises it.  The four waves' partials are
+// merged as above.  One 16-query tile at a time; a sequence with more queries than that streams its chunk once per tile.
+template <int HD>
+__global__ __launch_bounds__(256) void attn_stream_k(const AttnArgs a) {
+    if (a.active != nullptr && *a.active == 0) return;
+    constexpr int ES = HD / 32, ET = HD / 16;
+    const int CT = a.chunk;  // host: a multiple of 64
+    const int QS = gridDim.z / a.batch;
+    const int c = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z / QS, qs = blockIdx.z % QS;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l16 = lane & 15, g = lane >> 4;
+    const int G = a.nq / a.kv.n_kv;
+    const int r_first = a.row_off != nullptr ? a.row_off[b] : b * a.rps;
+    const int rps = a.row_off != nullptr ? a.row_off[b + 1] - r_first : a.rps;
+    const int QN = G * rps;
+    const int t0 = c * CT;
+    const bf16_t *kp = reinterpret_cast<const bf16_t *>(a.kv.k);
+    const bf16_t *vp = reinterpret_cast<const bf16_t *>(a.kv.v);
+
+    __shared__ __attribute__((aligned(16))) float sO[4][16][HD + 4];
+    __shared__ float sM[4][16], sL[4][16];
+
+    const int cap = a.kv.pages_per_seq * a.kv.page_tokens;
+    const bool has_qlo = a.qb_lo != 0;
+    const int last_pos = __builtin_amdgcn_readfirstlane(a.row_pos[r_first + rps - 1]);
+    if (t0 > last_pos) return;
+    const int n_live = last_pos / CT + 1;
+    // slabs of this chunk that hold a visible position (scalar: it bounds the loops around the matrix instructions)
+    const int NS = (min(CT, last_pos - t0 + 1) + 15) >> 4;
+
+    struct Slab { u32x4_t kf[ES]; u32x2_t vf[ET]; };
+    auto load_slab = [&](int sl, Slab &d) {
+        const int tw = t0 + 16 * sl;
+        const int pk = min(tw + l16, cap - 1);
+        const size_t kb = kv_index_k(a.kv, b, pk, kvh, 8 * g);
+#pragma unroll
+        for (int e = 0; e < ES; ++e) d.kf[e] = *reinterpret_cast<const u32x4_t *>(kp + kb + 32 * e);
+        const int pv = min(tw + 4 * g, cap - 4);
+        const size_t vb = kv_index_v(a.kv, b, pv, kvh, l16);
+#pragma unroll
+        for (int et = 0; et < ET; ++et)
+            d.vf[et] = *reinterpret_cast<const u32x2_t *>(vp + vb + (size_t)(16 * et) * a.kv.page_tokens);
+    };
+
+    const int QT = (QN + 15) / 16, TPW = (QT + QS - 1) / QS;
+    const int qt_end = min(QT, (qs + 1) * TPW);
+    for (int qt = qs * TPW; qt < qt_end; ++qt) {
+        // the first slab goes out before the queries are looked at
+        Slab A, B;
+        if (wave < NS) load_slab(wave, A);
+        const int qi = min(qt * 16 + l16, QN - 1);
+        const int gq = qi / rps, qrow = r_first + qi % rps, qh = kvh * G + gq;
+        const int qpos = a.row_pos[qrow];
+        u32x4_t qf[ES], ql[ES];
+        {
+            const bf16_t *qp = a.qb + ((size_t)qrow * a.nq + qh) * HD + 8 * g;
+#pragma unroll
+            for (int e = 0; e < ES; ++e) {
+                qf[e] = *reinterpret_cast<const u32x4_t *>(qp + 32 * e);
+                ql[e] = has_qlo ? *reinterpret_cast<const u32x4_t *>(qp + a.qb_lo + 32 * e) : u32x4_t{0u, 0u, 0u, 0u};
+            }
+        }
+        // a tile none of whose queries sees this chunk leaves no partial: the merge never reads one there
+        if (t0 > __builtin_amdgcn_readfirstlane(wave_max(qpos))) continue;
+
+        float m_run = -INFINITY, l_part = 0.f;
+        f32x4_t O[ET];
+#pragma unroll
+        for (int et = 0; et < ET; ++et) O[et] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+        auto process = [&](const Slab &d, int sl) {
+            const int tw = t0 + 16 * sl;
+            f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int e = 0; e < ES; ++e) {
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, d.kf[e]),
+                                                              __builtin_bit_cast(bf16x8_t, qf[e]), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, d.kf[e]),
+                                                              __builtin_bit_cast(bf16x8_t, ql[e]), acc, 0, 0, 0);
+            }
+            float sv[4], ms = -INFINITY;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                sv[v] = (tw + 4 * g + v) <= qpos ? acc[v] * a.scale : -INFINITY;
+                ms = fmaxf(ms, sv[v]);
+            }
+            ms = fmaxf(ms, __shfl_xor(ms, 16, WAVE));
+            ms = fmaxf(ms, __shfl_xor(ms, 32, WAVE));
+            const float m_new = fmaxf(m_run, ms);
+            // nothing visible yet: everything stays zero; first visible slab: the old (empty) state weighs nothing
+            const float alpha = m_new == -INFINITY ? 1.f : (m_run == -INFINITY ? 0.f : __expf(m_run - m_new));
+            float p[4], ps = 0.f;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                p[v] = m_new == -INFINITY ? 0.f : __expf(sv[v] - m_new);
+                ps += p[v];
+            }
+            l_part = l_part * alpha + ps;
+            m_run = m_new;
+            // the output tile holds query 4 g + v in register v: its factor sits in the lane whose column is that query
+            float aq[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) aq[v] = __shfl(alpha, 4 * g + v, WAVE);
+            u32x2_t pw, pl;
+            pw.x = pack_bf16x2(p[0], p[1]);
+            pw.y = pack_bf16x2(p[2], p[3]);
+            pl.x = pack_bf16x2(p[0] - bf16_lo(pw.x), p[1] - bf16_hi(pw.x));
+            pl.y = pack_bf16x2(p[2] - bf16_lo(pw.y), p[3] - bf16_hi(pw.y));
+#pragma unroll
+            for (int et = 0; et < ET; ++et) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) O[et][v] *= aq[v];
+                O[et] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, pw),
+                                                                  __builtin_bit_cast(s16x4_t, d.vf[et]), O[et], 0, 0, 0);
+                O[et] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, pl),
+                                                                  __builtin_bit_cast(s16x4_t, d.vf[et]), O[et], 0, 0, 0);
+            }
+        };
+        for (int sl = wave; sl < NS; sl += 8) {
+            if (sl + 4 < NS) load_slab(sl + 4, B);
+            process(A, sl);
+            if (sl + 4 < NS) {
+                if (sl + 8 < NS) load_slab(sl + 8, A);
+                process(B, sl + 4);
+            }
+        }
+        float l = l_part;
+        l += __shfl_xor(l, 16, WAVE);
+        l += __shfl_xor(l, 32, WAVE);
+        if (g == 0) { sM[wave][l16] = m_run; sL[wave][l16] = l; }
+#pragma unroll
+        for (int et = 0; et < ET; ++et)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) sO[wave][4 * g + v][16 * et + l16] = O[et][v];
+        __syncthreads();
+        {
+            constexpr int EPT = HD / 16;
+            const int q = threadIdx.x >> 4, e0 = (threadIdx.x & 15) * EPT;
+            const int qj = qt * 16 + q;
+            if (qj < QN) {
+                const float M = fmaxf(fmaxf(sM[0][q], sM[1][q]), fmaxf(sM[2][q], sM[3][q]));
+                float f[4], L = 0.f, acc[EPT];
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    f[w] = sM[w][q] == -INFINITY ? 0.f : __expf(sM[w][q] - M);
+                    L += f[w] * sL[w][q];
+                }
+#pragma unroll
+                for (int k = 0; k < EPT; ++k) acc[k] = 0.f;
+#pragma unroll
+                for (int w = 0; w < 4; ++w)
+#pragma unroll
+                    for (int k = 0; k < EPT; ++k) acc[k] += f[w] * sO[w][q][e0 + k];
+                const int rr = r_first + qj % rps, hh = kvh * G + qj / rps;
+                if (n_live == 1) {
+                    const size_t o = ((size_t)rr * a.nq + hh) * HD + e0;
+#pragma unroll
+                    for (int k = 0; k < EPT; ++k) {
+                        const float v = acc[k] / L;
+                        a.o[o + k] = v;
+                        store_split_bf16(a.ob, o + k, a.ob_lo, v);
+                    }
+                } else {
+                    const size_t pi = ((size_t)rr * a.nq + hh) * a.n_chunks + c;
+                    float *po = a.part_o + pi * HD + e0;
+#pragma unroll
+                    for (int k = 0; k < EPT; ++k) po[k] = acc[k];
+                    if (e0 == 0) { a.part_m[pi] = M; a.part_l[pi] = L; }
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
 // Merge of the chunk partials of the matrix-core kernel: o = sum_c w_c o_c with
 // w_c = exp(m_c - M) / sum_c exp(m_c - M) l_c, in chunk order.  One thread per (row, head, four channels);
 // rows of a sequence that fits one chunk were already written by attn_mfma_k.  The partials of all n_chunks
@@ -380,6 +560,15 @@ bool attention_uses_mfma(const AttnArgs &a, int hd) {
 
 template <int HD>
 static hipError_t launch_attn_mfma(const AttnArgs &a, dim3 grid, hipStream_t s) {
+    if (a.stream_chunks) {
+        hipLaunchKernelGGL((attn_stream_k<HD>), grid, dim3(256), 0, s, a);
+        const hipError_t e0 = hipGetLastError();
+        if (e0 != hipSuccess || a.n_chunks == 1) return e0;
+        const int items0 = a.R * a.nq * (HD / 4);
+        if (a.n_chunks <= 16) hipLaunchKernelGGL((attn_mfma_merge_k<HD, 16>), dim3((items0 + 255) / 256), dim3(256), 0, s, a);
+        else hipLaunchKernelGGL((attn_mfma_merge_k<HD, ATT_NC_MAX>), dim3((items0 + 255) / 256), dim3(256), 0, s, a);
+        return hipGetLastError();
+    }
     // queries held ahead: chunks of up to 128 positions (beyond, the K / V fragments leave no registers) and few
     // enough workgroups that a compute unit does not wait for a slot
     const bool ahead = a.chunk <= 128 && (size_t)grid.x * grid.y * grid.z <= 1024;

@@ -125,6 +125,7 @@ struct AttnArgs {
     const int32_t *row_off; // [batch + 1] first row of every sequence when they differ in rows (null: b * rps)
     const int32_t *row_pos, *row_seq;
     int32_t chunk;        // KV positions per workgroup
+    int32_t stream_chunks; // matrix-core kernels: 1 = the chunk is streamed slab by slab through two register buffers (chunks of 256 / 512)
     int32_t n_chunks;     // grid.x
     float scale;
     float *part_m, *part_l;  // [R][nq][n_chunks]
