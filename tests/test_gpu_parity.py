@@ -636,6 +636,44 @@ def test_verification_only_passes_match_the_oracle(pair_name, batch, kv_len):
     eng.close()
 
 
+@pytest.mark.parametrize("pair_name,batch", [("small-bf16", 3), ("8b", 1), ("8b", 4), ("13b", 2)])
+def test_two_runs_are_bit_identical(pair_name, batch):
+    """Every reduction of the path has a fixed order (wave partials in wave order, K slices in slice order whichever
+    workgroup arrives last, softmax partials in tile order), so a second run of the same generation must reproduce
+    the first bit for bit: tokens, accept counts, and every draft and target logit.  Doubles as a race detector."""
+    pk = _pk()
+    if pair_name == "small-bf16":
+        cfg = synth.pair(pair_name)
+        Wt, Wd = (to_gpu(W) for W in synth.make_pair_weights(cfg, 0))
+    else:
+        cfg = synth.shrink(synth.pair(pair_name), 2, 1)
+        Wt, Wd = synth.make_pair_weights(cfg, 0, device="cuda")
+        torch.cuda.synchronize()
+    prompts = synth.make_prompts(batch, 40, cfg.target.vocab, 5)
+    runs = []
+    for rep in range(2):
+        eng = pk.SpecEngine(cfg.target, Wt, cfg.draft, Wd, batch=batch, max_seq=40 + 8 * 17 + 8, gamma_max=16, temperature=1.0,
+                            seed=3, accept_mode=pk.ACCEPT_NATURAL, use_graphs=bool(rep))
+        eng.prefill(prompts)
+        rec = []
+        for step, gamma in enumerate((1, 4, 8, 15, 2, 16)):
+            eng.draft(gamma if batch == 1 else np.full(batch, gamma, dtype=np.int32))
+            eng.verify(gamma)
+            q = eng.debug_logits(0)
+            A, y, k = eng.accept()
+            p = eng.debug_logits(1)
+            rec.append((q.copy(), p.copy(), A.copy(), y.copy(), k.copy()))
+        toks = [eng.read_tokens(b).copy() for b in range(batch)]
+        eng.close()
+        runs.append((rec, toks))
+    (r0, t0), (r1, t1) = runs  # direct launches, then graphs
+    for step, (a, b) in enumerate(zip(r0, r1)):
+        for name, u, v in zip(("draft logits", "target logits", "A", "y", "k"), a, b):
+            assert np.array_equal(u, v), f"step {step}: {name} differ between two runs"
+    for u, v in zip(t0, t1):
+        assert np.array_equal(u, v)
+
+
 def test_plain_copy_kernel():
     pk = _pk()
     src = torch.randint(0, 255, (1 << 20,), dtype=torch.uint8, device="cuda")
