@@ -304,15 +304,15 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
     }
 }
 
-// ---- the same chunk streamed through two register buffers ---------------------------------------------------
+// ---- the same chunk streamed through three register buffers ---------------------------------------------------
 // For passes whose attention launches thousands of workgroups (many sequences decoding in lock-step) a workgroup
 // takes a long chunk (256 or 512 positions) and its waves walk their 16-position slabs w, w + 4, ... with the next
-// slab's K rows and V columns in flight while this one is multiplied: the loads never pause for the arithmetic, and a
+// two slabs' K rows and V columns in flight while this one is multiplied: the loads never pause for the arithmetic, and a
 // sequence leaves two or three partials instead of a dozen.  The softmax runs on line: a wave keeps a running
 // maximum per query, and rescales its sum and its output tile when a slab raises it.  The four waves' partials are
 // merged as above.  One 16-query tile at a time; a sequence with more queries than that streams its chunk once per tile.
 template <int HD>
-__global__ __launch_bounds__(256) void attn_stream_k(const AttnArgs a) {
+__global__ __launch_bounds__(256, 2) void attn_stream_k(const AttnArgs a) {
     if (a.active != nullptr && *a.active == 0) return;
     constexpr int ES = HD / 32, ET = HD / 16;
     const int CT = a.chunk;  // host: a multiple of 64
@@ -357,8 +357,9 @@ __global__ __launch_bounds__(256) void attn_stream_k(const AttnArgs a) {
     const int qt_end = min(QT, (qs + 1) * TPW);
     for (int qt = qs * TPW; qt < qt_end; ++qt) {
         // the first slab goes out before the queries are looked at
-        Slab A, B;
+        Slab A, B, C;
         if (wave < NS) load_slab(wave, A);
+        if (wave + 4 < NS) load_slab(wave + 4, B);
         const int qi = min(qt * 16 + l16, QN - 1);
         const int gq = qi / rps, qrow = r_first + qi % rps, qh = kvh * G + gq;
         const int qpos = a.row_pos[qrow];
@@ -427,12 +428,17 @@ __global__ __launch_bounds__(256) void attn_stream_k(const AttnArgs a) {
                                                                   __builtin_bit_cast(s16x4_t, d.vf[et]), O[et], 0, 0, 0);
             }
         };
-        for (int sl = wave; sl < NS; sl += 8) {
-            if (sl + 4 < NS) load_slab(sl + 4, B);
+        // three buffers in rotation: two slabs are in flight while one is multiplied
+        for (int sl = wave; sl < NS; sl += 12) {
+            if (sl + 8 < NS) load_slab(sl + 8, C);
             process(A, sl);
             if (sl + 4 < NS) {
-                if (sl + 8 < NS) load_slab(sl + 8, A);
+                if (sl + 12 < NS) load_slab(sl + 12, A);
                 process(B, sl + 4);
+            }
+            if (sl + 8 < NS) {
+                if (sl + 16 < NS) load_slab(sl + 16, B);
+                process(C, sl + 8);
             }
         }
         float l = l_part;
