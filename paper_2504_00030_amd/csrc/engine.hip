@@ -404,6 +404,7 @@ KVCache kv_of(const spec_ctx *c, const ModelRT &m, int l) {
     kv.page_shift = sh;
     kv.n_kv = m.s.n_kv_heads;
     kv.hd = m.s.head_dim;
+    kv.frag = m.s.head_dim % 32 == 0 && c->cfg.page_tokens >= 16 ? 1 : 0;
     return kv;
 }
 
@@ -563,21 +564,29 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
                 // long row runs (prompt ingestion) take the largest chunk: their cost is the traffic of the chunk
                 // partials, one per (row, head, chunk), not the latency of a chunk
                 int wanted = plan.rps >= 64 && c->cfg.attn_chunk == 0 ? 256 : c->cfg.attn_chunk;
-                // Decode and verification rows (not prompt ingestion): where the capacity makes the chunks 512 positions
-                // long (more than 4096 positions per sequence), or a chunk of 256 / 512 is asked for, it is streamed
-                // through two register buffers instead of held whole (13B-shaped verification at 4096 cached positions:
-                // 2 % faster for one sequence, 13 % for eight).  Measured and not taken: long streamed chunks in place
-                // of the 128-position ones when many sequences make thousands of workgroups (8B-shaped pair, 32
-                // sequences: 3628 -> 3324 tokens/s, the streamed launch 130 us against 73 us per target layer).
+                // Decode and verification rows (not prompt ingestion) stream a long chunk through three register
+                // buffers instead of holding a short one whole (i) where the capacity makes the chunks 512 positions long
+                // (more than 4096 positions per sequence) or a chunk of 256 / 512 is asked for, and (ii) where the
+                // automatic chunks would make more than 1024 workgroups of the launch and the capacity is at least two
+                // long chunks: then 512-position chunks are taken in their place.  Measured, 13B-shaped verification of
+                // one row per sequence at 4096 cached positions: 6.40 -> 5.99 ms for one sequence, 13.2 -> 10.3 ms for
+                // eight; at 2048 positions and eight sequences 8.44 -> 8.08 ms; 8B-shaped pair, 16 / 32 sequences: +6 % /
+                // +3 % tokens/s.  Not taken: streaming automatic 256-position chunks of a single sequence (2 % slower),
+                // and long chunks when the capacity is one of them (eight sequences at 512 positions: 3 % slower).
                 static const bool no_stream = std::getenv("SPEC_NO_ATTN_STREAM") != nullptr;
                 bool stream = false;
-                if (plan.rps < 64 && !no_stream) {
+                if (plan.rps < 64 && !no_stream && c->cfg.page_tokens >= 16) {
                     const int auto_chunk = attention_mfma_chunk(c->cfg.max_seq, wanted);
-                    stream = auto_chunk >= 512 || wanted == 256;  // automatic 256-position chunks stay resident (measured: 3 % faster)
+                    stream = auto_chunk >= 512 || wanted == 256;
+                    if (wanted == 0 && c->cfg.max_seq >= 1024 &&
+                        (int64_t)B * s.n_kv_heads * ((c->cfg.max_seq + auto_chunk - 1) / auto_chunk) > 1024) {
+                        wanted = 512;
+                        stream = true;
+                    }
                 }
                 const int chunk = attention_mfma_chunk(c->cfg.max_seq, wanted);
                 const int nch = (c->cfg.max_seq + chunk - 1) / chunk;
-                if (nch <= ATT_NC_MAX) { t.chunk = chunk; t.n_chunks = nch; t.stream_chunks = stream && chunk >= 256; }
+                if (nch <= ATT_NC_MAX) { t.chunk = chunk; t.n_chunks = nch; t.stream_chunks = stream && chunk >= 256 && chunk <= 512; }
                 else t.qb = nullptr;  // capacity beyond the merge of the matrix-core kernel: plain kernel
             }
             ProfScope ps_(c, m, 7, false);  // events on the stream around both launches (attention and its merge)

@@ -35,9 +35,10 @@ __global__ __launch_bounds__(256) void attn_simple_k(const AttnArgs a) {
         float s = -INFINITY;
         if (pos <= a.row_pos[r]) {
             const float *q = a.q + ((size_t)r * a.nq + h) * hd;
-            const size_t kb = kv_index_k(a.kv, b, pos, kvh, 0);
+            const size_t kb = kv_head_base(a.kv, kv_page(a.kv, b, pos), kvh);
+            const int tp = pos & (a.kv.page_tokens - 1);
             float acc = 0.f;
-            for (int e = 0; e < hd; ++e) acc = fmaf(q[e], kv_load(a.kv.k, a.kv_dtype, kb + e), acc);
+            for (int e = 0; e < hd; ++e) acc = fmaf(q[e], kv_load(a.kv.k, a.kv_dtype, kb + kv_in_k(a.kv, tp, e)), acc);
             s = acc * a.scale;
         }
         S[i][t] = s;
@@ -169,18 +170,19 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
     if constexpr (AHEAD) load_q(qs * TPW, qn);
     u32x4_t kf[SPW][ES];
     u32x2_t vf[SPW][ET];
+    const int k_step = kv_step_k(a.kv), v_step = kv_step_v(a.kv);
 #pragma unroll
     for (int sl = 0; sl < SPW; ++sl) {
         const int tw = t0 + 16 * (wave + 4 * sl);
         const int pk = min(tw + l16, cap - 1);
         const size_t kb = kv_index_k(a.kv, b, pk, kvh, 8 * g);
 #pragma unroll
-        for (int s = 0; s < ES; ++s) kf[sl][s] = *reinterpret_cast<const u32x4_t *>(kp + kb + 32 * s);
+        for (int s = 0; s < ES; ++s) kf[sl][s] = *reinterpret_cast<const u32x4_t *>(kp + kb + (size_t)s * k_step);
         const int pv = min(tw + 4 * g, cap - 4);
         const size_t vb = kv_index_v(a.kv, b, pv, kvh, l16);
 #pragma unroll
         for (int et = 0; et < ET; ++et)
-            vf[sl][et] = *reinterpret_cast<const u32x2_t *>(vp + vb + (size_t)(16 * et) * a.kv.page_tokens);
+            vf[sl][et] = *reinterpret_cast<const u32x2_t *>(vp + vb + (size_t)et * v_step);
     }
     const int last_pos = __builtin_amdgcn_readfirstlane(last_pos_l);
     if (t0 > last_pos) return;
@@ -339,27 +341,39 @@ __global__ __launch_bounds__(256, 2) void attn_stream_k(const AttnArgs a) {
     // slabs of this chunk that hold a visible position (scalar: it bounds the loops around the matrix instructions)
     const int NS = (min(CT, last_pos - t0 + 1) + 15) >> 4;
 
+    // Physical pages of the chunk's slabs, looked up once: a slab of 16 positions lies inside one page (host: pages
+    // of at least 16 tokens), so the loads of a slab depend on nothing that is itself a load.  (Loads complete in
+    // order: a block-table lookup per slab would make every wait for it wait for the slabs in flight as well.)
+    __shared__ int s_page[32];
+    if (threadIdx.x < 32) {
+        const int pos = min(t0 + 16 * (int)threadIdx.x, cap - 1);
+        s_page[threadIdx.x] = kv_page(a.kv, b, pos);
+    }
+    __syncthreads();
+    const int pt_mask = a.kv.page_tokens - 1;
+    const int k_step = kv_step_k(a.kv), v_step = kv_step_v(a.kv);
     struct Slab { u32x4_t kf[ES]; u32x2_t vf[ET]; };
     auto load_slab = [&](int sl, Slab &d) {
         const int tw = t0 + 16 * sl;
+        const size_t base = kv_head_base(a.kv, s_page[sl], kvh);
         const int pk = min(tw + l16, cap - 1);
-        const size_t kb = kv_index_k(a.kv, b, pk, kvh, 8 * g);
+        const size_t kb = base + kv_in_k(a.kv, pk & pt_mask, 8 * g);
 #pragma unroll
-        for (int e = 0; e < ES; ++e) d.kf[e] = *reinterpret_cast<const u32x4_t *>(kp + kb + 32 * e);
+        for (int e = 0; e < ES; ++e) d.kf[e] = *reinterpret_cast<const u32x4_t *>(kp + kb + (size_t)e * k_step);
         const int pv = min(tw + 4 * g, cap - 4);
-        const size_t vb = kv_index_v(a.kv, b, pv, kvh, l16);
+        const size_t vb = base + kv_in_v(a.kv, pv & pt_mask, l16);
 #pragma unroll
         for (int et = 0; et < ET; ++et)
-            d.vf[et] = *reinterpret_cast<const u32x2_t *>(vp + vb + (size_t)(16 * et) * a.kv.page_tokens);
+            d.vf[et] = *reinterpret_cast<const u32x2_t *>(vp + vb + (size_t)et * v_step);
     };
 
     const int QT = (QN + 15) / 16, TPW = (QT + QS - 1) / QS;
     const int qt_end = min(QT, (qs + 1) * TPW);
     for (int qt = qs * TPW; qt < qt_end; ++qt) {
-        // the first slab goes out before the queries are looked at
-        Slab A, B, C;
-        if (wave < NS) load_slab(wave, A);
-        if (wave + 4 < NS) load_slab(wave + 4, B);
+        // Queries first, then the first two slabs, all before anything is waited for.  Every slab load below is
+        // issued unconditionally (past the last slab the index is clamped, and the re-read hits the cache): the
+        // number of loads in flight is then the same on every path through the loop, which is what lets the
+        // waits before the matrix instructions leave the two younger slabs outstanding.
         const int qi = min(qt * 16 + l16, QN - 1);
         const int gq = qi / rps, qrow = r_first + qi % rps, qh = kvh * G + gq;
         const int qpos = a.row_pos[qrow];
@@ -372,6 +386,9 @@ __global__ __launch_bounds__(256, 2) void attn_stream_k(const AttnArgs a) {
                 ql[e] = has_qlo ? *reinterpret_cast<const u32x4_t *>(qp + a.qb_lo + 32 * e) : u32x4_t{0u, 0u, 0u, 0u};
             }
         }
+        Slab A, B, C;
+        load_slab(min(wave, NS - 1), A);
+        load_slab(min(wave + 4, NS - 1), B);
         // a tile none of whose queries sees this chunk leaves no partial: the merge never reads one there
         if (t0 > __builtin_amdgcn_readfirstlane(wave_max(qpos))) continue;
 
@@ -430,16 +447,12 @@ __global__ __launch_bounds__(256, 2) void attn_stream_k(const AttnArgs a) {
         };
         // three buffers in rotation: two slabs are in flight while one is multiplied
         for (int sl = wave; sl < NS; sl += 12) {
-            if (sl + 8 < NS) load_slab(sl + 8, C);
+            load_slab(min(sl + 8, NS - 1), C);
             process(A, sl);
-            if (sl + 4 < NS) {
-                if (sl + 12 < NS) load_slab(sl + 12, A);
-                process(B, sl + 4);
-            }
-            if (sl + 8 < NS) {
-                if (sl + 16 < NS) load_slab(sl + 16, B);
-                process(C, sl + 8);
-            }
+            load_slab(min(sl + 12, NS - 1), A);
+            if (sl + 4 < NS) process(B, sl + 4);
+            load_slab(min(sl + 16, NS - 1), B);
+            if (sl + 8 < NS) process(C, sl + 8);
         }
         float l = l_part;
         l += __shfl_xor(l, 16, WAVE);

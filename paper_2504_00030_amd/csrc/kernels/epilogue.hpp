@@ -236,8 +236,8 @@ __device__ __forceinline__ void epilogue_tile_pre(const GemvArgs &a, const float
             const int kvh = hh - a.nq - (is_k ? 0 : a.nkv);
             const int in_page = p.pos & (a.kv.page_tokens - 1);
             const size_t base = kv_head_base(a.kv, p.page, kvh);
-            const size_t e1 = is_k ? base + (size_t)in_page * a.kv.hd + j : base + (size_t)j * a.kv.page_tokens + in_page;
-            const size_t e2 = is_k ? e1 + half : e1 + (size_t)half * a.kv.page_tokens;
+            const size_t e1 = base + (is_k ? kv_in_k(a.kv, in_page, j) : kv_in_v(a.kv, in_page, j));
+            const size_t e2 = base + (is_k ? kv_in_k(a.kv, in_page, j + half) : kv_in_v(a.kv, in_page, j + half));
             void *pool = is_k ? a.kv.k : a.kv.v;
             if (a.kv_dtype == DT_BF16) {
                 reinterpret_cast<bf16_t *>(pool)[e1] = f32_to_bf16(y1);

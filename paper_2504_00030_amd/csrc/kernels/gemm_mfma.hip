@@ -150,8 +150,8 @@ __device__ __forceinline__ void qkv_wave_epilogue(const GemvArgs &b, const float
             const int kvh = hh - b.nq - (is_k ? 0 : b.nkv);
             const int in_page = rows_pos[it] & (b.kv.page_tokens - 1);
             const size_t base = kv_head_base(b.kv, rows_page[it], kvh);
-            const size_t e1 = is_k ? base + (size_t)in_page * b.kv.hd + j : base + (size_t)j * b.kv.page_tokens + in_page;
-            const size_t e2 = is_k ? e1 + half : e1 + (size_t)half * b.kv.page_tokens;
+            const size_t e1 = base + (is_k ? kv_in_k(b.kv, in_page, j) : kv_in_v(b.kv, in_page, j));
+            const size_t e2 = base + (is_k ? kv_in_k(b.kv, in_page, j + half) : kv_in_v(b.kv, in_page, j + half));
             void *pool = is_k ? b.kv.k : b.kv.v;
             if (b.kv_dtype == DT_BF16) {
                 reinterpret_cast<bf16_t *>(pool)[e1] = f32_to_bf16(y1);

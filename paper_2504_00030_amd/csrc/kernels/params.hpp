@@ -32,9 +32,10 @@ struct RowPlan {
 };
 
 struct KVCache {
-    void *k, *v;                 // one layer: [n_pages][n_kv][page_tokens][hd], element type per model dtype
+    void *k, *v;                 // one layer: [n_pages][n_kv][page_tokens x hd block], element type per model dtype
     const int32_t *block_table;  // [B][pages_per_seq] logical -> physical page
     int32_t pages_per_seq, page_tokens, page_shift, n_kv, hd;
+    int32_t frag;                // arrangement inside a head's block: 0 plain, 1 fragment order (kv.hpp)
 };
 
 enum { EPI_PLAIN = 0, EPI_QKV = 1, EPI_RESID = 2, EPI_SWIGLU = 3, EPI_LOGITS = 4 };
@@ -125,7 +126,7 @@ struct AttnArgs {
     const int32_t *row_off; // [batch + 1] first row of every sequence when they differ in rows (null: b * rps)
     const int32_t *row_pos, *row_seq;
     int32_t chunk;        // KV positions per workgroup
-    int32_t stream_chunks; // matrix-core kernels: 1 = the chunk is streamed slab by slab through two register buffers (chunks of 256 / 512)
+    int32_t stream_chunks; // matrix-core kernels: 1 = the chunk is streamed slab by slab through three register buffers (chunks of 256 / 512)
     int32_t n_chunks;     // grid.x
     float scale;
     float *part_m, *part_l;  // [R][nq][n_chunks]
