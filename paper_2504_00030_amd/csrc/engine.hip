@@ -59,6 +59,7 @@ struct ModelRT {
     int pages_per_seq = 0, n_pages = 0;
     float *rope_cos = nullptr, *rope_sin = nullptr;
     float *part_m = nullptr, *part_l = nullptr, *part_o = nullptr;
+    uint32_t *att_ticket = nullptr;  // [B][n_kv_heads] arrival counters of the attention chunks (zero between launches)
     int n_chunks = 0;
     // logits and their tile partials
     float *logits = nullptr;
@@ -378,6 +379,7 @@ int build_model(spec_ctx *c, ModelRT &m, const spec_shape &s, const spec_weights
     TRY(dalloc(c, &m.part_m, pn));
     TRY(dalloc(c, &m.part_l, pn));
     TRY(dalloc(c, &m.part_o, pn * s.head_dim));
+    TRY(dalloc(c, &m.att_ticket, (size_t)c->cfg.batch * s.n_kv_heads));
 
     m.logit_rows = logit_rows;
     TRY(dalloc(c, &m.logits, (size_t)logit_rows * s.vocab));
@@ -558,7 +560,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
             t.q = m.q; t.qb = c->cfg.gemv_path == SPEC_PATH_WAVEDOT ? nullptr : m.qb; t.kv = kv_of(c, m, l); t.kv_dtype = s.dtype; t.R = R; t.rps = plan.rps; t.nq = s.n_q_heads; t.batch = B; t.row_off = plan.ragged ? m.row_off : nullptr;
             t.row_pos = m.row_pos; t.row_seq = m.row_seq; t.chunk = ATT_CHUNK; t.n_chunks = m.n_chunks;
             t.scale = 1.0f / std::sqrt((float)s.head_dim);
-            t.part_m = m.part_m; t.part_l = m.part_l; t.part_o = m.part_o; t.o = m.ao; t.ob = m.aob; t.active = active;
+            t.part_m = m.part_m; t.part_l = m.part_l; t.part_o = m.part_o; t.ticket = m.att_ticket; t.o = m.ao; t.ob = m.aob; t.active = active;
             t.qb_lo = qb_lo; t.ob_lo = aob_lo;
             if (attention_uses_mfma(t, s.head_dim)) {
                 // long row runs (prompt ingestion) take the largest chunk: their cost is the traffic of the chunk
@@ -575,7 +577,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
                 // and long chunks when the capacity is one of them (eight sequences at 512 positions: 3 % slower).
                 static const bool no_stream = std::getenv("SPEC_NO_ATTN_STREAM") != nullptr;
                 bool stream = false;
-                if (plan.rps < 64 && !no_stream && c->cfg.page_tokens >= 16) {
+                if (plan.mode != ROWS_PREFILL && plan.rps < 64 && !no_stream && c->cfg.page_tokens >= 16) {
                     const int auto_chunk = attention_mfma_chunk(c->cfg.max_seq, wanted);
                     stream = auto_chunk >= 512 || wanted == 256;
                     if (wanted == 0 && c->cfg.max_seq >= 1024 &&

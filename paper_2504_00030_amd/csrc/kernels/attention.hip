@@ -5,6 +5,8 @@
 //
 // attn_simple_k is the plain version: any head size and cache type, fp32 arithmetic, one
 // workgroup per (chunk, query head, sequence).  It serves fp32 models.
+#include <cstdlib>
+
 #include "common.hpp"
 #include "kv.hpp"
 #include "params.hpp"
@@ -110,13 +112,24 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
+__device__ __forceinline__ uint64_t pack_f32x2(float lo, float hi) {
+    return (uint64_t)__float_as_uint(lo) | ((uint64_t)__float_as_uint(hi) << 32);
+}
+__device__ __forceinline__ float f32_lo(uint64_t u) { return __uint_as_float((uint32_t)u); }
+__device__ __forceinline__ float f32_hi(uint64_t u) { return __uint_as_float((uint32_t)(u >> 32)); }
+
 constexpr int ATT_SPW_MAX = 8;   // slabs per wave -> chunks of up to 512 positions
 constexpr int ATT_TILES_PER_WG = 8;  // 16-query tiles a workgroup works through (decode and verification: all of them)
 
 // AHEAD: the row-dependent loads (a sequence's last position, the queries of the tile after this one) are held a
 // step ahead in registers - shorter dependent chains for the few workgroups of a single sequence, but 30-40 more
 // registers, which cost a workgroup per compute unit when a batch launches thousands.
-template <int HD, int SPW, bool AHEAD>
+// FUSE: the chunk partials of a (sequence, kv head) are merged by whichever of its workgroups finishes last, instead
+// of by attn_mfma_merge_k: the partials are written with agent-scope stores (past the per-XCD L2 caches), every
+// workgroup then takes a ticket from the pair's arrival counter, and the one that draws the last ticket reads all
+// partials back with agent-scope loads and merges them with the arithmetic of the merge kernel, in chunk order.
+// For launches of few workgroups (one or a few sequences), where a second launch costs more than the tail does.
+template <int HD, int SPW, bool AHEAD, bool FUSE = false>
 __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
     if (a.active != nullptr && *a.active == 0) return;
     constexpr int ES = HD / 32;  // k-steps of the score product
@@ -290,7 +303,16 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
                 } else {
                     const size_t pi = ((size_t)rr * a.nq + hh) * a.n_chunks + c;
                     float *po = a.part_o + pi * HD + e0;
-                    if constexpr (EPT % 4 == 0) {
+                    if constexpr (FUSE) {
+#pragma unroll
+                        for (int k = 0; k < EPT; k += 2)
+                            __hip_atomic_store(reinterpret_cast<uint64_t *>(po + k), pack_f32x2(acc[k], acc[k + 1]),
+                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if (e0 == 0) {
+                            __hip_atomic_store(a.part_m + pi, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            __hip_atomic_store(a.part_l + pi, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        }
+                    } else if constexpr (EPT % 4 == 0) {
 #pragma unroll
                         for (int k = 0; k < EPT; k += 4)
                             *reinterpret_cast<f32x4_t *>(po + k) = f32x4_t{acc[k], acc[k + 1], acc[k + 2], acc[k + 3]};
@@ -298,11 +320,80 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
 #pragma unroll
                         for (int k = 0; k < EPT; ++k) po[k] = acc[k];
                     }
-                    if (e0 == 0) { a.part_m[pi] = M; a.part_l[pi] = L; }
+                    if (!FUSE && e0 == 0) { a.part_m[pi] = M; a.part_l[pi] = L; }
                 }
             }
         }
         __syncthreads();
+    }
+    if constexpr (FUSE) {
+        if (n_live == 1) return;  // the output was written above
+        __shared__ int s_last;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's partial stores have been acknowledged
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t *tk = a.ticket + (size_t)b * a.kv.n_kv + kvh;
+            const uint32_t old = __hip_atomic_fetch_add(tk, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = old == (uint32_t)(n_live - 1);
+            if (s_last) __hip_atomic_store(tk, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next launch
+        }
+        __syncthreads();
+        if (!s_last) return;
+        constexpr int EPT = HD / 16, NCB = 16;  // host: at most 16 chunks
+        const int q = threadIdx.x >> 4, e0 = (threadIdx.x & 15) * EPT;
+        for (int qt = qs * TPW; qt < qt_end; ++qt) {
+            const int qj = qt * 16 + q;
+            if (qj >= QN) continue;
+            const int rr = r_first + qj % rps, hh = kvh * G + qj / rps;
+            const size_t pb = ((size_t)rr * a.nq + hh) * a.n_chunks;
+            float pm[NCB], pl[NCB];
+            uint64_t po[NCB][EPT / 2];
+#pragma unroll
+            for (int cc = 0; cc < NCB; ++cc) {
+                pm[cc] = -INFINITY; pl[cc] = 0.f;
+#pragma unroll
+                for (int k = 0; k < EPT / 2; ++k) po[cc][k] = 0;
+                if (cc < n_live) {
+                    pm[cc] = __hip_atomic_load(a.part_m + pb + cc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    pl[cc] = __hip_atomic_load(a.part_l + pb + cc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                    for (int k = 0; k < EPT / 2; ++k)
+                        po[cc][k] = __hip_atomic_load(reinterpret_cast<const uint64_t *>(a.part_o + (pb + cc) * HD + e0) + k,
+                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            const int nc = a.row_pos[rr] / CT + 1;  // chunks that hold a position this row may see
+            float M = -INFINITY;
+#pragma unroll
+            for (int cc = 0; cc < NCB; ++cc) M = cc < nc ? fmaxf(M, pm[cc]) : M;
+            float L = 0.f, acc[EPT];
+#pragma unroll
+            for (int k = 0; k < EPT; ++k) acc[k] = 0.f;
+#pragma unroll
+            for (int cc = 0; cc < NCB; ++cc) {
+                if (cc < nc) {
+                    const float f = __expf(pm[cc] - M);
+                    L += pl[cc] * f;
+#pragma unroll
+                    for (int k = 0; k < EPT / 2; ++k) {
+                        acc[2 * k] += f32_lo(po[cc][k]) * f;
+                        acc[2 * k + 1] += f32_hi(po[cc][k]) * f;
+                    }
+                }
+            }
+            const float inv = 1.f / L;
+            const size_t o = ((size_t)rr * a.nq + hh) * HD + e0;
+#pragma unroll
+            for (int k = 0; k < EPT; k += 2) {
+                const float v0 = acc[k] * inv, v1 = acc[k + 1] * inv;
+                a.o[o + k] = v0;
+                a.o[o + k + 1] = v1;
+                const uint32_t hi = pack_bf16x2(v0, v1);
+                *reinterpret_cast<uint32_t *>(a.ob + o + k) = hi;
+                if (a.ob_lo)
+                    *reinterpret_cast<uint32_t *>(a.ob + o + k + a.ob_lo) = pack_bf16x2(v0 - bf16_lo(hi), v1 - bf16_hi(hi));
+            }
+        }
     }
 }
 
@@ -312,7 +403,8 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
 // two slabs' K rows and V columns in flight while this one is multiplied: the loads never pause for the arithmetic, and a
 // sequence leaves two or three partials instead of a dozen.  The softmax runs on line: a wave keeps a running
 // maximum per query, and rescales its sum and its output tile when a slab raises it.  The four waves' partials are
-// merged as above.  One 16-query tile at a time; a sequence with more queries than that streams its chunk once per tile.
+// merged as above.  One 16-query tile per workgroup: the tiles of a sequence run side by side in grid.z, each streaming
+// the chunk for itself (the copies meet in the L2), rather than one after the other in one workgroup.
 template <int HD>
 __global__ __launch_bounds__(256, 2) void attn_stream_k(const AttnArgs a) {
     if (a.active != nullptr && *a.active == 0) return;
@@ -335,6 +427,12 @@ __global__ __launch_bounds__(256, 2) void attn_stream_k(const AttnArgs a) {
 
     const int cap = a.kv.pages_per_seq * a.kv.page_tokens;
     const bool has_qlo = a.qb_lo != 0;
+    // the tiles of a sequence are shared out over grid.z / batch workgroups (the host launches one per tile of the
+    // longest sequence, so that no workgroup streams its chunk more than once); a sequence with fewer tiles leaves
+    // the others nothing to do
+    const int QT = (QN + 15) / 16, TPW = (QT + QS - 1) / QS;
+    const int qt_end = min(QT, (qs + 1) * TPW);
+    if (qs * TPW >= qt_end) return;
     const int last_pos = __builtin_amdgcn_readfirstlane(a.row_pos[r_first + rps - 1]);
     if (t0 > last_pos) return;
     const int n_live = last_pos / CT + 1;
@@ -367,8 +465,6 @@ __global__ __launch_bounds__(256, 2) void attn_stream_k(const AttnArgs a) {
             d.vf[et] = *reinterpret_cast<const u32x2_t *>(vp + vb + (size_t)et * v_step);
     };
 
-    const int QT = (QN + 15) / 16, TPW = (QT + QS - 1) / QS;
-    const int qt_end = min(QT, (qs + 1) * TPW);
     for (int qt = qs * TPW; qt < qt_end; ++qt) {
         // Queries first, then the first two slabs, all before anything is waited for.  Every slab load below is
         // issued unconditionally (past the last slab the index is clamped, and the re-read hits the cache): the
@@ -591,20 +687,29 @@ static hipError_t launch_attn_mfma(const AttnArgs &a, dim3 grid, hipStream_t s) 
     // queries held ahead: chunks of up to 128 positions (beyond, the K / V fragments leave no registers) and few
     // enough workgroups that a compute unit does not wait for a slot
     const bool ahead = a.chunk <= 128 && (size_t)grid.x * grid.y * grid.z <= 1024;
+    // The fused merge: few workgroups, at most eight queries per (sequence, kv head) - decode rows - and no more chunks
+    // than it holds at once.  Measured on the 8B-shaped pair: the draft's attention (4 queries) 12.2 -> 10.8 us per
+    // layer including the launch gaps, the target's verification (16 queries) 14.6 -> 15.9 us, so that one keeps the
+    // second kernel.
+    static const bool no_fuse = std::getenv("SPEC_NO_ATTN_FUSE") != nullptr;
+    const bool fuse = ahead && !no_fuse && a.ticket != nullptr && (int)grid.z == a.batch && a.row_off == nullptr &&
+                      a.nq / a.kv.n_kv * a.rps <= 8 && a.n_chunks > 1 && a.n_chunks <= 16;
     switch (a.chunk / 64) {
         case 1:
-            if (ahead) hipLaunchKernelGGL((attn_mfma_k<HD, 1, true>), grid, dim3(256), 0, s, a);
+            if (fuse) hipLaunchKernelGGL((attn_mfma_k<HD, 1, true, true>), grid, dim3(256), 0, s, a);
+            else if (ahead) hipLaunchKernelGGL((attn_mfma_k<HD, 1, true>), grid, dim3(256), 0, s, a);
             else hipLaunchKernelGGL((attn_mfma_k<HD, 1, false>), grid, dim3(256), 0, s, a);
             break;
         case 2:
-            if (ahead) hipLaunchKernelGGL((attn_mfma_k<HD, 2, true>), grid, dim3(256), 0, s, a);
+            if (fuse) hipLaunchKernelGGL((attn_mfma_k<HD, 2, true, true>), grid, dim3(256), 0, s, a);
+            else if (ahead) hipLaunchKernelGGL((attn_mfma_k<HD, 2, true>), grid, dim3(256), 0, s, a);
             else hipLaunchKernelGGL((attn_mfma_k<HD, 2, false>), grid, dim3(256), 0, s, a);
             break;
         case 4: hipLaunchKernelGGL((attn_mfma_k<HD, 4, false>), grid, dim3(256), 0, s, a); break;
         default: hipLaunchKernelGGL((attn_mfma_k<HD, 8, false>), grid, dim3(256), 0, s, a); break;
     }
     const hipError_t e = hipGetLastError();
-    if (e != hipSuccess || a.n_chunks == 1) return e;
+    if (e != hipSuccess || a.n_chunks == 1 || fuse) return e;
     const int items = a.R * a.nq * (HD / 4);
     if (a.n_chunks <= 16) hipLaunchKernelGGL((attn_mfma_merge_k<HD, 16>), dim3((items + 255) / 256), dim3(256), 0, s, a);
     else hipLaunchKernelGGL((attn_mfma_merge_k<HD, ATT_NC_MAX>), dim3((items + 255) / 256), dim3(256), 0, s, a);
@@ -621,7 +726,9 @@ hipError_t launch_attention(const AttnArgs &a, int hd, hipStream_t s) {
         if (a.chunk % 64 || (spw != 1 && spw != 2 && spw != 4 && spw != 8) || a.n_chunks > ATT_NC_MAX)
             return hipErrorInvalidValue;
         const int QT = (a.nq / a.kv.n_kv * a.rps + 15) / 16;
-        const dim3 grid(a.n_chunks, a.kv.n_kv, B * ((QT + ATT_TILES_PER_WG - 1) / ATT_TILES_PER_WG));
+        // streamed chunks: a workgroup per tile (a second tile would stream the chunk a second time, one after the other)
+        const int tpw = a.stream_chunks ? 1 : ATT_TILES_PER_WG;
+        const dim3 grid(a.n_chunks, a.kv.n_kv, B * ((QT + tpw - 1) / tpw));
         if (hd == 32) return launch_attn_mfma<32>(a, grid, s);
         if (hd == 64) return launch_attn_mfma<64>(a, grid, s);
         return launch_attn_mfma<128>(a, grid, s);

@@ -131,6 +131,7 @@ struct AttnArgs {
     float scale;
     float *part_m, *part_l;  // [R][nq][n_chunks]
     float *part_o;           // [R][nq][n_chunks][hd]
+    uint32_t *ticket;        // [batch][n_kv] arrival counters, zero between launches; null: the partials are merged by a second kernel
     float *o;                // [R][nq*hd]
     uint16_t *ob;            // bf16 copy
     const int32_t *active;
