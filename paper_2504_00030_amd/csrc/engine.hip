@@ -106,6 +106,7 @@ struct spec_ctx {
     int verify_only_rows = 0;  // rows of the last spec_debug_verify_rows pass (0: the last target pass was a step's)
     int cur_rows = 0;      // rows of the current step's verification pass when it is ragged, else 0
     bool ragged_ok = false;  // several sequences and a target whose attention takes ragged rows
+    bool compact_ok = false; // the same for the draft model: passes after the first hold only the sequences still drafting
     bool prefilled = false;
     std::map<int, hipGraphExec_t> g_draft, g_pass;  // whole draft phase per gamma, draft pass j
     // verification pass per (gamma, rows), with the logits tiling its LM-head launch uses: the accept kernels run
@@ -511,6 +512,7 @@ struct LogitsPlan {
     int rows = 0;           // logits rows produced
     int x_mul = 1, x_add = 0;
     int y_mul = 1, y_add = 0;
+    const int32_t *y_rows = nullptr;  // device: output row of every logical row (null: the row itself)
     int *tile = nullptr, *ntiles = nullptr;
 };
 
@@ -624,7 +626,7 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
         a.x_mul = lp.x_mul; a.x_add = lp.x_add;
         a.w0 = m.lm_head; a.n0 = s.vocab;
         a.ssq_in = m.ssq; a.ssq_in_slots = slots;
-        a.y = m.logits; a.y_mul = lp.y_mul; a.y_add = lp.y_add; a.y_stride = s.vocab;
+        a.y = m.logits; a.y_mul = lp.y_mul; a.y_add = lp.y_add; a.y_rows = lp.y_rows; a.y_stride = s.vocab;
         a.pm = m.pm; a.ps = m.ps; a.pa = m.pa; a.inv_t = c->scfg.inv_t;
         int nb = 0, tile = 0;
         a.wscale = tiled ? m.sc_lm : nullptr;
@@ -632,19 +634,22 @@ int forward(spec_ctx *c, ModelRT &m, const RowPlan &plan, const LogitsPlan &lp, 
         *lp.tile = tile;
         *lp.ntiles = nb;
         HIPCHK(c, launch_merge_partials(m.pm, m.ps, m.pa, nb, c->scfg.inv_t, m.pm2, m.ps2, m.pa2, lp.rows, lp.y_mul, lp.y_add,
-                                        active, st));
+                                        lp.y_rows, active, st));
     }
     return SPEC_OK;
 }
 
 // One draft pass: forward of the draft model and the sampler; pass 1 also opens the step.
-int enqueue_draft_pass(spec_ctx *c, int j) {
+// `rows` > 0 (passes after the first): only the `rows` sequences that still draft have a row, in sequence order
+// (embed_k finds them from the device's own k[b]); the caller knows their number from the planned gammas or from
+// what the previous pass's sampler reported.  The sampler works per sequence either way.
+int enqueue_draft_pass(spec_ctx *c, int j, int rows = 0) {
     if (j == 1) HIPCHK(c, launch_begin_draft(c->st, c->d_gamma_plan, c->stream));
     const int B = c->cfg.batch;
     RowPlan plan{};
     LogitsPlan lp{};
     lp.want = true;
-    lp.rows = B;
+    lp.rows = rows > 0 ? rows : B;
     lp.tile = &c->d_tile;
     lp.ntiles = &c->d_ntiles;
     lp.y_mul = c->cfg.gamma_max;
@@ -655,8 +660,9 @@ int enqueue_draft_pass(spec_ctx *c, int j) {
     } else {
         plan.mode = ROWS_DRAFT_NEXT; plan.rps = 1; plan.arg = j;
         lp.x_mul = 1; lp.x_add = 0;
+        if (rows > 0) { plan.ragged = 1; lp.y_rows = c->drf.row_seq; }
     }
-    TRY(forward(c, c->drf, plan, lp, true));
+    TRY(forward(c, c->drf, plan, lp, true, rows));
     DraftSampleArgs a{};
     a.st = c->st; a.cfg = c->scfg; a.j = j; a.gamma_max = c->cfg.gamma_max; a.logits = c->drf.logits;
     a.vocab = c->drf.s.vocab; a.pm = c->drf.pm; a.ps = c->drf.ps; a.pa = c->drf.pa;
@@ -802,7 +808,7 @@ hipError_t accept_on_scratch(uint8_t *buf, const AcceptScratch &L, const float *
     float *pm2 = reinterpret_cast<float *>(buf + L.o_pm2);
     double *ps2 = reinterpret_cast<double *>(buf + L.o_ps2);
     int32_t *pa2 = reinterpret_cast<int32_t *>(buf + L.o_pa2);
-    if ((e = launch_merge_partials(pm, ps, pa, n_tiles, inv_t, pm2, ps2, pa2, k + 1, 1, 0, nullptr, st)) != hipSuccess) return e;
+    if ((e = launch_merge_partials(pm, ps, pa, n_tiles, inv_t, pm2, ps2, pa2, k + 1, 1, 0, nullptr, nullptr, st)) != hipSuccess) return e;
     float *ql = reinterpret_cast<float *>(buf + L.o_ql), *qmax = reinterpret_cast<float *>(buf + L.o_qmax);
     double *qsum = reinterpret_cast<double *>(buf + L.o_qsum);
     if ((e = launch_gather_qstats(q_logits, drafted, k, vocab, qm, qs, qa, n_tiles, inv_t, ql, qmax, qsum, st)) != hipSuccess) return e;
@@ -986,6 +992,8 @@ int spec_init(const spec_shape *t, const spec_weights *tw, const spec_shape *d, 
     c->st.max_seq = g.max_seq;
     c->st.batch = B;
     c->ragged_ok = B > 1 && model_on_matrix_cores(c->cfg, *t) && attention_on_matrix_cores(c->cfg, *t);
+    c->compact_ok = B > 1 && model_on_matrix_cores(c->cfg, *d) && attention_on_matrix_cores(c->cfg, *d) &&
+                    std::getenv("SPEC_NO_DRAFT_COMPACT") == nullptr;
     c->h_len.assign(B, 0);
 
     void *hp = nullptr;
@@ -1153,26 +1161,43 @@ int spec_draft_batch(spec_ctx *c, const int32_t *gammas) {
     for (int b = 0; b < B; ++b)
         if (c->h_len[b] + gmax + 1 > c->cfg.max_seq) return fail(c, SPEC_ECAP, "draft: len + gamma + 1 > max_seq");
     for (int b = 0; b < B; ++b) c->h_gamma_plan[b] = gammas[b];
+    // One pass, with a row for every sequence (rows == 0) or only for the `rows` sequences that still draft.
+    auto launch_pass = [&](int j, int rows) -> int {
+        if (rows >= B) rows = 0;
+        if (c->cfg.use_graphs) {
+            const int key = rows * 128 + j;  // j <= 64
+            auto it = c->g_pass.find(key);
+            if (it == c->g_pass.end()) {
+                hipGraphExec_t ex = nullptr;
+                TRY(capture(c, [&] { return enqueue_draft_pass(c, j, rows); }, &ex));
+                it = c->g_pass.emplace(key, ex).first;
+            }
+            HIPCHK(c, hipGraphLaunch(it->second, c->stream));
+        } else {
+            TRY(enqueue_draft_pass(c, j, rows));
+        }
+        c->passes_launched += 1;
+        return SPEC_OK;
+    };
+    bool differ = false;
+    for (int b = 1; b < B; ++b) differ = differ || gammas[b] != gammas[0];
     if (c->scfg.tau > 0.f && gmax > 1) {
-        // early stopping: pass by pass, and the next pass only while a sequence still drafts
+        // early stopping: pass by pass, and the next pass only while a sequence still drafts - over those sequences
+        // alone where the draft model's kernels take packed rows
         for (int j = 1; j <= gmax; ++j) {
+            int active = B;
             if (j > 1) {
-                int active = 0;
                 TRY(wait_draft_pass(c, c->passes_launched, &active));
                 if (active == 0) break;
             }
-            if (c->cfg.use_graphs) {
-                auto it = c->g_pass.find(j);
-                if (it == c->g_pass.end()) {
-                    hipGraphExec_t ex = nullptr;
-                    TRY(capture(c, [&] { return enqueue_draft_pass(c, j); }, &ex));
-                    it = c->g_pass.emplace(j, ex).first;
-                }
-                HIPCHK(c, hipGraphLaunch(it->second, c->stream));
-            } else {
-                TRY(enqueue_draft_pass(c, j));
-            }
-            c->passes_launched += 1;
+            TRY(launch_pass(j, c->compact_ok ? active : 0));
+        }
+    } else if (c->compact_ok && differ) {
+        // planned gammas differ: pass j holds the sequences that planned at least j tokens
+        for (int j = 1; j <= gmax; ++j) {
+            int rows = 0;
+            for (int b = 0; b < B; ++b) rows += gammas[b] >= j;
+            TRY(launch_pass(j, rows));
         }
     } else if (c->cfg.use_graphs) {
         auto it = c->g_draft.find(gmax);

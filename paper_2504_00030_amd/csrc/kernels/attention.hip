@@ -146,6 +146,7 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
     // rows of this sequence: a.rps each, or its own count when the sequences of a verification pass differ
     const int r_first = a.row_off != nullptr ? a.row_off[b] : b * a.rps;
     const int rps = a.row_off != nullptr ? a.row_off[b + 1] - r_first : a.rps;
+    if (rps <= 0) return;  // a sequence without rows in this pass (draft passes over the sequences still drafting)
     const int QN = G * rps;
     const int t0 = c * CT;
     const bf16_t *kp = reinterpret_cast<const bf16_t *>(a.kv.k);
@@ -417,6 +418,7 @@ __global__ __launch_bounds__(256, 2) void attn_stream_k(const AttnArgs a) {
     const int G = a.nq / a.kv.n_kv;
     const int r_first = a.row_off != nullptr ? a.row_off[b] : b * a.rps;
     const int rps = a.row_off != nullptr ? a.row_off[b + 1] - r_first : a.rps;
+    if (rps <= 0) return;  // a sequence without rows in this pass (draft passes over the sequences still drafting)
     const int QN = G * rps;
     const int t0 = c * CT;
     const bf16_t *kp = reinterpret_cast<const bf16_t *>(a.kv.k);

@@ -123,7 +123,7 @@ __device__ __forceinline__ void epilogue_tile(const GemvArgs &a, const float *ti
             const int n = n_base + c;
             const bool valid = r < R && n < Ntot;
             const int rr = min(r, R - 1);
-            const int orow = rr * a.y_mul + a.y_add;
+            const int orow = (a.y_rows != nullptr ? a.y_rows[rr] : rr) * a.y_mul + a.y_add;
             const float v = valid ? tile[rr * TS + c] * scale[rr] : -INFINITY;
             if (valid) a.y[(size_t)orow * a.y_stride + n] = v;
             float m = v;

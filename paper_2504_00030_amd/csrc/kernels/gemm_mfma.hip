@@ -100,8 +100,12 @@ template <int EPI> __device__ __forceinline__ GemvArgs rows_from(const GemvArgs 
     } else if constexpr (EPI == EPI_QKV) {
         b.y += ro * a.nq * a.hd; b.yb += ro * a.nq * a.hd; b.row_pos += row0; b.row_seq += row0;
     } else if constexpr (EPI == EPI_LOGITS) {
-        const size_t orow = ro * a.y_mul;
-        b.y += orow * a.y_stride; b.pm += orow * a.n_tiles; b.ps += orow * a.n_tiles; b.pa += orow * a.n_tiles;
+        if (a.y_rows != nullptr) {
+            b.y_rows += row0;  // the rows' own output rows, looked up by the epilogue
+        } else {
+            const size_t orow = ro * a.y_mul;
+            b.y += orow * a.y_stride; b.pm += orow * a.n_tiles; b.ps += orow * a.n_tiles; b.pa += orow * a.n_tiles;
+        }
     }
     return b;
 }

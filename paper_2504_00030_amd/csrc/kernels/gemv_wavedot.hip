@@ -256,7 +256,8 @@ __global__ __launch_bounds__(256) void gemv_wavedot_k(const GemvArgs a) {
             const int n = t_begin + lane / RC;
             const int r = r0 + rc;
             const bool valid = lane < a.rpw * RC && n < Ntot && r < a.R && t_begin < Ntot;
-            const int orow = min(r, a.R - 1) * a.y_mul + a.y_add;
+            const int lrow = min(r, a.R - 1);
+            const int orow = (a.y_rows != nullptr ? a.y_rows[lrow] : lrow) * a.y_mul + a.y_add;
             float v = valid ? mine : -INFINITY;
             if (valid) a.y[(size_t)orow * a.y_stride + n] = v;
             float m = v;

@@ -42,7 +42,24 @@ __global__ __launch_bounds__(256) void embed_k(const EmbedArgs a) {
     if (a.plan.mode == ROWS_DRAFT_NEXT && a.st.ctl[1] == 0) return;
     const int r = blockIdx.x;
     int b = r / a.plan.rps, i = r % a.plan.rps;
-    if (a.plan.ragged) {
+    if (a.plan.ragged && a.plan.mode == ROWS_DRAFT_NEXT) {
+        // row r belongs to the r-th sequence that still drafts (a scan over at most 64 sequences); a row past their
+        // number (the host counted them) repeats the last one
+        int seen = 0;
+        b = 0;
+        for (int s = 0; s < a.st.batch; ++s) {
+            if (a.st.k[s] == 0) {
+                if (seen <= r) b = s;
+                ++seen;
+            }
+        }
+        i = 0;
+        if (r == 0 && threadIdx.x == 0) {
+            int o = 0;
+            for (int s = 0; s < a.st.batch; ++s) { a.row_off[s] = o; o += a.st.k[s] == 0; }
+            a.row_off[a.st.batch] = o;
+        }
+    } else if (a.plan.ragged) {
         // sequence b owns rows off_b .. off_b + gamma_b[b]: a scan over at most 64 sequences
         int off = 0;
         b = 0;

@@ -28,7 +28,8 @@ struct RowPlan {
     int32_t mode;   // ROWS_*
     int32_t rps;    // rows per sequence (ragged: the most any sequence has)
     int32_t arg;    // PREFILL: first position; DRAFT_NEXT: draft step j (>= 2)
-    int32_t ragged; // VERIFY only: sequence b has gamma_b[b] + 1 rows, packed one sequence after the other
+    int32_t ragged; // VERIFY: sequence b has gamma_b[b] + 1 rows, packed one sequence after the other;
+                    // DRAFT_NEXT: one row per sequence that still drafts (k[b] == 0), in sequence order
 };
 
 struct KVCache {
@@ -64,7 +65,8 @@ struct GemvArgs {
     uint32_t *ks_ticket;
     // ---- epilogue ----
     float *y;                 // PLAIN: [R][N]; LOGITS: logits base; QKV: q [R][nq*hd]
-    int32_t y_mul, y_add, y_stride;  // LOGITS: logical row r writes row r * y_mul + y_add
+    int32_t y_mul, y_add, y_stride;  // LOGITS: logical row r writes row r * y_mul + y_add ...
+    const int32_t *y_rows;    // ... or, when given, row y_rows[r] * y_mul + y_add (draft passes over the sequences still drafting)
     // RESID
     float *xres;              // [R][N] residual stream, read-modify-write
     const float *g_next;      // [N] weight of the norm that consumes the new residual (null -> ones)
@@ -218,8 +220,8 @@ hipError_t launch_accept(const AcceptArgs &a, hipStream_t s);
 hipError_t launch_row_partials(const float *logits, int rows, int vocab, int tile, float inv_t, float *pm, double *ps,
                                int32_t *pa, hipStream_t s);
 hipError_t launch_merge_partials(const float *pm, const double *ps, const int32_t *pa, int n1, float inv_t, float *pm2,
-                                 double *ps2, int32_t *pa2, int rows, int y_mul, int y_add, const int32_t *active,
-                                 hipStream_t s);
+                                 double *ps2, int32_t *pa2, int rows, int y_mul, int y_add, const int32_t *y_rows,
+                                 const int32_t *active, hipStream_t s);
 hipError_t launch_gather_qstats(const float *q_logits, const int32_t *drafted, int rows, int vocab, const float *pm,
                                 const double *ps, const int32_t *pa, int n_tiles, float inv_t, float *q_logit,
                                 float *q_max, double *q_sum, hipStream_t s);

@@ -153,10 +153,11 @@ __device__ int wave_sample_row(const float *logits, int vocab, const PartRow &p,
 // Level-2 partials: one wave merges 64 consecutive level-1 partials of one row.
 __global__ __launch_bounds__(64) void merge_partials_k(const float *pm, const double *ps, const int32_t *pa, int n1,
                                                        float inv_t, float *pm2, double *ps2, int32_t *pa2, int n2,
-                                                       int y_mul, int y_add, const int32_t *active) {
+                                                       int y_mul, int y_add, const int32_t *y_rows,
+                                                       const int32_t *active) {
     if (active != nullptr && *active == 0) return;
     const int j = blockIdx.x, lane = threadIdx.x;
-    const size_t row = (size_t)blockIdx.y * y_mul + y_add;
+    const size_t row = (size_t)(y_rows != nullptr ? y_rows[blockIdx.y] : (int)blockIdx.y) * y_mul + y_add;
     const int t0 = j * 64, n = min(64, n1 - t0);
     const RowStats r = wave_reduce_partials(pm + row * n1 + t0, ps + row * n1 + t0, pa + row * n1 + t0, n, (double)inv_t, lane);
     if (lane == 0) {
@@ -167,11 +168,11 @@ __global__ __launch_bounds__(64) void merge_partials_k(const float *pm, const do
 }
 
 hipError_t launch_merge_partials(const float *pm, const double *ps, const int32_t *pa, int n1, float inv_t, float *pm2,
-                                 double *ps2, int32_t *pa2, int rows, int y_mul, int y_add, const int32_t *active,
-                                 hipStream_t s) {
+                                 double *ps2, int32_t *pa2, int rows, int y_mul, int y_add, const int32_t *y_rows,
+                                 const int32_t *active, hipStream_t s) {
     const int n2 = (n1 + 63) / 64;
     hipLaunchKernelGGL(merge_partials_k, dim3(n2, rows), dim3(64), 0, s, pm, ps, pa, n1, inv_t, pm2, ps2, pa2, n2, y_mul,
-                       y_add, active);
+                       y_add, y_rows, active);
     return hipGetLastError();
 }
 

@@ -683,13 +683,19 @@ def test_plain_copy_kernel():
     assert torch.equal(dst, src)
 
 
-def test_small_bf16_pair_batch_forced_early_stop_graphs():
+@pytest.mark.parametrize("batch,n_generate", [(2, 48), (24, 24)])
+def test_small_bf16_pair_batch_forced_early_stop_graphs(batch, n_generate):
+    """Confidence stop with several sequences: after the first pass of a step the draft passes hold a row only for
+    the sequences that still draft (two sequences: one or two rows; 24: from 24 rows on the dense-contraction LM head,
+    whose logits rows are looked up per row, down to the streaming kernels), one graph per (pass, rows)."""
     cfg = synth.pair("small-bf16")
     alpha = synth.alpha_piecewise(256, 16)
-    c, toks, trace = _run_pair(cfg, controller="gammatune", temperature=0.7, seed=2, batch=2, accept_mode=1, alpha=alpha,
-                               tau=float(np.float32(0.4)), use_graphs=True, n_generate=48)
+    c, toks, trace = _run_pair(cfg, controller="gammatune", temperature=0.7, seed=2, batch=batch, accept_mode=1, alpha=alpha,
+                               tau=float(np.float32(0.4)), use_graphs=True, n_generate=n_generate)
     _assert_clean(c, full_coverage=False)
     assert max(int(r["gamma"].max()) for r in trace) >= 3
+    if batch > 2:  # the sequences of a step did stop at different passes
+        assert any(len({int(k) for k in np.atleast_1d(r["k"])}) > 1 for r in trace)
 
 
 @pytest.mark.parametrize("pair,batch,gamma", [("small-bf16", 24, 7), ("small-bf16-hd128", 40, 15), ("small-bf16", 64, 15),
