@@ -1561,7 +1561,7 @@ int spec_k_gemm_tiled(const void *w_tiled, int32_t N, int32_t K, const float *x,
                       void *workspace, int64_t workspace_bytes, void *stream) {
     if (!w_tiled || !x || !y || N < 16 || K < 32 || N % 16 || K % 32 || R < 1 || workspace_bytes < 0) return SPEC_EINVAL;
     const int shape = cfg % 1000, shares = cfg / 1000;
-    if (cfg < 0 || (shape != 0 && shape != 408 && shape != 404 && shape != 304 && shape != 204 && shape != 104 && shape != 808) || shares > 8) return SPEC_EINVAL;
+    if (cfg < 0 || (shape != 0 && shape != 408 && shape != 404 && shape != 304 && shape != 204 && shape != 104 && shape != 808 && shape != 524) || shares > 8) return SPEC_EINVAL;
     GemvArgs a{};
     a.w0 = w_tiled; a.n0 = N; a.K = K; a.R = R; a.x = x; a.x_mul = 1; a.y = y;
     const hipStream_t st = reinterpret_cast<hipStream_t>(stream);

@@ -626,6 +626,10 @@ static hipError_t launch_gemm_cfg(const GemvArgs &a, int Ntot, int forced, float
         if ((cfg == 404 || cfg == 408) && a.R <= 64) cfg = a.R <= 32 ? 104 : 204;
         // (the 96-row block also wherever it needs no more blocks than the 128-row one: 129-192 rows, 257-288)
         if (cfg == 404 && (a.R + 95) / 96 == (a.R + 127) / 128) cfg = 304;
+        // 97-128 rows (one 128-row block): eight waves of 32 x 64 on the 128 x 128 block where the matrix gives every
+        // compute unit a block (measured, gate/up shape at 128 rows: 87 -> 71 us), else two 64-row blocks, which make
+        // twice the workgroups (down / QKV / output projection shapes: 57 -> 51, 35 -> 32, 30 -> 27 us)
+        if (cfg == 404 && a.R > 96 && a.R <= 128 && !q8) cfg = (Ntot + 127) / 128 >= 200 ? 524 : 204;
     }
     if (ksplit == 0) ksplit = ((cfg == 404 || cfg == 304 || cfg == 204 || cfg == 104) && ws != nullptr) ? pick_ksplit(Ntot, a.K, a.R, ws_bytes, q8) : 1;
     if (ksplit > 1) {
@@ -646,6 +650,7 @@ static hipError_t launch_gemm_cfg(const GemvArgs &a, int Ntot, int forced, float
             case 408: e = launch_gemm_one<EPI_PLAIN, 4, 8, false, 0>(p, Ntot, ksplit, stride, ev0, ev1, s); break;
             case 1408: e = launch_gemm_one<EPI_PLAIN, 4, 8, false, 1>(p, Ntot, ksplit, stride, ev0, ev1, s); break;
             case 808: e = launch_gemm_one<EPI_PLAIN, 4, 8, false, 0, 4>(p, Ntot, ksplit, stride, ev0, ev1, s); break;
+            case 524: e = launch_gemm_one<EPI_PLAIN, 2, 4, true, 0, 4>(p, Ntot, ksplit, stride, ev0, ev1, s); break;
             case 1808: e = launch_gemm_one<EPI_PLAIN, 4, 8, false, 1, 4>(p, Ntot, ksplit, stride, ev0, ev1, s); break;
         }
         if (e != hipSuccess) return e;
@@ -663,6 +668,7 @@ static hipError_t launch_gemm_cfg(const GemvArgs &a, int Ntot, int forced, float
         case 1204: return launch_gemm_one<EPI, 2, 4, true, 1>(a, Ntot, 1, 0, ev0, ev1, s);
         case 1408: return launch_gemm_one<EPI, 4, 8, false, 1>(a, Ntot, 1, 0, ev0, ev1, s);
         case 808: return launch_gemm_one<EPI, 4, 8, false, 0, 4>(a, Ntot, 1, 0, ev0, ev1, s);
+        case 524: return launch_gemm_one<EPI, 2, 4, true, 0, 4>(a, Ntot, 1, 0, ev0, ev1, s);
         case 1808: return launch_gemm_one<EPI, 4, 8, false, 1, 4>(a, Ntot, 1, 0, ev0, ev1, s);
         case 1404: return launch_gemm_one<EPI, 4, 4, true, 1>(a, Ntot, 1, 0, ev0, ev1, s);
     }
