@@ -97,8 +97,8 @@ __global__ __launch_bounds__(128) void attn_combine_k(const AttnArgs a) {
 
 // ---- matrix-core version for 16-bit caches --------------------------------------------------------
 // One workgroup per (chunk of 64 * SPW positions, kv head, sequence); wave w owns the 16-position slabs
-// w, w + 4, ... of the chunk.  A wave first issues every load of its slabs (K rows and transposed V
-// columns, straight into the operand layouts; positions past the last visible one are clamped, so the
+// w, w + 4, ... of the chunk.  A wave first issues every load of its slabs (K and V fragments
+// - kv.hpp - straight into the operand layouts; positions past the last visible one are clamped, so the
 // loads and the matrix instructions need no branch), then per 16-query tile forms S^T = K Q^T with
 // v_mfma_f32_16x16x32_bf16, takes the softmax over its slabs, and multiplies by V with
 // v_mfma_f32_16x16x16_bf16: the S^T result registers already are the A operand (query = lane % 16, four
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(256) void attn_mfma_k(const AttnArgs a) {
     __shared__ float sM[4][16], sL[4][16];
 
     // K fragment: position tw + l16, channels 32 s + 8 g .. + 8; V fragment: channel 16 et + l16, positions
-    // tw + 4 g .. + 4 (contiguous in the transposed page).  Positions are clamped to the cache capacity only, not to
+    // tw + 4 g .. + 4 (eight contiguous bytes in either arrangement of the page).  Positions are clamped to the cache capacity only, not to
     // the sequence length: the loads then depend on nothing but the block table and start at once; whatever finite
     // values lie beyond the last visible position meet a zero probability.
     const int cap = a.kv.pages_per_seq * a.kv.page_tokens;
