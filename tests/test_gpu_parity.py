@@ -1,4 +1,6 @@
 """GPU parity: the HIP path against the CPU oracle on the same seeded inputs, through the C ABI."""
+import os
+
 import numpy as np
 import pytest
 
@@ -672,6 +674,27 @@ def test_two_runs_are_bit_identical(pair_name, batch):
             assert np.array_equal(u, v), f"step {step}: {name} differ between two runs"
     for u, v in zip(t0, t1):
         assert np.array_equal(u, v)
+
+
+@pytest.mark.parametrize("batch", [1, 2])
+def test_merge_in_the_attention_kernel_equals_the_merge_kernel(batch):
+    """Decode rows merge their chunk partials in the attention kernel's last workgroup, with the arithmetic of the
+    merge kernel in the same order: a generation with that path switched off (the switch is read once per process,
+    hence two child processes) must give the same bits - every draft and target logit, accept result and token."""
+    import subprocess
+    import sys
+    here = os.path.dirname(os.path.abspath(__file__))
+    digests = []
+    for extra in ({}, {"SPEC_NO_ATTN_FUSE": "1"}):
+        env = {k: v for k, v in os.environ.items() if k != "SPEC_NO_ATTN_FUSE"}
+        env.update(extra)
+        out = subprocess.run([sys.executable, os.path.join(here, "gpu_digest_run.py"), str(batch)], env=env, capture_output=True,
+                             text=True, timeout=240)
+        assert out.returncode == 0, out.stderr[-2000:]
+        lines = [ln for ln in out.stdout.splitlines() if ln.startswith("DIGEST ")]
+        assert len(lines) == 1, out.stdout[-2000:]
+        digests.append(lines[0].split()[1])
+    assert digests[0] == digests[1]
 
 
 def test_plain_copy_kernel():
