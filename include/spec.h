@@ -124,7 +124,7 @@ int spec_prefill_ragged(spec_ctx *ctx, const int32_t *host_tokens, int32_t n_max
  * Philox(seed; counter = (step, i, DRAFT, b)) (argmax if T == 0), appends it to the
  * sequence, and keeps the draft logits row for the accept phase.  With early stopping
  * enabled drafting of a sequence ends after the first x_i whose confidence is below tau;
- * that x_i is kept; the call then launches pass by pass and waits for each pass's verdict (a few words
+ * that x_i is kept; the call then launches pass by pass and waits for each pass's outcome (a few words
  * in pinned memory) before it launches the next, so it returns when the last pass has been enqueued.  1 <= gamma <= gamma_max.  SPEC_ECAP if len + gamma + 1 > max_seq. */
 int spec_draft(spec_ctx *ctx, int32_t gamma);
 
